@@ -1,0 +1,123 @@
+/*
+ * dgo.h -- CPU oracle for the DistGrid training hot path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is a plain, slow, single-threaded, double
+ * precision restatement of what the hot path computes, written from the
+ * paper (DistGrid, arXiv 2405.04416) and from the published Instant-NGP
+ * equations the paper inherits.  It shares no code, header, table or
+ * constant generator with the HIP library and must never be linked, imported
+ * or called by it.  Only tests, the smoke check and the benchmark's
+ * cpu-baseline leg may use it.
+ *
+ * All pointers are host pointers.  Arrays are row-major, innermost dimension
+ * last.  Floating point inputs that the method fixes as fp32 (coordinates,
+ * tables, ray data) are float; every result the oracle computes is double,
+ * except the two places where the method demands bit-exact fp32/integer
+ * bookkeeping (segment times and vertex indices).
+ *
+ * Parity pins (tests/test_oracle_*.py): every function below is pinned to a
+ * closed form, an invariant, a library routine or brute force; none is
+ * "parity unpinned" except dgo_grid_param_count against the two parameter
+ * totals the paper prints (Sec. 5.3), whose scene extents are not given.
+ */
+#ifndef DGO_H
+#define DGO_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DGO_MAX_LEVELS 16
+
+/* Deformable multi-resolution hash grid geometry (Sec. 3.2, Sec. 4.1). */
+typedef struct {
+    uint32_t L;                         /* number of levels                       */
+    uint32_t F;                         /* features per entry                     */
+    uint32_t log2_T;                    /* hash table length T = 2^log2_T         */
+    uint32_t N[DGO_MAX_LEVELS];         /* N_l: voxels along the longest axis     */
+    uint32_t shape[DGO_MAX_LEVELS][3];  /* voxels per axis: ceil(a_d/s * N_l)     */
+    uint32_t is_dense[DGO_MAX_LEVELS];  /* one-to-one map if #vertices <= T       */
+    uint64_t first[DGO_MAX_LEVELS + 1]; /* first entry of each level in the table */
+    float    gain[DGO_MAX_LEVELS][3];   /* grid position = u_d * gain[l][d]       */
+} dgo_grid;
+
+/* N_l = floor(N_min * b^l) (Instant-NGP Eq. 2), shape per Sec. 4.1. */
+int dgo_grid_init(dgo_grid *g, uint32_t L, uint32_t F, uint32_t log2_T,
+                  uint32_t N_min, double growth, const double extent[3]);
+/* b = exp((ln N_max - ln N_min)/(L-1)) (Instant-NGP Eq. 3). */
+double dgo_growth_factor(uint32_t N_min, uint32_t N_max, uint32_t L);
+uint64_t dgo_grid_param_count(const dgo_grid *g);
+
+/* Spatial hash of integer vertex coordinates (Instant-NGP Eq. 4), T = 2^log2_T. */
+uint32_t dgo_hash(uint32_t x, uint32_t y, uint32_t z, uint32_t log2_T);
+/* Entry index (relative to the level's first entry) of vertex (x,y,z). */
+uint32_t dgo_vertex_entry(const dgo_grid *g, uint32_t level, uint32_t x, uint32_t y, uint32_t z);
+
+/* Encode forward: feat[n, l*F+f] = sum over the 8 cell corners of w_c * table[entry_c, f].
+ * idx (nullable) receives the absolute entry index of each corner: [N, L, 8]. */
+void dgo_encode_fwd(const dgo_grid *g, const float *table, const float *u, uint64_t n,
+                    double *feat, uint32_t *idx, int abs_terms);
+/* Encode backward (transpose): dtable[entry_c, f] += w_c * dfeat[n, l*F+f]. */
+void dgo_encode_bwd(const dgo_grid *g, const float *u, const double *dfeat, uint64_t n,
+                    double *dtable);
+
+/* Ray / AABB slab test against P boxes; ordered segment list per ray (Sec. 4.2.1, Fig. 2 step 2). */
+void dgo_ray_aabb_segments(const float *o, const float *d, uint32_t R, const float *aabb, uint32_t P,
+                           float t_min, uint32_t k_max, uint32_t *seg_count, float *seg_t,
+                           int32_t *seg_part, uint32_t *status);
+/* Stable distribution of (ray, slot) pairs to partitions (Fig. 2 step 3). */
+void dgo_bucket_segments(const uint32_t *seg_count, const int32_t *seg_part, uint32_t R, uint32_t k_max,
+                         uint32_t P, uint32_t *part_offset, uint32_t *seg_ray, uint32_t *seg_slot);
+/* Counter-based jitter in [0,1) for (seed, ray, slot, sample). */
+float dgo_jitter(uint64_t seed, uint32_t ray, uint32_t slot, uint32_t s);
+/* Stratified samples of segments [seg_begin, seg_end) that all lie in box `aabb6`. */
+void dgo_sample_segments(const float *o, const float *d, const float *seg_t, const uint32_t *seg_ray,
+                         const uint32_t *seg_slot, uint32_t seg_begin, uint32_t seg_end, uint32_t k_max,
+                         const float *aabb6, uint32_t S, uint64_t seed, const float *jitter,
+                         float *u, float *delta);
+
+/* Real spherical harmonics, bands l = 0..degree-1, on normalised d: out [n, degree^2]. */
+void dgo_sh(const float *d, uint64_t n, uint32_t degree, double *out);
+
+/* fp16 round-to-nearest-even of a double, returned as double. */
+double dgo_round_f16(double x);
+
+/* Field MLP pair (density then colour, Sec. 3.2 / Sec. 5.1). */
+typedef struct {
+    uint32_t n_feat;      /* density input width (L*F)                        */
+    uint32_t n_hidden_d;  /* density hidden width (one ReLU hidden layer)     */
+    uint32_t n_geo;       /* density output width; out[0] is the raw density  */
+    uint32_t n_dir;       /* direction-encoding width                         */
+    uint32_t n_hidden_c;  /* colour hidden width                              */
+    uint32_t n_layers_c;  /* colour hidden layers: 1 or 2                     */
+    uint32_t act_c;       /* colour hidden activation: 0 ReLU, 1 sigmoid      */
+    uint32_t round_f16;   /* 1: apply the fp16 rounding points; 0: pure double */
+} dgo_mlp;
+uint64_t dgo_mlp_weight_count(const dgo_mlp *m);
+void dgo_mlp_fwd(const dgo_mlp *m, const double *w, const double *feat, const double *dir_enc,
+                 uint32_t S, uint64_t n, double *sigma, double *rgb);
+void dgo_mlp_bwd(const dgo_mlp *m, const double *w, const double *feat, const double *dir_enc,
+                 uint32_t S, uint64_t n, const double *dsigma, const double *drgb, double loss_scale,
+                 double *dfeat, double *dw);
+
+/* Discrete volume rendering of one segment of S samples (Eq. 3 by quadrature). */
+void dgo_composite_fwd(const double *sigma, const double *rgb, const double *delta, uint32_t n_seg,
+                       uint32_t S, double *C, double *T);
+void dgo_composite_bwd(const double *sigma, const double *rgb, const double *delta, uint32_t n_seg,
+                       uint32_t S, const double *gC, const double *gT, double *dsigma, double *drgb);
+
+/* Segmented volume rendering merge (Eq. 5, 6) and its backward (Eq. 7, 8). */
+void dgo_merge_fwd(const double *Ck, const double *Tk, const uint32_t *seg_count, uint32_t R,
+                   uint32_t k_max, double *C, double *T);
+void dgo_merge_bwd(const double *Ck, const double *Tk, const uint32_t *seg_count, uint32_t R,
+                   uint32_t k_max, const double *gC, const double *gT, double *gCk, double *gTk);
+
+/* Loss (Eq. 9 as a mean, plus lambda1 * Eq. 10) and its gradient seeds. */
+double dgo_loss(const double *C, const double *T, const double *Cgt, uint32_t R, double lambda1,
+                double *gC, double *gT);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
