@@ -1,0 +1,203 @@
+/*
+ * distgrid.h -- C ABI of the MI355X (gfx950) library for the DistGrid training hot path
+ * (DistGrid: Scalable Scene Reconstruction with Distributed Multi-resolution Hash Grid,
+ *  arXiv 2405.04416).
+ *
+ * Conventions, valid for every entry point unless its comment says otherwise:
+ *  - every function returns int: DG_OK, or a negative DG_ERR_* code; argument checks run
+ *    synchronously on the host before anything is enqueued; dg_last_error() returns a
+ *    human-readable description of the last failure on the calling thread;
+ *  - "device" pointers are HIP device memory owned by the caller; the library never
+ *    allocates, frees or retains them; "host" pointers are ordinary memory;
+ *  - all work is enqueued on the caller's stream (a hipStream_t passed as void*; NULL is
+ *    the default stream) and the call returns without synchronising;
+ *  - arrays are row-major, innermost dimension last; fp16 means IEEE binary16;
+ *  - outputs documented as "+=" accumulate into what the buffer holds (the caller zeroes
+ *    it); all other outputs are overwritten;
+ *  - data-dependent overflow (more than k_max segments on a ray) is reported through a
+ *    device-side status word, not through the return code.
+ */
+#ifndef DISTGRID_H
+#define DISTGRID_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DG_OK               0
+#define DG_ERR_ARG         (-1)  /* null / misaligned / inconsistent argument          */
+#define DG_ERR_UNSUPPORTED (-2)  /* a shape the kernels are not built for              */
+#define DG_ERR_WORKSPACE   (-3)  /* workspace smaller than the *_workspace_bytes query */
+#define DG_ERR_HIP         (-4)  /* a HIP call or kernel launch failed                 */
+
+#define DG_F32 0u
+#define DG_F16 1u
+#define DG_MAX_LEVELS 16
+#define DG_MAX_PARTITIONS 64
+
+const char *dg_last_error(void);
+
+/* ------------------------------------------------------------------------------------
+ * Deformable multi-resolution hash grid (Sec. 3.2, Sec. 4.1).
+ * A host-side descriptor, built once per sub-model and passed by pointer (it is copied).
+ * Level l has n_voxels[l] = floor(N_min * growth^l) voxels along the longest box axis
+ * (Instant-NGP Eq. 2-3), res[l][d] = ceil(a_d/s * n_voxels[l]) voxels along axis d
+ * (Sec. 4.1), cubic voxels of side s/n_voxels[l].  A level whose vertex count
+ * prod(res+1) is <= T = 2^log2_T is stored one-to-one (x fastest), otherwise its
+ * vertices are hashed into T entries (Sec. 4.1; hash: Instant-NGP Eq. 4).  Level l
+ * occupies entries [offset[l], offset[l+1]) of the table, each entry n_features floats.
+ * A sample with unit coordinates u in [0,1]^3 (clamped) sits at grid position
+ * u_d * scale[l][d] (one fp32 multiply), in the cell floor(.) clamped to res-1.
+ * ---------------------------------------------------------------------------------- */
+typedef struct dg_grid_desc {
+    uint32_t n_levels;                    /* L <= 16                      */
+    uint32_t n_features;                  /* F, must be 2                 */
+    uint32_t log2_T;
+    uint32_t n_entries;                   /* offset[n_levels]             */
+    uint32_t n_voxels[DG_MAX_LEVELS];
+    uint32_t res[DG_MAX_LEVELS][3];
+    uint32_t dense[DG_MAX_LEVELS];
+    uint32_t offset[DG_MAX_LEVELS + 1];
+    float    scale[DG_MAX_LEVELS][3];
+} dg_grid_desc;
+
+/* growth factor b = exp((ln N_max - ln N_min) / (L-1)) (Instant-NGP Eq. 3). */
+double dg_growth_factor(uint32_t N_min, uint32_t N_max, uint32_t L);
+/* Fills *desc (host).  extent = side lengths (a,b,c) of the sub-model's box.
+ * DG_ERR_ARG on null pointers or non-positive extents, DG_ERR_UNSUPPORTED if L > 16,
+ * F != 2, log2_T > 24 or the table would exceed 2^32 entries. */
+int dg_grid_desc_init(dg_grid_desc *desc, uint32_t L, uint32_t F, uint32_t log2_T,
+                      uint32_t N_min, double growth, const double extent[3]);
+
+/* ------------------------------------------------------------------------------------
+ * Ray / box segments and their distribution to partitions (Sec. 4.2.1, Sec. 4.4.2,
+ * Fig. 2 steps 2-3).
+ * o, d [R,3] fp32 device; parts [P,6] fp32 device, each (lo_x,lo_y,lo_z,hi_x,hi_y,hi_z),
+ * closely paved and non-overlapping, neighbours storing the same float for a shared face.
+ * Slab test in fp32 with one rounding per operation: t = (face - o) * (1/d); a ray
+ * parallel to a slab is inside iff lo <= o < hi.  A box is hit iff t_out > max(t_near,
+ * t_min).  Per ray the hits are ordered front to back (ties by box index); the first
+ * k_max are kept and bit 0 of *status is set if any ray had more.
+ * Outputs (device): seg_count [R]; seg_t [R,k_max,2] = (t_in,t_out), consecutive segments
+ * share a bit-identical boundary; seg_part [R,k_max] box index (-1 in unused slots).
+ * If part_offset is non-null the (ray,slot) pairs are also distributed to their boxes by
+ * a stable counting sort: part_offset [P+1], seg_ray / seg_slot [R*k_max capacity] hold
+ * box p's segments at [part_offset[p], part_offset[p+1]) in ascending (ray,slot) order.
+ * That step needs dg_segments_workspace_bytes(R,P) bytes of device workspace.
+ * P <= DG_MAX_PARTITIONS, 1 <= k_max <= 8.
+ * ---------------------------------------------------------------------------------- */
+size_t dg_segments_workspace_bytes(uint32_t R, uint32_t P);
+int dg_ray_aabb_segments(const float *o, const float *d, uint32_t R,
+                         const float *parts, uint32_t P, float t_min, uint32_t k_max,
+                         uint32_t *seg_count, float *seg_t, int32_t *seg_part,
+                         uint32_t *part_offset, uint32_t *seg_ray, uint32_t *seg_slot,
+                         uint32_t *status, void *ws, size_t ws_bytes, void *stream);
+
+/* Stratified jittered samples of the n_seg segments listed in seg_ray/seg_slot (device,
+ * already offset to one box's list), all inside box `box` (host, 6 floats).
+ * Sample s of a segment: dt = (t_out-t_in)/S, t = t_in + (s+xi)*dt, x = fma(t,d,o),
+ * u = (x-lo) * (1/(hi-lo)); each step one fp32 rounding.  xi in [0,1) is jitter[j*S+s]
+ * if jitter != NULL, else a counter-based generator keyed by (seed, ray, slot, s):
+ * splitmix64 output mix of seed + 0x9E3779B97F4A7C15*(ctr+1), ctr = ray<<32|slot<<16|s,
+ * top 24 bits scaled by 2^-24.
+ * Outputs (device): u [n_seg*S,3] fp32 unit coordinates, delta [n_seg*S] stratum widths. */
+int dg_sample_segments(const float *o, const float *d, const float *seg_t,
+                       const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t n_seg,
+                       uint32_t k_max, const float *box, uint32_t S, uint64_t seed,
+                       const float *jitter, float *u, float *delta, void *stream);
+
+/* Direction encoding: real spherical harmonics of bands 0..degree-1 (degree 1..4) of the
+ * normalised direction of ray index[i] (index NULL: i itself); out [n, degree^2] fp16.
+ * Band l, order m is stored at l*l + l + m; Condon-Shortley phase included. */
+int dg_dir_encode(const float *d, const uint32_t *index, uint64_t n, uint32_t degree,
+                  void *out, void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * Hash-grid encode (Sec. 3.2): feat[n, l*F+f] = sum over the 8 cell corners of
+ * w_c * table[entry_c, f], trilinear weights w_c, entry by dense map or hash.
+ * table [n_entries, F] fp32 device; u [N,3] fp32 device; feat [N, L*F] device, fp32 or
+ * fp16 (feat_dtype DG_F32 / DG_F16; fp16 is rounded once from the fp32 sum).
+ * ---------------------------------------------------------------------------------- */
+int dg_hashgrid_encode_fwd(const dg_grid_desc *desc, const float *table, const float *u,
+                           uint64_t N, void *feat, uint32_t feat_dtype, void *stream);
+/* Transpose of the above: dtable[entry_c, f] += w_c * dfeat[n, l*F+f] (fp32 atomics, so
+ * the summation order is not fixed).  dfeat [N, L*F] fp32 device; dtable "+=". */
+int dg_hashgrid_encode_bwd(const dg_grid_desc *desc, const float *u, const float *dfeat,
+                           uint64_t N, float *dtable, void *stream);
+/* Absolute table entry of every corner: idx [N, L, 8] uint32, corner c = cx + 2cy + 4cz. */
+int dg_hashgrid_corner_indices(const dg_grid_desc *desc, const float *u, uint64_t N,
+                               uint32_t *idx, void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * Field MLPs (Sec. 3.2 "shallow MLP"; Sec. 5.1: sigmoid hidden activation in the colour
+ * net, outputs of both nets clipped to [-15,15] before the output activations).
+ *   density: feat[n_feat] -> n_hidden_d (ReLU) -> geo[n_geo];  sigma = exp(clip(geo[0]))
+ *   colour : [geo | dir_enc] -> n_hidden_c (act_c) [-> n_hidden_c (act_c)] -> 3;
+ *            rgb = sigmoid(clip(.))
+ * No biases.  Inputs, weights and every hidden activation are fp16 (round to nearest
+ * even), products accumulate in fp32.  weights: fp16 device, the matrices
+ * Wd1[n_hidden_d,n_feat], Wd2[n_geo,n_hidden_d], Wc1[n_hidden_c,n_geo+n_dir],
+ * (Wc2[n_hidden_c,n_hidden_c]), Wc3[3,n_hidden_c] one after another, each [out,in].
+ * feat [N,n_feat] fp16; dir_enc [ceil(N/S), n_dir] fp16, row n/S serves sample n.
+ * Outputs: sigma [N] fp32, rgb [N,3] fp32.
+ * Supported shapes: (n_feat,n_hidden_d,n_geo,n_dir,n_hidden_c,n_layers_c) =
+ * (32,64,16,16,64,2) and (8,32,16,4,32,1); others return DG_ERR_UNSUPPORTED.
+ * ---------------------------------------------------------------------------------- */
+typedef struct dg_mlp_desc {
+    uint32_t n_feat, n_hidden_d, n_geo, n_dir, n_hidden_c, n_layers_c;
+    uint32_t act_c;                       /* 0 ReLU, 1 sigmoid */
+} dg_mlp_desc;
+size_t dg_mlp_weight_count(const dg_mlp_desc *desc);
+int dg_mlp_fwd(const dg_mlp_desc *desc, const void *weights, const void *feat,
+               const void *dir_enc, uint32_t S, uint64_t N, float *sigma, float *rgb,
+               void *stream);
+/* Backward of the above; activations are recomputed, nothing is saved by dg_mlp_fwd.
+ * dsigma [N], drgb [N,3] fp32.  Every back-propagated delta is multiplied by loss_scale
+ * (a power of two is advisable) before it is rounded to fp16, and dfeat / dW are divided
+ * by it again in fp32.  Outputs: dfeat [N,n_feat] fp32 (overwritten); dW fp32, "+=",
+ * same packing as weights.  ws: dg_mlp_bwd_workspace_bytes(desc) bytes. */
+size_t dg_mlp_bwd_workspace_bytes(const dg_mlp_desc *desc);
+int dg_mlp_bwd(const dg_mlp_desc *desc, const void *weights, const void *feat,
+               const void *dir_enc, uint32_t S, uint64_t N, const float *dsigma,
+               const float *drgb, float loss_scale, float *dfeat, float *dW,
+               void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * Local volume rendering of one box's segments (Eq. 3 by quadrature; Fig. 2 step 4):
+ * alpha_i = 1-exp(-sigma_i delta_i), T_i = prod_{j<i}(1-alpha_j),
+ * C_k = sum_i T_i alpha_i c_i, T_k = prod_i (1-alpha_i).
+ * sigma, delta [n_seg*S], rgb [n_seg*S,3] fp32 device; segment j belongs to ray
+ * seg_ray[j], slot seg_slot[j]; results are written to Ck [R,k_max,3], Tk [R,k_max]
+ * at that (ray,slot) (Fig. 2 step 5).
+ * ---------------------------------------------------------------------------------- */
+int dg_composite_segment_fwd(const float *sigma, const float *rgb, const float *delta,
+                             uint32_t n_seg, uint32_t S, const uint32_t *seg_ray,
+                             const uint32_t *seg_slot, uint32_t k_max, float *Ck, float *Tk,
+                             void *stream);
+/* Backward: from gCk [R,k_max,3], gTk [R,k_max] to dsigma [n_seg*S], drgb [n_seg*S,3]. */
+int dg_composite_segment_bwd(const float *sigma, const float *rgb, const float *delta,
+                             uint32_t n_seg, uint32_t S, const uint32_t *seg_ray,
+                             const uint32_t *seg_slot, uint32_t k_max, const float *gCk,
+                             const float *gTk, float *dsigma, float *drgb, void *stream);
+
+/* Segmented volume rendering (Eq. 5, 6; Fig. 2 step 6): C = sum_k (prod_{j<k} T_j) C_k,
+ * T = prod_k T_k over the first seg_count[r] slots; a ray with no segment gives C=0, T=1. */
+int dg_merge_segments(const float *Ck, const float *Tk, const uint32_t *seg_count,
+                      uint32_t R, uint32_t k_max, float *C, float *T, void *stream);
+/* Its backward (Eq. 7, 8), evaluated without dividing by any T_k; unused slots get 0. */
+int dg_merge_segments_bwd(const float *Ck, const float *Tk, const uint32_t *seg_count,
+                          uint32_t R, uint32_t k_max, const float *gC, const float *gT,
+                          float *gCk, float *gTk, void *stream);
+
+/* Loss seeds (Eq. 9 as a mean over rays, Eq. 10 weighted by lambda1):
+ * gC = 2 (C - Cgt)/R, gT = lambda1 / (R (1-T)) where 1-T >= 1e-6, else 0;
+ * *loss (device scalar, "+=", may be NULL) accumulates the loss value. */
+int dg_loss_seed(const float *C, const float *T, const float *Cgt, uint32_t R,
+                 float lambda1, float *gC, float *gT, float *loss, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -459,10 +459,13 @@ void dgo_composite_fwd(const double *sigma, const double *rgb, const double *del
         double trans = 1.0, col[3] = {0, 0, 0};
         for (uint32_t s = 0; s < S; ++s) {
             uint64_t n = (uint64_t)j * S + s;
-            double alpha = 1.0 - exp(-sigma[n] * delta[n]);
+            /* alpha = 1 - exp(-sigma delta); its complement is taken as exp(-sigma delta) itself,
+               not as 1 - alpha, which cancels to nothing in double once sigma*delta > 36 */
+            double keep = exp(-sigma[n] * delta[n]);
+            double alpha = -expm1(-sigma[n] * delta[n]);
             double wgt = trans * alpha;
             for (int c = 0; c < 3; ++c) col[c] += wgt * rgb[3 * n + c];
-            trans *= 1.0 - alpha;
+            trans *= keep;
         }
         for (int c = 0; c < 3; ++c) C[3 * j + c] = col[c];
         T[j] = trans;
@@ -485,7 +488,7 @@ void dgo_composite_bwd(const double *sigma, const double *rgb, const double *del
         for (uint32_t s = S; s-- > 0;) {
             uint64_t n = (uint64_t)j * S + s;
             double keep = exp(-sigma[n] * delta[n]);     /* 1 - alpha_s */
-            double wgt = trans_before[s] * (1.0 - keep);
+            double wgt = trans_before[s] * -expm1(-sigma[n] * delta[n]);
             double ds = 0.0;
             for (int c = 0; c < 3; ++c) {
                 drgb[3 * n + c] = wgt * gC[3 * j + c];

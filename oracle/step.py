@@ -1,0 +1,73 @@
+"""Oracle-side forward + backward pass of the whole hot path -- TEST INFRASTRUCTURE ONLY.
+
+Chains the oracle's functions in the order of the paper's training procedure (Sec. 4.4.2, Fig. 2)
+on host arrays.  Used by the parity tests, the smoke check and the benchmark's cpu-baseline leg.
+"""
+import numpy as np
+
+import oracle as O
+
+
+def make_models(cfg, seed=0):
+    """Grid geometry, MLP descriptor and seeded parameters for every partition of a configuration."""
+    import dg_inputs as di
+    g, m = cfg["grid"], cfg["mlp"]
+    models = {}
+    for p in cfg.get("resident_list", range(cfg["parts"].shape[0])):
+        growth = g.get("growth") or O.growth_factor(g["n_min"], g["n_max"], g["L"])
+        grid = O.grid_init(g["L"], g["F"], g["log2_T"], g["n_min"], growth, di.box_extent(cfg["parts"][p]))
+        n_feat = g["L"] * g["F"]
+        mlp = O.mlp_desc(n_feat, m["n_hidden_d"], m["n_geo"], m["sh_degree"] ** 2, m["n_hidden_c"], m["n_layers_c"], 1, 1)
+        table = di.make_table(grid.n_entries, g["F"], cfg["table_range"], seed=seed + 1000 * p)
+        weights = di.make_mlp_weights(n_feat, m, seed=seed + 1000 * p)
+        models[p] = dict(grid=grid, mlp=mlp, table=table, weights=weights)
+    return models
+
+
+def run_step(cfg, models, o, d, Cgt, jitter=None, seed=0, lambda1=0.0, loss_scale=65536.0, resident=None,
+             foreign=None, want_bwd=True):
+    """Returns a dict of every intermediate the GPU path can be compared with."""
+    parts, S, k_max = cfg["parts"], cfg["S"], cfg["k_max"]
+    P, R = parts.shape[0], o.shape[0]
+    deg = cfg["mlp"]["sh_degree"]
+    resident = list(range(P)) if resident is None else list(resident)
+    out = {}
+    cnt, seg_t, seg_part, status = O.ray_aabb_segments(o, d, parts, 0.0, k_max)
+    off, seg_ray, seg_slot = O.bucket_segments(cnt, seg_part, P)
+    out.update(seg_count=cnt, seg_t=seg_t, seg_part=seg_part, status=status, part_offset=off, seg_ray=seg_ray,
+               seg_slot=seg_slot)
+    Ck = np.zeros((R, k_max, 3)); Tk = np.ones((R, k_max))
+    per = {}
+    for p in resident:
+        b, e = int(off[p]), int(off[p + 1])
+        if e == b:
+            continue
+        m = models[p]
+        jit = None if jitter is None else jitter[b * S:e * S]
+        u, delta = O.sample_segments(o, d, seg_t, seg_ray, seg_slot, b, e, parts[p], S, seed=seed, jitter_arr=jit)
+        dir_enc = O.sh(d[seg_ray[b:e]], deg)
+        feat = O.encode_fwd(m["grid"], m["table"], u)
+        sigma, rgb = O.mlp_fwd(m["mlp"], m["weights"].astype(np.float64), feat, dir_enc, S)
+        Cseg, Tseg = O.composite_fwd(sigma, rgb, delta.astype(np.float64), S)
+        Ck[seg_ray[b:e], seg_slot[b:e]] = Cseg
+        Tk[seg_ray[b:e], seg_slot[b:e]] = Tseg
+        per[p] = dict(u=u, delta=delta, dir_enc=dir_enc, feat=feat, sigma=sigma, rgb=rgb, b=b, e=e)
+    if foreign is not None:
+        foreign(Ck, Tk, out)
+        cnt = out["seg_count"]
+    C, T = O.merge_fwd(Ck, Tk, cnt)
+    loss, gC, gT = O.loss(C, T, Cgt, lambda1)
+    out.update(Ck=Ck, Tk=Tk, C=C, T=T, loss=loss, gC=gC, gT=gT, per=per)
+    if not want_bwd:
+        return out
+    gCk, gTk = O.merge_bwd(Ck, Tk, cnt, gC, gT)
+    out.update(gCk=gCk, gTk=gTk)
+    for p, q in per.items():
+        b, e = q["b"], q["e"]
+        m = models[p]
+        dsigma, drgb = O.composite_bwd(q["sigma"], q["rgb"], q["delta"].astype(np.float64), S,
+                                       gCk[seg_ray[b:e], seg_slot[b:e]], gTk[seg_ray[b:e], seg_slot[b:e]])
+        dfeat, dW = O.mlp_bwd(m["mlp"], m["weights"].astype(np.float64), q["feat"], q["dir_enc"], S, dsigma, drgb, loss_scale)
+        dtable = O.encode_bwd(m["grid"], q["u"], dfeat)
+        q.update(dsigma=dsigma, drgb=drgb, dfeat=dfeat, dW=dW, dtable=dtable)
+    return out

@@ -1,0 +1,220 @@
+"""Thin ctypes binding over libdistgrid.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (include/distgrid.h) and does
+nothing but check tensor dtype / device / contiguity, pass raw pointers and the current HIP
+stream, and raise on a non-zero return code.  PyTorch supplies device memory and streams; all
+arithmetic of the hot path runs in the library's kernels.  There is no fallback: if the shared
+library is missing the import of this module's `lib()` raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdistgrid.so")
+
+DG_F32, DG_F16 = 0, 1
+MAX_LEVELS = 16
+
+
+class GridDesc(C.Structure):
+    _fields_ = [("n_levels", C.c_uint32), ("n_features", C.c_uint32), ("log2_T", C.c_uint32),
+                ("n_entries", C.c_uint32),
+                ("n_voxels", C.c_uint32 * MAX_LEVELS),
+                ("res", (C.c_uint32 * 3) * MAX_LEVELS),
+                ("dense", C.c_uint32 * MAX_LEVELS),
+                ("offset", C.c_uint32 * (MAX_LEVELS + 1)),
+                ("scale", (C.c_float * 3) * MAX_LEVELS)]
+
+
+class MlpDesc(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("n_feat", "n_hidden_d", "n_geo", "n_dir", "n_hidden_c", "n_layers_c",
+                                          "act_c")]
+
+
+class DistGridError(RuntimeError):
+    pass
+
+
+_lib = None
+
+_SIGNATURES = {
+    "dg_last_error": (C.c_char_p, []),
+    "dg_growth_factor": (C.c_double, [C.c_uint32] * 3),
+    "dg_grid_desc_init": (C.c_int, [C.POINTER(GridDesc), C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_double,
+                                    C.POINTER(C.c_double)]),
+    "dg_segments_workspace_bytes": (C.c_size_t, [C.c_uint32, C.c_uint32]),
+    "dg_ray_aabb_segments": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_float, C.c_uint32,
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_size_t, C.c_void_p]),
+    "dg_sample_segments": (C.c_int, [C.c_void_p] * 5 + [C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.c_uint32,
+                                                        C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dg_dir_encode": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p]),
+    "dg_hashgrid_encode_fwd": (C.c_int, [C.POINTER(GridDesc), C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32,
+                                         C.c_void_p]),
+    "dg_hashgrid_encode_bwd": (C.c_int, [C.POINTER(GridDesc), C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
+    "dg_hashgrid_corner_indices": (C.c_int, [C.POINTER(GridDesc), C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
+    "dg_mlp_weight_count": (C.c_size_t, [C.POINTER(MlpDesc)]),
+    "dg_mlp_fwd": (C.c_int, [C.POINTER(MlpDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p,
+                             C.c_void_p, C.c_void_p]),
+    "dg_mlp_bwd_workspace_bytes": (C.c_size_t, [C.POINTER(MlpDesc)]),
+    "dg_mlp_bwd": (C.c_int, [C.POINTER(MlpDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p,
+                             C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "dg_composite_segment_fwd": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32,
+                                                              C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dg_composite_segment_bwd": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32]
+                                 + [C.c_void_p] * 5),
+    "dg_merge_segments": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32] + [C.c_void_p] * 3),
+    "dg_merge_segments_bwd": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32] + [C.c_void_p] * 5),
+    "dg_loss_seed": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_float] + [C.c_void_p] * 4),
+}
+
+EXPORTS = tuple(_SIGNATURES)
+
+
+def lib():
+    """Loads the HIP library; raises if it has not been built (there is no CPU fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise DistGridError("libdistgrid.so is not built: run `python -m paper_2405_04416_amd.build`")
+        handle = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise DistGridError("libdistgrid error %d: %s" % (rc, lib().dg_last_error().decode()))
+
+
+def _ptr(t, dtype=None, optional=False):
+    if t is None:
+        if optional:
+            return None
+        raise DistGridError("missing tensor argument")
+    if not t.is_cuda:
+        raise DistGridError("tensor must live on the GPU")
+    if dtype is not None and t.dtype != dtype:
+        raise DistGridError("expected %s, got %s" % (dtype, t.dtype))
+    if not t.is_contiguous():
+        raise DistGridError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+# ------------------------------------------------------------------ host helpers
+def dg_growth_factor(n_min, n_max, L):
+    return lib().dg_growth_factor(n_min, n_max, L)
+
+
+def dg_grid_desc_init(L, F, log2_T, n_min, growth, extent):
+    desc = GridDesc()
+    ext = (C.c_double * 3)(*[float(e) for e in extent])
+    _check(lib().dg_grid_desc_init(C.byref(desc), L, F, log2_T, n_min, float(growth), ext))
+    return desc
+
+
+def dg_mlp_desc(n_feat, n_hidden_d, n_geo, n_dir, n_hidden_c, n_layers_c, act_c=1):
+    return MlpDesc(n_feat, n_hidden_d, n_geo, n_dir, n_hidden_c, n_layers_c, act_c)
+
+
+def dg_mlp_weight_count(desc):
+    return int(lib().dg_mlp_weight_count(C.byref(desc)))
+
+
+def dg_segments_workspace_bytes(R, P):
+    return int(lib().dg_segments_workspace_bytes(R, P))
+
+
+def dg_mlp_bwd_workspace_bytes(desc):
+    return int(lib().dg_mlp_bwd_workspace_bytes(C.byref(desc)))
+
+
+# ------------------------------------------------------------------ device entry points
+def dg_ray_aabb_segments(o, d, parts, t_min, k_max, seg_count, seg_t, seg_part, status, part_offset=None, seg_ray=None,
+                         seg_slot=None, ws=None):
+    R, P = o.shape[0], parts.shape[0]
+    _check(lib().dg_ray_aabb_segments(
+        _ptr(o, torch.float32), _ptr(d, torch.float32), R, _ptr(parts, torch.float32), P, t_min, k_max,
+        _ptr(seg_count, torch.int32), _ptr(seg_t, torch.float32), _ptr(seg_part, torch.int32),
+        _ptr(part_offset, torch.int32, True), _ptr(seg_ray, torch.int32, True), _ptr(seg_slot, torch.int32, True),
+        _ptr(status, torch.int32), _ptr(ws, None, True), 0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+def dg_sample_segments(o, d, seg_t, seg_ray, seg_slot, n_seg, k_max, box, S, seed, jitter, u, delta):
+    box_c = (C.c_float * 6)(*[float(b) for b in box])
+    _check(lib().dg_sample_segments(
+        _ptr(o, torch.float32), _ptr(d, torch.float32), _ptr(seg_t, torch.float32), _ptr(seg_ray, torch.int32),
+        _ptr(seg_slot, torch.int32), n_seg, k_max, box_c, S, seed, _ptr(jitter, torch.float32, True),
+        _ptr(u, torch.float32), _ptr(delta, torch.float32), _stream()))
+
+
+def dg_dir_encode(d, index, n, degree, out):
+    _check(lib().dg_dir_encode(_ptr(d, torch.float32), _ptr(index, torch.int32, True), n, degree,
+                               _ptr(out, torch.float16), _stream()))
+
+
+def dg_hashgrid_encode_fwd(desc, table, u, N, feat):
+    dt = DG_F16 if feat.dtype == torch.float16 else DG_F32
+    _check(lib().dg_hashgrid_encode_fwd(C.byref(desc), _ptr(table, torch.float32), _ptr(u, torch.float32), N,
+                                        _ptr(feat, torch.float16 if dt else torch.float32), dt, _stream()))
+
+
+def dg_hashgrid_encode_bwd(desc, u, dfeat, N, dtable):
+    _check(lib().dg_hashgrid_encode_bwd(C.byref(desc), _ptr(u, torch.float32), _ptr(dfeat, torch.float32), N,
+                                        _ptr(dtable, torch.float32), _stream()))
+
+
+def dg_hashgrid_corner_indices(desc, u, N, idx):
+    _check(lib().dg_hashgrid_corner_indices(C.byref(desc), _ptr(u, torch.float32), N, _ptr(idx, torch.int32), _stream()))
+
+
+def dg_mlp_fwd(desc, weights, feat, dir_enc, S, N, sigma, rgb):
+    _check(lib().dg_mlp_fwd(C.byref(desc), _ptr(weights, torch.float16), _ptr(feat, torch.float16),
+                            _ptr(dir_enc, torch.float16), S, N, _ptr(sigma, torch.float32), _ptr(rgb, torch.float32),
+                            _stream()))
+
+
+def dg_mlp_bwd(desc, weights, feat, dir_enc, S, N, dsigma, drgb, loss_scale, dfeat, dW, ws):
+    _check(lib().dg_mlp_bwd(C.byref(desc), _ptr(weights, torch.float16), _ptr(feat, torch.float16),
+                            _ptr(dir_enc, torch.float16), S, N, _ptr(dsigma, torch.float32), _ptr(drgb, torch.float32),
+                            loss_scale, _ptr(dfeat, torch.float32), _ptr(dW, torch.float32), _ptr(ws),
+                            ws.numel() * ws.element_size(), _stream()))
+
+
+def dg_composite_segment_fwd(sigma, rgb, delta, n_seg, S, seg_ray, seg_slot, k_max, Ck, Tk):
+    _check(lib().dg_composite_segment_fwd(
+        _ptr(sigma, torch.float32), _ptr(rgb, torch.float32), _ptr(delta, torch.float32), n_seg, S,
+        _ptr(seg_ray, torch.int32), _ptr(seg_slot, torch.int32), k_max, _ptr(Ck, torch.float32), _ptr(Tk, torch.float32),
+        _stream()))
+
+
+def dg_composite_segment_bwd(sigma, rgb, delta, n_seg, S, seg_ray, seg_slot, k_max, gCk, gTk, dsigma, drgb):
+    _check(lib().dg_composite_segment_bwd(
+        _ptr(sigma, torch.float32), _ptr(rgb, torch.float32), _ptr(delta, torch.float32), n_seg, S,
+        _ptr(seg_ray, torch.int32), _ptr(seg_slot, torch.int32), k_max, _ptr(gCk, torch.float32), _ptr(gTk, torch.float32),
+        _ptr(dsigma, torch.float32), _ptr(drgb, torch.float32), _stream()))
+
+
+def dg_merge_segments(Ck, Tk, seg_count, R, k_max, Cout, Tout):
+    _check(lib().dg_merge_segments(_ptr(Ck, torch.float32), _ptr(Tk, torch.float32), _ptr(seg_count, torch.int32), R, k_max,
+                                   _ptr(Cout, torch.float32), _ptr(Tout, torch.float32), _stream()))
+
+
+def dg_merge_segments_bwd(Ck, Tk, seg_count, R, k_max, gC, gT, gCk, gTk):
+    _check(lib().dg_merge_segments_bwd(_ptr(Ck, torch.float32), _ptr(Tk, torch.float32), _ptr(seg_count, torch.int32), R,
+                                       k_max, _ptr(gC, torch.float32), _ptr(gT, torch.float32), _ptr(gCk, torch.float32),
+                                       _ptr(gTk, torch.float32), _stream()))
+
+
+def dg_loss_seed(Cin, Tin, Cgt, R, lambda1, gC, gT, loss=None):
+    _check(lib().dg_loss_seed(_ptr(Cin, torch.float32), _ptr(Tin, torch.float32), _ptr(Cgt, torch.float32), R, lambda1,
+                              _ptr(gC, torch.float32), _ptr(gT, torch.float32), _ptr(loss, torch.float32, True), _stream()))

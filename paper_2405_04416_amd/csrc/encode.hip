@@ -1,0 +1,220 @@
+// Multi-resolution hash-grid encode: forward gather and backward scatter-add (Sec. 3.2, Sec. 4.1).
+//
+// Work is split by (tile of samples) x (group of levels).  Workgroup b serves level group
+// b % n_groups; on MI355X consecutive workgroups go round-robin to the eight XCDs, each with
+// its own L2, so with n_groups == 8 one XCD keeps meeting the same few levels and their table
+// slices stay resident in that L2.  This is a placement hint only: results do not depend on it.
+#include "dg_internal.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr uint32_t kPrimeY = 2654435761u, kPrimeZ = 805459861u;   // Instant-NGP Eq. 4 (x prime is 1)
+
+struct LevelGeom {
+    uint32_t res[3];
+    uint32_t dense;
+    uint32_t offset;
+    float scale[3];
+};
+
+__device__ __forceinline__ LevelGeom level_of(const dg_grid_desc &g, uint32_t l)
+{
+    LevelGeom v;
+    v.res[0] = g.res[l][0]; v.res[1] = g.res[l][1]; v.res[2] = g.res[l][2];
+    v.dense = g.dense[l];
+    v.offset = g.offset[l];
+    v.scale[0] = g.scale[l][0]; v.scale[1] = g.scale[l][1]; v.scale[2] = g.scale[l][2];
+    return v;
+}
+
+// cell and fractional position of a sample at one level; one fp32 multiply, no contraction
+__device__ __forceinline__ void locate(const LevelGeom &lv, const float u[3], uint32_t cell[3], float frac[3])
+{
+#pragma clang fp contract(off)
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+        float c = u[a];
+        c = c >= 0.0f ? c : 0.0f;     // NaN lands on 0 as well
+        c = c > 1.0f ? 1.0f : c;
+        const float pos = c * lv.scale[a];
+        uint32_t i = (uint32_t)floorf(pos);
+        const uint32_t last = lv.res[a] - 1u;
+        i = i > last ? last : i;
+        cell[a] = i;
+        frac[a] = pos - (float)i;
+    }
+}
+
+// entry indices (relative to the level) of the 8 corners, corner c = cx + 2cy + 4cz
+__device__ __forceinline__ void corner_entries(const LevelGeom &lv, uint32_t mask, const uint32_t cell[3], uint32_t e[8])
+{
+    if (lv.dense) {
+        const uint32_t nx = lv.res[0] + 1u, nxy = nx * (lv.res[1] + 1u);
+        const uint32_t base = cell[0] + nx * cell[1] + nxy * cell[2];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) e[c] = base + (c & 1) + ((c >> 1) & 1) * nx + ((c >> 2) & 1) * nxy;
+    } else {
+        const uint32_t hy0 = cell[1] * kPrimeY, hy1 = hy0 + kPrimeY;
+        const uint32_t hz0 = cell[2] * kPrimeZ, hz1 = hz0 + kPrimeZ;
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            e[c] = ((cell[0] + (c & 1)) ^ ((c & 2) ? hy1 : hy0) ^ ((c & 4) ? hz1 : hz0)) & mask;
+    }
+}
+
+__device__ __forceinline__ void corner_weights(const float frac[3], float w[8])
+{
+    const float wx[2] = {1.0f - frac[0], frac[0]}, wy[2] = {1.0f - frac[1], frac[1]}, wz[2] = {1.0f - frac[2], frac[2]};
+#pragma unroll
+    for (int c = 0; c < 8; ++c) w[c] = wx[c & 1] * wy[(c >> 1) & 1] * wz[(c >> 2) & 1];
+}
+
+template <bool kHalf>
+__global__ void __launch_bounds__(kBlock)
+encode_fwd_kernel(dg_grid_desc g, const float2 *__restrict__ table, const float *__restrict__ u, uint64_t N,
+                  void *__restrict__ feat, uint32_t n_groups)
+{
+    const uint32_t group = blockIdx.x % n_groups;
+    const uint64_t n = (uint64_t)(blockIdx.x / n_groups) * kBlock + threadIdx.x;
+    if (n >= N) return;
+    const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
+    const uint32_t mask = (1u << g.log2_T) - 1u;
+    const uint32_t width = g.n_levels * 2u;
+    for (uint32_t l = group; l < g.n_levels; l += n_groups) {
+        const LevelGeom lv = level_of(g, l);
+        uint32_t cell[3], e[8];
+        float frac[3], w[8];
+        locate(lv, uu, cell, frac);
+        corner_entries(lv, mask, cell, e);
+        corner_weights(frac, w);
+        float2 v[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) v[c] = table[(size_t)lv.offset + e[c]];
+        float f0 = 0.0f, f1 = 0.0f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) { f0 = fmaf(w[c], v[c].x, f0); f1 = fmaf(w[c], v[c].y, f1); }
+        if (kHalf) {
+            reinterpret_cast<__half2 *>(feat)[n * g.n_levels + l] = __floats2half2_rn(f0, f1);
+        } else {
+            reinterpret_cast<float2 *>(feat)[n * g.n_levels + l] = make_float2(f0, f1);
+        }
+    }
+    (void)width;
+}
+
+__global__ void __launch_bounds__(kBlock)
+encode_bwd_kernel(dg_grid_desc g, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
+                  float *__restrict__ dtable, uint32_t n_groups)
+{
+    const uint32_t group = blockIdx.x % n_groups;
+    const uint64_t n = (uint64_t)(blockIdx.x / n_groups) * kBlock + threadIdx.x;
+    if (n >= N) return;
+    const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
+    const uint32_t mask = (1u << g.log2_T) - 1u;
+    for (uint32_t l = group; l < g.n_levels; l += n_groups) {
+        const LevelGeom lv = level_of(g, l);
+        uint32_t cell[3], e[8];
+        float frac[3], w[8];
+        locate(lv, uu, cell, frac);
+        corner_entries(lv, mask, cell, e);
+        corner_weights(frac, w);
+        const float2 gfe = dfeat[n * g.n_levels + l];
+        if (gfe.x == 0.0f && gfe.y == 0.0f) continue;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            float *dst = dtable + 2 * ((size_t)lv.offset + e[c]);
+            unsafeAtomicAdd(dst, w[c] * gfe.x);
+            unsafeAtomicAdd(dst + 1, w[c] * gfe.y);
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+corner_index_kernel(dg_grid_desc g, const float *__restrict__ u, uint64_t N, uint32_t *__restrict__ idx)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (t >= N * g.n_levels) return;
+    const uint64_t n = t / g.n_levels;
+    const uint32_t l = (uint32_t)(t % g.n_levels);
+    const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
+    const LevelGeom lv = level_of(g, l);
+    uint32_t cell[3], e[8];
+    float frac[3];
+    locate(lv, uu, cell, frac);
+    corner_entries(lv, (1u << g.log2_T) - 1u, cell, e);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) idx[t * 8 + c] = lv.offset + e[c];
+}
+
+int check_desc(const dg_grid_desc *d, const char *who)
+{
+    DG_REQUIRE(d, DG_ERR_ARG, "%s: null descriptor", who);
+    DG_REQUIRE(d->n_levels >= 1 && d->n_levels <= DG_MAX_LEVELS && d->n_features == 2 && d->log2_T <= 24,
+               DG_ERR_UNSUPPORTED, "%s: unsupported grid (L=%u F=%u log2_T=%u)", who, d->n_levels, d->n_features, d->log2_T);
+    for (uint32_t l = 0; l < d->n_levels; ++l) {
+        const uint64_t verts = (uint64_t)(d->res[l][0] + 1) * (d->res[l][1] + 1) * (d->res[l][2] + 1);
+        const uint64_t len = (uint64_t)d->offset[l + 1] - d->offset[l];
+        DG_REQUIRE(d->res[l][0] >= 1 && d->res[l][1] >= 1 && d->res[l][2] >= 1, DG_ERR_ARG, "%s: empty level %u", who, l);
+        DG_REQUIRE(d->offset[l + 1] > d->offset[l] && (d->dense[l] ? verts <= len : len == (1ull << d->log2_T)),
+                   DG_ERR_ARG, "%s: level %u does not fit its table slice", who, l);
+    }
+    DG_REQUIRE(d->offset[d->n_levels] == d->n_entries, DG_ERR_ARG, "%s: n_entries disagrees with offsets", who);
+    return DG_OK;
+}
+
+int grid_for(uint64_t N, uint32_t n_groups, uint32_t *n_blocks, const char *who)
+{
+    const uint64_t tiles = (N + kBlock - 1) / kBlock;
+    DG_REQUIRE(tiles * n_groups <= 0x7fffffffull, DG_ERR_UNSUPPORTED, "%s: N too large for one launch", who);
+    *n_blocks = (uint32_t)(tiles * n_groups);
+    return DG_OK;
+}
+
+}  // namespace
+
+extern "C" int dg_hashgrid_encode_fwd(const dg_grid_desc *desc, const float *table, const float *u, uint64_t N,
+                                      void *feat, uint32_t feat_dtype, void *stream)
+{
+    if (int rc = check_desc(desc, "dg_hashgrid_encode_fwd")) return rc;
+    DG_REQUIRE(feat_dtype == DG_F32 || feat_dtype == DG_F16, DG_ERR_ARG, "dg_hashgrid_encode_fwd: bad feat_dtype");
+    if (N == 0) return DG_OK;
+    DG_REQUIRE(table && u && feat, DG_ERR_ARG, "dg_hashgrid_encode_fwd: null pointer");
+    DG_REQUIRE(dg::aligned(table, 8) && dg::aligned(feat, feat_dtype == DG_F16 ? 4 : 8), DG_ERR_ARG,
+               "dg_hashgrid_encode_fwd: table/feat misaligned");
+    const uint32_t n_groups = desc->n_levels < 8 ? desc->n_levels : 8;
+    uint32_t n_blocks;
+    if (int rc = grid_for(N, n_groups, &n_blocks, "dg_hashgrid_encode_fwd")) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    if (feat_dtype == DG_F16)
+        encode_fwd_kernel<true><<<n_blocks, kBlock, 0, st>>>(*desc, (const float2 *)table, u, N, feat, n_groups);
+    else
+        encode_fwd_kernel<false><<<n_blocks, kBlock, 0, st>>>(*desc, (const float2 *)table, u, N, feat, n_groups);
+    return dg::launch_status("dg_hashgrid_encode_fwd");
+}
+
+extern "C" int dg_hashgrid_encode_bwd(const dg_grid_desc *desc, const float *u, const float *dfeat, uint64_t N,
+                                      float *dtable, void *stream)
+{
+    if (int rc = check_desc(desc, "dg_hashgrid_encode_bwd")) return rc;
+    if (N == 0) return DG_OK;
+    DG_REQUIRE(u && dfeat && dtable, DG_ERR_ARG, "dg_hashgrid_encode_bwd: null pointer");
+    DG_REQUIRE(dg::aligned(dfeat, 8) && dg::aligned(dtable, 8), DG_ERR_ARG, "dg_hashgrid_encode_bwd: misaligned pointer");
+    const uint32_t n_groups = desc->n_levels < 8 ? desc->n_levels : 8;
+    uint32_t n_blocks;
+    if (int rc = grid_for(N, n_groups, &n_blocks, "dg_hashgrid_encode_bwd")) return rc;
+    encode_bwd_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(*desc, u, (const float2 *)dfeat, N, dtable, n_groups);
+    return dg::launch_status("dg_hashgrid_encode_bwd");
+}
+
+extern "C" int dg_hashgrid_corner_indices(const dg_grid_desc *desc, const float *u, uint64_t N, uint32_t *idx,
+                                          void *stream)
+{
+    if (int rc = check_desc(desc, "dg_hashgrid_corner_indices")) return rc;
+    if (N == 0) return DG_OK;
+    DG_REQUIRE(u && idx, DG_ERR_ARG, "dg_hashgrid_corner_indices: null pointer");
+    const uint64_t n_blocks = (N * desc->n_levels + kBlock - 1) / kBlock;
+    DG_REQUIRE(n_blocks <= 0x7fffffffull, DG_ERR_UNSUPPORTED, "dg_hashgrid_corner_indices: N too large");
+    corner_index_kernel<<<(uint32_t)n_blocks, kBlock, 0, (hipStream_t)stream>>>(*desc, u, N, idx);
+    return dg::launch_status("dg_hashgrid_corner_indices");
+}

@@ -1,0 +1,297 @@
+// Ray / box segments, distribution to partitions, stratified sampling, direction encoding
+// (Sec. 4.2.1, Sec. 4.4.2, Fig. 2 steps 2-3).  All of it is light streaming work: one thread
+// per ray or per sample, coalesced where the layout allows.
+//
+// The fp32 bookkeeping here must round after every operation (segment times are compared bit
+// for bit between boxes), so this file is built with -ffp-contract=off.
+#include "dg_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr uint32_t kMaxK = 8;
+
+// ---------------------------------------------------------------- ray / box slab test
+__global__ void __launch_bounds__(kBlock)
+ray_aabb_kernel(const float *__restrict__ o, const float *__restrict__ d, uint32_t R,
+                const float *__restrict__ parts, uint32_t P, float t_min, uint32_t k_max,
+                uint32_t *__restrict__ seg_count, float *__restrict__ seg_t, int32_t *__restrict__ seg_part,
+                uint32_t *__restrict__ status)
+{
+    __shared__ float boxes[DG_MAX_PARTITIONS * 6];
+    for (uint32_t i = threadIdx.x; i < P * 6; i += kBlock) boxes[i] = parts[i];
+    __syncthreads();
+    const uint32_t r = blockIdx.x * kBlock + threadIdx.x;
+    if (r >= R) return;
+    const float ox = o[3 * r], oy = o[3 * r + 1], oz = o[3 * r + 2];
+    const float dx = d[3 * r], dy = d[3 * r + 1], dz = d[3 * r + 2];
+    const float oo[3] = {ox, oy, oz}, dd[3] = {dx, dy, dz};
+    float inv[3];
+    for (int a = 0; a < 3; ++a) inv[a] = dd[a] != 0.0f ? 1.0f / dd[a] : 0.0f;
+
+    float tin[kMaxK], tout[kMaxK];
+    int32_t pid[kMaxK];
+    uint32_t cnt = 0;
+    bool overflow = false;
+    for (uint32_t p = 0; p < P; ++p) {
+        const float *lo = boxes + 6 * p, *hi = lo + 3;
+        float tn = -INFINITY, tf = INFINITY;
+        bool miss = false;
+        for (int a = 0; a < 3; ++a) {
+            if (dd[a] == 0.0f) {
+                if (!(lo[a] <= oo[a] && oo[a] < hi[a])) miss = true;   // half-open: shared faces go up
+                continue;
+            }
+            const float t1 = (lo[a] - oo[a]) * inv[a];
+            const float t2 = (hi[a] - oo[a]) * inv[a];
+            tn = fmaxf(tn, fminf(t1, t2));
+            tf = fminf(tf, fmaxf(t1, t2));
+        }
+        const float t_in = fmaxf(tn, t_min), t_out = tf;
+        if (miss || !(t_out > t_in)) continue;
+        // sorted insert, front to back; boxes are visited in index order so ties keep that order
+        uint32_t pos = cnt;
+        while (pos > 0 && tin[pos - 1] > t_in) --pos;
+        if (cnt >= k_max) overflow = true;
+        if (pos >= k_max) continue;
+        const uint32_t last = cnt < k_max ? cnt : k_max - 1;
+        for (uint32_t k = last; k > pos; --k) { tin[k] = tin[k - 1]; tout[k] = tout[k - 1]; pid[k] = pid[k - 1]; }
+        tin[pos] = t_in; tout[pos] = t_out; pid[pos] = (int32_t)p;
+        if (cnt < k_max) ++cnt;
+    }
+    seg_count[r] = cnt;
+    for (uint32_t k = 0; k < k_max; ++k) {
+        const bool used = k < cnt;
+        seg_t[((size_t)r * k_max + k) * 2] = used ? tin[k] : 0.0f;
+        seg_t[((size_t)r * k_max + k) * 2 + 1] = used ? tout[k] : 0.0f;
+        seg_part[(size_t)r * k_max + k] = used ? pid[k] : -1;
+    }
+    if (overflow) atomicOr(status, 1u);
+}
+
+// ---------------------------------------------------------------- stable distribution to boxes
+// Three passes: per-block histogram, scan over blocks, scatter with in-block stable ranks.
+// A convex box is crossed at most once by a ray, so a ray holds at most one segment per box.
+__global__ void __launch_bounds__(kBlock)
+bucket_count_kernel(const uint32_t *__restrict__ seg_count, const int32_t *__restrict__ seg_part, uint32_t R,
+                    uint32_t k_max, uint32_t P, uint32_t n_blocks, uint32_t *__restrict__ block_hist)
+{
+    __shared__ uint32_t hist[DG_MAX_PARTITIONS];
+    if (threadIdx.x < DG_MAX_PARTITIONS) hist[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t r = blockIdx.x * kBlock + threadIdx.x;
+    if (r < R) {
+        const uint32_t cnt = seg_count[r];
+        for (uint32_t k = 0; k < cnt; ++k) atomicAdd(&hist[seg_part[(size_t)r * k_max + k]], 1u);
+    }
+    __syncthreads();
+    if (threadIdx.x < P) block_hist[(size_t)threadIdx.x * n_blocks + blockIdx.x] = hist[threadIdx.x];
+}
+
+// one wavefront per box at a time: exclusive scan of that box's per-block counts; then box offsets
+constexpr int kScanThreads = 1024;
+__global__ void __launch_bounds__(kScanThreads)
+bucket_scan_kernel(uint32_t P, uint32_t n_blocks, uint32_t *__restrict__ block_hist, uint32_t *__restrict__ part_offset)
+{
+    __shared__ uint32_t totals[DG_MAX_PARTITIONS];
+    const uint32_t wave = threadIdx.x / dg::kWave, lane = threadIdx.x % dg::kWave;
+    for (uint32_t p = wave; p < P; p += kScanThreads / dg::kWave) {
+        uint32_t *row = block_hist + (size_t)p * n_blocks;
+        uint32_t carry = 0;
+        for (uint32_t base = 0; base < n_blocks; base += dg::kWave) {
+            const uint32_t i = base + lane;
+            const uint32_t v = i < n_blocks ? row[i] : 0u;
+            uint32_t incl = v;
+            for (int off = 1; off < dg::kWave; off <<= 1) {
+                const uint32_t up = __shfl_up(incl, off, dg::kWave);
+                if ((int)lane >= off) incl += up;
+            }
+            if (i < n_blocks) row[i] = carry + incl - v;
+            carry += __shfl(incl, dg::kWave - 1, dg::kWave);
+        }
+        if (lane == 0) totals[p] = carry;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (uint32_t q = 0; q < P; ++q) { part_offset[q] = run; run += totals[q]; }
+        part_offset[P] = run;
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+bucket_scatter_kernel(const uint32_t *__restrict__ seg_count, const int32_t *__restrict__ seg_part, uint32_t R,
+                      uint32_t k_max, uint32_t P, uint32_t n_blocks, const uint32_t *__restrict__ block_hist,
+                      const uint32_t *__restrict__ part_offset, uint32_t *__restrict__ seg_ray,
+                      uint32_t *__restrict__ seg_slot)
+{
+    constexpr int kWaves = kBlock / dg::kWave;
+    __shared__ uint32_t wave_count[kWaves];
+    const uint32_t r = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t lane = threadIdx.x % dg::kWave, wave = threadIdx.x / dg::kWave;
+    uint32_t cnt = 0;
+    int32_t mine[kMaxK];
+    if (r < R) {
+        cnt = seg_count[r];
+        for (uint32_t k = 0; k < kMaxK; ++k) mine[k] = (k < cnt && k < k_max) ? seg_part[(size_t)r * k_max + k] : -1;
+    }
+    for (uint32_t p = 0; p < P; ++p) {
+        int slot = -1;
+        for (uint32_t k = 0; k < kMaxK; ++k) if (k < cnt && mine[k] == (int32_t)p) slot = (int)k;
+        const unsigned long long vote = __ballot(slot >= 0);
+        const uint32_t before = __popcll(vote & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_count[wave] = __popcll(vote);
+        __syncthreads();
+        uint32_t base = 0;
+        for (uint32_t w = 0; w < wave; ++w) base += wave_count[w];
+        __syncthreads();
+        if (slot >= 0) {
+            const uint32_t dst = part_offset[p] + block_hist[(size_t)p * n_blocks + blockIdx.x] + base + before;
+            seg_ray[dst] = r;
+            seg_slot[dst] = (uint32_t)slot;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- stratified samples
+__device__ __forceinline__ float counter_jitter(uint64_t seed, uint32_t ray, uint32_t slot, uint32_t s)
+{
+    const uint64_t ctr = ((uint64_t)ray << 32) | ((uint64_t)(slot & 0xffffu) << 16) | (uint64_t)(s & 0xffffu);
+    uint64_t z = seed + 0x9E3779B97F4A7C15ull * (ctr + 1ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return (float)(uint32_t)(z >> 40) * (1.0f / 16777216.0f);
+}
+
+struct BoxArgs { float lo[3], inv_ext[3]; };
+
+__global__ void __launch_bounds__(kBlock)
+sample_kernel(const float *__restrict__ o, const float *__restrict__ d, const float *__restrict__ seg_t,
+              const uint32_t *__restrict__ seg_ray, const uint32_t *__restrict__ seg_slot, uint64_t n_samples,
+              uint32_t k_max, BoxArgs box, uint32_t S, uint64_t seed, const float *__restrict__ jitter,
+              float *__restrict__ u, float *__restrict__ delta)
+{
+    const uint64_t n = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (n >= n_samples) return;
+    const uint32_t j = (uint32_t)(n / S), s = (uint32_t)(n % S);
+    const uint32_t r = seg_ray[j], k = seg_slot[j];
+    const float t_in = seg_t[((size_t)r * k_max + k) * 2], t_out = seg_t[((size_t)r * k_max + k) * 2 + 1];
+    const float dt = (t_out - t_in) / (float)S;
+    const float xi = jitter ? jitter[n] : counter_jitter(seed, r, k, s);
+    const float t = t_in + ((float)s + xi) * dt;
+    for (int a = 0; a < 3; ++a) {
+        const float x = __builtin_fmaf(t, d[3 * r + a], o[3 * r + a]);
+        u[3 * n + a] = (x - box.lo[a]) * box.inv_ext[a];
+    }
+    delta[n] = dt;
+}
+
+// ---------------------------------------------------------------- real spherical harmonics
+// Cartesian forms of Y_l^m for l <= 3 on the unit vector, Condon-Shortley phase included.
+__global__ void __launch_bounds__(kBlock)
+dir_encode_kernel(const float *__restrict__ d, const uint32_t *__restrict__ index, uint64_t n, uint32_t degree,
+                  __half *__restrict__ out)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const size_t r = index ? index[i] : i;
+    float x = d[3 * r], y = d[3 * r + 1], z = d[3 * r + 2];
+    const float len = sqrtf(x * x + y * y + z * z);
+    if (len > 0.0f) { const float q = 1.0f / len; x *= q; y *= q; z *= q; } else { x = 0.0f; y = 0.0f; z = 1.0f; }
+    float v[16];
+    v[0] = 0.28209479177387814f;
+    v[1] = -0.4886025119029199f * y;
+    v[2] = 0.4886025119029199f * z;
+    v[3] = -0.4886025119029199f * x;
+    const float xx = x * x, yy = y * y, zz = z * z;
+    v[4] = 1.0925484305920792f * x * y;
+    v[5] = -1.0925484305920792f * y * z;
+    v[6] = 0.31539156525252005f * (3.0f * zz - 1.0f);
+    v[7] = -1.0925484305920792f * x * z;
+    v[8] = 0.5462742152960396f * (xx - yy);
+    v[9] = -0.5900435899266435f * y * (3.0f * xx - yy);
+    v[10] = 2.890611442640554f * x * y * z;
+    v[11] = -0.4570457994644658f * y * (5.0f * zz - 1.0f);
+    v[12] = 0.3731763325901154f * z * (5.0f * zz - 3.0f);
+    v[13] = -0.4570457994644658f * x * (5.0f * zz - 1.0f);
+    v[14] = 1.445305721320277f * z * (xx - yy);
+    v[15] = -0.5900435899266435f * x * (xx - 3.0f * yy);
+    const uint32_t nd = degree * degree;
+    for (uint32_t k = 0; k < nd; ++k) out[i * nd + k] = __float2half_rn(v[k]);
+}
+
+}  // namespace
+
+extern "C" size_t dg_segments_workspace_bytes(uint32_t R, uint32_t P)
+{
+    const size_t n_blocks = ((size_t)R + kBlock - 1) / kBlock;
+    return (n_blocks ? n_blocks : 1) * (size_t)P * sizeof(uint32_t);
+}
+
+extern "C" int dg_ray_aabb_segments(const float *o, const float *d, uint32_t R, const float *parts, uint32_t P,
+                                    float t_min, uint32_t k_max, uint32_t *seg_count, float *seg_t,
+                                    int32_t *seg_part, uint32_t *part_offset, uint32_t *seg_ray,
+                                    uint32_t *seg_slot, uint32_t *status, void *ws, size_t ws_bytes, void *stream)
+{
+    DG_REQUIRE(P >= 1 && P <= DG_MAX_PARTITIONS, DG_ERR_UNSUPPORTED, "dg_ray_aabb_segments: P=%u outside 1..%d", P, DG_MAX_PARTITIONS);
+    DG_REQUIRE(k_max >= 1 && k_max <= kMaxK, DG_ERR_UNSUPPORTED, "dg_ray_aabb_segments: k_max=%u outside 1..%u", k_max, kMaxK);
+    DG_REQUIRE(parts && status, DG_ERR_ARG, "dg_ray_aabb_segments: null parts/status");
+    DG_REQUIRE(R == 0 || (o && d && seg_count && seg_t && seg_part), DG_ERR_ARG, "dg_ray_aabb_segments: null ray or output pointer");
+    hipStream_t st = (hipStream_t)stream;
+    const uint32_t n_blocks = (R + kBlock - 1) / kBlock;
+    if (part_offset) {
+        DG_REQUIRE(R == 0 || (seg_ray && seg_slot), DG_ERR_ARG, "dg_ray_aabb_segments: part_offset given without seg_ray/seg_slot");
+        DG_REQUIRE(ws && ws_bytes >= dg_segments_workspace_bytes(R, P), DG_ERR_WORKSPACE,
+                   "dg_ray_aabb_segments: workspace %zu < %zu bytes", ws_bytes, dg_segments_workspace_bytes(R, P));
+    }
+    if (R > 0) {
+        ray_aabb_kernel<<<n_blocks, kBlock, 0, st>>>(o, d, R, parts, P, t_min, k_max, seg_count, seg_t, seg_part, status);
+    }
+    if (part_offset) {
+        uint32_t *hist = (uint32_t *)ws;
+        if (R > 0)
+            bucket_count_kernel<<<n_blocks, kBlock, 0, st>>>(seg_count, seg_part, R, k_max, P, n_blocks, hist);
+        bucket_scan_kernel<<<1, kScanThreads, 0, st>>>(P, n_blocks, hist, part_offset);
+        if (R > 0)
+            bucket_scatter_kernel<<<n_blocks, kBlock, 0, st>>>(seg_count, seg_part, R, k_max, P, n_blocks, hist,
+                                                               part_offset, seg_ray, seg_slot);
+    }
+    return dg::launch_status("dg_ray_aabb_segments");
+}
+
+extern "C" int dg_sample_segments(const float *o, const float *d, const float *seg_t, const uint32_t *seg_ray,
+                                  const uint32_t *seg_slot, uint32_t n_seg, uint32_t k_max, const float *box,
+                                  uint32_t S, uint64_t seed, const float *jitter, float *u, float *delta,
+                                  void *stream)
+{
+    DG_REQUIRE(box && S >= 1 && S <= 65535 && k_max >= 1, DG_ERR_ARG, "dg_sample_segments: bad box/S/k_max");
+    if (n_seg == 0) return DG_OK;
+    DG_REQUIRE(o && d && seg_t && seg_ray && seg_slot && u && delta, DG_ERR_ARG, "dg_sample_segments: null pointer");
+    BoxArgs b;
+    for (int a = 0; a < 3; ++a) {
+        DG_REQUIRE(box[3 + a] > box[a], DG_ERR_ARG, "dg_sample_segments: empty box");
+        b.lo[a] = box[a];
+        b.inv_ext[a] = 1.0f / (box[3 + a] - box[a]);
+    }
+    const uint64_t n = (uint64_t)n_seg * S;
+    const uint64_t n_blocks = (n + kBlock - 1) / kBlock;
+    DG_REQUIRE(n_blocks <= 0x7fffffffull, DG_ERR_UNSUPPORTED, "dg_sample_segments: too many samples");
+    sample_kernel<<<(uint32_t)n_blocks, kBlock, 0, (hipStream_t)stream>>>(o, d, seg_t, seg_ray, seg_slot, n, k_max, b, S,
+                                                                          seed, jitter, u, delta);
+    return dg::launch_status("dg_sample_segments");
+}
+
+extern "C" int dg_dir_encode(const float *d, const uint32_t *index, uint64_t n, uint32_t degree, void *out,
+                             void *stream)
+{
+    DG_REQUIRE(degree >= 1 && degree <= 4, DG_ERR_UNSUPPORTED, "dg_dir_encode: degree %u outside 1..4", degree);
+    if (n == 0) return DG_OK;
+    DG_REQUIRE(d && out, DG_ERR_ARG, "dg_dir_encode: null pointer");
+    const uint64_t n_blocks = (n + kBlock - 1) / kBlock;
+    DG_REQUIRE(n_blocks <= 0x7fffffffull, DG_ERR_UNSUPPORTED, "dg_dir_encode: too many rows");
+    dir_encode_kernel<<<(uint32_t)n_blocks, kBlock, 0, (hipStream_t)stream>>>(d, index, n, degree, (__half *)out);
+    return dg::launch_status("dg_dir_encode");
+}

@@ -1,0 +1,117 @@
+"""One forward + backward pass of the DistGrid hot path on one GPU: call sequencing only.
+
+`TrainStep` owns the device buffers and issues the library calls in the order of the paper's
+training procedure (Sec. 4.4.2, Fig. 2): ray/box segments -> distribution to the resident
+sub-models -> per sub-model sampling, encode, MLPs, local compositing -> merge -> loss seeds ->
+merge backward (Eq. 7-8) -> per sub-model compositing / MLP / encode backward.  Every arithmetic
+step happens inside libdistgrid; this file allocates, slices and calls.
+"""
+import torch
+
+from . import binding as B
+
+
+class SubModel:
+    """Parameters and gradient buffers of one partition's sub-NeRF (hash table + MLP weights)."""
+
+    def __init__(self, grid_desc, mlp_desc, table, weights):
+        self.grid, self.mlp = grid_desc, mlp_desc
+        self.table, self.weights = table, weights
+        self.dtable = torch.zeros_like(table)
+        self.dW = torch.zeros(weights.numel(), dtype=torch.float32, device=weights.device)
+
+
+class TrainStep:
+    def __init__(self, parts, models, resident, R, S, k_max, sh_degree, loss_scale=65536.0, lambda1=0.0, seed=0,
+                 device="cuda:0", max_segments=None):
+        """parts: [P,6] float tensor (device); models: {partition index: SubModel}; resident: partition indices served."""
+        self.dev = torch.device(device)
+        self.parts, self.models, self.resident = parts, models, list(resident)
+        self.parts_host = parts.cpu().tolist()
+        self.P, self.R, self.S, self.k_max, self.deg = parts.shape[0], R, S, k_max, sh_degree
+        self.loss_scale, self.lambda1, self.seed = float(loss_scale), float(lambda1), seed
+        i32, f32, f16 = torch.int32, torch.float32, torch.float16
+        z = lambda *shape, dt=f32: torch.zeros(*shape, dtype=dt, device=self.dev)
+        cap = R * k_max if max_segments is None else max_segments
+        self.cap = cap
+        self.seg_count, self.seg_t, self.seg_part = z(R, dt=i32), z(R, k_max, 2), z(R, k_max, dt=i32)
+        self.part_offset, self.status = z(self.P + 1, dt=i32), z(1, dt=i32)
+        self.seg_ray, self.seg_slot = z(R * k_max, dt=i32), z(R * k_max, dt=i32)
+        self.ws_seg = z(max(B.dg_segments_workspace_bytes(R, self.P) // 4, 1), dt=i32)
+        n = cap * S
+        any_model = next(iter(models.values()))
+        self.n_feat = any_model.grid.n_levels * any_model.grid.n_features
+        self.u, self.delta = z(n, 3), z(n)
+        self.dir_enc = z(cap, sh_degree * sh_degree, dt=f16)
+        self.feat = z(n, self.n_feat, dt=f16)
+        self.sigma, self.rgb = z(n), z(n, 3)
+        self.dsigma, self.drgb = z(n), z(n, 3)
+        self.dfeat = z(n, self.n_feat)
+        self.Ck, self.Tk = z(R, k_max, 3), z(R, k_max)
+        self.gCk, self.gTk = z(R, k_max, 3), z(R, k_max)
+        self.C, self.T, self.gC, self.gT = z(R, 3), z(R), z(R, 3), z(R)
+        self.loss = z(1)
+        self.ws_mlp = z(max(B.dg_mlp_bwd_workspace_bytes(any_model.mlp) // 4, 1))
+        self.offsets = None
+
+    # -- forward ---------------------------------------------------------------------------
+    def segments(self, o, d, t_min=0.0):
+        self.status.zero_()
+        B.dg_ray_aabb_segments(o, d, self.parts, t_min, self.k_max, self.seg_count, self.seg_t, self.seg_part,
+                               self.status, self.part_offset, self.seg_ray, self.seg_slot, self.ws_seg)
+        self.offsets = self.part_offset.cpu().tolist()      # P+1 integers: how many segments each sub-model got
+        if self.offsets[-1] > self.cap:
+            raise B.DistGridError("segment capacity %d exceeded (%d)" % (self.cap, self.offsets[-1]))
+
+    def _slices(self, p):
+        b, e = self.offsets[p], self.offsets[p + 1]
+        return b, e, slice(b * self.S, e * self.S)
+
+    def forward(self, o, d, Cgt, jitter=None, foreign=None):
+        """foreign: optional callable(self) that fills partials of non-resident partitions into Ck/Tk."""
+        S = self.S
+        self.segments(o, d)
+        for p in self.resident:
+            b, e, sl = self._slices(p)
+            n_seg = e - b
+            if n_seg == 0:
+                continue
+            m = self.models[p]
+            N = n_seg * S
+            jit = None if jitter is None else jitter[sl]
+            B.dg_sample_segments(o, d, self.seg_t, self.seg_ray[b:e], self.seg_slot[b:e], n_seg, self.k_max,
+                                 self.parts_host[p], S, self.seed, jit, self.u[sl], self.delta[sl])
+            B.dg_dir_encode(d, self.seg_ray[b:e], n_seg, self.deg, self.dir_enc[b:e])
+            B.dg_hashgrid_encode_fwd(m.grid, m.table, self.u[sl], N, self.feat[sl])
+            B.dg_mlp_fwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[b:e], S, N, self.sigma[sl], self.rgb[sl])
+            B.dg_composite_segment_fwd(self.sigma[sl], self.rgb[sl], self.delta[sl], n_seg, S, self.seg_ray[b:e],
+                                       self.seg_slot[b:e], self.k_max, self.Ck, self.Tk)
+        if foreign is not None:
+            foreign(self)
+        B.dg_merge_segments(self.Ck, self.Tk, self.seg_count, self.R, self.k_max, self.C, self.T)
+        self.loss.zero_()
+        B.dg_loss_seed(self.C, self.T, Cgt, self.R, self.lambda1, self.gC, self.gT, self.loss)
+
+    # -- backward --------------------------------------------------------------------------
+    def backward(self):
+        S = self.S
+        B.dg_merge_segments_bwd(self.Ck, self.Tk, self.seg_count, self.R, self.k_max, self.gC, self.gT, self.gCk,
+                                self.gTk)
+        for p in self.resident:
+            b, e, sl = self._slices(p)
+            n_seg = e - b
+            m = self.models[p]
+            m.dtable.zero_()
+            m.dW.zero_()
+            if n_seg == 0:
+                continue
+            N = n_seg * S
+            B.dg_composite_segment_bwd(self.sigma[sl], self.rgb[sl], self.delta[sl], n_seg, S, self.seg_ray[b:e],
+                                       self.seg_slot[b:e], self.k_max, self.gCk, self.gTk, self.dsigma[sl], self.drgb[sl])
+            B.dg_mlp_bwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[b:e], S, N, self.dsigma[sl], self.drgb[sl],
+                         self.loss_scale, self.dfeat[sl], m.dW, self.ws_mlp)
+            B.dg_hashgrid_encode_bwd(m.grid, self.u[sl], self.dfeat[sl], N, m.dtable)
+
+    def step(self, o, d, Cgt, jitter=None, foreign=None):
+        self.forward(o, d, Cgt, jitter, foreign)
+        self.backward()

@@ -1,0 +1,301 @@
+"""GPU parity: every entry point of libdistgrid against the CPU oracle on the same seeded inputs.
+
+Bar: bit-exact for segment bookkeeping, bucket lists, sample coordinates and corner indices;
+relative error <= 1e-5 for the fp32 encode, composite and merge; <= 2e-3 for the fp16-input MLPs
+and for gradients accumulated with atomics.  Sizes span several tiles and a ragged tail.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import dg_inputs as di
+import oracle
+import oracle.step as ostep
+from paper_2405_04416_amd import binding as B
+
+from gpu_util import (DEV, TOL_F16, TOL_F32, dev, gpu_grid, gpu_mlp, gpu_models, have_gpu, host, make_step, rel_err)
+
+pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not have_gpu(), reason="needs a GPU")]
+
+
+def say(msg):
+    print("[case]", msg)
+    sys.stdout.flush()
+
+
+def ora_grid(cfg, part=0):
+    g = cfg["grid"]
+    b = g.get("growth") or oracle.growth_factor(g["n_min"], g["n_max"], g["L"])
+    return oracle.grid_init(g["L"], g["F"], g["log2_T"], g["n_min"], b, di.box_extent(cfg["parts"][part]))
+
+
+# ---------------------------------------------------------------------------- segments
+def _run_segments(o, d, parts, k_max, t_min=0.0):
+    R, P = o.shape[0], parts.shape[0]
+    i32 = torch.int32
+    cnt = torch.zeros(max(R, 1), dtype=i32, device=DEV)
+    seg_t = torch.zeros(max(R, 1), k_max, 2, device=DEV)
+    part = torch.zeros(max(R, 1), k_max, dtype=i32, device=DEV)
+    off = torch.zeros(P + 1, dtype=i32, device=DEV)
+    ray = torch.zeros(max(R * k_max, 1), dtype=i32, device=DEV)
+    slot = torch.zeros(max(R * k_max, 1), dtype=i32, device=DEV)
+    status = torch.zeros(1, dtype=i32, device=DEV)
+    ws = torch.zeros(max(B.dg_segments_workspace_bytes(R, P) // 4, 1), dtype=i32, device=DEV)
+    od, dd = (dev(o), dev(d)) if R else (torch.zeros(1, 3, device=DEV), torch.zeros(1, 3, device=DEV))
+    B.dg_ray_aabb_segments(od[:R], dd[:R], dev(parts), t_min, k_max, cnt, seg_t, part, status, off, ray, slot, ws)
+    torch.cuda.synchronize()
+    return host(cnt)[:R], host(seg_t)[:R], host(part)[:R], int(host(status)[0]), host(off), host(ray), host(slot)
+
+
+@pytest.mark.parametrize("name,R,k_max", [("c3_2x2", 5000, 4), ("c5_share", 3001, 6), ("c2_ngp", 1000, 1),
+                                          ("c1_tiny", 1024, 1), ("c5_share", 2000, 2)])
+def test_segments_bit_exact(name, R, k_max):
+    say("segments %s R=%d k_max=%d" % (name, R, k_max))
+    cfg = di.config(name)
+    o, d = di.make_rays(cfg, seed=7, R=R)
+    # a few hand-placed rays: inside a shared face, parallel to an axis, missing everything
+    o[:3] = [[0.0, -3.0, 0.1], [0.5, 0.5, 5.0], [50.0, 50.0, 50.0]]
+    d[:3] = [[0.0, 1.0, 0.0], [0.0, 0.0, -1.0], [0.0, 0.0, 1.0]]
+    P = cfg["parts"].shape[0]
+    cnt, seg_t, part, status, off, ray, slot = _run_segments(o, d, cfg["parts"], k_max)
+    rc, rt, rp, rs = oracle.ray_aabb_segments(o, d, cfg["parts"], 0.0, k_max)
+    np.testing.assert_array_equal(cnt, rc)
+    np.testing.assert_array_equal(seg_t.view(np.uint32), rt.view(np.uint32))      # bit for bit
+    np.testing.assert_array_equal(part, rp)
+    assert status == rs
+    roff, rray, rslot = oracle.bucket_segments(rc, rp, P)
+    np.testing.assert_array_equal(off, roff)
+    n = int(roff[-1])
+    np.testing.assert_array_equal(ray[:n], rray)
+    np.testing.assert_array_equal(slot[:n], rslot)
+
+
+def test_segments_empty_batch():
+    cfg = di.config("c3_2x2")
+    cnt, seg_t, part, status, off, ray, slot = _run_segments(np.zeros((0, 3), np.float32), np.zeros((0, 3), np.float32),
+                                                            cfg["parts"], 4)
+    assert list(off) == [0] * 5 and status == 0
+
+
+@pytest.mark.parametrize("use_array", [True, False])
+def test_sampling_bit_exact(use_array):
+    say("sampling array=%s" % use_array)
+    cfg = di.config("c3_2x2")
+    parts, S, k_max, R = cfg["parts"], 24, 4, 3000
+    o, d = di.make_rays(cfg, seed=8, R=R)
+    rc, rt, rp, _ = oracle.ray_aabb_segments(o, d, parts, 0.0, k_max)
+    off, ray, slot = oracle.bucket_segments(rc, rp, 4)
+    od, dd, td = dev(o), dev(d), dev(rt)
+    rayd, slotd = dev(ray.astype(np.int32)), dev(slot.astype(np.int32))
+    for p in range(4):
+        b, e = int(off[p]), int(off[p + 1])
+        n = (e - b) * S
+        jit = di.make_jitter(n, seed=p) if use_array else None
+        u = torch.zeros(n, 3, device=DEV); delta = torch.zeros(n, device=DEV)
+        B.dg_sample_segments(od, dd, td, rayd[b:e], slotd[b:e], e - b, k_max, parts[p], S, 99,
+                             None if jit is None else dev(jit), u, delta)
+        ru, rdelta = oracle.sample_segments(o, d, rt, ray, slot, b, e, parts[p], S, seed=99, jitter_arr=jit)
+        np.testing.assert_array_equal(host(u).view(np.uint32), ru.view(np.uint32))
+        np.testing.assert_array_equal(host(delta).view(np.uint32), rdelta.view(np.uint32))
+
+
+@pytest.mark.parametrize("degree", [1, 2, 3, 4])
+def test_dir_encode(degree):
+    d = np.random.default_rng(3).standard_normal((1000, 3)).astype(np.float32)
+    d[0] = [0, 0, 1]; d[1] = [0, 0, 0]
+    idx = np.random.default_rng(4).integers(0, 1000, 777).astype(np.int32)
+    out = torch.zeros(777, degree * degree, dtype=torch.float16, device=DEV)
+    B.dg_dir_encode(dev(d), dev(idx), 777, degree, out)
+    ref = oracle.sh(d[idx], degree)
+    ref[idx == 1] = oracle.sh(np.array([[0, 0, 1]], np.float32), degree)      # zero vector: library uses +z
+    assert np.max(np.abs(host(out).astype(np.float64) - ref)) <= 1e-3          # fp16 rounding of values <= 1.1
+    out2 = torch.zeros(1000, degree * degree, dtype=torch.float16, device=DEV)
+    B.dg_dir_encode(dev(d), None, 1000, degree, out2)
+    np.testing.assert_array_equal(host(out2)[idx], host(out))
+
+
+# ---------------------------------------------------------------------------- encode
+GRIDS = {
+    "c1": lambda: (di.config("c1_tiny"), None),
+    "c2": lambda: (di.config("c2_ngp"), None),
+    "mixed_small": lambda: (None, dict(L=6, F=2, log2_T=10, n_min=4, growth=1.7, extent=[1.0, 2.0, 0.5])),
+    "one_level_dense": lambda: (None, dict(L=1, F=2, log2_T=12, n_min=15, growth=1.0, extent=[1.0, 1.0, 1.0])),
+}
+
+
+def _both_grids(key):
+    cfg, spec = GRIDS[key]()
+    if cfg is not None:
+        return gpu_grid(cfg), ora_grid(cfg), cfg["table_range"]
+    g = B.dg_grid_desc_init(spec["L"], spec["F"], spec["log2_T"], spec["n_min"], spec["growth"], spec["extent"])
+    r = oracle.grid_init(spec["L"], spec["F"], spec["log2_T"], spec["n_min"], spec["growth"], spec["extent"])
+    return g, r, 1.0
+
+
+@pytest.mark.parametrize("key,N", [("c1", 32768), ("c2", 10007), ("mixed_small", 3333), ("one_level_dense", 257),
+                                   ("c2", 1), ("c2", 0)])
+def test_encode_fwd_and_indices(key, N):
+    say("encode fwd %s N=%d" % (key, N))
+    g, r, rng_range = _both_grids(key)
+    L = g.n_levels
+    table = di.make_table(r.n_entries, 2, rng_range, seed=1)
+    u = di.make_unit_coords(max(N, 1), seed=2)[:N]
+    if N > 16:
+        u[:6] = [[0, 0, 0], [1, 1, 1], [-0.3, 0.5, 2.0], [1, 0, 0.5], [0.999999, 0.999999, 0.999999], [0.5, 0.5, 0.5]]
+    td, ud = dev(table), dev(u) if N else torch.zeros(1, 3, device=DEV)[:0]
+    idx = torch.zeros(max(N, 1), L, 8, dtype=torch.int32, device=DEV)
+    feat = torch.zeros(max(N, 1), 2 * L, device=DEV)
+    feat16 = torch.zeros(max(N, 1), 2 * L, dtype=torch.float16, device=DEV)
+    B.dg_hashgrid_corner_indices(g, ud, N, idx)
+    B.dg_hashgrid_encode_fwd(g, td, ud, N, feat)
+    B.dg_hashgrid_encode_fwd(g, td, ud, N, feat16)
+    torch.cuda.synchronize()
+    if N == 0:
+        return
+    ref, ridx = oracle.encode_fwd(r, table, u, want_idx=True)
+    np.testing.assert_array_equal(host(idx).view(np.uint32), ridx)                 # bit-exact indices
+    bound = oracle.encode_fwd(r, table, u, abs_terms=True)                          # sum |w||theta| per output
+    err = np.abs(host(feat).astype(np.float64) - ref)
+    assert np.all(err <= TOL_F32 * bound + 1e-30), float(np.max(err / (bound + 1e-30)))
+    # fp16 output: the fp32 value rounded once
+    err16 = np.abs(host(feat16).astype(np.float64) - ref)
+    assert np.all(err16 <= 2.0 ** -11 * np.abs(ref) + TOL_F32 * bound + 6e-8)
+
+
+@pytest.mark.parametrize("key,N", [("c1", 32768), ("c2", 10007), ("mixed_small", 3333)])
+def test_encode_bwd(key, N):
+    say("encode bwd %s N=%d" % (key, N))
+    g, r, _ = _both_grids(key)
+    L = g.n_levels
+    u = di.make_unit_coords(N, seed=5)
+    dfeat = (np.random.default_rng(6).standard_normal((N, 2 * L)) * 1e-3).astype(np.float32)
+    dfeat[::7] = 0.0
+    dtable = torch.zeros(r.n_entries, 2, device=DEV)
+    B.dg_hashgrid_encode_bwd(g, dev(u), dev(dfeat), N, dtable)
+    B.dg_hashgrid_encode_bwd(g, dev(u), dev(dfeat), N, dtable)       # "+=": twice gives twice
+    ref = 2.0 * oracle.encode_bwd(r, u, dfeat.astype(np.float64))
+    got = host(dtable).astype(np.float64)
+    for l in range(L):                                                # judged level by level
+        sl = slice(r.first[l], r.first[l + 1])
+        assert rel_err(got[sl], ref[sl]) <= TOL_F16, l
+    assert np.all(got[ref == 0] == 0)                                 # untouched entries stay untouched
+
+
+# ---------------------------------------------------------------------------- MLPs
+def _mlp_inputs(cfg, n, S, seed, scale=1.0):
+    m = cfg["mlp"]
+    n_feat = cfg["grid"]["L"] * cfg["grid"]["F"]
+    w = di.make_mlp_weights(n_feat, m, seed=seed)
+    rng = np.random.default_rng(seed + 1)
+    feat = (rng.standard_normal((n, n_feat)) * scale).astype(np.float16)
+    dirs = rng.standard_normal((-(-n // S), 3)).astype(np.float32)
+    dir_enc = oracle.sh(dirs, m["sh_degree"]).astype(np.float16)
+    odesc = oracle.mlp_desc(n_feat, m["n_hidden_d"], m["n_geo"], m["sh_degree"] ** 2, m["n_hidden_c"], m["n_layers_c"], 1, 1)
+    return w, feat, dir_enc, odesc
+
+
+@pytest.mark.parametrize("name,n,S", [("c2_ngp", 5000, 64), ("c1_tiny", 3001, 32), ("c2_ngp", 130, 7)])
+def test_mlp_fwd(name, n, S):
+    say("mlp fwd %s n=%d" % (name, n))
+    cfg = di.config(name)
+    w, feat, dir_enc, odesc = _mlp_inputs(cfg, n, S, seed=11)
+    sigma = torch.zeros(n, device=DEV); rgb = torch.zeros(n, 3, device=DEV)
+    B.dg_mlp_fwd(gpu_mlp(cfg), dev(w), dev(feat), dev(dir_enc), S, n, sigma, rgb)
+    rs, rr = oracle.mlp_fwd(odesc, w.astype(np.float64), feat.astype(np.float64), dir_enc.astype(np.float64), S)
+    assert rel_err(host(sigma), rs) <= TOL_F16
+    assert rel_err(host(rgb), rr) <= TOL_F16
+
+
+@pytest.mark.parametrize("name,n,S", [("c2_ngp", 5000, 64), ("c1_tiny", 3001, 32)])
+def test_mlp_bwd(name, n, S):
+    say("mlp bwd %s n=%d" % (name, n))
+    cfg = di.config(name)
+    w, feat, dir_enc, odesc = _mlp_inputs(cfg, n, S, seed=12)
+    rng = np.random.default_rng(13)
+    dsigma = (rng.standard_normal(n) * 1e-6).astype(np.float32)
+    drgb = (rng.standard_normal((n, 3)) * 1e-6).astype(np.float32)
+    scale = 2.0 ** 18
+    mdesc = gpu_mlp(cfg)
+    dfeat = torch.zeros(n, feat.shape[1], device=DEV)
+    dW = torch.zeros(w.size, device=DEV)
+    ws = torch.zeros(B.dg_mlp_bwd_workspace_bytes(mdesc) // 4, device=DEV)
+    B.dg_mlp_bwd(mdesc, dev(w), dev(feat), dev(dir_enc), S, n, dev(dsigma), dev(drgb), scale, dfeat, dW, ws)
+    rdf, rdw = oracle.mlp_bwd(odesc, w.astype(np.float64), feat.astype(np.float64), dir_enc.astype(np.float64), S,
+                              dsigma.astype(np.float64), drgb.astype(np.float64), scale)
+    assert rel_err(host(dfeat), rdf) <= TOL_F16
+    pos = 0
+    for (no, ni) in di.mlp_layer_shapes(feat.shape[1], cfg["mlp"]):       # judged matrix by matrix
+        assert rel_err(host(dW)[pos:pos + no * ni], rdw[pos:pos + no * ni]) <= TOL_F16
+        pos += no * ni
+
+
+# ---------------------------------------------------------------------------- rendering
+@pytest.mark.parametrize("S,n_seg", [(64, 3000), (32, 1025), (48, 700), (7, 300), (150, 41), (1, 100)])
+def test_composite_fwd_bwd(S, n_seg):
+    say("composite S=%d n_seg=%d" % (S, n_seg))
+    rng = np.random.default_rng(S)
+    n = n_seg * S
+    sigma = np.exp(rng.standard_normal(n) * 2.0).astype(np.float32)
+    rgb = rng.random((n, 3), dtype=np.float32)
+    delta = (rng.random(n, dtype=np.float32) * 0.05 + 0.001).astype(np.float32)
+    R, k_max = n_seg + 5, 3
+    seg_ray = rng.permutation(R)[:n_seg].astype(np.int32)
+    seg_slot = rng.integers(0, k_max, n_seg).astype(np.int32)
+    Ck = torch.zeros(R, k_max, 3, device=DEV); Tk = torch.ones(R, k_max, device=DEV)
+    sd, rd, dd, rayd, slotd = dev(sigma), dev(rgb), dev(delta), dev(seg_ray), dev(seg_slot)
+    B.dg_composite_segment_fwd(sd, rd, dd, n_seg, S, rayd, slotd, k_max, Ck, Tk)
+    rC, rT = oracle.composite_fwd(sigma, rgb, delta, S)
+    assert rel_err(host(Ck)[seg_ray, seg_slot], rC, floor=1e-30) <= TOL_F32       # all terms positive: plain relative
+    assert rel_err(host(Tk)[seg_ray, seg_slot], rT, floor=1e-20) <= TOL_F32       # below 1e-20: judged absolutely
+    gCk = rng.standard_normal((R, k_max, 3)).astype(np.float32)
+    gTk = rng.standard_normal((R, k_max)).astype(np.float32)
+    dsigma = torch.zeros(n, device=DEV); drgb = torch.zeros(n, 3, device=DEV)
+    B.dg_composite_segment_bwd(sd, rd, dd, n_seg, S, rayd, slotd, k_max, dev(gCk), dev(gTk), dsigma, drgb)
+    rds, rdc = oracle.composite_bwd(sigma, rgb, delta, S, gCk[seg_ray, seg_slot], gTk[seg_ray, seg_slot])
+    assert rel_err(host(drgb), rdc, floor=1e-30) <= TOL_F32
+    # d sigma mixes signs: judged against the magnitude of its own positive and negative parts
+    mag = oracle.composite_bwd(sigma, rgb, delta, S, np.abs(gCk[seg_ray, seg_slot]), -np.abs(gTk[seg_ray, seg_slot]))[0]
+    mag = np.abs(mag) + np.abs(rds)
+    assert np.all(np.abs(host(dsigma) - rds) <= 20 * TOL_F32 * np.maximum(mag, np.mean(mag)))
+
+
+@pytest.mark.parametrize("k_max", [1, 4, 8])
+def test_merge_fwd_bwd(k_max):
+    rng = np.random.default_rng(k_max)
+    R = 5003
+    Ck = rng.random((R, k_max, 3), dtype=np.float32)
+    Tk = rng.random((R, k_max), dtype=np.float32)
+    Tk[rng.random((R, k_max)) < 0.1] = 0.0
+    cnt = rng.integers(0, k_max + 1, R).astype(np.int32)
+    gC = rng.standard_normal((R, 3)).astype(np.float32)
+    gT = rng.standard_normal(R).astype(np.float32)
+    C = torch.zeros(R, 3, device=DEV); T = torch.zeros(R, device=DEV)
+    B.dg_merge_segments(dev(Ck), dev(Tk), dev(cnt), R, k_max, C, T)
+    rC, rT = oracle.merge_fwd(Ck, Tk, cnt)
+    assert rel_err(host(C), rC, floor=1e-30) <= TOL_F32 and rel_err(host(T), rT, floor=1e-30) <= TOL_F32
+    assert np.all(host(C)[cnt == 0] == 0) and np.all(host(T)[cnt == 0] == 1)
+    gCk = torch.full((R, k_max, 3), 7.0, device=DEV); gTk = torch.full((R, k_max), 7.0, device=DEV)
+    B.dg_merge_segments_bwd(dev(Ck), dev(Tk), dev(cnt), R, k_max, dev(gC), dev(gT), gCk, gTk)
+    rgCk, rgTk = oracle.merge_bwd(Ck, Tk, cnt, gC, gT)
+    assert rel_err(host(gCk), rgCk, floor=1e-30) <= TOL_F32
+    mag = oracle.merge_bwd(Ck, Tk, cnt, np.abs(gC), np.abs(gT))[1]
+    assert np.all(np.abs(host(gTk) - rgTk) <= 4 * TOL_F32 * np.maximum(mag, 1e-30))
+    for r in range(0, R, 97):
+        assert np.all(host(gCk)[r, cnt[r]:] == 0) and np.all(host(gTk)[r, cnt[r]:] == 0)
+
+
+def test_loss_seed():
+    rng = np.random.default_rng(0)
+    R = 4099
+    C, Cgt = rng.random((R, 3), dtype=np.float32), rng.random((R, 3), dtype=np.float32)
+    T = rng.random(R, dtype=np.float32); T[:50] = 1.0
+    for lam in (0.0, 1e-3):
+        gC = torch.zeros(R, 3, device=DEV); gT = torch.zeros(R, device=DEV); loss = torch.zeros(1, device=DEV)
+        B.dg_loss_seed(dev(C), dev(T), dev(Cgt), R, lam, gC, gT, loss)
+        rl, rgC, rgT = oracle.loss(C, T, Cgt, lam)
+        assert abs(float(loss.item()) - rl) <= 1e-5 * abs(rl)
+        scale = np.mean(np.abs(rgC))
+        assert np.all(np.abs(host(gC) - rgC) <= 1e-6 * scale + TOL_F32 * np.abs(rgC))
+        assert rel_err(host(gT), rgT, floor=1e-30) <= TOL_F32 if lam else np.all(host(gT) == 0)

@@ -143,6 +143,19 @@ def test_composite_homogeneous_closed_form():
             np.testing.assert_allclose(Cc[0], c * (1 - np.exp(-sig * length)), rtol=1e-13, atol=1e-16)
 
 
+def test_composite_transmittance_is_exp_of_optical_depth():
+    # Eq. 3: T = exp(-int sigma); in the quadrature T_k = exp(-sum sigma_i delta_i), also where single
+    # samples are nearly opaque (sigma*delta up to ~100) and 1 - alpha would cancel in double
+    rng = np.random.default_rng(0)
+    S = 16
+    sigma = np.exp(rng.standard_normal(40 * S) * 2.5)
+    delta = rng.random(40 * S) * 0.05 + 0.001
+    _, T = oracle.composite_fwd(sigma, rng.random((40 * S, 3)), delta, S)
+    depth = (sigma * delta).reshape(40, S).sum(1)
+    assert depth.max() > 60
+    np.testing.assert_allclose(T, np.exp(-depth), rtol=1e-12)
+
+
 def _random_samples(n_seg, S, seed):
     rng = np.random.default_rng(seed)
     sigma = np.exp(rng.standard_normal(n_seg * S) * 1.5)
