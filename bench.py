@@ -1,0 +1,162 @@
+"""Benchmark of the DistGrid training hot path on one MI355X.
+
+One "step" is one forward + backward pass of every hot-path stage (ray/box segments, distribution,
+sampling, direction encoding, hash-grid encode, MLPs, segment compositing, merge, loss seeds and
+all their backward passes, including zeroing the gradient buffers) over one batch of synthetic
+rays that is already resident in HBM.  The workload is the Instant-NGP-scale single-partition
+configuration (2^18 rays x 64 samples, L=16, F=2, T=2^19).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_ngp] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA, published
+
+
+def algorithmic_work(entry, L, F, n_samples, mlp_flops_fwd):
+    """(bound, units of work per launch) for an entry point; bytes for HBM-bound ones, flops for the MLPs.
+
+    encode fwd : 12 B coordinates + L*8 corners*F*4 B table reads + L*F*2 B fp16 features per sample
+    encode bwd : 12 B coordinates + L*F*4 B feature gradient + L*8*F*4 B of atomic adds per sample
+    MLP fwd    : useful multiply-adds of both networks x 2;  MLP bwd: twice that again (dgrad + wgrad)
+                 plus the recomputed forward
+    """
+    gather = L * 8 * F * 4
+    if entry == "dg_hashgrid_encode_fwd":
+        return "hbm", n_samples * (12 + gather + L * F * 2)
+    if entry == "dg_hashgrid_encode_bwd":
+        return "hbm", n_samples * (12 + L * F * 4 + gather)
+    if entry == "dg_mlp_fwd":
+        return "mfma", n_samples * mlp_flops_fwd
+    if entry == "dg_mlp_bwd":
+        return "mfma", n_samples * mlp_flops_fwd * 3
+    return "hbm", None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2_ngp")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rays", type=int, default=16384)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not available. "
+                 "value is the one GPU's throughput." % args.gpus)
+
+    import numpy as np
+    import torch
+    import dg_inputs as di
+    from paper_2405_04416_amd import binding as B
+    from paper_2405_04416_amd.step import SubModel, TrainStep
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    B.lib()                                    # fail loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    cfg = di.config(args.workload)
+    g, m = cfg["grid"], cfg["mlp"]
+    R, S, k_max, P = cfg["R"], cfg["S"], cfg["k_max"], cfg["parts"].shape[0]
+    resident = [cfg["resident"]] if "resident" in cfg else list(range(P))
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    # seeded synthetic inputs, moved to HBM before anything is timed
+    o, d = di.make_rays(cfg, seed=0)
+    Cgt = di.make_targets(R, seed=0)
+    growth = g.get("growth") or B.dg_growth_factor(g["n_min"], g["n_max"], g["L"])
+    n_feat = g["L"] * g["F"]
+    models = {}
+    for p in resident:
+        grid = B.dg_grid_desc_init(g["L"], g["F"], g["log2_T"], g["n_min"], growth, di.box_extent(cfg["parts"][p]))
+        mlp = B.dg_mlp_desc(n_feat, m["n_hidden_d"], m["n_geo"], m["sh_degree"] ** 2, m["n_hidden_c"], m["n_layers_c"], 1)
+        table = to_dev(di.make_table(grid.n_entries, g["F"], cfg["table_range"], seed=1000 * p))
+        weights = to_dev(di.make_mlp_weights(n_feat, m, seed=1000 * p))
+        models[p] = SubModel(grid, mlp, table, weights)
+    od, dd, Cd = to_dev(o), to_dev(d), to_dev(Cgt)
+    step = TrainStep(to_dev(cfg["parts"]), models, resident, R, S, k_max, m["sh_degree"], loss_scale=65536.0,
+                     lambda1=1e-3, seed=0)
+
+    for w in range(args.warmup):
+        step.seed = w
+        step.step(od, dd, Cd)
+    torch.cuda.synchronize()
+    step.timings = {}
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step.seed = args.warmup + k            # fresh jitter every step, drawn inside the sampling kernel
+        step.step(od, dd, Cd)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = 1e3 * wall / args.steps
+    n_seg = step.offsets[-1]
+    n_samples = n_seg * S
+    per_call = step.timing_summary()           # HIP events on the launch stream, inside the timed region
+
+    shapes = di.mlp_layer_shapes(n_feat, m)
+    mlp_flops_fwd = 2 * sum(no * ni for no, ni in shapes)
+    breakdown = {k: round(ms / args.steps, 4) for k, (n, ms) in sorted(per_call.items(), key=lambda kv: -kv[1][1])}
+    dominant = next(iter(breakdown))
+    calls, total_ms = per_call[dominant]
+    avg_ms = total_ms / calls
+    per_launch_samples = n_samples / max(len(resident), 1)
+    bound, work = algorithmic_work(dominant, g["L"], g["F"], per_launch_samples, mlp_flops_fwd)
+    if work is None:
+        roofline = {"kernel": dominant, "bound": bound, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": None, "traffic": None, "avg_launch_ms": round(avg_ms, 4)}
+    elif bound == "hbm":
+        ach = work / (avg_ms * 1e-3) / 1e9
+        roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None, "avg_launch_ms": round(avg_ms, 4)}
+    else:
+        ach = work / (avg_ms * 1e-3) / 1e12
+        roofline = {"kernel": dominant, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_F16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(ach / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None,
+                    "avg_launch_ms": round(avg_ms, 4)}
+    # the other headline kernels, same accounting
+    others = {}
+    for entry in ("dg_hashgrid_encode_fwd", "dg_hashgrid_encode_bwd", "dg_mlp_fwd", "dg_mlp_bwd"):
+        if entry in per_call:
+            c, t = per_call[entry]
+            b, wk = algorithmic_work(entry, g["L"], g["F"], per_launch_samples, mlp_flops_fwd)
+            rate = wk / (t / c * 1e-3)
+            others[entry] = ({"GB/s": round(rate / 1e9, 1), "frac_hbm": round(rate / 1e9 / HBM_PEAK_GBS, 4)} if b == "hbm"
+                             else {"TFLOP/s": round(rate / 1e12, 2), "frac_mfma": round(rate / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)})
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle.step as ostep            # the oracle, as it stands, on the host cores of this machine
+        Rc = min(args.cpu_rays, R)
+        hm = ostep.make_models(dict(cfg, resident_list=resident), seed=0)
+        t1 = time.perf_counter()
+        ostep.run_step(cfg, hm, o[:Rc], d[:Rc], Cgt[:Rc], seed=0, lambda1=1e-3, loss_scale=65536.0, resident=resident)
+        cpu_s = time.perf_counter() - t1
+        cpu = {"value": round(Rc / cpu_s, 2), "unit": "rays/s", "cores": 1, "kind": "oracle",
+               "sample": "first %d rays of the same batch, full-size tables, one fwd+bwd pass, %.1f s" % (Rc, cpu_s)}
+
+    out = {
+        "metric": "training rays/s (fwd+bwd)", "value": round(R / (ms_per_step * 1e-3), 1), "unit": "rays/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "rays": R, "samples_per_segment": S, "segments": n_seg,
+                   "samples": n_samples, "levels": g["L"], "features": g["F"], "log2_T": g["log2_T"],
+                   "partitions_resident": len(resident), "mlp_operands": "f16, f32 accumulate"},
+        "samples_per_s": round(n_samples / (ms_per_step * 1e-3), 1),
+        "roofline": roofline, "kernels": others, "ms_per_call": breakdown, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -6,6 +6,8 @@ sub-models -> per sub-model sampling, encode, MLPs, local compositing -> merge -
 merge backward (Eq. 7-8) -> per sub-model compositing / MLP / encode backward.  Every arithmetic
 step happens inside libdistgrid; this file allocates, slices and calls.
 """
+import contextlib
+
 import torch
 
 from . import binding as B
@@ -53,12 +55,31 @@ class TrainStep:
         self.loss = z(1)
         self.ws_mlp = z(max(B.dg_mlp_bwd_workspace_bytes(any_model.mlp) // 4, 1))
         self.offsets = None
+        self.timings = None     # set to {} to collect (start, end) event pairs per entry point
+
+    @contextlib.contextmanager
+    def _timed(self, name):
+        """Brackets one library call with events on the stream it is launched on (the current stream)."""
+        if self.timings is None:
+            yield
+            return
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        yield
+        b.record()
+        self.timings.setdefault(name, []).append((a, b))
+
+    def timing_summary(self):
+        """{entry point: (calls, total ms)} from the collected events; synchronises."""
+        torch.cuda.synchronize()
+        return {k: (len(v), sum(a.elapsed_time(b) for a, b in v)) for k, v in (self.timings or {}).items()}
 
     # -- forward ---------------------------------------------------------------------------
     def segments(self, o, d, t_min=0.0):
         self.status.zero_()
-        B.dg_ray_aabb_segments(o, d, self.parts, t_min, self.k_max, self.seg_count, self.seg_t, self.seg_part,
-                               self.status, self.part_offset, self.seg_ray, self.seg_slot, self.ws_seg)
+        with self._timed("dg_ray_aabb_segments"):
+            B.dg_ray_aabb_segments(o, d, self.parts, t_min, self.k_max, self.seg_count, self.seg_t, self.seg_part,
+                                   self.status, self.part_offset, self.seg_ray, self.seg_slot, self.ws_seg)
         self.offsets = self.part_offset.cpu().tolist()      # P+1 integers: how many segments each sub-model got
         if self.offsets[-1] > self.cap:
             raise B.DistGridError("segment capacity %d exceeded (%d)" % (self.cap, self.offsets[-1]))
@@ -79,38 +100,50 @@ class TrainStep:
             m = self.models[p]
             N = n_seg * S
             jit = None if jitter is None else jitter[sl]
-            B.dg_sample_segments(o, d, self.seg_t, self.seg_ray[b:e], self.seg_slot[b:e], n_seg, self.k_max,
-                                 self.parts_host[p], S, self.seed, jit, self.u[sl], self.delta[sl])
-            B.dg_dir_encode(d, self.seg_ray[b:e], n_seg, self.deg, self.dir_enc[b:e])
-            B.dg_hashgrid_encode_fwd(m.grid, m.table, self.u[sl], N, self.feat[sl])
-            B.dg_mlp_fwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[b:e], S, N, self.sigma[sl], self.rgb[sl])
-            B.dg_composite_segment_fwd(self.sigma[sl], self.rgb[sl], self.delta[sl], n_seg, S, self.seg_ray[b:e],
-                                       self.seg_slot[b:e], self.k_max, self.Ck, self.Tk)
+            with self._timed("dg_sample_segments"):
+                B.dg_sample_segments(o, d, self.seg_t, self.seg_ray[b:e], self.seg_slot[b:e], n_seg, self.k_max,
+                                     self.parts_host[p], S, self.seed, jit, self.u[sl], self.delta[sl])
+            with self._timed("dg_dir_encode"):
+                B.dg_dir_encode(d, self.seg_ray[b:e], n_seg, self.deg, self.dir_enc[b:e])
+            with self._timed("dg_hashgrid_encode_fwd"):
+                B.dg_hashgrid_encode_fwd(m.grid, m.table, self.u[sl], N, self.feat[sl])
+            with self._timed("dg_mlp_fwd"):
+                B.dg_mlp_fwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[b:e], S, N, self.sigma[sl], self.rgb[sl])
+            with self._timed("dg_composite_segment_fwd"):
+                B.dg_composite_segment_fwd(self.sigma[sl], self.rgb[sl], self.delta[sl], n_seg, S, self.seg_ray[b:e],
+                                           self.seg_slot[b:e], self.k_max, self.Ck, self.Tk)
         if foreign is not None:
             foreign(self)
-        B.dg_merge_segments(self.Ck, self.Tk, self.seg_count, self.R, self.k_max, self.C, self.T)
+        with self._timed("dg_merge_segments"):
+            B.dg_merge_segments(self.Ck, self.Tk, self.seg_count, self.R, self.k_max, self.C, self.T)
         self.loss.zero_()
-        B.dg_loss_seed(self.C, self.T, Cgt, self.R, self.lambda1, self.gC, self.gT, self.loss)
+        with self._timed("dg_loss_seed"):
+            B.dg_loss_seed(self.C, self.T, Cgt, self.R, self.lambda1, self.gC, self.gT, self.loss)
 
     # -- backward --------------------------------------------------------------------------
     def backward(self):
         S = self.S
-        B.dg_merge_segments_bwd(self.Ck, self.Tk, self.seg_count, self.R, self.k_max, self.gC, self.gT, self.gCk,
-                                self.gTk)
+        with self._timed("dg_merge_segments_bwd"):
+            B.dg_merge_segments_bwd(self.Ck, self.Tk, self.seg_count, self.R, self.k_max, self.gC, self.gT, self.gCk,
+                                    self.gTk)
         for p in self.resident:
             b, e, sl = self._slices(p)
             n_seg = e - b
             m = self.models[p]
-            m.dtable.zero_()
-            m.dW.zero_()
+            with self._timed("zero_gradients"):
+                m.dtable.zero_()
+                m.dW.zero_()
             if n_seg == 0:
                 continue
             N = n_seg * S
-            B.dg_composite_segment_bwd(self.sigma[sl], self.rgb[sl], self.delta[sl], n_seg, S, self.seg_ray[b:e],
-                                       self.seg_slot[b:e], self.k_max, self.gCk, self.gTk, self.dsigma[sl], self.drgb[sl])
-            B.dg_mlp_bwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[b:e], S, N, self.dsigma[sl], self.drgb[sl],
-                         self.loss_scale, self.dfeat[sl], m.dW, self.ws_mlp)
-            B.dg_hashgrid_encode_bwd(m.grid, self.u[sl], self.dfeat[sl], N, m.dtable)
+            with self._timed("dg_composite_segment_bwd"):
+                B.dg_composite_segment_bwd(self.sigma[sl], self.rgb[sl], self.delta[sl], n_seg, S, self.seg_ray[b:e],
+                                           self.seg_slot[b:e], self.k_max, self.gCk, self.gTk, self.dsigma[sl], self.drgb[sl])
+            with self._timed("dg_mlp_bwd"):
+                B.dg_mlp_bwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[b:e], S, N, self.dsigma[sl], self.drgb[sl],
+                             self.loss_scale, self.dfeat[sl], m.dW, self.ws_mlp)
+            with self._timed("dg_hashgrid_encode_bwd"):
+                B.dg_hashgrid_encode_bwd(m.grid, self.u[sl], self.dfeat[sl], N, m.dtable)
 
     def step(self, o, d, Cgt, jitter=None, foreign=None):
         self.forward(o, d, Cgt, jitter, foreign)
