@@ -103,14 +103,25 @@ encode_fwd_kernel(dg_grid_desc g, const float2 *__restrict__ table, const float 
     (void)width;
 }
 
+// Backward scatter.  A wavefront holds 64 consecutive samples, i.e. a stretch of one ray, so at the
+// coarser levels neighbouring lanes sit in the same cell and add into the same 8 entries.  Global
+// fp32 atomics retire at a fixed rate per distinct cache line touched by an instruction, whatever the
+// scope or table size, so the kernel spends ALU to shrink that count:
+//  * lanes are grouped into runs of equal cell; a segmented wavefront scan sums each run's 16
+//    corner x feature values and only the run's last lane issues atomics;
+//  * where runs are short (fine levels) the scan is skipped and lane pairs (2k, 2k+1) serve first the
+//    even lane's sample, then the odd lane's: the two lanes add the .x and .y of the same entry in one
+//    instruction, which the memory pipeline treats as one request.
 __global__ void __launch_bounds__(kBlock)
 encode_bwd_kernel(dg_grid_desc g, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
                   float *__restrict__ dtable, uint32_t n_groups)
 {
     const uint32_t group = blockIdx.x % n_groups;
     const uint64_t n = (uint64_t)(blockIdx.x / n_groups) * kBlock + threadIdx.x;
-    if (n >= N) return;
-    const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
+    const bool live = n < N;
+    const uint64_t nn = live ? n : N - 1;
+    const int lane = threadIdx.x % dg::kWave;
+    const float uu[3] = {u[3 * nn], u[3 * nn + 1], u[3 * nn + 2]};
     const uint32_t mask = (1u << g.log2_T) - 1u;
     for (uint32_t l = group; l < g.n_levels; l += n_groups) {
         const LevelGeom lv = level_of(g, l);
@@ -119,13 +130,55 @@ encode_bwd_kernel(dg_grid_desc g, const float *__restrict__ u, const float2 *__r
         locate(lv, uu, cell, frac);
         corner_entries(lv, mask, cell, e);
         corner_weights(frac, w);
-        const float2 gfe = dfeat[n * g.n_levels + l];
-        if (gfe.x == 0.0f && gfe.y == 0.0f) continue;
+        float2 gfe = dfeat[nn * g.n_levels + l];
+        if (!live) gfe = make_float2(0.0f, 0.0f);
+        float *level_base = dtable + 2 * (size_t)lv.offset;
+
+        // runs of lanes that share a cell
+        bool head = lane == 0;
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            float *dst = dtable + 2 * ((size_t)lv.offset + e[c]);
-            unsafeAtomicAdd(dst, w[c] * gfe.x);
-            unsafeAtomicAdd(dst + 1, w[c] * gfe.y);
+        for (int a = 0; a < 3; ++a) head |= __shfl_up(cell[a], 1, dg::kWave) != cell[a];
+        const unsigned long long heads = __ballot(head);
+        float vx[8], vy[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) { vx[c] = w[c] * gfe.x; vy[c] = w[c] * gfe.y; }
+
+        if (__popcll(heads) <= 40) {
+            const int start = 63 - __clzll(heads & (~0ull >> (63 - lane)));
+#pragma unroll
+            for (int off = 1; off < dg::kWave; off <<= 1) {
+                const bool take = lane - off >= start;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    const float tx = __shfl_up(vx[c], off, dg::kWave), ty = __shfl_up(vy[c], off, dg::kWave);
+                    if (take) { vx[c] += tx; vy[c] += ty; }
+                }
+            }
+            const bool tail = lane == dg::kWave - 1 || ((heads >> (lane + 1)) & 1ull);
+            if (tail) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    if (vx[c] != 0.0f) unsafeAtomicAdd(level_base + 2 * (size_t)e[c], vx[c]);
+                    if (vy[c] != 0.0f) unsafeAtomicAdd(level_base + 2 * (size_t)e[c] + 1, vy[c]);
+                }
+            }
+        } else {
+            const int sub = lane & 1;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                // even lane's sample: even lane adds x, odd lane adds the even lane's y
+                const uint32_t e_dn = __shfl_up(e[c], 1, dg::kWave);
+                const float y_dn = __shfl_up(vy[c], 1, dg::kWave);
+                const uint32_t ea = sub ? e_dn : e[c];
+                const float va = sub ? y_dn : vx[c];
+                if (va != 0.0f) unsafeAtomicAdd(level_base + 2 * (size_t)ea + sub, va);
+                // odd lane's sample: even lane adds the odd lane's x, odd lane adds its own y
+                const uint32_t e_up = __shfl_down(e[c], 1, dg::kWave);
+                const float x_up = __shfl_down(vx[c], 1, dg::kWave);
+                const uint32_t eb = sub ? e[c] : e_up;
+                const float vb = sub ? vy[c] : x_up;
+                if (vb != 0.0f) unsafeAtomicAdd(level_base + 2 * (size_t)eb + sub, vb);
+            }
         }
     }
 }
