@@ -33,6 +33,14 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 
 constexpr int kWave = 64;
 
+// matrix-core path of the 32-64-16 / 32-64-64-3 field MLPs (mlp_mfma.hip)
+size_t mlp_mfma_workspace_bytes();
+void mlp_mfma_fwd(const void *weights, const void *feat, const void *dir_enc, uint32_t S, uint64_t N, uint32_t act_c,
+                  float *sigma, float *rgb, hipStream_t st);
+void mlp_mfma_bwd(const void *weights, const void *feat, const void *dir_enc, uint32_t S, uint64_t N, uint32_t act_c,
+                  const float *dsigma, const float *drgb, float loss_scale, float *dfeat, float *dW, void *ws,
+                  hipStream_t st);
+
 }  // namespace dg
 
 #define DG_REQUIRE(cond, code, ...)                     \

@@ -245,10 +245,10 @@ extern "C" int dg_mlp_fwd(const dg_mlp_desc *desc, const void *weights, const vo
     const uint64_t n_blocks = (N + kFwdBlock - 1) / kFwdBlock;
     DG_REQUIRE(n_blocks <= 0x7fffffffull, DG_ERR_UNSUPPORTED, "dg_mlp_fwd: N too large");
     hipStream_t st = (hipStream_t)stream;
-    if (net == 1)
-        mlp_fwd_kernel<NetNgp><<<(uint32_t)n_blocks, kFwdBlock, 0, st>>>((const __half *)weights, (const __half *)feat,
-                                                                          (const __half *)dir_enc, S, N, desc->act_c, sigma, rgb);
-    else
+    if (net == 1) {
+        DG_REQUIRE(dg::aligned(feat, 16) && dg::aligned(dir_enc, 16), DG_ERR_ARG, "dg_mlp_fwd: feat / dir_enc must be 16-byte aligned");
+        dg::mlp_mfma_fwd(weights, feat, dir_enc, S, N, desc->act_c, sigma, rgb, st);
+    } else
         mlp_fwd_kernel<NetTiny><<<(uint32_t)n_blocks, kFwdBlock, 0, st>>>((const __half *)weights, (const __half *)feat,
                                                                            (const __half *)dir_enc, S, N, desc->act_c, sigma, rgb);
     return dg::launch_status("dg_mlp_fwd");
@@ -256,7 +256,11 @@ extern "C" int dg_mlp_fwd(const dg_mlp_desc *desc, const void *weights, const vo
 
 extern "C" size_t dg_mlp_bwd_workspace_bytes(const dg_mlp_desc *desc)
 {
-    return (size_t)kBwdGrid * dg_mlp_weight_count(desc) * sizeof(float);
+    if (!desc) return 0;
+    const size_t scalar = (size_t)kBwdGrid * dg_mlp_weight_count(desc) * sizeof(float);
+    const bool ngp = desc->n_feat == 32 && desc->n_hidden_d == 64 && desc->n_geo == 16 && desc->n_dir == 16 &&
+                     desc->n_hidden_c == 64 && desc->n_layers_c == 2;
+    return ngp ? dg::mlp_mfma_workspace_bytes() : scalar;
 }
 
 extern "C" int dg_mlp_bwd(const dg_mlp_desc *desc, const void *weights, const void *feat, const void *dir_enc,
@@ -274,12 +278,14 @@ extern "C" int dg_mlp_bwd(const dg_mlp_desc *desc, const void *weights, const vo
     const uint32_t grid = (uint32_t)(n_tiles < kBwdGrid ? n_tiles : kBwdGrid);
     const uint32_t n_w = (uint32_t)dg_mlp_weight_count(desc);
     hipStream_t st = (hipStream_t)stream;
-    if (net == 1)
-        mlp_bwd_kernel<NetNgp><<<grid, kBwdBlock, 0, st>>>((const __half *)weights, (const __half *)feat, (const __half *)dir_enc,
-                                                           S, N, desc->act_c, dsigma, drgb, loss_scale, dfeat, (float *)ws);
-    else
-        mlp_bwd_kernel<NetTiny><<<grid, kBwdBlock, 0, st>>>((const __half *)weights, (const __half *)feat, (const __half *)dir_enc,
-                                                            S, N, desc->act_c, dsigma, drgb, loss_scale, dfeat, (float *)ws);
+    if (net == 1) {
+        DG_REQUIRE(dg::aligned(feat, 16) && dg::aligned(dir_enc, 16) && dg::aligned(dfeat, 16), DG_ERR_ARG,
+                   "dg_mlp_bwd: feat / dir_enc / dfeat must be 16-byte aligned");
+        dg::mlp_mfma_bwd(weights, feat, dir_enc, S, N, desc->act_c, dsigma, drgb, loss_scale, dfeat, dW, ws, st);
+        return dg::launch_status("dg_mlp_bwd");
+    }
+    mlp_bwd_kernel<NetTiny><<<grid, kBwdBlock, 0, st>>>((const __half *)weights, (const __half *)feat, (const __half *)dir_enc,
+                                                        S, N, desc->act_c, dsigma, drgb, loss_scale, dfeat, (float *)ws);
     fold_partials_kernel<<<(n_w + 255) / 256, 256, 0, st>>>((const float *)ws, grid, n_w, 1.0f / loss_scale, dW);
     return dg::launch_status("dg_mlp_bwd");
 }

@@ -1,0 +1,451 @@
+// Field MLPs on the matrix cores (v_mfma_f32_32x32x16_f16) for the 32 -> 64 -> 16 density net and
+// the (16 + 16) -> 64 -> 64 -> 3 colour net (Sec. 3.2; activations and output clip of Sec. 5.1).
+//
+// One wavefront owns a tile of 32 samples and keeps every activation of the tile in registers.
+// Layers are evaluated transposed, out^T = W . in^T: the weight matrix is the A operand (rows = output
+// features), the activations are the B operand (columns = samples).  The result tile then has the
+// sample on the lane and the features on the registers, which is again a B operand for the next
+// layer once the registers are rounded to fp16 and packed -- the feature order this produces is
+// baked into the weight images, so layers chain with no data movement.
+//
+// Operand and result layouts (lane = 32 h + c, element j / register r):
+//   A[row c][k = 8 h + j]     B[k = 8 h + j][col c]     D[row 8 (r / 4) + 4 h + r % 4][col c]
+// "Images" are weight tiles pre-arranged in LDS so that one 16-byte read per lane yields an operand.
+//
+// Backward recomputes the forward, then walks the chain back.  Weight gradients contract over the
+// samples, so they need each (delta, activation) pair with the samples on the k axis; a product with
+// a 0/1 selection matrix on the matrix cores transposes a tile exactly (fp16 values times one,
+// summed with zeros).  Every wavefront accumulates its share of dW in registers over all its tiles,
+// writes it to the workspace once, and a second kernel folds the shares in a fixed order.
+#include "dg_internal.h"
+
+namespace dg_mlp_mfma {
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+constexpr int NF = 32, HD = 64, NG = 16, ND = 16, HC = 64, CI = NG + ND;
+constexpr int oWd1 = 0, oWd2 = oWd1 + HD * NF, oWc1 = oWd2 + NG * HD, oWc2 = oWc1 + HC * CI, oWc3 = oWc2 + HC * HC;
+constexpr int kTotal = oWc3 + 3 * HC;
+
+// image chunks (1 KB each: 64 lanes x 8 halves)
+constexpr int cD1 = 0, cD2 = 4, cC1 = 8, cC2 = 12, cC3 = 20, kFwdChunks = 24;
+constexpr int cC3T = 24, cC2T = 26, cC1T = 34, cD2T = 38, cD1T = 40, cSelT = 44, cSelN = 46, kAllChunks = 48;
+
+constexpr int kBlock = 256;
+constexpr int kWavesPerBlock = kBlock / 64;
+
+// feature held by slot j of lane half h in k-step ks
+__device__ __forceinline__ int feat_tiled(int ks, int h, int j) { return 32 * (ks >> 1) + 8 * (2 * (ks & 1) + (j >> 2)) + 4 * h + (j & 3); }
+__device__ __forceinline__ int feat_natural(int ks, int h, int j) { return 16 * ks + 8 * h + j; }
+
+// kind: 0 tiled, 1 natural, 2 colour-net input (k-step 0 tiled geometry, k-step 1 natural direction)
+__device__ __forceinline__ int feat_of(int kind, int ks, int h, int j)
+{
+    if (kind == 0) return feat_tiled(ks, h, j);
+    if (kind == 1) return feat_natural(ks, h, j);
+    return ks == 0 ? feat_tiled(0, h, j) : feat_natural(1, h, j);
+}
+
+// A-operand image of a weight matrix W[n_out][n_in] (row-major): rows = outputs (transpose == false)
+// or rows = inputs (transpose == true, for the data gradient)
+__device__ void build_image(__half *img, const __half *W, int n_out, int n_in, int rows_real, int k_real,
+                            int n_mt, int n_ks, int kind, bool transpose)
+{
+    for (int idx = threadIdx.x; idx < n_mt * n_ks * 512; idx += kBlock) {
+        const int j = idx & 7, lane = (idx >> 3) & 63, chunk = idx >> 9;
+        const int ks = chunk % n_ks, mt = chunk / n_ks;
+        const int row = 32 * mt + (lane & 31), k = feat_of(kind, ks, lane >> 5, j);
+        __half v = __float2half(0.0f);
+        if (row < rows_real && k < k_real) v = transpose ? W[k * n_in + row] : W[row * n_in + k];
+        img[idx] = v;
+    }
+    (void)n_out;
+}
+
+__device__ void build_selection(__half *img, int kind)
+{
+    for (int idx = threadIdx.x; idx < 2 * 512; idx += kBlock) {
+        const int j = idx & 7, lane = (idx >> 3) & 63, p = idx >> 9;
+        const int f = (kind == 0 ? feat_tiled(p, lane >> 5, j) : feat_natural(p, lane >> 5, j)) & 31;
+        img[idx] = __float2half(f == (lane & 31) ? 1.0f : 0.0f);
+    }
+}
+
+__device__ void build_forward_images(__half *lds, const __half *w)
+{
+    build_image(lds + cD1 * 512, w + oWd1, HD, NF, HD, NF, 2, 2, 1, false);
+    build_image(lds + cD2 * 512, w + oWd2, NG, HD, NG, HD, 1, 4, 0, false);
+    build_image(lds + cC1 * 512, w + oWc1, HC, CI, HC, CI, 2, 2, 2, false);
+    build_image(lds + cC2 * 512, w + oWc2, HC, HC, HC, HC, 2, 4, 0, false);
+    build_image(lds + cC3 * 512, w + oWc3, 3, HC, 3, HC, 1, 4, 0, false);
+}
+
+__device__ void build_backward_images(__half *lds, const __half *w)
+{
+    build_image(lds + cC3T * 512, w + oWc3, 3, HC, HC, 3, 2, 1, 0, true);
+    build_image(lds + cC2T * 512, w + oWc2, HC, HC, HC, HC, 2, 4, 0, true);
+    build_image(lds + cC1T * 512, w + oWc1, HC, CI, NG, HC, 1, 4, 0, true);     // direction inputs get no gradient
+    build_image(lds + cD2T * 512, w + oWd2, NG, HD, HD, NG, 2, 1, 0, true);
+    build_image(lds + cD1T * 512, w + oWd1, HD, NF, NF, HD, 1, 4, 0, true);
+    build_selection(lds + cSelT * 512, 0);
+    build_selection(lds + cSelN * 512, 1);
+}
+
+__device__ __forceinline__ h8 image(const __half *lds, int chunk, int lane)
+{
+    return reinterpret_cast<const h8 *>(lds)[chunk * 64 + lane];
+}
+
+__device__ __forceinline__ f16v mma(h8 a, h8 b, f16v c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+
+__device__ __forceinline__ f16v zero16()
+{
+    f16v z;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) z[i] = 0.0f;
+    return z;
+}
+
+__device__ __forceinline__ float fast_sigmoid(float x)
+{
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+}
+__device__ __forceinline__ float clip15(float x) { return fminf(fmaxf(x, -15.0f), 15.0f); }
+
+// registers 8p .. 8p+7 of a result tile, activated, rounded to fp16 and packed: k-step (m, p) of the next operand
+template <int ACT>   // 0 identity, 1 ReLU, 2 sigmoid
+__device__ __forceinline__ h8 pack_half(const f16v &c, int p)
+{
+    h8 out;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        float v = c[8 * p + j];
+        if (ACT == 1) v = fmaxf(v, 0.0f);
+        if (ACT == 2) v = fast_sigmoid(v);
+        out[j] = (_Float16)v;
+    }
+    return out;
+}
+
+struct Tile {
+    h8 x0[2], h1[4], xc[2], c1[4], c2[4];
+    float geo0, sigma, raw[3], rgb[3];     // meaningful on lanes with h == 0
+};
+
+__device__ __forceinline__ void forward_tile(const __half *lds, int lane, uint32_t act_c, Tile &t)
+{
+    f16v acc[2];
+    // density layer 1: 32 -> 64, ReLU
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        acc[mt] = zero16();
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) acc[mt] = mma(image(lds, cD1 + mt * 2 + ks, lane), t.x0[ks], acc[mt]);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) t.h1[ks] = pack_half<1>(acc[ks >> 1], ks & 1);
+    // density layer 2: 64 -> 16, raw
+    f16v geo = zero16();
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) geo = mma(image(lds, cD2 + ks, lane), t.h1[ks], geo);
+    t.geo0 = geo[0];
+    t.sigma = __expf(clip15(geo[0]));
+    t.xc[0] = pack_half<0>(geo, 0);
+    // colour layer 1: (16 + 16) -> 64
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        acc[mt] = zero16();
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) acc[mt] = mma(image(lds, cC1 + mt * 2 + ks, lane), t.xc[ks], acc[mt]);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) t.c1[ks] = act_c ? pack_half<2>(acc[ks >> 1], ks & 1) : pack_half<1>(acc[ks >> 1], ks & 1);
+    // colour layer 2: 64 -> 64
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        acc[mt] = zero16();
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) acc[mt] = mma(image(lds, cC2 + mt * 4 + ks, lane), t.c1[ks], acc[mt]);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) t.c2[ks] = act_c ? pack_half<2>(acc[ks >> 1], ks & 1) : pack_half<1>(acc[ks >> 1], ks & 1);
+    // colour layer 3: 64 -> 3, raw
+    f16v out = zero16();
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) out = mma(image(lds, cC3 + ks, lane), t.c2[ks], out);
+#pragma unroll
+    for (int c = 0; c < 3; ++c) { t.raw[c] = out[c]; t.rgb[c] = fast_sigmoid(clip15(out[c])); }
+}
+
+__device__ __forceinline__ void load_inputs(const __half *feat, const __half *dir_enc, uint32_t S, uint64_t n,
+                                            bool valid, int h, Tile &t)
+{
+    const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (valid) {
+        const h8 *row = reinterpret_cast<const h8 *>(feat + n * NF);
+        t.x0[0] = row[h];            // features 8h .. 8h+7
+        t.x0[1] = row[2 + h];        // features 16 + 8h ..
+        t.xc[1] = reinterpret_cast<const h8 *>(dir_enc + (n / S) * ND)[h];
+    } else {
+        t.x0[0] = zero; t.x0[1] = zero; t.xc[1] = zero;
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+fwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, const __half *__restrict__ dir_enc,
+           uint32_t S, uint64_t n_samples, uint32_t act_c, float *__restrict__ sigma, float *__restrict__ rgb)
+{
+    __shared__ __attribute__((aligned(16))) __half lds[kFwdChunks * 512];
+    build_forward_images(lds, weights);
+    __syncthreads();
+    const int lane = threadIdx.x & 63, h = lane >> 5;
+    const uint64_t n_tiles = (n_samples + 31) / 32;
+    const uint64_t wave = (uint64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
+    for (uint64_t tile = wave; tile < n_tiles; tile += n_waves) {
+        const uint64_t n = tile * 32 + (lane & 31);
+        const bool valid = n < n_samples;
+        Tile t;
+        load_inputs(feat, dir_enc, S, n, valid, h, t);
+        forward_tile(lds, lane, act_c, t);
+        if (valid && h == 0) {
+            sigma[n] = t.sigma;
+            rgb[3 * n] = t.rgb[0]; rgb[3 * n + 1] = t.rgb[1]; rgb[3 * n + 2] = t.rgb[2];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------- backward
+
+// transpose of one 32-feature tile of a packed tensor: x0 / x1 are the two k-steps that hold the tile,
+// sel0 / sel1 the matching selection images; result: the two sample k-steps of the transposed tile
+__device__ __forceinline__ void transpose_tile(h8 x0, h8 x1, h8 sel0, h8 sel1, h8 out[2])
+{
+    f16v c = zero16();
+    c = mma(x0, sel0, c);
+    c = mma(x1, sel1, c);
+    out[0] = pack_half<0>(c, 0);
+    out[1] = pack_half<0>(c, 1);
+}
+__device__ __forceinline__ void transpose_half_tile(h8 x0, h8 sel0, h8 out[2])
+{
+    f16v c = zero16();
+    c = mma(x0, sel0, c);
+    out[0] = pack_half<0>(c, 0);
+    out[1] = pack_half<0>(c, 1);
+}
+
+// delta = fp16(g * act'(a)) for one k-step; a is the packed (rounded) activation
+template <int ACT>   // 1 ReLU, 2 sigmoid
+__device__ __forceinline__ h8 delta_from(const f16v &g, int p, h8 a)
+{
+    h8 out;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float av = (float)a[j];
+        const float d = ACT == 2 ? av * (1.0f - av) : (av > 0.0f ? 1.0f : 0.0f);
+        out[j] = (_Float16)(g[8 * p + j] * d);
+    }
+    return out;
+}
+
+__device__ __forceinline__ void store_share(float *dst, int n_in, int rows_real, int ot, int it, int lane, const f16v &acc)
+{
+    const int h = lane >> 5, i = 32 * it + (lane & 31);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int o = 32 * ot + 8 * (r >> 2) + 4 * h + (r & 3);
+        if (o < rows_real) dst[o * n_in + i] = acc[r];
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, const __half *__restrict__ dir_enc,
+           uint32_t S, uint64_t n_samples, uint32_t act_c, const float *__restrict__ dsigma,
+           const float *__restrict__ drgb, float loss_scale, float *__restrict__ dfeat, float *__restrict__ shares)
+{
+    __shared__ __attribute__((aligned(16))) __half lds[kAllChunks * 512];
+    build_forward_images(lds, weights);
+    build_backward_images(lds, weights);
+    __syncthreads();
+    const int lane = threadIdx.x & 63, h = lane >> 5;
+    const uint64_t n_tiles = (n_samples + 31) / 32;
+    const uint64_t wave = (uint64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
+    const float inv_scale = 1.0f / loss_scale;
+    const h8 selT0 = image(lds, cSelT, lane), selT1 = image(lds, cSelT + 1, lane);
+    const h8 selN0 = image(lds, cSelN, lane), selN1 = image(lds, cSelN + 1, lane);
+    const h8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+
+    f16v gWc3[2], gWc2[2][2], gWc1[2], gWd2[2], gWd1[2];      // [output tile][input tile]
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        gWc3[a] = zero16(); gWc1[a] = zero16(); gWd2[a] = zero16(); gWd1[a] = zero16();
+        gWc2[a][0] = zero16(); gWc2[a][1] = zero16();
+    }
+
+    for (uint64_t tile = wave; tile < n_tiles; tile += n_waves) {
+        const uint64_t n = tile * 32 + (lane & 31);
+        const bool valid = n < n_samples;
+        Tile t;
+        load_inputs(feat, dir_enc, S, n, valid, h, t);
+        forward_tile(lds, lane, act_c, t);
+
+        // ---- output layer of the colour net
+        h8 d3 = zero8;
+        if (valid && h == 0) {
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                const bool pass = t.raw[c] >= -15.0f && t.raw[c] <= 15.0f;
+                d3[c] = (_Float16)(pass ? loss_scale * drgb[3 * n + c] * t.rgb[c] * (1.0f - t.rgb[c]) : 0.0f);
+            }
+        }
+        h8 td[2][2], ta[2][2];      // transposed delta / activation: [feature tile][sample k-step]
+        transpose_half_tile(d3, selT0, td[0]);
+        transpose_tile(t.c2[0], t.c2[1], selT0, selT1, ta[0]);
+        transpose_tile(t.c2[2], t.c2[3], selT0, selT1, ta[1]);
+#pragma unroll
+        for (int it = 0; it < 2; ++it)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) gWc3[it] = mma(td[0][p], ta[it][p], gWc3[it]);
+        f16v g[2];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) g[mt] = mma(image(lds, cC3T + mt, lane), d3, zero16());
+
+        // ---- second hidden layer of the colour net
+        h8 dl[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) dl[ks] = act_c ? delta_from<2>(g[ks >> 1], ks & 1, t.c2[ks]) : delta_from<1>(g[ks >> 1], ks & 1, t.c2[ks]);
+        transpose_tile(dl[0], dl[1], selT0, selT1, td[0]);
+        transpose_tile(dl[2], dl[3], selT0, selT1, td[1]);
+        transpose_tile(t.c1[0], t.c1[1], selT0, selT1, ta[0]);
+        transpose_tile(t.c1[2], t.c1[3], selT0, selT1, ta[1]);
+#pragma unroll
+        for (int ot = 0; ot < 2; ++ot)
+#pragma unroll
+            for (int it = 0; it < 2; ++it)
+#pragma unroll
+                for (int p = 0; p < 2; ++p) gWc2[ot][it] = mma(td[ot][p], ta[it][p], gWc2[ot][it]);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            g[mt] = zero16();
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) g[mt] = mma(image(lds, cC2T + mt * 4 + ks, lane), dl[ks], g[mt]);
+        }
+
+        // ---- first hidden layer of the colour net
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) dl[ks] = act_c ? delta_from<2>(g[ks >> 1], ks & 1, t.c1[ks]) : delta_from<1>(g[ks >> 1], ks & 1, t.c1[ks]);
+        transpose_tile(dl[0], dl[1], selT0, selT1, td[0]);
+        transpose_tile(dl[2], dl[3], selT0, selT1, td[1]);
+        transpose_tile(t.xc[0], t.xc[1], selT0, selN1, ta[0]);
+#pragma unroll
+        for (int ot = 0; ot < 2; ++ot)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) gWc1[ot] = mma(td[ot][p], ta[0][p], gWc1[ot]);
+        f16v gx = zero16();
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) gx = mma(image(lds, cC1T + ks, lane), dl[ks], gx);
+
+        // ---- density net output: geometry features feed the colour net, output 0 also feeds exp()
+        if (valid && h == 0) {
+            const bool pass0 = t.geo0 >= -15.0f && t.geo0 <= 15.0f;
+            gx[0] += pass0 ? loss_scale * dsigma[n] * t.sigma : 0.0f;
+        }
+        const h8 dg = pack_half<0>(gx, 0);
+        transpose_half_tile(dg, selT0, td[0]);
+        transpose_tile(t.h1[0], t.h1[1], selT0, selT1, ta[0]);
+        transpose_tile(t.h1[2], t.h1[3], selT0, selT1, ta[1]);
+#pragma unroll
+        for (int it = 0; it < 2; ++it)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) gWd2[it] = mma(td[0][p], ta[it][p], gWd2[it]);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) g[mt] = mma(image(lds, cD2T + mt, lane), dg, zero16());
+
+        // ---- hidden layer of the density net
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) dl[ks] = delta_from<1>(g[ks >> 1], ks & 1, t.h1[ks]);
+        transpose_tile(dl[0], dl[1], selT0, selT1, td[0]);
+        transpose_tile(dl[2], dl[3], selT0, selT1, td[1]);
+        transpose_tile(t.x0[0], t.x0[1], selN0, selN1, ta[0]);
+#pragma unroll
+        for (int ot = 0; ot < 2; ++ot)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) gWd1[ot] = mma(td[ot][p], ta[0][p], gWd1[ot]);
+        f16v gf = zero16();
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) gf = mma(image(lds, cD1T + ks, lane), dl[ks], gf);
+        if (valid) {
+            float4 *row = reinterpret_cast<float4 *>(dfeat + n * NF);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)       // registers 4q .. 4q+3 hold features 8q + 4h .. + 3
+                row[2 * q + h] = make_float4(gf[4 * q] * inv_scale, gf[4 * q + 1] * inv_scale, gf[4 * q + 2] * inv_scale,
+                                             gf[4 * q + 3] * inv_scale);
+        }
+    }
+
+    float *mine = shares + wave * kTotal;
+    store_share(mine + oWc3, HC, 3, 0, 0, lane, gWc3[0]);
+    store_share(mine + oWc3, HC, 3, 0, 1, lane, gWc3[1]);
+#pragma unroll
+    for (int ot = 0; ot < 2; ++ot) {
+        store_share(mine + oWc2, HC, HC, ot, 0, lane, gWc2[ot][0]);
+        store_share(mine + oWc2, HC, HC, ot, 1, lane, gWc2[ot][1]);
+        store_share(mine + oWc1, CI, HC, ot, 0, lane, gWc1[ot]);
+        store_share(mine + oWd1, NF, HD, ot, 0, lane, gWd1[ot]);
+    }
+    store_share(mine + oWd2, HD, NG, 0, 0, lane, gWd2[0]);
+    store_share(mine + oWd2, HD, NG, 0, 1, lane, gWd2[1]);
+}
+
+__global__ void __launch_bounds__(256)
+fold_shares_kernel(const float *__restrict__ shares, uint32_t n_shares, float inv_scale, float *__restrict__ dW)
+{
+    const uint32_t e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= (uint32_t)kTotal) return;
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    uint32_t b = 0;
+    for (; b + 4 <= n_shares; b += 4) {
+        s0 += shares[(size_t)b * kTotal + e]; s1 += shares[(size_t)(b + 1) * kTotal + e];
+        s2 += shares[(size_t)(b + 2) * kTotal + e]; s3 += shares[(size_t)(b + 3) * kTotal + e];
+    }
+    for (; b < n_shares; ++b) s0 += shares[(size_t)b * kTotal + e];
+    dW[e] += ((s0 + s1) + (s2 + s3)) * inv_scale;
+}
+
+constexpr uint32_t kGridMax = 256;     // persistent workgroups: one per compute unit of MI355X
+
+}  // namespace dg_mlp_mfma
+
+namespace dg {
+
+size_t mlp_mfma_workspace_bytes()
+{
+    return (size_t)dg_mlp_mfma::kGridMax * dg_mlp_mfma::kWavesPerBlock * dg_mlp_mfma::kTotal * sizeof(float);
+}
+
+void mlp_mfma_fwd(const void *weights, const void *feat, const void *dir_enc, uint32_t S, uint64_t N, uint32_t act_c,
+                  float *sigma, float *rgb, hipStream_t st)
+{
+    using namespace dg_mlp_mfma;
+    const uint64_t tiles = (N + 31) / 32, blocks_needed = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    const uint32_t grid = (uint32_t)(blocks_needed < 8 * kGridMax ? blocks_needed : 8 * kGridMax);
+    fwd_kernel<<<grid, kBlock, 0, st>>>((const __half *)weights, (const __half *)feat, (const __half *)dir_enc, S, N, act_c,
+                                        sigma, rgb);
+}
+
+void mlp_mfma_bwd(const void *weights, const void *feat, const void *dir_enc, uint32_t S, uint64_t N, uint32_t act_c,
+                  const float *dsigma, const float *drgb, float loss_scale, float *dfeat, float *dW, void *ws,
+                  hipStream_t st)
+{
+    using namespace dg_mlp_mfma;
+    const uint64_t tiles = (N + 31) / 32, blocks_needed = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    const uint32_t grid = (uint32_t)(blocks_needed < kGridMax ? blocks_needed : kGridMax);
+    bwd_kernel<<<grid, kBlock, 0, st>>>((const __half *)weights, (const __half *)feat, (const __half *)dir_enc, S, N, act_c,
+                                        dsigma, drgb, loss_scale, dfeat, (float *)ws);
+    fold_shares_kernel<<<(kTotal + 255) / 256, 256, 0, st>>>((const float *)ws, grid * kWavesPerBlock, 1.0f / loss_scale, dW);
+}
+
+}  // namespace dg
