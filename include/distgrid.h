@@ -122,10 +122,16 @@ int dg_dir_encode(const float *d, const uint32_t *index, uint64_t n, uint32_t de
  * ---------------------------------------------------------------------------------- */
 int dg_hashgrid_encode_fwd(const dg_grid_desc *desc, const float *table, const float *u,
                            uint64_t N, void *feat, uint32_t feat_dtype, void *stream);
-/* Transpose of the above: dtable[entry_c, f] += w_c * dfeat[n, l*F+f] (fp32 atomics, so
- * the summation order is not fixed).  dfeat [N, L*F] fp32 device; dtable "+=". */
+/* Transpose of the above: dtable[entry_c, f] += w_c * dfeat[n, l*F+f]; the summation order is not
+ * fixed.  dfeat [N, L*F] fp32 device; dtable "+=".
+ * With ws == NULL every contribution is a global fp32 atomic (after merging lanes that share a cell).
+ * With a workspace of dg_hashgrid_encode_bwd_workspace_bytes(desc, N) bytes the contributions are
+ * binned by table region and summed in on-chip memory first (much faster for large N); a smaller
+ * workspace is accepted and makes the call run in batches, DG_ERR_WORKSPACE if it cannot hold 1024
+ * samples. */
+size_t dg_hashgrid_encode_bwd_workspace_bytes(const dg_grid_desc *desc, uint64_t N);
 int dg_hashgrid_encode_bwd(const dg_grid_desc *desc, const float *u, const float *dfeat,
-                           uint64_t N, float *dtable, void *stream);
+                           uint64_t N, float *dtable, void *ws, size_t ws_bytes, void *stream);
 /* Absolute table entry of every corner: idx [N, L, 8] uint32, corner c = cx + 2cy + 4cz. */
 int dg_hashgrid_corner_indices(const dg_grid_desc *desc, const float *u, uint64_t N,
                                uint32_t *idx, void *stream);

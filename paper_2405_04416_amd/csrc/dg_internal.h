@@ -33,6 +33,11 @@ inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_
 
 constexpr int kWave = 64;
 
+// binned backward of the hash-grid encode (encode_bwd_binned.hip)
+size_t encode_bwd_binned_workspace_bytes(const dg_grid_desc *d, uint64_t N);
+int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat, uint64_t N, float *dtable, void *ws,
+                      size_t ws_bytes, hipStream_t st);
+
 // matrix-core path of the 32-64-16 / 32-64-64-3 field MLPs (mlp_mfma.hip)
 size_t mlp_mfma_workspace_bytes();
 void mlp_mfma_fwd(const void *weights, const void *feat, const void *dir_enc, uint32_t S, uint64_t N, uint32_t act_c,

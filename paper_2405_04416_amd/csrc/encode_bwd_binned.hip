@@ -1,0 +1,410 @@
+// Hash-grid encode backward without global atomics in the inner loop (Sec. 3.2: the transpose of the
+// encode).
+//
+// Global fp32 atomics on MI355X retire at a fixed rate per distinct cache line an instruction touches
+// (about 21 G lines/s measured, whatever the scope or table size), far below what the 8 x N x L
+// scattered adds of this pass need.  LDS atomics do not have that limit.  So the table gradient is
+// built by binning:
+//   * levels whose tables fit LDS together (the coarse prefix) are accumulated directly: persistent
+//     workgroups sweep the samples, merge runs of lanes that share a cell, add into an LDS copy of
+//     those tables and flush it once;
+//   * every other level is cut into bins of 8192 entries (64 KB of float2).  A counting sweep and a
+//     filling sweep over the samples (same persistent tiling, so each workgroup owns a private, pre-
+//     computed slice of every bin's queue: no global atomics, no overflow) write one record
+//     (entry within bin, w*g.x, w*g.y) per corner, staged through LDS so that each bin receives
+//     contiguous runs.  Then one workgroup per (bin, split) streams its queue, accumulates in LDS and
+//     adds the finished bin into dtable with coalesced atomics.
+#include "encode_common.h"
+
+namespace dg_encode_binned {
+
+using namespace dg_encode;
+
+constexpr int kChunkLog2 = 13;
+constexpr uint32_t kChunk = 1u << kChunkLog2;      // entries per bin
+constexpr int kMaxBins = 2048;                     // per level: 2^24 entries / 8192
+constexpr int kTile = 1024;                        // samples per tile == threads per binning workgroup
+constexpr int kRecords = kTile * 8;
+constexpr int kBinGrid = 256;                      // persistent binning workgroups (one per compute unit)
+constexpr int kAccBlock = 512;
+constexpr uint32_t kAccRecords = 1u << 18;          // records one accumulate workgroup sums
+constexpr int kCoarseBlock = 256;
+constexpr int kCoarseGrid = 1024;
+
+struct Plan {
+    uint32_t first_level;                  // levels below are accumulated directly in LDS
+    uint32_t n_keys;                       // (level, bin) pairs of the binned levels
+    uint32_t key_base[DG_MAX_LEVELS + 1];  // first key of each level
+    uint32_t n_bins[DG_MAX_LEVELS];
+};
+
+__global__ void __launch_bounds__(256) zero_u32_kernel(uint32_t *p, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// ------------------------------------------------------------------ coarse prefix: accumulate in LDS
+__global__ void __launch_bounds__(kCoarseBlock)
+coarse_kernel(dg_grid_desc g, uint32_t first_level, const float *__restrict__ u, const float2 *__restrict__ dfeat,
+              uint64_t N, float *__restrict__ dtable)
+{
+    extern __shared__ float tab[];          // 2 floats per entry of levels [0, first_level)
+    const uint32_t n_floats = 2u * g.offset[first_level];
+    for (uint32_t i = threadIdx.x; i < n_floats; i += kCoarseBlock) tab[i] = 0.0f;
+    __syncthreads();
+    const int lane = threadIdx.x % dg::kWave;
+    const uint32_t mask = (1u << g.log2_T) - 1u;
+    const uint64_t n_tiles = (N + kCoarseBlock - 1) / kCoarseBlock;
+    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint64_t n = tile * kCoarseBlock + threadIdx.x;
+        const bool live = n < N;
+        const uint64_t nn = live ? n : N - 1;
+        const float uu[3] = {u[3 * nn], u[3 * nn + 1], u[3 * nn + 2]};
+        for (uint32_t l = 0; l < first_level; ++l) {
+            const LevelGeom lv = level_of(g, l);
+            uint32_t cell[3], e[8];
+            float frac[3], w[8];
+            locate(lv, uu, cell, frac);
+            corner_entries(lv, mask, cell, e);
+            corner_weights(frac, w);
+            float2 gfe = dfeat[nn * g.n_levels + l];
+            if (!live) gfe = make_float2(0.0f, 0.0f);
+            bool head = lane == 0;
+#pragma unroll
+            for (int a = 0; a < 3; ++a) head |= __shfl_up(cell[a], 1, dg::kWave) != cell[a];
+            const unsigned long long heads = __ballot(head);
+            const int start = 63 - __clzll(heads & (~0ull >> (63 - lane)));
+            float vx[8], vy[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) { vx[c] = w[c] * gfe.x; vy[c] = w[c] * gfe.y; }
+            if (__popcll(heads) < dg::kWave) {       // some lanes share a cell: merge each run into its last lane
+#pragma unroll
+                for (int off = 1; off < dg::kWave; off <<= 1) {
+                    const bool take = lane - off >= start;
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) {
+                        const float tx = __shfl_up(vx[c], off, dg::kWave), ty = __shfl_up(vy[c], off, dg::kWave);
+                        if (take) { vx[c] += tx; vy[c] += ty; }
+                    }
+                }
+            }
+            const bool tail = lane == dg::kWave - 1 || ((heads >> ((lane + 1) & 63)) & 1ull);
+            if (tail) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    const uint32_t slot = 2u * (lv.offset + e[c]);
+                    if (vx[c] != 0.0f) __hip_atomic_fetch_add(&tab[slot], vx[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    if (vy[c] != 0.0f) __hip_atomic_fetch_add(&tab[slot + 1], vy[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < n_floats; i += kCoarseBlock) {
+        const float v = tab[i];
+        if (v != 0.0f) unsafeAtomicAdd(dtable + i, v);
+    }
+}
+
+// ------------------------------------------------------------------ binning sweeps
+// exclusive scan of cnt[0, n) into start[0, n) by the whole workgroup (n <= 2 * kTile)
+__device__ __forceinline__ void block_exclusive_scan(const uint32_t *cnt, uint32_t *start, uint32_t n, uint32_t *wave_tot)
+{
+    const uint32_t t = threadIdx.x, lane = t % dg::kWave, wave = t / dg::kWave;
+    const uint32_t a = 2 * t < n ? cnt[2 * t] : 0u, b = 2 * t + 1 < n ? cnt[2 * t + 1] : 0u;
+    uint32_t incl = a + b;
+#pragma unroll
+    for (int off = 1; off < dg::kWave; off <<= 1) {
+        const uint32_t up = __shfl_up(incl, off, dg::kWave);
+        if ((int)lane >= off) incl += up;
+    }
+    if (lane == dg::kWave - 1) wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t base = 0;
+    for (uint32_t w = 0; w < wave; ++w) base += wave_tot[w];
+    const uint32_t excl = base + incl - (a + b);
+    if (2 * t < n) start[2 * t] = excl;
+    if (2 * t + 1 < n) start[2 * t + 1] = excl + a;
+    __syncthreads();
+}
+
+template <bool FILL>
+__global__ void __launch_bounds__(kTile)
+bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t n0,
+           uint64_t nb, uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
+           uint16_t *__restrict__ q_idx, float *__restrict__ q_vx, float *__restrict__ q_vy)
+{
+    extern __shared__ uint32_t smem[];
+    uint32_t *cnt = smem;                               // [kMaxBins]
+    uint32_t *start = cnt + kMaxBins;                   // [kMaxBins]
+    uint32_t *gbase = start + kMaxBins;                 // [kMaxBins]
+    uint32_t *wave_tot = gbase + kMaxBins;              // [16]
+    uint32_t *stage_e = wave_tot + 16;                  // [kRecords]   (FILL only)
+    float *stage_x = reinterpret_cast<float *>(stage_e + kRecords);
+    float *stage_y = stage_x + kRecords;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t mask = (1u << g.log2_T) - 1u;
+    uint32_t *row = rows + (size_t)blockIdx.x * plan.n_keys;
+    const uint64_t n_tiles = (nb + kTile - 1) / kTile;
+    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint64_t rel = tile * kTile + tid;
+        const bool live = rel < nb;
+        const uint64_t n = n0 + (live ? rel : nb - 1);
+        const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
+        for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
+            const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
+            for (uint32_t i = tid; i < n_bins; i += kTile) cnt[i] = 0u;
+            __syncthreads();
+            const LevelGeom lv = level_of(g, l);
+            uint32_t cell[3], e[8], rank[8];
+            float frac[3], w[8];
+            locate(lv, uu, cell, frac);
+            corner_entries(lv, mask, cell, e);
+            if (live) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) rank[c] = atomicAdd(&cnt[e[c] >> kChunkLog2], 1u);
+            }
+            __syncthreads();
+            if (!FILL) {
+                for (uint32_t i = tid; i < n_bins; i += kTile) row[key0 + i] += cnt[i];
+                __syncthreads();
+                continue;
+            }
+            block_exclusive_scan(cnt, start, n_bins, wave_tot);
+            for (uint32_t i = tid; i < n_bins; i += kTile) {
+                const uint32_t mine = row[key0 + i];
+                gbase[i] = binbase[key0 + i] + mine;
+                row[key0 + i] = mine + cnt[i];
+            }
+            if (live) {
+                corner_weights(frac, w);
+                const float2 gfe = dfeat[n * g.n_levels + l];
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    const uint32_t slot = start[e[c] >> kChunkLog2] + rank[c];
+                    stage_e[slot] = e[c];
+                    stage_x[slot] = w[c] * gfe.x;
+                    stage_y[slot] = w[c] * gfe.y;
+                }
+            }
+            __syncthreads();
+            const uint32_t total = start[n_bins - 1] + cnt[n_bins - 1];
+            for (uint32_t s = tid; s < total; s += kTile) {
+                const uint32_t ee = stage_e[s], bin = ee >> kChunkLog2;
+                const size_t dst = (size_t)gbase[bin] + (s - start[bin]);
+                q_idx[dst] = (uint16_t)(ee & (kChunk - 1u));
+                q_vx[dst] = stage_x[s];
+                q_vy[dst] = stage_y[s];
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// rows[b][k] (per-workgroup counts) -> exclusive prefix over workgroups; totals[k]
+__global__ void __launch_bounds__(256)
+scan_rows_kernel(uint32_t *__restrict__ rows, uint32_t n_rows, uint32_t n_keys, uint32_t *__restrict__ totals)
+{
+    const uint32_t k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= n_keys) return;
+    uint32_t run = 0;
+    for (uint32_t b = 0; b < n_rows; ++b) {
+        const uint32_t t = rows[(size_t)b * n_keys + k];
+        rows[(size_t)b * n_keys + k] = run;
+        run += t;
+    }
+    totals[k] = run;
+}
+
+// binbase = exclusive scan of totals; blkbase = exclusive scan of the number of accumulate workgroups each
+// bin gets (one per kAccRecords records), so that work is balanced whatever the bins hold
+// (one workgroup; n_keys is at most a few tens of thousands)
+__global__ void __launch_bounds__(1024)
+scan_totals_kernel(const uint32_t *__restrict__ totals, uint32_t n_keys, uint32_t *__restrict__ binbase,
+                   uint32_t *__restrict__ blkbase)
+{
+    __shared__ uint32_t part[1024], part_b[1024];
+    const uint32_t per = (n_keys + 1023) / 1024, lo = threadIdx.x * per;
+    uint32_t s = 0, sb = 0;
+    for (uint32_t i = lo; i < lo + per && i < n_keys; ++i) { s += totals[i]; sb += (totals[i] + kAccRecords - 1) / kAccRecords; }
+    part[threadIdx.x] = s;
+    part_b[threadIdx.x] = sb;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0, run_b = 0;
+        for (int i = 0; i < 1024; ++i) {
+            const uint32_t t = part[i], tb = part_b[i];
+            part[i] = run; part_b[i] = run_b;
+            run += t; run_b += tb;
+        }
+        binbase[n_keys] = run;
+        blkbase[n_keys] = run_b;
+    }
+    __syncthreads();
+    uint32_t run = part[threadIdx.x], run_b = part_b[threadIdx.x];
+    for (uint32_t i = lo; i < lo + per && i < n_keys; ++i) {
+        binbase[i] = run; blkbase[i] = run_b;
+        run += totals[i]; run_b += (totals[i] + kAccRecords - 1) / kAccRecords;
+    }
+}
+
+// ------------------------------------------------------------------ accumulate one (bin, split)
+__global__ void __launch_bounds__(kAccBlock)
+accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbase, const uint32_t *__restrict__ blkbase,
+                  const uint16_t *__restrict__ q_idx, const float *__restrict__ q_vx, const float *__restrict__ q_vy,
+                  float *__restrict__ dtable)
+{
+    __shared__ float tab[2 * kChunk];
+    if (blockIdx.x >= blkbase[plan.n_keys]) return;
+    // the bin this workgroup serves: last key whose first workgroup is <= blockIdx.x
+    uint32_t lo_k = 0, hi_k = plan.n_keys;
+    while (hi_k - lo_k > 1) {
+        const uint32_t mid = (lo_k + hi_k) / 2;
+        if (blkbase[mid] <= blockIdx.x) lo_k = mid; else hi_k = mid;
+    }
+    const uint32_t key = lo_k, part = blockIdx.x - blkbase[key];
+    const size_t begin = (size_t)binbase[key] + (size_t)part * kAccRecords;
+    const size_t end = min(begin + (size_t)kAccRecords, (size_t)binbase[key + 1]);
+    for (uint32_t i = threadIdx.x; i < 2 * kChunk; i += kAccBlock) tab[i] = 0.0f;
+    __syncthreads();
+    for (size_t i = begin + threadIdx.x; i < end; i += kAccBlock) {
+        const uint32_t e = q_idx[i];
+        __hip_atomic_fetch_add(&tab[2 * e], q_vx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_add(&tab[2 * e + 1], q_vy[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    __syncthreads();
+    uint32_t l = plan.first_level;
+    while (l + 1 < g.n_levels && key >= plan.key_base[l + 1]) ++l;
+    const uint32_t bin = key - plan.key_base[l];
+    const uint32_t level_len = g.offset[l + 1] - g.offset[l];
+    const uint32_t first = bin * kChunk, n_valid = min(kChunk, level_len - first);
+    float *dst = dtable + 2 * ((size_t)g.offset[l] + first);
+    for (uint32_t i = threadIdx.x; i < 2 * n_valid; i += kAccBlock) {
+        const float v = tab[i];
+        if (v != 0.0f) unsafeAtomicAdd(dst + i, v);
+    }
+}
+
+Plan make_plan(const dg_grid_desc *d)
+{
+    Plan p{};
+    uint32_t l = 0;
+    while (l < d->n_levels && d->offset[l + 1] <= kChunk) ++l;     // coarse prefix: tables that fit LDS together
+    p.first_level = l;
+    uint32_t key = 0;
+    for (; l < d->n_levels; ++l) {
+        p.key_base[l] = key;
+        p.n_bins[l] = (d->offset[l + 1] - d->offset[l] + kChunk - 1) / kChunk;
+        key += p.n_bins[l];
+    }
+    p.key_base[d->n_levels] = key;
+    p.n_keys = key;
+    return p;
+}
+
+inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+struct Layout {
+    size_t rows, totals, binbase, blkbase, q_idx, q_vx, q_vy, total;
+    uint64_t batch;      // samples per batch
+};
+
+// workspace layout for a batch of `batch` samples
+Layout make_layout(const dg_grid_desc *d, const Plan &p, uint64_t batch)
+{
+    Layout L{};
+    const uint64_t records = batch * 8ull * (d->n_levels - p.first_level);
+    size_t off = 0;
+    L.rows = off; off = align256(off + (size_t)kBinGrid * p.n_keys * 4);
+    L.totals = off; off = align256(off + (size_t)p.n_keys * 4);
+    L.binbase = off; off = align256(off + (size_t)(p.n_keys + 1) * 4);
+    L.blkbase = off; off = align256(off + (size_t)(p.n_keys + 1) * 4);
+    L.q_idx = off; off = align256(off + records * 2);
+    L.q_vx = off; off = align256(off + records * 4);
+    L.q_vy = off; off = align256(off + records * 4);
+    L.total = off;
+    L.batch = batch;
+    return L;
+}
+
+uint64_t max_batch(const dg_grid_desc *d, const Plan &p)
+{
+    const uint64_t per_sample = 8ull * (d->n_levels - p.first_level);
+    if (per_sample == 0) return ~0ull;
+    return (0xffffffffull / per_sample) / kTile * kTile;           // record offsets stay below 2^32
+}
+
+}  // namespace dg_encode_binned
+
+namespace dg {
+
+size_t encode_bwd_binned_workspace_bytes(const dg_grid_desc *d, uint64_t N)
+{
+    using namespace dg_encode_binned;
+    const Plan p = make_plan(d);
+    if (p.n_keys == 0) return 256;
+    uint64_t batch = (N + kTile - 1) / kTile * kTile;
+    const uint64_t cap = max_batch(d, p);
+    if (batch > cap) batch = cap;
+    if (batch == 0) batch = kTile;
+    return make_layout(d, p, batch).total;
+}
+
+int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat, uint64_t N, float *dtable, void *ws,
+                      size_t ws_bytes, hipStream_t st)
+{
+    using namespace dg_encode_binned;
+    const Plan p = make_plan(d);
+    static bool lds_opt_in = false;
+    if (!lds_opt_in) {
+        const int fill_lds = (3 * kMaxBins + 16 + 3 * kRecords) * 4;
+        hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(&bin_kernel<true>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds);
+        if (e1 != hipSuccess) return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot reserve %d bytes of LDS: %s", fill_lds,
+                                          hipGetErrorString(e1));
+        lds_opt_in = true;
+    }
+    if (p.first_level > 0) {
+        const uint64_t tiles = (N + kCoarseBlock - 1) / kCoarseBlock;
+        const uint32_t grid = (uint32_t)(tiles < kCoarseGrid ? tiles : kCoarseGrid);
+        coarse_kernel<<<grid, kCoarseBlock, 2 * d->offset[p.first_level] * sizeof(float), st>>>(
+            *d, p.first_level, u, (const float2 *)dfeat, N, dtable);
+    }
+    if (p.n_keys == 0) return launch_status("dg_hashgrid_encode_bwd");
+
+    // largest batch the workspace holds
+    uint64_t batch = (N + kTile - 1) / kTile * kTile;
+    const uint64_t cap = max_batch(d, p);
+    if (batch > cap) batch = cap;
+    while (batch > kTile && make_layout(d, p, batch).total > ws_bytes) batch = (batch / 2 + kTile - 1) / kTile * kTile;
+    const Layout L = make_layout(d, p, batch);
+    if (L.total > ws_bytes)
+        return fail(DG_ERR_WORKSPACE, "dg_hashgrid_encode_bwd: workspace %zu bytes cannot hold one tile (%zu needed)", ws_bytes, L.total);
+    char *base = static_cast<char *>(ws);
+    uint32_t *rows = reinterpret_cast<uint32_t *>(base + L.rows);
+    uint32_t *totals = reinterpret_cast<uint32_t *>(base + L.totals);
+    uint32_t *binbase = reinterpret_cast<uint32_t *>(base + L.binbase);
+    uint32_t *blkbase = reinterpret_cast<uint32_t *>(base + L.blkbase);
+    uint16_t *q_idx = reinterpret_cast<uint16_t *>(base + L.q_idx);
+    float *q_vx = reinterpret_cast<float *>(base + L.q_vx);
+    float *q_vy = reinterpret_cast<float *>(base + L.q_vy);
+    const size_t n_rows_words = (size_t)kBinGrid * p.n_keys;
+    const int count_lds = (3 * kMaxBins + 16) * 4, fill_lds = (3 * kMaxBins + 16 + 3 * kRecords) * 4;
+
+    for (uint64_t n0 = 0; n0 < N; n0 += batch) {
+        const uint64_t nb = N - n0 < batch ? N - n0 : batch;
+        zero_u32_kernel<<<(uint32_t)((n_rows_words + 255) / 256), 256, 0, st>>>(rows, n_rows_words);
+        bin_kernel<false><<<kBinGrid, kTile, count_lds, st>>>(*d, p, u, (const float2 *)dfeat, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
+        scan_rows_kernel<<<(p.n_keys + 255) / 256, 256, 0, st>>>(rows, kBinGrid, p.n_keys, totals);
+        scan_totals_kernel<<<1, 1024, 0, st>>>(totals, p.n_keys, binbase, blkbase);
+        bin_kernel<true><<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
+        const uint64_t records = nb * 8ull * (d->n_levels - p.first_level);
+        const uint32_t acc_grid = (uint32_t)(records / kAccRecords) + p.n_keys;       // upper bound of the workgroups needed
+        accumulate_kernel<<<acc_grid, kAccBlock, 0, st>>>(*d, p, binbase, blkbase, q_idx, q_vx, q_vy, dtable);
+    }
+    return launch_status("dg_hashgrid_encode_bwd");
+}
+
+}  // namespace dg

@@ -25,7 +25,7 @@ class SubModel:
 
 class TrainStep:
     def __init__(self, parts, models, resident, R, S, k_max, sh_degree, loss_scale=65536.0, lambda1=0.0, seed=0,
-                 device="cuda:0", max_segments=None):
+                 device="cuda:0", max_segments=None, binned_backward=True, encode_ws_cap=48 << 30):
         """parts: [P,6] float tensor (device); models: {partition index: SubModel}; resident: partition indices served."""
         self.dev = torch.device(device)
         self.parts, self.models, self.resident = parts, models, list(resident)
@@ -54,6 +54,9 @@ class TrainStep:
         self.C, self.T, self.gC, self.gT = z(R, 3), z(R), z(R, 3), z(R)
         self.loss = z(1)
         self.ws_mlp = z(max(B.dg_mlp_bwd_workspace_bytes(any_model.mlp) // 4, 1))
+        # workspace of the binned table-gradient pass, capped (the call batches itself when it is smaller than ideal)
+        want = max(B.dg_hashgrid_encode_bwd_workspace_bytes(mm.grid, n) for mm in models.values())
+        self.ws_enc = torch.zeros(min(want, encode_ws_cap) // 4 + 64, dtype=f32, device=self.dev) if binned_backward else None
         self.offsets = None
         self.timings = None     # set to {} to collect (start, end) event pairs per entry point
 
@@ -143,7 +146,7 @@ class TrainStep:
                 B.dg_mlp_bwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[b:e], S, N, self.dsigma[sl], self.drgb[sl],
                              self.loss_scale, self.dfeat[sl], m.dW, self.ws_mlp)
             with self._timed("dg_hashgrid_encode_bwd"):
-                B.dg_hashgrid_encode_bwd(m.grid, self.u[sl], self.dfeat[sl], N, m.dtable)
+                B.dg_hashgrid_encode_bwd(m.grid, self.u[sl], self.dfeat[sl], N, m.dtable, self.ws_enc)
 
     def step(self, o, d, Cgt, jitter=None, foreign=None):
         self.forward(o, d, Cgt, jitter, foreign)

@@ -164,17 +164,24 @@ def test_encode_fwd_and_indices(key, N):
     assert np.all(err16 <= 2.0 ** -11 * np.abs(ref) + TOL_F32 * bound + 6e-8)
 
 
-@pytest.mark.parametrize("key,N", [("c1", 32768), ("c2", 10007), ("mixed_small", 3333)])
-def test_encode_bwd(key, N):
-    say("encode bwd %s N=%d" % (key, N))
+@pytest.mark.parametrize("mode", ["atomic", "binned", "binned_batched"])
+@pytest.mark.parametrize("key,N", [("c1", 32768), ("c2", 10007), ("mixed_small", 3333), ("one_level_dense", 700)])
+def test_encode_bwd(key, N, mode):
+    say("encode bwd %s N=%d %s" % (key, N, mode))
     g, r, _ = _both_grids(key)
     L = g.n_levels
     u = di.make_unit_coords(N, seed=5)
     dfeat = (np.random.default_rng(6).standard_normal((N, 2 * L)) * 1e-3).astype(np.float32)
     dfeat[::7] = 0.0
     dtable = torch.zeros(r.n_entries, 2, device=DEV)
-    B.dg_hashgrid_encode_bwd(g, dev(u), dev(dfeat), N, dtable)
-    B.dg_hashgrid_encode_bwd(g, dev(u), dev(dfeat), N, dtable)       # "+=": twice gives twice
+    ws = None
+    if mode != "atomic":
+        need = B.dg_hashgrid_encode_bwd_workspace_bytes(g, N)
+        if mode == "binned_batched":                                   # room for a few tiles only: several batches
+            need = B.dg_hashgrid_encode_bwd_workspace_bytes(g, 2048)
+        ws = torch.zeros(need // 4 + 64, device=DEV)
+    B.dg_hashgrid_encode_bwd(g, dev(u), dev(dfeat), N, dtable, ws)
+    B.dg_hashgrid_encode_bwd(g, dev(u), dev(dfeat), N, dtable, ws)   # "+=": twice gives twice
     ref = 2.0 * oracle.encode_bwd(r, u, dfeat.astype(np.float64))
     got = host(dtable).astype(np.float64)
     for l in range(L):                                                # judged level by level
