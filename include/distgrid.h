@@ -115,15 +115,19 @@ int dg_dir_encode(const float *d, const uint32_t *index, uint64_t n, uint32_t de
                   void *out, void *stream);
 
 /* ------------------------------------------------------------------------------------
- * Hash-grid encode (Sec. 3.2): feat[n, l*F+f] = sum over the 8 cell corners of
- * w_c * table[entry_c, f], trilinear weights w_c, entry by dense map or hash.
- * table [n_entries, F] fp32 device; u [N,3] fp32 device; feat [N, L*F] device, fp32 or
- * fp16 (feat_dtype DG_F32 / DG_F16; fp16 is rounded once from the fp32 sum).
+ * Hash-grid encode (Sec. 3.2): feature f of level l of sample n = sum over the 8 cell
+ * corners of w_c * table[entry_c, f], trilinear weights w_c, entry by dense map or hash.
+ * table [n_entries, F] fp32 device; u [N,3] fp32 device.
+ * Feature layout, here and in every call below that takes features or their gradient:
+ * LEVEL-MAJOR planes, feat [L, N, F] (the concatenated embedding of sample n is the
+ * column feat[:, n, :]); fp32 or fp16 (feat_dtype DG_F32 / DG_F16; fp16 is rounded once
+ * from the fp32 sum).  Kernels walk one level at a time, so planes keep their accesses
+ * contiguous.
  * ---------------------------------------------------------------------------------- */
 int dg_hashgrid_encode_fwd(const dg_grid_desc *desc, const float *table, const float *u,
                            uint64_t N, void *feat, uint32_t feat_dtype, void *stream);
-/* Transpose of the above: dtable[entry_c, f] += w_c * dfeat[n, l*F+f]; the summation order is not
- * fixed.  dfeat [N, L*F] fp32 device; dtable "+=".
+/* Transpose of the above: dtable[entry_c, f] += w_c * dfeat[l, n, f]; the summation order is not
+ * fixed.  dfeat [L, N, F] fp32 device (level-major planes); dtable "+=".
  * With ws == NULL every contribution is a global fp32 atomic (after merging lanes that share a cell).
  * With a workspace of dg_hashgrid_encode_bwd_workspace_bytes(desc, N) bytes the contributions are
  * binned by table region and summed in on-chip memory first (much faster for large N); a smaller
@@ -146,7 +150,8 @@ int dg_hashgrid_corner_indices(const dg_grid_desc *desc, const float *u, uint64_
  * even), products accumulate in fp32.  weights: fp16 device, the matrices
  * Wd1[n_hidden_d,n_feat], Wd2[n_geo,n_hidden_d], Wc1[n_hidden_c,n_geo+n_dir],
  * (Wc2[n_hidden_c,n_hidden_c]), Wc3[3,n_hidden_c] one after another, each [out,in].
- * feat [N,n_feat] fp16; dir_enc [ceil(N/S), n_dir] fp16, row n/S serves sample n.
+ * feat [n_feat/2, N, 2] fp16 (the encode's level-major planes; input i of sample n is
+ * feat[i/2, n, i%2]); dir_enc [ceil(N/S), n_dir] fp16, row n/S serves sample n.
  * Outputs: sigma [N] fp32, rgb [N,3] fp32.
  * Supported shapes: (n_feat,n_hidden_d,n_geo,n_dir,n_hidden_c,n_layers_c) =
  * (32,64,16,16,64,2) and (8,32,16,4,32,1); others return DG_ERR_UNSUPPORTED.
@@ -162,7 +167,7 @@ int dg_mlp_fwd(const dg_mlp_desc *desc, const void *weights, const void *feat,
 /* Backward of the above; activations are recomputed, nothing is saved by dg_mlp_fwd.
  * dsigma [N], drgb [N,3] fp32.  Every back-propagated delta is multiplied by loss_scale
  * (a power of two is advisable) before it is rounded to fp16, and dfeat / dW are divided
- * by it again in fp32.  Outputs: dfeat [N,n_feat] fp32 (overwritten); dW fp32, "+=",
+ * by it again in fp32.  Outputs: dfeat [n_feat/2, N, 2] fp32 planes (overwritten); dW fp32, "+=",
  * same packing as weights.  ws: dg_mlp_bwd_workspace_bytes(desc) bytes. */
 size_t dg_mlp_bwd_workspace_bytes(const dg_mlp_desc *desc);
 int dg_mlp_bwd(const dg_mlp_desc *desc, const void *weights, const void *feat,

@@ -1,9 +1,7 @@
 // Multi-resolution hash-grid encode: forward gather and backward scatter-add (Sec. 3.2, Sec. 4.1).
 //
-// Work is split by (tile of samples) x (group of levels).  Workgroup b serves level group
-// b % n_groups; on MI355X consecutive workgroups go round-robin to the eight XCDs, each with
-// its own L2, so with n_groups == 8 one XCD keeps meeting the same few levels and their table
-// slices stay resident in that L2.  This is a placement hint only: results do not depend on it.
+// Features and their gradients are level-major planes, [L][N][2]: every kernel here walks one level
+// at a time and then reads or writes consecutive samples contiguously.
 #include "encode_common.h"
 
 namespace {
@@ -11,37 +9,37 @@ namespace {
 using namespace dg_encode;
 
 constexpr int kBlock = 256;
+// Forward gather, level-major: workgroups are ordered level after level, so at any moment the chip
+// works on one level (two at a boundary) and that level's table slice -- at most T entries, 4 MB for
+// T = 2^19 -- stays resident in every XCD's L2 while all samples stream past it.  Features are written
+// as one plane per level, feat[l][n][2], so the stores of a wavefront are contiguous.
 template <bool kHalf>
 __global__ void __launch_bounds__(kBlock)
 encode_fwd_kernel(dg_grid_desc g, const float2 *__restrict__ table, const float *__restrict__ u, uint64_t N,
-                  void *__restrict__ feat, uint32_t n_groups)
+                  void *__restrict__ feat, uint32_t n_tiles)
 {
-    const uint32_t group = blockIdx.x % n_groups;
-    const uint64_t n = (uint64_t)(blockIdx.x / n_groups) * kBlock + threadIdx.x;
+    const uint32_t l = blockIdx.x / n_tiles;
+    const uint64_t n = (uint64_t)(blockIdx.x % n_tiles) * kBlock + threadIdx.x;
     if (n >= N) return;
     const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
     const uint32_t mask = (1u << g.log2_T) - 1u;
-    const uint32_t width = g.n_levels * 2u;
-    for (uint32_t l = group; l < g.n_levels; l += n_groups) {
-        const LevelGeom lv = level_of(g, l);
-        uint32_t cell[3], e[8];
-        float frac[3], w[8];
-        locate(lv, uu, cell, frac);
-        corner_entries(lv, mask, cell, e);
-        corner_weights(frac, w);
-        float2 v[8];
+    const LevelGeom lv = level_of(g, l);
+    uint32_t cell[3], e[8];
+    float frac[3], w[8];
+    locate(lv, uu, cell, frac);
+    corner_entries(lv, mask, cell, e);
+    corner_weights(frac, w);
+    float2 v[8];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) v[c] = table[(size_t)lv.offset + e[c]];
-        float f0 = 0.0f, f1 = 0.0f;
+    for (int c = 0; c < 8; ++c) v[c] = table[(size_t)lv.offset + e[c]];
+    float f0 = 0.0f, f1 = 0.0f;
 #pragma unroll
-        for (int c = 0; c < 8; ++c) { f0 = fmaf(w[c], v[c].x, f0); f1 = fmaf(w[c], v[c].y, f1); }
-        if (kHalf) {
-            reinterpret_cast<__half2 *>(feat)[n * g.n_levels + l] = __floats2half2_rn(f0, f1);
-        } else {
-            reinterpret_cast<float2 *>(feat)[n * g.n_levels + l] = make_float2(f0, f1);
-        }
+    for (int c = 0; c < 8; ++c) { f0 = fmaf(w[c], v[c].x, f0); f1 = fmaf(w[c], v[c].y, f1); }
+    if (kHalf) {
+        reinterpret_cast<__half2 *>(feat)[(size_t)l * N + n] = __floats2half2_rn(f0, f1);
+    } else {
+        reinterpret_cast<float2 *>(feat)[(size_t)l * N + n] = make_float2(f0, f1);
     }
-    (void)width;
 }
 
 // Backward scatter.  A wavefront holds 64 consecutive samples, i.e. a stretch of one ray, so at the
@@ -71,7 +69,7 @@ encode_bwd_kernel(dg_grid_desc g, const float *__restrict__ u, const float2 *__r
         locate(lv, uu, cell, frac);
         corner_entries(lv, mask, cell, e);
         corner_weights(frac, w);
-        float2 gfe = dfeat[nn * g.n_levels + l];
+        float2 gfe = dfeat[(size_t)l * N + nn];
         if (!live) gfe = make_float2(0.0f, 0.0f);
         float *level_base = dtable + 2 * (size_t)lv.offset;
 
@@ -176,14 +174,14 @@ extern "C" int dg_hashgrid_encode_fwd(const dg_grid_desc *desc, const float *tab
     DG_REQUIRE(table && u && feat, DG_ERR_ARG, "dg_hashgrid_encode_fwd: null pointer");
     DG_REQUIRE(dg::aligned(table, 8) && dg::aligned(feat, feat_dtype == DG_F16 ? 4 : 8), DG_ERR_ARG,
                "dg_hashgrid_encode_fwd: table/feat misaligned");
-    const uint32_t n_groups = desc->n_levels < 8 ? desc->n_levels : 8;
     uint32_t n_blocks;
-    if (int rc = grid_for(N, n_groups, &n_blocks, "dg_hashgrid_encode_fwd")) return rc;
+    if (int rc = grid_for(N, desc->n_levels, &n_blocks, "dg_hashgrid_encode_fwd")) return rc;
+    const uint32_t n_tiles = n_blocks / desc->n_levels;
     hipStream_t st = (hipStream_t)stream;
     if (feat_dtype == DG_F16)
-        encode_fwd_kernel<true><<<n_blocks, kBlock, 0, st>>>(*desc, (const float2 *)table, u, N, feat, n_groups);
+        encode_fwd_kernel<true><<<n_blocks, kBlock, 0, st>>>(*desc, (const float2 *)table, u, N, feat, n_tiles);
     else
-        encode_fwd_kernel<false><<<n_blocks, kBlock, 0, st>>>(*desc, (const float2 *)table, u, N, feat, n_groups);
+        encode_fwd_kernel<false><<<n_blocks, kBlock, 0, st>>>(*desc, (const float2 *)table, u, N, feat, n_tiles);
     return dg::launch_status("dg_hashgrid_encode_fwd");
 }
 

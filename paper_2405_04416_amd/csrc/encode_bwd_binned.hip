@@ -68,7 +68,7 @@ coarse_kernel(dg_grid_desc g, uint32_t first_level, const float *__restrict__ u,
             locate(lv, uu, cell, frac);
             corner_entries(lv, mask, cell, e);
             corner_weights(frac, w);
-            float2 gfe = dfeat[nn * g.n_levels + l];
+            float2 gfe = dfeat[(size_t)l * N + nn];
             if (!live) gfe = make_float2(0.0f, 0.0f);
             bool head = lane == 0;
 #pragma unroll
@@ -131,8 +131,8 @@ __device__ __forceinline__ void block_exclusive_scan(const uint32_t *cnt, uint32
 
 template <bool FILL>
 __global__ void __launch_bounds__(kTile)
-bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t n0,
-           uint64_t nb, uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
+bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
+           uint64_t n0, uint64_t nb, uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
            uint16_t *__restrict__ q_idx, float *__restrict__ q_vx, float *__restrict__ q_vy)
 {
     extern __shared__ uint32_t smem[];
@@ -180,7 +180,7 @@ bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 
             }
             if (live) {
                 corner_weights(frac, w);
-                const float2 gfe = dfeat[n * g.n_levels + l];
+                const float2 gfe = dfeat[(size_t)l * N + n];
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {
                     const uint32_t slot = start[e[c] >> kChunkLog2] + rank[c];
@@ -404,10 +404,10 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     for (uint64_t n0 = 0; n0 < N; n0 += batch) {
         const uint64_t nb = N - n0 < batch ? N - n0 : batch;
         zero_u32_kernel<<<(uint32_t)((n_rows_words + 255) / 256), 256, 0, st>>>(rows, n_rows_words);
-        bin_kernel<false><<<kBinGrid, kTile, count_lds, st>>>(*d, p, u, (const float2 *)dfeat, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
+        bin_kernel<false><<<kBinGrid, kTile, count_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
         scan_rows_kernel<<<(p.n_keys + 255) / 256, 256, 0, st>>>(rows, kBinGrid, p.n_keys, totals);
         scan_totals_kernel<<<1, 1024, 0, st>>>(totals, p.n_keys, binbase, blkbase);
-        bin_kernel<true><<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
+        bin_kernel<true><<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
         const uint64_t records = nb * 8ull * (d->n_levels - p.first_level);
         const uint32_t acc_grid = (uint32_t)(records / kAccRecords) + p.n_keys;       // upper bound of the workgroups needed
         accumulate_kernel<<<acc_grid, kAccBlock, 2 * kChunk * sizeof(double), st>>>(*d, p, binbase, blkbase, q_idx, q_vx, q_vy, dtable);

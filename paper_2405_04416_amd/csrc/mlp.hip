@@ -55,11 +55,12 @@ struct Acts {
 };
 
 template <class N>
-__device__ __forceinline__ void forward_one(const __half *w, const __half *feat_row, const __half *dir_row,
-                                            uint32_t act_c, Acts<N> &a)
+__device__ __forceinline__ void forward_one(const __half *w, const __half *feat, uint64_t n_samples, uint64_t n,
+                                            const __half *dir_row, uint32_t act_c, Acts<N> &a)
 {
     float z[N::kHD > N::kHC ? N::kHD : N::kHC];
-    for (int i = 0; i < N::kNF; ++i) a.x0[i] = __half2float(feat_row[i]);
+    // features are level-major planes [n_feat / 2][n_samples][2]
+    for (int i = 0; i < N::kNF; ++i) a.x0[i] = __half2float(feat[((size_t)(i >> 1) * n_samples + n) * 2 + (i & 1)]);
     matvec<N::kHD, N::kNF>(w + N::oWd1, a.x0, z);
     for (int i = 0; i < N::kHD; ++i) a.h1[i] = r16(fmaxf(z[i], 0.0f));
     matvec<N::kNG, N::kHD>(w + N::oWd2, a.h1, a.geo);
@@ -91,7 +92,7 @@ mlp_fwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ fe
     const uint64_t n = (uint64_t)blockIdx.x * kFwdBlock + threadIdx.x;
     if (n >= n_samples) return;
     Acts<N> a;
-    forward_one<N>(w, feat + n * N::kNF, dir_enc + (n / S) * N::kND, act_c, a);
+    forward_one<N>(w, feat, n_samples, n, dir_enc + (n / S) * N::kND, act_c, a);
     sigma[n] = a.sigma;
     rgb[3 * n] = a.rgb[0]; rgb[3 * n + 1] = a.rgb[1]; rgb[3 * n + 2] = a.rgb[2];
 }
@@ -165,7 +166,7 @@ mlp_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ fe
         const uint64_t nn = live ? n : 0;
         const int n_live = (int)min((uint64_t)kBwdBlock, n_samples - tile * kBwdBlock);
         Acts<N> a;
-        forward_one<N>(w, feat + nn * N::kNF, dir_enc + (nn / S) * N::kND, act_c, a);
+        forward_one<N>(w, feat, n_samples, nn, dir_enc + (nn / S) * N::kND, act_c, a);
 
         float d3[3], g[kMaxIn], dl[kMaxOut];
         for (int c = 0; c < 3; ++c) {
@@ -197,7 +198,7 @@ mlp_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ fe
         wgrad_tile<N::kHD, N::kNF>(s_dl, s_av, n_live, aWd1);
         matvec_t<N::kHD, N::kNF>(w + N::oWd1, dl, g);
         if (live)
-            for (int k = 0; k < N::kNF; ++k) dfeat[n * N::kNF + k] = g[k] * inv_scale;
+            for (int k = 0; k < N::kNF; ++k) dfeat[((size_t)(k >> 1) * n_samples + n) * 2 + (k & 1)] = g[k] * inv_scale;
     }
     float *mine = partial + (size_t)blockIdx.x * N::kTotal;
     flush<N::kHD, N::kNF>(aWd1, mine + N::oWd1);
@@ -246,7 +247,7 @@ extern "C" int dg_mlp_fwd(const dg_mlp_desc *desc, const void *weights, const vo
     DG_REQUIRE(n_blocks <= 0x7fffffffull, DG_ERR_UNSUPPORTED, "dg_mlp_fwd: N too large");
     hipStream_t st = (hipStream_t)stream;
     if (net == 1) {
-        DG_REQUIRE(dg::aligned(feat, 16) && dg::aligned(dir_enc, 16), DG_ERR_ARG, "dg_mlp_fwd: feat / dir_enc must be 16-byte aligned");
+        DG_REQUIRE(dg::aligned(feat, 4) && dg::aligned(dir_enc, 16), DG_ERR_ARG, "dg_mlp_fwd: feat must be 4-byte, dir_enc 16-byte aligned");
         dg::mlp_mfma_fwd(weights, feat, dir_enc, S, N, desc->act_c, sigma, rgb, st);
     } else
         mlp_fwd_kernel<NetTiny><<<(uint32_t)n_blocks, kFwdBlock, 0, st>>>((const __half *)weights, (const __half *)feat,
@@ -279,8 +280,8 @@ extern "C" int dg_mlp_bwd(const dg_mlp_desc *desc, const void *weights, const vo
     const uint32_t n_w = (uint32_t)dg_mlp_weight_count(desc);
     hipStream_t st = (hipStream_t)stream;
     if (net == 1) {
-        DG_REQUIRE(dg::aligned(feat, 16) && dg::aligned(dir_enc, 16) && dg::aligned(dfeat, 16), DG_ERR_ARG,
-                   "dg_mlp_bwd: feat / dir_enc / dfeat must be 16-byte aligned");
+        DG_REQUIRE(dg::aligned(feat, 4) && dg::aligned(dir_enc, 16) && dg::aligned(dfeat, 8), DG_ERR_ARG,
+                   "dg_mlp_bwd: feat must be 4-byte, dfeat 8-byte, dir_enc 16-byte aligned");
         dg::mlp_mfma_bwd(weights, feat, dir_enc, S, N, desc->act_c, dsigma, drgb, loss_scale, dfeat, dW, ws, st);
         return dg::launch_status("dg_mlp_bwd");
     }

@@ -178,14 +178,22 @@ __device__ __forceinline__ void forward_tile(const __half *lds, int lane, uint32
     for (int c = 0; c < 3; ++c) { t.raw[c] = out[c]; t.rgb[c] = fast_sigmoid(clip15(out[c])); }
 }
 
-__device__ __forceinline__ void load_inputs(const __half *feat, const __half *dir_enc, uint32_t S, uint64_t n,
-                                            bool valid, int h, Tile &t)
+// features arrive as level-major planes [16][n_samples] of half2; slot j of k-step ks on lane half h
+// is feature 16 ks + 8 h + j, i.e. component j % 2 of level 8 ks + 4 h + j / 2
+__device__ __forceinline__ void load_inputs(const __half *feat, const __half *dir_enc, uint32_t S, uint64_t n_samples,
+                                            uint64_t n, bool valid, int h, Tile &t)
 {
     const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     if (valid) {
-        const h8 *row = reinterpret_cast<const h8 *>(feat + n * NF);
-        t.x0[0] = row[h];            // features 8h .. 8h+7
-        t.x0[1] = row[2 + h];        // features 16 + 8h ..
+        typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+        const uint32_t *planes = reinterpret_cast<const uint32_t *>(feat);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            u4 bits;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) bits[q] = planes[(size_t)(8 * ks + 4 * h + q) * n_samples + n];
+            t.x0[ks] = __builtin_bit_cast(h8, bits);
+        }
         t.xc[1] = reinterpret_cast<const h8 *>(dir_enc + (n / S) * ND)[h];
     } else {
         t.x0[0] = zero; t.x0[1] = zero; t.xc[1] = zero;
@@ -207,7 +215,7 @@ fwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, 
         const uint64_t n = tile * 32 + (lane & 31);
         const bool valid = n < n_samples;
         Tile t;
-        load_inputs(feat, dir_enc, S, n, valid, h, t);
+        load_inputs(feat, dir_enc, S, n_samples, n, valid, h, t);
         forward_tile(lds, lane, act_c, t);
         if (valid && h == 0) {
             sigma[n] = t.sigma;
@@ -289,7 +297,7 @@ bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, 
         const uint64_t n = tile * 32 + (lane & 31);
         const bool valid = n < n_samples;
         Tile t;
-        load_inputs(feat, dir_enc, S, n, valid, h, t);
+        load_inputs(feat, dir_enc, S, n_samples, n, valid, h, t);
         forward_tile(lds, lane, act_c, t);
 
         // ---- output layer of the colour net
@@ -378,11 +386,13 @@ bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, 
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) gf = mma(image(lds, cD1T + ks, lane), dl[ks], gf);
         if (valid) {
-            float4 *row = reinterpret_cast<float4 *>(dfeat + n * NF);
+            // registers 4q .. 4q+3 hold features 8q + 4h .. + 3: levels 4q + 2h and 4q + 2h + 1 of the planes [16][n_samples][2]
+            float2 *planes = reinterpret_cast<float2 *>(dfeat);
 #pragma unroll
-            for (int q = 0; q < 4; ++q)       // registers 4q .. 4q+3 hold features 8q + 4h .. + 3
-                row[2 * q + h] = make_float4(gf[4 * q] * inv_scale, gf[4 * q + 1] * inv_scale, gf[4 * q + 2] * inv_scale,
-                                             gf[4 * q + 3] * inv_scale);
+            for (int q = 0; q < 4; ++q) {
+                planes[(size_t)(4 * q + 2 * h) * n_samples + n] = make_float2(gf[4 * q] * inv_scale, gf[4 * q + 1] * inv_scale);
+                planes[(size_t)(4 * q + 2 * h + 1) * n_samples + n] = make_float2(gf[4 * q + 2] * inv_scale, gf[4 * q + 3] * inv_scale);
+            }
         }
     }
 

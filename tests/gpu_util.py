@@ -29,6 +29,19 @@ def host(t):
     return t.detach().cpu().numpy()
 
 
+def to_planes(rows):
+    """[N, 2L] sample-major rows (the oracle's layout) -> [L, N, 2] level-major planes (the library's)."""
+    rows = np.asarray(rows)
+    n, w = rows.shape
+    return np.ascontiguousarray(rows.reshape(n, w // 2, 2).transpose(1, 0, 2))
+
+
+def from_planes(t, n, width):
+    """Device tensor holding [width/2, n, 2] planes (any leading shape, contiguous) -> host [n, width] rows."""
+    a = host(t).reshape(-1)[:n * width].reshape(width // 2, n, 2)
+    return np.ascontiguousarray(a.transpose(1, 0, 2)).reshape(n, width)
+
+
 def rel_err(got, ref, floor=None):
     """max |got-ref| / max(|ref|, floor); floor defaults to the mean magnitude of ref (so entries that
     cancel to ~0 are judged against the size of the tensor they live in)."""

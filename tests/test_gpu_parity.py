@@ -15,7 +15,8 @@ import oracle
 import oracle.step as ostep
 from paper_2405_04416_amd import binding as B
 
-from gpu_util import (DEV, TOL_F16, TOL_F32, dev, gpu_grid, gpu_mlp, gpu_models, have_gpu, host, make_step, rel_err)
+from gpu_util import (DEV, TOL_F16, TOL_F32, dev, from_planes, gpu_grid, gpu_mlp, gpu_models, have_gpu, host, make_step,
+                      rel_err, to_planes)
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not have_gpu(), reason="needs a GPU")]
 
@@ -146,8 +147,8 @@ def test_encode_fwd_and_indices(key, N):
         u[:6] = [[0, 0, 0], [1, 1, 1], [-0.3, 0.5, 2.0], [1, 0, 0.5], [0.999999, 0.999999, 0.999999], [0.5, 0.5, 0.5]]
     td, ud = dev(table), dev(u) if N else torch.zeros(1, 3, device=DEV)[:0]
     idx = torch.zeros(max(N, 1), L, 8, dtype=torch.int32, device=DEV)
-    feat = torch.zeros(max(N, 1), 2 * L, device=DEV)
-    feat16 = torch.zeros(max(N, 1), 2 * L, dtype=torch.float16, device=DEV)
+    feat = torch.zeros(L, max(N, 1), 2, device=DEV)[:, :N].contiguous()            # level-major planes
+    feat16 = torch.zeros(L, max(N, 1), 2, dtype=torch.float16, device=DEV)[:, :N].contiguous()
     B.dg_hashgrid_corner_indices(g, ud, N, idx)
     B.dg_hashgrid_encode_fwd(g, td, ud, N, feat)
     B.dg_hashgrid_encode_fwd(g, td, ud, N, feat16)
@@ -157,10 +158,10 @@ def test_encode_fwd_and_indices(key, N):
     ref, ridx = oracle.encode_fwd(r, table, u, want_idx=True)
     np.testing.assert_array_equal(host(idx).view(np.uint32), ridx)                 # bit-exact indices
     bound = oracle.encode_fwd(r, table, u, abs_terms=True)                          # sum |w||theta| per output
-    err = np.abs(host(feat).astype(np.float64) - ref)
+    err = np.abs(from_planes(feat, N, 2 * L).astype(np.float64) - ref)
     assert np.all(err <= TOL_F32 * bound + 1e-30), float(np.max(err / (bound + 1e-30)))
     # fp16 output: the fp32 value rounded once
-    err16 = np.abs(host(feat16).astype(np.float64) - ref)
+    err16 = np.abs(from_planes(feat16, N, 2 * L).astype(np.float64) - ref)
     assert np.all(err16 <= 2.0 ** -11 * np.abs(ref) + TOL_F32 * bound + 6e-8)
 
 
@@ -180,8 +181,8 @@ def test_encode_bwd(key, N, mode):
         if mode == "binned_batched":                                   # room for a few tiles only: several batches
             need = B.dg_hashgrid_encode_bwd_workspace_bytes(g, 2048)
         ws = torch.zeros(need // 4 + 64, device=DEV)
-    B.dg_hashgrid_encode_bwd(g, dev(u), dev(dfeat), N, dtable, ws)
-    B.dg_hashgrid_encode_bwd(g, dev(u), dev(dfeat), N, dtable, ws)   # "+=": twice gives twice
+    B.dg_hashgrid_encode_bwd(g, dev(u), dev(to_planes(dfeat)), N, dtable, ws)
+    B.dg_hashgrid_encode_bwd(g, dev(u), dev(to_planes(dfeat)), N, dtable, ws)   # "+=": twice gives twice
     ref = 2.0 * oracle.encode_bwd(r, u, dfeat.astype(np.float64))
     got = host(dtable).astype(np.float64)
     for l in range(L):                                                # judged level by level
@@ -209,7 +210,7 @@ def test_mlp_fwd(name, n, S):
     cfg = di.config(name)
     w, feat, dir_enc, odesc = _mlp_inputs(cfg, n, S, seed=11)
     sigma = torch.zeros(n, device=DEV); rgb = torch.zeros(n, 3, device=DEV)
-    B.dg_mlp_fwd(gpu_mlp(cfg), dev(w), dev(feat), dev(dir_enc), S, n, sigma, rgb)
+    B.dg_mlp_fwd(gpu_mlp(cfg), dev(w), dev(to_planes(feat)), dev(dir_enc), S, n, sigma, rgb)
     rs, rr = oracle.mlp_fwd(odesc, w.astype(np.float64), feat.astype(np.float64), dir_enc.astype(np.float64), S)
     assert rel_err(host(sigma), rs) <= TOL_F16
     assert rel_err(host(rgb), rr) <= TOL_F16
@@ -228,10 +229,10 @@ def test_mlp_bwd(name, n, S):
     dfeat = torch.zeros(n, feat.shape[1], device=DEV)
     dW = torch.zeros(w.size, device=DEV)
     ws = torch.zeros(B.dg_mlp_bwd_workspace_bytes(mdesc) // 4, device=DEV)
-    B.dg_mlp_bwd(mdesc, dev(w), dev(feat), dev(dir_enc), S, n, dev(dsigma), dev(drgb), scale, dfeat, dW, ws)
+    B.dg_mlp_bwd(mdesc, dev(w), dev(to_planes(feat)), dev(dir_enc), S, n, dev(dsigma), dev(drgb), scale, dfeat, dW, ws)
     rdf, rdw = oracle.mlp_bwd(odesc, w.astype(np.float64), feat.astype(np.float64), dir_enc.astype(np.float64), S,
                               dsigma.astype(np.float64), drgb.astype(np.float64), scale)
-    assert rel_err(host(dfeat), rdf) <= TOL_F16
+    assert rel_err(from_planes(dfeat, n, feat.shape[1]), rdf) <= TOL_F16
     pos = 0
     for (no, ni) in di.mlp_layer_shapes(feat.shape[1], cfg["mlp"]):       # judged matrix by matrix
         assert rel_err(host(dW)[pos:pos + no * ni], rdw[pos:pos + no * ni]) <= TOL_F16

@@ -15,7 +15,7 @@ import oracle
 import oracle.step as ostep
 from paper_2405_04416_amd import binding as B
 
-from gpu_util import (DEV, TOL_F16, TOL_F32, assert_close_robust, dev, gpu_models, have_gpu, host, make_step,
+from gpu_util import (DEV, TOL_F16, TOL_F32, assert_close_robust, dev, from_planes, gpu_models, have_gpu, host, make_step,
                       rel_err)
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not have_gpu(), reason="needs a GPU")]
@@ -52,7 +52,8 @@ def _compare_step(cfg, R, seed, lambda1, loss_scale, use_jitter_array, table_gai
         np.testing.assert_array_equal(host(step.u[sl]).view(np.uint32), q["u"].view(np.uint32))
         np.testing.assert_array_equal(host(step.delta[sl]).view(np.uint32), q["delta"].view(np.uint32))
         # encode output is fp16 here: one rounding of a value that matches to 1e-5
-        assert rel_err(host(step.feat[sl]).astype(np.float64), q["feat"]) <= 1e-3
+        n_p, width = (q["e"] - q["b"]) * S, q["feat"].shape[1]
+        assert rel_err(from_planes(step.feat[sl], n_p, width).astype(np.float64), q["feat"]) <= 1e-3
         assert_close_robust(host(step.sigma[sl]), q["sigma"], TOL_F16, "sigma")
         assert_close_robust(host(step.rgb[sl]), q["rgb"], TOL_F16, "rgb")
     # rendering
@@ -71,7 +72,7 @@ def _compare_step(cfg, R, seed, lambda1, loss_scale, use_jitter_array, table_gai
         sl = slice(q["b"] * S, q["e"] * S)
         assert_close_robust(host(step.dsigma[sl]), q["dsigma"], TOL_F16, "dsigma")
         assert_close_robust(host(step.drgb[sl]), q["drgb"], TOL_F16, "drgb")
-        assert_close_robust(host(step.dfeat[sl]), q["dfeat"], TOL_F16, "dfeat")
+        assert_close_robust(from_planes(step.dfeat[sl], (q["e"] - q["b"]) * S, q["dfeat"].shape[1]), q["dfeat"], TOL_F16, "dfeat")
         assert_close_robust(host(gm[p].dW), q["dW"], TOL_F16, "dW")
         grid = hm[p]["grid"]
         got = host(gm[p].dtable).astype(np.float64)
@@ -201,17 +202,17 @@ def test_step_full_size_bench_configuration():
     # (b) properties that hold at any size
     m = gm[0]
     L = m.grid.n_levels
-    dfeat = step.dfeat[:N].double()
+    dfeat = step.dfeat[:N].reshape(L, N, 2).double()          # level-major planes
     dtab = m.dtable.double()
     # trilinear weights sum to one: per level and feature, the table gradient sums to the feature gradient
-    col = dfeat.sum(0).cpu().numpy().reshape(L, 2)
+    col = dfeat.sum(1).cpu().numpy()
     for l in range(L):
         tot = dtab[m.grid.offset[l]:m.grid.offset[l + 1]].sum(0).cpu().numpy()
-        mag = dfeat.abs().sum(0).cpu().numpy().reshape(L, 2)[l]
+        mag = dfeat.abs().sum(1).cpu().numpy()[l]
         assert np.all(np.abs(tot - col[l]) <= TOL_F16 * mag), l
     # transpose identity <dfeat, E(theta')> = <dtable, theta'> with a second random table
     probe = torch.rand_like(m.table) - 0.5
-    f2 = torch.zeros(N, 2 * L, device=DEV)
+    f2 = torch.zeros(L, N, 2, device=DEV)
     B.dg_hashgrid_encode_fwd(m.grid, probe, step.u[:N], N, f2)
     lhs = float((dfeat * f2.double()).sum()); rhs = float((dtab * probe.double()).sum())
     mag = float((dfeat.abs() * f2.double().abs()).sum())
