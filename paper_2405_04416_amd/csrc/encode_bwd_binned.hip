@@ -23,9 +23,9 @@ using namespace dg_encode;
 constexpr int kChunkLog2 = 13;
 constexpr uint32_t kChunk = 1u << kChunkLog2;      // entries per bin
 constexpr int kMaxBins = 2048;                     // per level: 2^24 entries / 8192
-constexpr int kTile = 1024;                        // samples per tile == threads per binning workgroup
+constexpr int kTile = 512;                         // samples per tile == threads per binning workgroup
 constexpr int kRecords = kTile * 8;
-constexpr int kBinGrid = 256;                      // persistent binning workgroups (one per compute unit)
+constexpr int kBinGrid = 768;                      // persistent binning workgroups (three per compute unit)
 constexpr int kAccBlock = 1024;
 constexpr uint32_t kAccRecords = 1u << 18;          // records one accumulate workgroup sums
 constexpr int kCoarseBlock = 256;
@@ -36,6 +36,7 @@ struct Plan {
     uint32_t n_keys;                       // (level, bin) pairs of the binned levels
     uint32_t key_base[DG_MAX_LEVELS + 1];  // first key of each level
     uint32_t n_bins[DG_MAX_LEVELS];
+    uint32_t max_bins;
 };
 
 __global__ void __launch_bounds__(256) zero_u32_kernel(uint32_t *p, size_t n)
@@ -108,25 +109,30 @@ coarse_kernel(dg_grid_desc g, uint32_t first_level, const float *__restrict__ u,
 }
 
 // ------------------------------------------------------------------ binning sweeps
-// exclusive scan of cnt[0, n) into start[0, n) by the whole workgroup (n <= 2 * kTile)
+// exclusive scan of cnt[0, n) into start[0, n) by the whole workgroup, 2 * kTile counters per round
 __device__ __forceinline__ void block_exclusive_scan(const uint32_t *cnt, uint32_t *start, uint32_t n, uint32_t *wave_tot)
 {
     const uint32_t t = threadIdx.x, lane = t % dg::kWave, wave = t / dg::kWave;
-    const uint32_t a = 2 * t < n ? cnt[2 * t] : 0u, b = 2 * t + 1 < n ? cnt[2 * t + 1] : 0u;
-    uint32_t incl = a + b;
+    uint32_t carry = 0;
+    for (uint32_t lo = 0; lo < n; lo += 2 * kTile) {
+        const uint32_t i0 = lo + 2 * t, i1 = i0 + 1;
+        const uint32_t a = i0 < n ? cnt[i0] : 0u, b = i1 < n ? cnt[i1] : 0u;
+        uint32_t incl = a + b;
 #pragma unroll
-    for (int off = 1; off < dg::kWave; off <<= 1) {
-        const uint32_t up = __shfl_up(incl, off, dg::kWave);
-        if ((int)lane >= off) incl += up;
+        for (int off = 1; off < dg::kWave; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off, dg::kWave);
+            if ((int)lane >= off) incl += up;
+        }
+        if (lane == dg::kWave - 1) wave_tot[wave] = incl;
+        __syncthreads();
+        uint32_t base = carry, all = 0;
+        for (uint32_t w = 0; w < kTile / dg::kWave; ++w) { if (w < wave) base += wave_tot[w]; all += wave_tot[w]; }
+        const uint32_t excl = base + incl - (a + b);
+        if (i0 < n) start[i0] = excl;
+        if (i1 < n) start[i1] = excl + a;
+        carry += all;
+        __syncthreads();
     }
-    if (lane == dg::kWave - 1) wave_tot[wave] = incl;
-    __syncthreads();
-    uint32_t base = 0;
-    for (uint32_t w = 0; w < wave; ++w) base += wave_tot[w];
-    const uint32_t excl = base + incl - (a + b);
-    if (2 * t < n) start[2 * t] = excl;
-    if (2 * t + 1 < n) start[2 * t + 1] = excl + a;
-    __syncthreads();
 }
 
 template <bool FILL>
@@ -136,10 +142,11 @@ bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 
            uint16_t *__restrict__ q_idx, float *__restrict__ q_vx, float *__restrict__ q_vy)
 {
     extern __shared__ uint32_t smem[];
-    uint32_t *cnt = smem;                               // [kMaxBins]
-    uint32_t *start = cnt + kMaxBins;                   // [kMaxBins]
-    uint32_t *gbase = start + kMaxBins;                 // [kMaxBins]
-    uint32_t *wave_tot = gbase + kMaxBins;              // [16]
+    const uint32_t cap = plan.max_bins;                 // largest bin count of any level
+    uint32_t *cnt = smem;                               // [cap]
+    uint32_t *start = cnt + cap;                        // [cap]
+    uint32_t *gbase = start + cap;                      // [cap]
+    uint32_t *wave_tot = gbase + cap;                   // [16]
     uint32_t *stage_e = wave_tot + 16;                  // [kRecords]   (FILL only)
     float *stage_x = reinterpret_cast<float *>(stage_e + kRecords);
     float *stage_y = stage_x + kRecords;
@@ -155,6 +162,8 @@ bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 
         const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
         for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
             const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
+            float2 gfe = make_float2(0.0f, 0.0f);
+            if (FILL && live) gfe = dfeat[(size_t)l * N + n];      // issued early: needed only after the two barriers below
             for (uint32_t i = tid; i < n_bins; i += kTile) cnt[i] = 0u;
             __syncthreads();
             const LevelGeom lv = level_of(g, l);
@@ -162,7 +171,18 @@ bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 
             float frac[3], w[8];
             locate(lv, uu, cell, frac);
             corner_entries(lv, mask, cell, e);
-            if (live) {
+            // A wavefront holds 64 consecutive samples of a ray; lanes that share a cell form a run whose
+            // 16 values are summed into the run's last lane, which alone emits records (both sweeps take
+            // the same decision from the same data).  Skipped where runs are short.
+            const int lane = tid % dg::kWave;
+            bool head = lane == 0 || !live;
+#pragma unroll
+            for (int a = 0; a < 3; ++a) head |= __shfl_up(cell[a], 1, dg::kWave) != cell[a];
+            const unsigned long long heads = __ballot(head);
+            const bool merge = __popcll(heads) <= 44;
+            const bool tail = lane == dg::kWave - 1 || ((heads >> ((lane + 1) & 63)) & 1ull);
+            const bool emit = live && (!merge || tail);
+            if (emit) {
 #pragma unroll
                 for (int c = 0; c < 8; ++c) rank[c] = atomicAdd(&cnt[e[c] >> kChunkLog2], 1u);
             }
@@ -178,15 +198,31 @@ bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 
                 gbase[i] = binbase[key0 + i] + mine;
                 row[key0 + i] = mine + cnt[i];
             }
-            if (live) {
+            {
                 corner_weights(frac, w);
-                const float2 gfe = dfeat[(size_t)l * N + n];
+                float vx[8], vy[8];
 #pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    const uint32_t slot = start[e[c] >> kChunkLog2] + rank[c];
-                    stage_e[slot] = e[c];
-                    stage_x[slot] = w[c] * gfe.x;
-                    stage_y[slot] = w[c] * gfe.y;
+                for (int c = 0; c < 8; ++c) { vx[c] = w[c] * gfe.x; vy[c] = w[c] * gfe.y; }
+                if (merge) {
+                    const int first = 63 - __clzll(heads & (~0ull >> (63 - lane)));
+#pragma unroll
+                    for (int off = 1; off < dg::kWave; off <<= 1) {
+                        const bool take = lane - off >= first;
+#pragma unroll
+                        for (int c = 0; c < 8; ++c) {
+                            const float tx = __shfl_up(vx[c], off, dg::kWave), ty = __shfl_up(vy[c], off, dg::kWave);
+                            if (take) { vx[c] += tx; vy[c] += ty; }
+                        }
+                    }
+                }
+                if (emit) {
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) {
+                        const uint32_t slot = start[e[c] >> kChunkLog2] + rank[c];
+                        stage_e[slot] = e[c];
+                        stage_x[slot] = vx[c];
+                        stage_y[slot] = vy[c];
+                    }
                 }
             }
             __syncthreads();
@@ -270,10 +306,25 @@ accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbas
     const size_t end = min(begin + (size_t)kAccRecords, (size_t)binbase[key + 1]);
     for (uint32_t i = threadIdx.x; i < 2 * kChunk; i += kAccBlock) tab[i] = 0.0;
     __syncthreads();
-    for (size_t i = begin + threadIdx.x; i < end; i += kAccBlock) {
-        const uint32_t e = q_idx[i];
-        __hip_atomic_fetch_add(&tab[2 * e], (double)q_vx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        __hip_atomic_fetch_add(&tab[2 * e + 1], (double)q_vy[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    // four records in flight per thread so that the queue streams at memory speed
+    for (size_t i0 = begin + threadIdx.x; i0 < end; i0 += 4 * kAccBlock) {
+        uint32_t e[4];
+        float x[4], y[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const size_t i = i0 + (size_t)k * kAccBlock;
+            const bool ok = i < end;
+            e[k] = ok ? q_idx[i] : 0u;
+            x[k] = ok ? q_vx[i] : 0.0f;
+            y[k] = ok ? q_vy[i] : 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (i0 + (size_t)k * kAccBlock < end) {
+                __hip_atomic_fetch_add(&tab[2 * e[k]], (double)x[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(&tab[2 * e[k] + 1], (double)y[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
     }
     __syncthreads();
     uint32_t l = plan.first_level;
@@ -299,7 +350,9 @@ Plan make_plan(const dg_grid_desc *d)
         p.key_base[l] = key;
         p.n_bins[l] = (d->offset[l + 1] - d->offset[l] + kChunk - 1) / kChunk;
         key += p.n_bins[l];
+        if (p.n_bins[l] > p.max_bins) p.max_bins = p.n_bins[l];
     }
+    p.max_bins = (p.max_bins + 63) / 64 * 64;
     p.key_base[d->n_levels] = key;
     p.n_keys = key;
     return p;
@@ -360,7 +413,7 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     const Plan p = make_plan(d);
     static bool lds_opt_in = false;
     if (!lds_opt_in) {
-        const int fill_lds = (3 * kMaxBins + 16 + 3 * kRecords) * 4;
+        const int fill_lds = (3 * kMaxBins + 16 + 3 * kRecords) * 4;      // the most a launch may ask for
         hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(&bin_kernel<true>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds);
         if (e1 != hipSuccess) return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot reserve %d bytes of LDS: %s", fill_lds,
@@ -399,7 +452,7 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     float *q_vx = reinterpret_cast<float *>(base + L.q_vx);
     float *q_vy = reinterpret_cast<float *>(base + L.q_vy);
     const size_t n_rows_words = (size_t)kBinGrid * p.n_keys;
-    const int count_lds = (3 * kMaxBins + 16) * 4, fill_lds = (3 * kMaxBins + 16 + 3 * kRecords) * 4;
+    const int count_lds = (3 * (int)p.max_bins + 16) * 4, fill_lds = (3 * (int)p.max_bins + 16 + 3 * kRecords) * 4;
 
     for (uint64_t n0 = 0; n0 < N; n0 += batch) {
         const uint64_t nb = N - n0 < batch ? N - n0 : batch;
