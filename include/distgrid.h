@@ -168,8 +168,8 @@ int dg_mlp_fwd(const dg_mlp_desc *desc, const void *weights, const void *feat,
  * dsigma [N], drgb [N,3] fp32.  Every back-propagated delta is multiplied by loss_scale
  * (a power of two is advisable) before it is rounded to fp16, and dfeat / dW are divided
  * by it again in fp32.  Outputs: dfeat [n_feat/2, N, 2] fp32 planes (overwritten); dW fp32, "+=",
- * same packing as weights.  ws: dg_mlp_bwd_workspace_bytes(desc) bytes. */
-size_t dg_mlp_bwd_workspace_bytes(const dg_mlp_desc *desc);
+ * same packing as weights.  ws: dg_mlp_bwd_workspace_bytes(desc, N) bytes, 256-byte aligned. */
+size_t dg_mlp_bwd_workspace_bytes(const dg_mlp_desc *desc, uint64_t N);
 int dg_mlp_bwd(const dg_mlp_desc *desc, const void *weights, const void *feat,
                const void *dir_enc, uint32_t S, uint64_t N, const float *dsigma,
                const float *drgb, float loss_scale, float *dfeat, float *dW,

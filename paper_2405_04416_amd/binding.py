@@ -60,7 +60,7 @@ _SIGNATURES = {
     "dg_mlp_weight_count": (C.c_size_t, [C.POINTER(MlpDesc)]),
     "dg_mlp_fwd": (C.c_int, [C.POINTER(MlpDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p,
                              C.c_void_p, C.c_void_p]),
-    "dg_mlp_bwd_workspace_bytes": (C.c_size_t, [C.POINTER(MlpDesc)]),
+    "dg_mlp_bwd_workspace_bytes": (C.c_size_t, [C.POINTER(MlpDesc), C.c_uint64]),
     "dg_mlp_bwd": (C.c_int, [C.POINTER(MlpDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p,
                              C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "dg_composite_segment_fwd": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32,
@@ -136,8 +136,8 @@ def dg_segments_workspace_bytes(R, P):
     return int(lib().dg_segments_workspace_bytes(R, P))
 
 
-def dg_mlp_bwd_workspace_bytes(desc):
-    return int(lib().dg_mlp_bwd_workspace_bytes(C.byref(desc)))
+def dg_mlp_bwd_workspace_bytes(desc, N):
+    return int(lib().dg_mlp_bwd_workspace_bytes(C.byref(desc), N))
 
 
 # ------------------------------------------------------------------ device entry points

@@ -39,7 +39,7 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
                       size_t ws_bytes, hipStream_t st);
 
 // matrix-core path of the 32-64-16 / 32-64-64-3 field MLPs (mlp_mfma.hip)
-size_t mlp_mfma_workspace_bytes();
+size_t mlp_mfma_workspace_bytes(uint64_t N);
 void mlp_mfma_fwd(const void *weights, const void *feat, const void *dir_enc, uint32_t S, uint64_t N, uint32_t act_c,
                   float *sigma, float *rgb, hipStream_t st);
 void mlp_mfma_bwd(const void *weights, const void *feat, const void *dir_enc, uint32_t S, uint64_t N, uint32_t act_c,

@@ -255,13 +255,13 @@ extern "C" int dg_mlp_fwd(const dg_mlp_desc *desc, const void *weights, const vo
     return dg::launch_status("dg_mlp_fwd");
 }
 
-extern "C" size_t dg_mlp_bwd_workspace_bytes(const dg_mlp_desc *desc)
+extern "C" size_t dg_mlp_bwd_workspace_bytes(const dg_mlp_desc *desc, uint64_t N)
 {
     if (!desc) return 0;
     const size_t scalar = (size_t)kBwdGrid * dg_mlp_weight_count(desc) * sizeof(float);
     const bool ngp = desc->n_feat == 32 && desc->n_hidden_d == 64 && desc->n_geo == 16 && desc->n_dir == 16 &&
                      desc->n_hidden_c == 64 && desc->n_layers_c == 2;
-    return ngp ? dg::mlp_mfma_workspace_bytes() : scalar;
+    return ngp ? dg::mlp_mfma_workspace_bytes(N) : scalar;
 }
 
 extern "C" int dg_mlp_bwd(const dg_mlp_desc *desc, const void *weights, const void *feat, const void *dir_enc,
@@ -273,8 +273,9 @@ extern "C" int dg_mlp_bwd(const dg_mlp_desc *desc, const void *weights, const vo
     DG_REQUIRE(S >= 1 && loss_scale > 0.0f, DG_ERR_ARG, "dg_mlp_bwd: S >= 1 and loss_scale > 0 required");
     if (N == 0) return DG_OK;
     DG_REQUIRE(weights && feat && dir_enc && dsigma && drgb && dfeat && dW, DG_ERR_ARG, "dg_mlp_bwd: null pointer");
-    DG_REQUIRE(ws && ws_bytes >= dg_mlp_bwd_workspace_bytes(desc), DG_ERR_WORKSPACE, "dg_mlp_bwd: workspace %zu < %zu bytes",
-               ws_bytes, dg_mlp_bwd_workspace_bytes(desc));
+    DG_REQUIRE(ws && ws_bytes >= dg_mlp_bwd_workspace_bytes(desc, N), DG_ERR_WORKSPACE, "dg_mlp_bwd: workspace %zu < %zu bytes",
+               ws_bytes, dg_mlp_bwd_workspace_bytes(desc, N));
+    DG_REQUIRE(dg::aligned(ws, 256), DG_ERR_ARG, "dg_mlp_bwd: workspace must be 256-byte aligned");
     const uint64_t n_tiles = (N + kBwdBlock - 1) / kBwdBlock;
     const uint32_t grid = (uint32_t)(n_tiles < kBwdGrid ? n_tiles : kBwdGrid);
     const uint32_t n_w = (uint32_t)dg_mlp_weight_count(desc);

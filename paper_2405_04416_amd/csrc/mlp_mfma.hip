@@ -268,10 +268,17 @@ __device__ __forceinline__ void store_share(float *dst, int n_in, int rows_real,
     }
 }
 
+// The backward pass runs as two kernels so that neither has to hold all twelve dW tiles (192
+// accumulator registers) next to the activations:
+//   colour_bwd : recomputes the whole forward, back-propagates the colour net, accumulates dWc1..3
+//                and leaves delta_geo (gradient of the 16 density outputs, sigma term included,
+//                already scaled and rounded to fp16, in operand order) in the workspace;
+//   density_bwd: recomputes the density hidden layer, back-propagates it from delta_geo, accumulates
+//                dWd1..2 and writes the feature gradient planes.
 __global__ void __launch_bounds__(kBlock)
-bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, const __half *__restrict__ dir_enc,
-           uint32_t S, uint64_t n_samples, uint32_t act_c, const float *__restrict__ dsigma,
-           const float *__restrict__ drgb, float loss_scale, float *__restrict__ dfeat, float *__restrict__ shares)
+colour_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, const __half *__restrict__ dir_enc,
+                  uint32_t S, uint64_t n_samples, uint32_t act_c, const float *__restrict__ dsigma,
+                  const float *__restrict__ drgb, float loss_scale, h8 *__restrict__ dgeo, float *__restrict__ shares)
 {
     __shared__ __attribute__((aligned(16))) __half lds[kAllChunks * 512];
     build_forward_images(lds, weights);
@@ -281,24 +288,24 @@ bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, 
     const uint64_t n_tiles = (n_samples + 31) / 32;
     const uint64_t wave = (uint64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
-    const float inv_scale = 1.0f / loss_scale;
-    const h8 selT0 = image(lds, cSelT, lane), selT1 = image(lds, cSelT + 1, lane);
-    const h8 selN0 = image(lds, cSelN, lane), selN1 = image(lds, cSelN + 1, lane);
     const h8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
-    f16v gWc3[2], gWc2[2][2], gWc1[2], gWd2[2], gWd1[2];      // [output tile][input tile]
+    f16v gWc3[2], gWc2[2][2], gWc1[2];      // [output tile][input tile]
 #pragma unroll
-    for (int a = 0; a < 2; ++a) {
-        gWc3[a] = zero16(); gWc1[a] = zero16(); gWd2[a] = zero16(); gWd1[a] = zero16();
-        gWc2[a][0] = zero16(); gWc2[a][1] = zero16();
-    }
+    for (int a = 0; a < 2; ++a) { gWc3[a] = zero16(); gWc1[a] = zero16(); gWc2[a][0] = zero16(); gWc2[a][1] = zero16(); }
 
     for (uint64_t tile = wave; tile < n_tiles; tile += n_waves) {
         const uint64_t n = tile * 32 + (lane & 31);
         const bool valid = n < n_samples;
         Tile t;
         load_inputs(feat, dir_enc, S, n_samples, n, valid, h, t);
+        float ds = 0.0f, dc[3] = {0.0f, 0.0f, 0.0f};
+        if (valid && h == 0) {                 // issued before the forward so the latency hides behind it
+            ds = dsigma[n];
+            dc[0] = drgb[3 * n]; dc[1] = drgb[3 * n + 1]; dc[2] = drgb[3 * n + 2];
+        }
         forward_tile(lds, lane, act_c, t);
+        const h8 selT0 = image(lds, cSelT, lane), selT1 = image(lds, cSelT + 1, lane);
 
         // ---- output layer of the colour net
         h8 d3 = zero8;
@@ -306,7 +313,7 @@ bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, 
 #pragma unroll
             for (int c = 0; c < 3; ++c) {
                 const bool pass = t.raw[c] >= -15.0f && t.raw[c] <= 15.0f;
-                d3[c] = (_Float16)(pass ? loss_scale * drgb[3 * n + c] * t.rgb[c] * (1.0f - t.rgb[c]) : 0.0f);
+                d3[c] = (_Float16)(pass ? loss_scale * dc[c] * t.rgb[c] * (1.0f - t.rgb[c]) : 0.0f);
             }
         }
         h8 td[2][2], ta[2][2];      // transposed delta / activation: [feature tile][sample k-step]
@@ -347,7 +354,7 @@ bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, 
         for (int ks = 0; ks < 4; ++ks) dl[ks] = act_c ? delta_from<2>(g[ks >> 1], ks & 1, t.c1[ks]) : delta_from<1>(g[ks >> 1], ks & 1, t.c1[ks]);
         transpose_tile(dl[0], dl[1], selT0, selT1, td[0]);
         transpose_tile(dl[2], dl[3], selT0, selT1, td[1]);
-        transpose_tile(t.xc[0], t.xc[1], selT0, selN1, ta[0]);
+        transpose_tile(t.xc[0], t.xc[1], selT0, image(lds, cSelN + 1, lane), ta[0]);
 #pragma unroll
         for (int ot = 0; ot < 2; ++ot)
 #pragma unroll
@@ -359,9 +366,76 @@ bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, 
         // ---- density net output: geometry features feed the colour net, output 0 also feeds exp()
         if (valid && h == 0) {
             const bool pass0 = t.geo0 >= -15.0f && t.geo0 <= 15.0f;
-            gx[0] += pass0 ? loss_scale * dsigma[n] * t.sigma : 0.0f;
+            gx[0] += pass0 ? loss_scale * ds * t.sigma : 0.0f;
         }
-        const h8 dg = pack_half<0>(gx, 0);
+        if (valid) dgeo[2 * n + h] = pack_half<0>(gx, 0);
+    }
+
+    float *mine = shares + wave * (kTotal - oWc1) - oWc1;       // colour shares hold elements [oWc1, kTotal)
+    store_share(mine + oWc3, HC, 3, 0, 0, lane, gWc3[0]);
+    store_share(mine + oWc3, HC, 3, 0, 1, lane, gWc3[1]);
+#pragma unroll
+    for (int ot = 0; ot < 2; ++ot) {
+        store_share(mine + oWc2, HC, HC, ot, 0, lane, gWc2[ot][0]);
+        store_share(mine + oWc2, HC, HC, ot, 1, lane, gWc2[ot][1]);
+        store_share(mine + oWc1, CI, HC, ot, 0, lane, gWc1[ot]);
+    }
+}
+
+__global__ void __launch_bounds__(kBlock, 2)
+density_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, uint64_t n_samples,
+                   const h8 *__restrict__ dgeo, float loss_scale, float *__restrict__ dfeat, float *__restrict__ shares)
+{
+    // images: density layer 1 forward (4 chunks), Wd2^T (2), Wd1^T (4), selections (4)
+    constexpr int kD1 = 0, kD2T = 4, kD1T = 6, kST = 10, kSN = 12, kChunks = 14;
+    __shared__ __attribute__((aligned(16))) __half lds[kChunks * 512];
+    build_image(lds + kD1 * 512, weights + oWd1, HD, NF, HD, NF, 2, 2, 1, false);
+    build_image(lds + kD2T * 512, weights + oWd2, NG, HD, HD, NG, 2, 1, 0, true);
+    build_image(lds + kD1T * 512, weights + oWd1, HD, NF, NF, HD, 1, 4, 0, true);
+    build_selection(lds + kST * 512, 0);
+    build_selection(lds + kSN * 512, 1);
+    __syncthreads();
+    const int lane = threadIdx.x & 63, h = lane >> 5;
+    const uint64_t n_tiles = (n_samples + 31) / 32;
+    const uint64_t wave = (uint64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
+    const float inv_scale = 1.0f / loss_scale;
+    const h8 selT0 = image(lds, kST, lane), selT1 = image(lds, kST + 1, lane);
+    const h8 selN0 = image(lds, kSN, lane), selN1 = image(lds, kSN + 1, lane);
+    const h8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+
+    f16v gWd2[2], gWd1[2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) { gWd2[a] = zero16(); gWd1[a] = zero16(); }
+
+    for (uint64_t tile = wave; tile < n_tiles; tile += n_waves) {
+        const uint64_t n = tile * 32 + (lane & 31);
+        const bool valid = n < n_samples;
+        Tile t;
+        load_inputs(feat, nullptr, 1, n_samples, n, false, h, t);      // zeroes
+        if (valid) {
+            typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+            const uint32_t *planes = reinterpret_cast<const uint32_t *>(feat);
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                u4 bits;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) bits[q] = planes[(size_t)(8 * ks + 4 * h + q) * n_samples + n];
+                t.x0[ks] = __builtin_bit_cast(h8, bits);
+            }
+        }
+        const h8 dg = valid ? dgeo[2 * n + h] : zero8;
+        f16v acc[2];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            acc[mt] = zero16();
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) acc[mt] = mma(image(lds, kD1 + mt * 2 + ks, lane), t.x0[ks], acc[mt]);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) t.h1[ks] = pack_half<1>(acc[ks >> 1], ks & 1);
+
+        h8 td[2][2], ta[2][2];
         transpose_half_tile(dg, selT0, td[0]);
         transpose_tile(t.h1[0], t.h1[1], selT0, selT1, ta[0]);
         transpose_tile(t.h1[2], t.h1[3], selT0, selT1, ta[1]);
@@ -369,10 +443,11 @@ bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, 
         for (int it = 0; it < 2; ++it)
 #pragma unroll
             for (int p = 0; p < 2; ++p) gWd2[it] = mma(td[0][p], ta[it][p], gWd2[it]);
+        f16v g[2];
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) g[mt] = mma(image(lds, cD2T + mt, lane), dg, zero16());
+        for (int mt = 0; mt < 2; ++mt) g[mt] = mma(image(lds, kD2T + mt, lane), dg, zero16());
 
-        // ---- hidden layer of the density net
+        h8 dl[4];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) dl[ks] = delta_from<1>(g[ks >> 1], ks & 1, t.h1[ks]);
         transpose_tile(dl[0], dl[1], selT0, selT1, td[0]);
@@ -384,7 +459,7 @@ bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, 
             for (int p = 0; p < 2; ++p) gWd1[ot] = mma(td[ot][p], ta[0][p], gWd1[ot]);
         f16v gf = zero16();
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) gf = mma(image(lds, cD1T + ks, lane), dl[ks], gf);
+        for (int ks = 0; ks < 4; ++ks) gf = mma(image(lds, kD1T + ks, lane), dl[ks], gf);
         if (valid) {
             // registers 4q .. 4q+3 hold features 8q + 4h .. + 3: levels 4q + 2h and 4q + 2h + 1 of the planes [16][n_samples][2]
             float2 *planes = reinterpret_cast<float2 *>(dfeat);
@@ -396,44 +471,48 @@ bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, 
         }
     }
 
-    float *mine = shares + wave * kTotal;
-    store_share(mine + oWc3, HC, 3, 0, 0, lane, gWc3[0]);
-    store_share(mine + oWc3, HC, 3, 0, 1, lane, gWc3[1]);
+    float *mine = shares + wave * oWc1;                         // density shares hold elements [0, oWc1)
 #pragma unroll
-    for (int ot = 0; ot < 2; ++ot) {
-        store_share(mine + oWc2, HC, HC, ot, 0, lane, gWc2[ot][0]);
-        store_share(mine + oWc2, HC, HC, ot, 1, lane, gWc2[ot][1]);
-        store_share(mine + oWc1, CI, HC, ot, 0, lane, gWc1[ot]);
-        store_share(mine + oWd1, NF, HD, ot, 0, lane, gWd1[ot]);
-    }
+    for (int ot = 0; ot < 2; ++ot) store_share(mine + oWd1, NF, HD, ot, 0, lane, gWd1[ot]);
     store_share(mine + oWd2, HD, NG, 0, 0, lane, gWd2[0]);
     store_share(mine + oWd2, HD, NG, 0, 1, lane, gWd2[1]);
 }
 
+// dW[e] += (sum of the wavefronts' shares of element e) / loss_scale, in a fixed order.  Elements below
+// oWc1 (density net) come from density_shares [n_d][oWc1], the rest from colour_shares [n_c][kTotal - oWc1].
 __global__ void __launch_bounds__(256)
-fold_shares_kernel(const float *__restrict__ shares, uint32_t n_shares, float inv_scale, float *__restrict__ dW)
+fold_shares_kernel(const float *__restrict__ density_shares, uint32_t n_d, const float *__restrict__ colour_shares,
+                   uint32_t n_c, float inv_scale, float *__restrict__ dW)
 {
     const uint32_t e = blockIdx.x * 256 + threadIdx.x;
     if (e >= (uint32_t)kTotal) return;
+    const bool dens = e < (uint32_t)oWc1;
+    const float *src = dens ? density_shares + e : colour_shares + (e - oWc1);
+    const uint32_t stride = dens ? oWc1 : kTotal - oWc1, n = dens ? n_d : n_c;
     float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
     uint32_t b = 0;
-    for (; b + 4 <= n_shares; b += 4) {
-        s0 += shares[(size_t)b * kTotal + e]; s1 += shares[(size_t)(b + 1) * kTotal + e];
-        s2 += shares[(size_t)(b + 2) * kTotal + e]; s3 += shares[(size_t)(b + 3) * kTotal + e];
+    for (; b + 4 <= n; b += 4) {
+        s0 += src[(size_t)b * stride]; s1 += src[(size_t)(b + 1) * stride];
+        s2 += src[(size_t)(b + 2) * stride]; s3 += src[(size_t)(b + 3) * stride];
     }
-    for (; b < n_shares; ++b) s0 += shares[(size_t)b * kTotal + e];
+    for (; b < n; ++b) s0 += src[(size_t)b * stride];
     dW[e] += ((s0 + s1) + (s2 + s3)) * inv_scale;
 }
 
-constexpr uint32_t kGridMax = 256;     // persistent workgroups: one per compute unit of MI355X
+constexpr uint32_t kGridColour = 256;      // persistent workgroups: one per compute unit of MI355X
+constexpr uint32_t kGridDensity = 512;     // the lighter kernel fits two workgroups per compute unit
+
+inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
 }  // namespace dg_mlp_mfma
 
 namespace dg {
 
-size_t mlp_mfma_workspace_bytes()
+size_t mlp_mfma_workspace_bytes(uint64_t N)
 {
-    return (size_t)dg_mlp_mfma::kGridMax * dg_mlp_mfma::kWavesPerBlock * dg_mlp_mfma::kTotal * sizeof(float);
+    using namespace dg_mlp_mfma;
+    return align256((size_t)kGridDensity * kWavesPerBlock * oWc1 * sizeof(float)) +
+           align256((size_t)kGridColour * kWavesPerBlock * (kTotal - oWc1) * sizeof(float)) + align256((size_t)N * 32);
 }
 
 void mlp_mfma_fwd(const void *weights, const void *feat, const void *dir_enc, uint32_t S, uint64_t N, uint32_t act_c,
@@ -441,7 +520,7 @@ void mlp_mfma_fwd(const void *weights, const void *feat, const void *dir_enc, ui
 {
     using namespace dg_mlp_mfma;
     const uint64_t tiles = (N + 31) / 32, blocks_needed = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    const uint32_t grid = (uint32_t)(blocks_needed < 8 * kGridMax ? blocks_needed : 8 * kGridMax);
+    const uint32_t grid = (uint32_t)(blocks_needed < 2048 ? blocks_needed : 2048);
     fwd_kernel<<<grid, kBlock, 0, st>>>((const __half *)weights, (const __half *)feat, (const __half *)dir_enc, S, N, act_c,
                                         sigma, rgb);
 }
@@ -452,10 +531,19 @@ void mlp_mfma_bwd(const void *weights, const void *feat, const void *dir_enc, ui
 {
     using namespace dg_mlp_mfma;
     const uint64_t tiles = (N + 31) / 32, blocks_needed = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    const uint32_t grid = (uint32_t)(blocks_needed < kGridMax ? blocks_needed : kGridMax);
-    bwd_kernel<<<grid, kBlock, 0, st>>>((const __half *)weights, (const __half *)feat, (const __half *)dir_enc, S, N, act_c,
-                                        dsigma, drgb, loss_scale, dfeat, (float *)ws);
-    fold_shares_kernel<<<(kTotal + 255) / 256, 256, 0, st>>>((const float *)ws, grid * kWavesPerBlock, 1.0f / loss_scale, dW);
+    const uint32_t grid_c = (uint32_t)(blocks_needed < kGridColour ? blocks_needed : kGridColour);
+    const uint32_t grid_d = (uint32_t)(blocks_needed < kGridDensity ? blocks_needed : kGridDensity);
+    char *base = static_cast<char *>(ws);
+    float *density_shares = reinterpret_cast<float *>(base);
+    float *colour_shares = reinterpret_cast<float *>(base + align256((size_t)kGridDensity * kWavesPerBlock * oWc1 * sizeof(float)));
+    h8 *dgeo = reinterpret_cast<h8 *>(reinterpret_cast<char *>(colour_shares) +
+                                      align256((size_t)kGridColour * kWavesPerBlock * (kTotal - oWc1) * sizeof(float)));
+    colour_bwd_kernel<<<grid_c, kBlock, 0, st>>>((const __half *)weights, (const __half *)feat, (const __half *)dir_enc, S, N,
+                                                 act_c, dsigma, drgb, loss_scale, dgeo, colour_shares);
+    density_bwd_kernel<<<grid_d, kBlock, 0, st>>>((const __half *)weights, (const __half *)feat, N, dgeo, loss_scale, dfeat,
+                                                  density_shares);
+    fold_shares_kernel<<<(kTotal + 255) / 256, 256, 0, st>>>(density_shares, grid_d * kWavesPerBlock, colour_shares,
+                                                             grid_c * kWavesPerBlock, 1.0f / loss_scale, dW);
 }
 
 }  // namespace dg

@@ -53,7 +53,7 @@ class TrainStep:
         self.gCk, self.gTk = z(R, k_max, 3), z(R, k_max)
         self.C, self.T, self.gC, self.gT = z(R, 3), z(R), z(R, 3), z(R)
         self.loss = z(1)
-        self.ws_mlp = z(max(B.dg_mlp_bwd_workspace_bytes(any_model.mlp) // 4, 1))
+        self.ws_mlp = z(B.dg_mlp_bwd_workspace_bytes(any_model.mlp, n) // 4 + 64)
         # workspace of the binned table-gradient pass, capped (the call batches itself when it is smaller than ideal)
         want = max(B.dg_hashgrid_encode_bwd_workspace_bytes(mm.grid, n) for mm in models.values())
         self.ws_enc = torch.zeros(min(want, encode_ws_cap) // 4 + 64, dtype=f32, device=self.dev) if binned_backward else None

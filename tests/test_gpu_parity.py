@@ -228,7 +228,7 @@ def test_mlp_bwd(name, n, S):
     mdesc = gpu_mlp(cfg)
     dfeat = torch.zeros(n, feat.shape[1], device=DEV)
     dW = torch.zeros(w.size, device=DEV)
-    ws = torch.zeros(B.dg_mlp_bwd_workspace_bytes(mdesc) // 4, device=DEV)
+    ws = torch.zeros(B.dg_mlp_bwd_workspace_bytes(mdesc, n) // 4 + 64, device=DEV)
     B.dg_mlp_bwd(mdesc, dev(w), dev(to_planes(feat)), dev(dir_enc), S, n, dev(dsigma), dev(drgb), scale, dfeat, dW, ws)
     rdf, rdw = oracle.mlp_bwd(odesc, w.astype(np.float64), feat.astype(np.float64), dir_enc.astype(np.float64), S,
                               dsigma.astype(np.float64), drgb.astype(np.float64), scale)
