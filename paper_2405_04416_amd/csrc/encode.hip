@@ -84,8 +84,9 @@ encode_bwd_kernel(dg_grid_desc g, const float *__restrict__ u, const float2 *__r
 
         if (__popcll(heads) <= 40) {
             const int start = 63 - __clzll(heads & (~0ull >> (63 - lane)));
+            const int longest = longest_run(heads);
 #pragma unroll
-            for (int off = 1; off < dg::kWave; off <<= 1) {
+            for (int off = 1; off < longest; off <<= 1) {      // a run of length r is summed after ceil(log2 r) steps
                 const bool take = lane - off >= start;
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {

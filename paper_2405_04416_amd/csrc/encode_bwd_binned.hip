@@ -25,7 +25,8 @@ constexpr uint32_t kChunk = 1u << kChunkLog2;      // entries per bin
 constexpr int kMaxBins = 2048;                     // per level: 2^24 entries / 8192
 constexpr int kTile = 512;                         // samples per tile == threads per binning workgroup
 constexpr int kRecords = kTile * 8;
-constexpr int kBinGrid = 768;                      // persistent binning workgroups (three per compute unit)
+constexpr uint32_t kLdsKeys = 4096;                // (level, bin) cursors kept in LDS when there are at most this many
+constexpr int kBinGrid = 512;                      // persistent binning workgroups (two per compute unit)
 constexpr int kAccBlock = 1024;
 constexpr uint32_t kAccRecords = 1u << 18;          // records one accumulate workgroup sums
 constexpr int kCoarseBlock = 256;
@@ -147,13 +148,21 @@ bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 
     uint32_t *start = cnt + cap;                        // [cap]
     uint32_t *gbase = start + cap;                      // [cap]
     uint32_t *wave_tot = gbase + cap;                   // [16]
-    uint32_t *stage_e = wave_tot + 16;                  // [kRecords]   (FILL only)
-    float *stage_x = reinterpret_cast<float *>(stage_e + kRecords);
-    float *stage_y = stage_x + kRecords;
+    // staged records, 16 bytes each (entry, value bits, pad) so that one LDS access moves a record  (FILL only)
+    uint4 *stage = reinterpret_cast<uint4 *>(wave_tot + 16);
+    uint32_t *stage_end = reinterpret_cast<uint32_t *>(stage + (FILL ? kRecords : 0));     // [kLdsKeys]
 
     const uint32_t tid = threadIdx.x;
     const uint32_t mask = (1u << g.log2_T) - 1u;
-    uint32_t *row = rows + (size_t)blockIdx.x * plan.n_keys;
+    // this workgroup's counters (count sweep) / queue cursors (fill sweep), one per (level, bin): kept in LDS for
+    // the whole sweep when they fit, so the per-tile bookkeeping never waits on global memory
+    uint32_t *row_global = rows + (size_t)blockIdx.x * plan.n_keys;
+    const bool row_in_lds = plan.n_keys <= kLdsKeys;
+    uint32_t *row = row_in_lds ? stage_end : row_global;
+    if (row_in_lds) {
+        for (uint32_t i = tid; i < plan.n_keys; i += kTile) row[i] = FILL ? binbase[i] + row_global[i] : 0u;
+        __syncthreads();
+    }
     const uint64_t n_tiles = (nb + kTile - 1) / kTile;
     for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const uint64_t rel = tile * kTile + tid;
@@ -194,9 +203,9 @@ bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 
             }
             block_exclusive_scan(cnt, start, n_bins, wave_tot);
             for (uint32_t i = tid; i < n_bins; i += kTile) {
-                const uint32_t mine = row[key0 + i];
-                gbase[i] = binbase[key0 + i] + mine;
-                row[key0 + i] = mine + cnt[i];
+                const uint32_t mine = row[key0 + i] + (row_in_lds ? 0u : binbase[key0 + i]);
+                gbase[i] = mine - start[i];                          // queue position of staged slot s is gbase[bin] + s
+                row[key0 + i] += cnt[i];
             }
             {
                 corner_weights(frac, w);
@@ -205,8 +214,9 @@ bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 
                 for (int c = 0; c < 8; ++c) { vx[c] = w[c] * gfe.x; vy[c] = w[c] * gfe.y; }
                 if (merge) {
                     const int first = 63 - __clzll(heads & (~0ull >> (63 - lane)));
+                    const int longest = longest_run(heads);
 #pragma unroll
-                    for (int off = 1; off < dg::kWave; off <<= 1) {
+                    for (int off = 1; off < longest; off <<= 1) {      // a run of length r is summed after ceil(log2 r) steps
                         const bool take = lane - off >= first;
 #pragma unroll
                         for (int c = 0; c < 8; ++c) {
@@ -219,24 +229,25 @@ bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 
 #pragma unroll
                     for (int c = 0; c < 8; ++c) {
                         const uint32_t slot = start[e[c] >> kChunkLog2] + rank[c];
-                        stage_e[slot] = e[c];
-                        stage_x[slot] = vx[c];
-                        stage_y[slot] = vy[c];
+                        stage[slot] = make_uint4(e[c], __float_as_uint(vx[c]), __float_as_uint(vy[c]), 0u);
                     }
                 }
             }
             __syncthreads();
             const uint32_t total = start[n_bins - 1] + cnt[n_bins - 1];
             for (uint32_t s = tid; s < total; s += kTile) {
-                const uint32_t ee = stage_e[s], bin = ee >> kChunkLog2;
-                const size_t dst = (size_t)gbase[bin] + (s - start[bin]);
+                const uint4 rec = stage[s];
+                const uint32_t ee = rec.x, bin = ee >> kChunkLog2;
+                const size_t dst = (size_t)(gbase[bin] + s);
                 q_idx[dst] = (uint16_t)(ee & (kChunk - 1u));
-                q_vx[dst] = stage_x[s];
-                q_vy[dst] = stage_y[s];
+                q_vx[dst] = __uint_as_float(rec.y);
+                q_vy[dst] = __uint_as_float(rec.z);
             }
             __syncthreads();
         }
     }
+    if (!FILL && row_in_lds)
+        for (uint32_t i = tid; i < plan.n_keys; i += kTile) row_global[i] = row[i];
 }
 
 // rows[b][k] (per-workgroup counts) -> exclusive prefix over workgroups; totals[k]
@@ -413,7 +424,7 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     const Plan p = make_plan(d);
     static bool lds_opt_in = false;
     if (!lds_opt_in) {
-        const int fill_lds = (3 * kMaxBins + 16 + 3 * kRecords) * 4;      // the most a launch may ask for
+        const int fill_lds = (3 * kMaxBins + 16 + 4 * kRecords + (int)kLdsKeys) * 4;      // the most a launch may ask for
         hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(&bin_kernel<true>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds);
         if (e1 != hipSuccess) return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot reserve %d bytes of LDS: %s", fill_lds,
@@ -452,7 +463,8 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     float *q_vx = reinterpret_cast<float *>(base + L.q_vx);
     float *q_vy = reinterpret_cast<float *>(base + L.q_vy);
     const size_t n_rows_words = (size_t)kBinGrid * p.n_keys;
-    const int count_lds = (3 * (int)p.max_bins + 16) * 4, fill_lds = (3 * (int)p.max_bins + 16 + 3 * kRecords) * 4;
+    const int keys_lds = p.n_keys <= kLdsKeys ? (int)p.n_keys : 0;
+    const int count_lds = (3 * (int)p.max_bins + 16 + keys_lds) * 4, fill_lds = (3 * (int)p.max_bins + 16 + 4 * kRecords + keys_lds) * 4;
 
     for (uint64_t n0 = 0; n0 < N; n0 += batch) {
         const uint64_t nb = N - n0 < batch ? N - n0 : batch;

@@ -67,4 +67,13 @@ __device__ __forceinline__ void corner_weights(const float frac[3], float w[8])
 }
 
 
+// length of the longest run of lanes that share a cell, from the mask of run heads (wavefront-uniform)
+__device__ __forceinline__ int longest_run(unsigned long long heads)
+{
+    unsigned long long inner = ~heads;      // lanes that continue a run
+    int len = 1;
+    while (inner) { inner &= inner << 1; ++len; }
+    return len;
+}
+
 }  // namespace dg_encode
