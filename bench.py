@@ -21,6 +21,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA, published
 
+# HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (scaled by a known elementwise kernel), summed over the
+# kernels an entry point launches; measured once per workload and recorded in profiles/<workload>_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = {
+    "c2_ngp": {"dg_hashgrid_encode_bwd": 21.1e9, "dg_hashgrid_encode_fwd": 7.51e9, "dg_mlp_fwd": 1.08e9, "dg_mlp_bwd": 4.54e9},
+}
+
 
 def algorithmic_work(entry, L, F, n_samples, mlp_flops_fwd):
     """(bound, units of work per launch) for an entry point; bytes for HBM-bound ones, flops for the MLPs.
@@ -50,6 +56,9 @@ def main():
     ap.add_argument("--workload", default="c2_ngp")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rays", type=int, default=16384)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="after the timed region, stream 1 GiB through one elementwise kernel (known traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not available. "
@@ -67,9 +76,28 @@ def main():
     dev = torch.device("cuda:0")
     cfg = di.config(args.workload)
     g, m = cfg["grid"], cfg["mlp"]
-    R, S, k_max, P = cfg["R"], cfg["S"], cfg["k_max"], cfg["parts"].shape[0]
-    resident = [cfg["resident"]] if "resident" in cfg else list(range(P))
+    R, S, k_max = cfg["R"], cfg["S"], cfg["k_max"]
     to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    foreign = None
+    if "resident" in cfg:
+        # one GPU's share of a larger tiling: only the resident box is traced; for a seeded fraction of the rays
+        # 1..k_max-1 partials of other partitions are synthetic (colour, transmittance) pairs placed around the local one
+        cfg["parts"] = cfg["parts"][cfg["resident"]:cfg["resident"] + 1]
+        cfg["rays"] = "oblique"
+        before, after, fC, fT = di.make_extra_partials(R, k_max, cfg["extra_fraction"], seed=0)
+        before_d, total_d = to_dev(before.astype(np.int64)), to_dev((before + after + 1).astype(np.int32))
+        fC_d, fT_d = to_dev(fC), to_dev(fT)
+
+        def foreign(st):
+            n = st.offsets[1]
+            ray = st.seg_ray[:n].long()
+            loc_c, loc_t = st.Ck[ray, 0].clone(), st.Tk[ray, 0].clone()
+            st.Ck.copy_(fC_d); st.Tk.copy_(fT_d)
+            st.Ck[ray, before_d[ray]] = loc_c; st.Tk[ray, before_d[ray]] = loc_t
+            st.seg_slot[:n] = before_d[ray].int()
+            st.seg_count.mul_(total_d)
+    P = cfg["parts"].shape[0]
+    resident = list(range(P))
 
     # seeded synthetic inputs, moved to HBM before anything is timed
     o, d = di.make_rays(cfg, seed=0)
@@ -89,19 +117,26 @@ def main():
 
     for w in range(args.warmup):
         step.seed = w
-        step.step(od, dd, Cd)
+        step.step(od, dd, Cd, None, foreign)
     torch.cuda.synchronize()
     step.timings = {}
     t0 = time.perf_counter()
     for k in range(args.steps):
         step.seed = args.warmup + k            # fresh jitter every step, drawn inside the sampling kernel
-        step.step(od, dd, Cd)
+        step.step(od, dd, Cd, None, foreign)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = 1e3 * wall / args.steps
-    n_seg = step.offsets[-1]
+    n_seg = sum(step.offsets[p + 1] - step.offsets[p] for p in resident)
     n_samples = n_seg * S
     per_call = step.timing_summary()           # HIP events on the launch stream, inside the timed region
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1.0, out=dst)           # 1 GiB read + 1 GiB written by one plain elementwise kernel
+        torch.cuda.synchronize()
 
     shapes = di.mlp_layer_shapes(n_feat, m)
     mlp_flops_fwd = 2 * sum(no * ni for no, ni in shapes)
@@ -111,17 +146,19 @@ def main():
     avg_ms = total_ms / calls
     per_launch_samples = n_samples / max(len(resident), 1)
     bound, work = algorithmic_work(dominant, g["L"], g["F"], per_launch_samples, mlp_flops_fwd)
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dominant)
     if work is None:
         roofline = {"kernel": dominant, "bound": bound, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": None, "traffic": None, "avg_launch_ms": round(avg_ms, 4)}
     elif bound == "hbm":
         ach = work / (avg_ms * 1e-3) / 1e9
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None, "avg_launch_ms": round(avg_ms, 4)}
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic, "algorithmic_bytes": work,
+                    "avg_launch_ms": round(avg_ms, 4)}
     else:
         ach = work / (avg_ms * 1e-3) / 1e12
         roofline = {"kernel": dominant, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_F16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(ach / MFMA_F16_PEAK_TFLOPS, 4), "traffic": None,
+                    "unit": "TFLOP/s", "frac": round(ach / MFMA_F16_PEAK_TFLOPS, 4), "traffic": traffic,
                     "avg_launch_ms": round(avg_ms, 4)}
     # the other headline kernels, same accounting
     others = {}
@@ -139,7 +176,7 @@ def main():
         Rc = min(args.cpu_rays, R)
         hm = ostep.make_models(dict(cfg, resident_list=resident), seed=0)
         t1 = time.perf_counter()
-        ostep.run_step(cfg, hm, o[:Rc], d[:Rc], Cgt[:Rc], seed=0, lambda1=1e-3, loss_scale=65536.0, resident=resident)
+        ostep.run_step(cfg, hm, o[:Rc], d[:Rc], Cgt[:Rc], seed=0, lambda1=1e-3, loss_scale=65536.0, resident=resident)   # (without the synthetic foreign partials)
         cpu_s = time.perf_counter() - t1
         cpu = {"value": round(Rc / cpu_s, 2), "unit": "rays/s", "cores": 1, "kind": "oracle",
                "sample": "first %d rays of the same batch, full-size tables, one fwd+bwd pass, %.1f s" % (Rc, cpu_s)}
