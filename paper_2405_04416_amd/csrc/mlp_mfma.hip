@@ -200,7 +200,7 @@ __device__ __forceinline__ void load_inputs(const __half *feat, const __half *di
     }
 }
 
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kBlock, 2)
 fwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, const __half *__restrict__ dir_enc,
            uint32_t S, uint64_t n_samples, uint32_t act_c, float *__restrict__ sigma, float *__restrict__ rgb)
 {
