@@ -317,23 +317,25 @@ accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbas
     const size_t end = min(begin + (size_t)kAccRecords, (size_t)binbase[key + 1]);
     for (uint32_t i = threadIdx.x; i < 2 * kChunk; i += kAccBlock) tab[i] = 0.0;
     __syncthreads();
-    // four records in flight per thread so that the queue streams at memory speed
-    for (size_t i0 = begin + threadIdx.x; i0 < end; i0 += 4 * kAccBlock) {
-        uint32_t e[4];
-        float x[4], y[4];
+    // eight records in flight per thread so that the queue streams at memory speed: the loads are unconditional
+    // (index clamped into the range) so that they issue back to back; a clamped duplicate adds 0
+    if (begin < end) {
+        const size_t last = end - 1;
+        for (size_t i0 = begin + threadIdx.x; i0 < end; i0 += 8 * kAccBlock) {
+            uint32_t e[8];
+            float x[8], y[8];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const size_t i = i0 + (size_t)k * kAccBlock;
-            const bool ok = i < end;
-            e[k] = ok ? q_idx[i] : 0u;
-            x[k] = ok ? q_vx[i] : 0.0f;
-            y[k] = ok ? q_vy[i] : 0.0f;
-        }
+            for (int k = 0; k < 8; ++k) {
+                const size_t want = i0 + (size_t)k * kAccBlock, i = want < last ? want : last;
+                e[k] = q_idx[i];
+                x[k] = q_vx[i];
+                y[k] = q_vy[i];
+            }
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if (i0 + (size_t)k * kAccBlock < end) {
-                __hip_atomic_fetch_add(&tab[2 * e[k]], (double)x[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                __hip_atomic_fetch_add(&tab[2 * e[k] + 1], (double)y[k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            for (int k = 0; k < 8; ++k) {
+                const bool ok = i0 + (size_t)k * kAccBlock < end;
+                __hip_atomic_fetch_add(&tab[2 * e[k]], ok ? (double)x[k] : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(&tab[2 * e[k] + 1], ok ? (double)y[k] : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
     }
