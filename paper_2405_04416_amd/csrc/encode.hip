@@ -83,18 +83,8 @@ encode_bwd_kernel(dg_grid_desc g, const float *__restrict__ u, const float2 *__r
         for (int c = 0; c < 8; ++c) { vx[c] = w[c] * gfe.x; vy[c] = w[c] * gfe.y; }
 
         if (__popcll(heads) <= 40) {
-            const int start = 63 - __clzll(heads & (~0ull >> (63 - lane)));
-            const int longest = longest_run(heads);
-#pragma unroll
-            for (int off = 1; off < longest; off <<= 1) {      // a run of length r is summed after ceil(log2 r) steps
-                const bool take = lane - off >= start;
-#pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    const float tx = __shfl_up(vx[c], off, dg::kWave), ty = __shfl_up(vy[c], off, dg::kWave);
-                    if (take) { vx[c] += tx; vy[c] += ty; }
-                }
-            }
-            const bool tail = lane == dg::kWave - 1 || ((heads >> (lane + 1)) & 1ull);
+            segmented_sum(vx, vy, head, heads);
+            const bool tail = lane == dg::kWave - 1 || ((heads >> ((lane + 1) & 63)) & 1ull);
             if (tail) {
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {

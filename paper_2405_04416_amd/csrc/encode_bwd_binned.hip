@@ -29,8 +29,8 @@ constexpr uint32_t kLdsKeys = 4096;                // (level, bin) cursors kept 
 constexpr int kBinGrid = 512;                      // persistent binning workgroups (two per compute unit)
 constexpr int kAccBlock = 1024;
 constexpr uint32_t kAccRecords = 1u << 18;          // records one accumulate workgroup sums
-constexpr int kCoarseBlock = 256;
-constexpr int kCoarseGrid = 1024;
+constexpr int kCoarseBlock = 1024;
+constexpr int kCoarseGrid = 256;
 
 struct Plan {
     uint32_t first_level;                  // levels below are accumulated directly in LDS
@@ -76,21 +76,10 @@ coarse_kernel(dg_grid_desc g, uint32_t first_level, const float *__restrict__ u,
 #pragma unroll
             for (int a = 0; a < 3; ++a) head |= __shfl_up(cell[a], 1, dg::kWave) != cell[a];
             const unsigned long long heads = __ballot(head);
-            const int start = 63 - __clzll(heads & (~0ull >> (63 - lane)));
             float vx[8], vy[8];
 #pragma unroll
             for (int c = 0; c < 8; ++c) { vx[c] = w[c] * gfe.x; vy[c] = w[c] * gfe.y; }
-            if (__popcll(heads) < dg::kWave) {       // some lanes share a cell: merge each run into its last lane
-#pragma unroll
-                for (int off = 1; off < dg::kWave; off <<= 1) {
-                    const bool take = lane - off >= start;
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) {
-                        const float tx = __shfl_up(vx[c], off, dg::kWave), ty = __shfl_up(vy[c], off, dg::kWave);
-                        if (take) { vx[c] += tx; vy[c] += ty; }
-                    }
-                }
-            }
+            if (__popcll(heads) < dg::kWave) segmented_sum(vx, vy, head, heads);     // merge each run into its last lane
             const bool tail = lane == dg::kWave - 1 || ((heads >> ((lane + 1) & 63)) & 1ull);
             if (tail) {
 #pragma unroll
@@ -212,36 +201,38 @@ bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 
                 float vx[8], vy[8];
 #pragma unroll
                 for (int c = 0; c < 8; ++c) { vx[c] = w[c] * gfe.x; vy[c] = w[c] * gfe.y; }
-                if (merge) {
-                    const int first = 63 - __clzll(heads & (~0ull >> (63 - lane)));
-                    const int longest = longest_run(heads);
-#pragma unroll
-                    for (int off = 1; off < longest; off <<= 1) {      // a run of length r is summed after ceil(log2 r) steps
-                        const bool take = lane - off >= first;
-#pragma unroll
-                        for (int c = 0; c < 8; ++c) {
-                            const float tx = __shfl_up(vx[c], off, dg::kWave), ty = __shfl_up(vy[c], off, dg::kWave);
-                            if (take) { vx[c] += tx; vy[c] += ty; }
-                        }
-                    }
-                }
+                if (merge) segmented_sum(vx, vy, head, heads);
                 if (emit) {
+                    uint32_t slot[8];
 #pragma unroll
-                    for (int c = 0; c < 8; ++c) {
-                        const uint32_t slot = start[e[c] >> kChunkLog2] + rank[c];
-                        stage[slot] = make_uint4(e[c], __float_as_uint(vx[c]), __float_as_uint(vy[c]), 0u);
-                    }
+                    for (int c = 0; c < 8; ++c) slot[c] = start[e[c] >> kChunkLog2];
+#pragma unroll
+                    for (int c = 0; c < 8; ++c)
+                        stage[slot[c] + rank[c]] = make_uint4(e[c], __float_as_uint(vx[c]), __float_as_uint(vy[c]), 0u);
                 }
             }
             __syncthreads();
             const uint32_t total = start[n_bins - 1] + cnt[n_bins - 1];
-            for (uint32_t s = tid; s < total; s += kTile) {
-                const uint4 rec = stage[s];
-                const uint32_t ee = rec.x, bin = ee >> kChunkLog2;
-                const size_t dst = (size_t)(gbase[bin] + s);
-                q_idx[dst] = (uint16_t)(ee & (kChunk - 1u));
-                q_vx[dst] = __uint_as_float(rec.y);
-                q_vy[dst] = __uint_as_float(rec.z);
+            // copy the staged, bin-sorted records out; four per thread in flight, reads clamped so they batch
+            if (total > 0) {
+                for (uint32_t s0 = tid; s0 < total; s0 += 4 * kTile) {
+                    uint4 rec[4];
+                    uint32_t base[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) rec[k] = stage[min(s0 + k * kTile, total - 1u)];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) base[k] = gbase[rec[k].x >> kChunkLog2];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const uint32_t s = s0 + k * kTile;
+                        if (s < total) {
+                            const size_t dst = (size_t)(base[k] + s);
+                            q_idx[dst] = (uint16_t)(rec[k].x & (kChunk - 1u));
+                            q_vx[dst] = __uint_as_float(rec[k].y);
+                            q_vy[dst] = __uint_as_float(rec[k].z);
+                        }
+                    }
+                }
             }
             __syncthreads();
         }

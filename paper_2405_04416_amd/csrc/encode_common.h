@@ -76,4 +76,36 @@ __device__ __forceinline__ int longest_run(unsigned long long heads)
     return len;
 }
 
+// ---- segmented sum over the wavefront with DPP moves (no LDS traffic, no waits) ----------------------
+// Lanes form runs (a run starts where `head` is set; lane 0 always starts one).  After the call the last
+// lane of every run holds the sum of that run's 16 values.  One step combines each lane with a lane
+// further down: (v, f) <- (f ? v : v + v_src, f | f_src), f meaning "a run start lies in the span summed so
+// far".  Steps: row_shr 1, 2, 4, 8 inside rows of 16 lanes, then row_bcast:15 into rows 1 and 3 and
+// row_bcast:31 into rows 2 and 3 -- the classic wavefront scan, made segment-aware.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void seg_step(float (&vx)[8], float (&vy)[8], int &f)
+{
+    const int fs = __builtin_amdgcn_update_dpp(0, f, CTRL, ROW_MASK, 0xF, true);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        const float tx = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(vx[c]), CTRL, ROW_MASK, 0xF, true));
+        const float ty = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(vy[c]), CTRL, ROW_MASK, 0xF, true));
+        vx[c] += f ? 0.0f : tx;
+        vy[c] += f ? 0.0f : ty;
+    }
+    f |= fs;
+}
+
+__device__ __forceinline__ void segmented_sum(float (&vx)[8], float (&vy)[8], bool head, unsigned long long heads)
+{
+    int f = head ? 1 : 0;
+    const int longest = longest_run(heads);         // wavefront-uniform: steps a run of that length cannot need are skipped
+    if (longest > 1) seg_step<0x111, 0xF>(vx, vy, f);
+    if (longest > 2) seg_step<0x112, 0xF>(vx, vy, f);
+    if (longest > 4) seg_step<0x114, 0xF>(vx, vy, f);
+    if (longest > 8) seg_step<0x118, 0xF>(vx, vy, f);
+    if (!((heads >> 16) & 1ull) || !((heads >> 48) & 1ull)) seg_step<0x142, 0xA>(vx, vy, f);
+    if (!((heads >> 32) & 1ull)) seg_step<0x143, 0xC>(vx, vy, f);
+}
+
 }  // namespace dg_encode
