@@ -241,6 +241,168 @@ bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 
         for (uint32_t i = tid; i < plan.n_keys; i += kTile) row_global[i] = row[i];
 }
 
+// ---- sweeps for grids whose levels all have at most 64 bins: the bookkeeping of a level fits one register per lane
+// Which records a sample emits at a level (both sweeps take the same decision from the same data).  A wavefront
+// holds 64 consecutive samples of a ray; lanes that share a cell form a run whose 16 values are summed into the
+// run's last lane, which alone emits records.  Skipped where runs are short.
+struct Emission {
+    uint32_t e[8];
+    float frac[3];
+    unsigned long long heads;
+    bool head, merge, emit;
+};
+
+__device__ __forceinline__ Emission classify(const LevelGeom &lv, uint32_t mask, const float (&uu)[3], bool live, int lane)
+{
+    Emission o;
+    uint32_t cell[3];
+    locate(lv, uu, cell, o.frac);
+    corner_entries(lv, mask, cell, o.e);
+    o.head = lane == 0 || !live;
+#pragma unroll
+    for (int a = 0; a < 3; ++a) o.head |= __shfl_up(cell[a], 1, dg::kWave) != cell[a];
+    o.heads = __ballot(o.head);
+    o.merge = __popcll(o.heads) <= 44;
+    const bool tail = lane == dg::kWave - 1 || ((o.heads >> ((lane + 1) & 63)) & 1ull);
+    o.emit = live && (!o.merge || tail);
+    return o;
+}
+
+// count sweep with this workgroup's counters in LDS: one LDS add per record, no barriers inside the sweep
+__global__ void __launch_bounds__(kTile)
+count_lds_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, uint64_t n0, uint64_t nb, uint32_t *__restrict__ rows)
+{
+    extern __shared__ uint32_t smem[];
+    uint32_t *row = smem;                                // [n_keys]
+    const uint32_t tid = threadIdx.x;
+    const int lane = tid % dg::kWave;
+    const uint32_t mask = (1u << g.log2_T) - 1u;
+    for (uint32_t i = tid; i < plan.n_keys; i += kTile) row[i] = 0u;
+    __syncthreads();
+    const uint64_t n_tiles = (nb + kTile - 1) / kTile;
+    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint64_t rel = tile * kTile + tid;
+        const bool live = rel < nb;
+        const uint64_t n = n0 + (live ? rel : nb - 1);
+        const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
+        for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
+            const Emission em = classify(level_of(g, l), mask, uu, live, lane);
+            if (em.emit) {
+                uint32_t *c = row + plan.key_base[l];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) atomicAdd(&c[em.e[k] >> kChunkLog2], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t *row_global = rows + (size_t)blockIdx.x * plan.n_keys;
+    for (uint32_t i = tid; i < plan.n_keys; i += kTile) row_global[i] = row[i];
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void scan_step(uint32_t &v)
+{
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, true);
+}
+
+// inclusive prefix sum over the wavefront (DPP moves: rows of 16 lanes, then across rows)
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
+{
+    scan_step<0x111, 0xF>(v);
+    scan_step<0x112, 0xF>(v);
+    scan_step<0x114, 0xF>(v);
+    scan_step<0x118, 0xF>(v);
+    scan_step<0x142, 0xA>(v);
+    scan_step<0x143, 0xC>(v);
+    return v;
+}
+
+// Fill sweep for at most 64 bins per level.  Every wavefront reads the 64 tile counters of the level and scans them
+// itself, so staging offsets and queue positions sit in one register per lane (lane == bin) and are fetched with
+// wavefront shuffles: two barriers per (tile, level) instead of six.  The tile counters are double-buffered so that
+// the buffer of the next level is cleared while this level is staged.
+__global__ void __launch_bounds__(kTile)
+fill64_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
+              uint64_t n0, uint64_t nb, const uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
+              uint16_t *__restrict__ q_idx, float *__restrict__ q_vx, float *__restrict__ q_vy)
+{
+    extern __shared__ uint32_t smem[];
+    uint32_t *cnt = smem;                                // [2][64]
+    uint32_t *row = cnt + 128;                           // [n_keys] this workgroup's queue cursors
+    uint4 *stage = reinterpret_cast<uint4 *>(row + (plan.n_keys + 3) / 4 * 4);      // [kRecords]
+    const uint32_t tid = threadIdx.x;
+    const int lane = tid % dg::kWave;
+    const uint32_t mask = (1u << g.log2_T) - 1u;
+    const uint32_t *row_global = rows + (size_t)blockIdx.x * plan.n_keys;
+    for (uint32_t i = tid; i < plan.n_keys; i += kTile) row[i] = binbase[i] + row_global[i];
+    if (tid < 128) cnt[tid] = 0u;
+    __syncthreads();
+    uint32_t parity = 0;
+    const uint64_t n_tiles = (nb + kTile - 1) / kTile;
+    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint64_t rel = tile * kTile + tid;
+        const bool live = rel < nb;
+        const uint64_t n = n0 + (live ? rel : nb - 1);
+        const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
+        for (uint32_t l = plan.first_level; l < g.n_levels; ++l, parity ^= 1u) {
+            uint32_t *c_cur = cnt + 64 * parity, *c_next = cnt + 64 * (parity ^ 1u);
+            const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
+            float2 gfe = dfeat[(size_t)l * N + n];                   // issued early: needed only after the barrier
+            if (!live) gfe = make_float2(0.0f, 0.0f);
+            const Emission em = classify(level_of(g, l), mask, uu, live, lane);
+            uint32_t rank[8];
+            if (em.emit) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) rank[c] = atomicAdd(&c_cur[em.e[c] >> kChunkLog2], 1u);
+            }
+            __syncthreads();
+            // lane b: records of bin b in this tile, their first staging slot, and where staged slot s of the bin
+            // goes in the queue (queue_base + s)
+            const uint32_t in_bin = c_cur[lane];
+            const uint32_t incl = wave_inclusive_scan(in_bin);
+            const uint32_t first_slot = incl - in_bin;
+            const uint32_t total = __shfl(incl, dg::kWave - 1, dg::kWave);
+            const uint32_t cursor = (uint32_t)lane < n_bins ? row[key0 + lane] : 0u;
+            const uint32_t queue_base = cursor - first_slot;
+            if (tid < dg::kWave) c_next[tid] = 0u;                   // last read two barriers ago
+            float w[8], vx[8], vy[8];
+            corner_weights(em.frac, w);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) { vx[c] = w[c] * gfe.x; vy[c] = w[c] * gfe.y; }
+            if (em.merge) segmented_sum(vx, vy, em.head, em.heads);
+            uint32_t slot[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) slot[c] = __shfl(first_slot, (int)(em.e[c] >> kChunkLog2), dg::kWave);
+            if (em.emit) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c)
+                    stage[slot[c] + rank[c]] = make_uint4(em.e[c], __float_as_uint(vx[c]), __float_as_uint(vy[c]), 0u);
+            }
+            __syncthreads();
+            if (tid < n_bins) row[key0 + tid] = cursor + in_bin;     // every wavefront read its copy before the barrier
+            // copy the staged, bin-sorted records out; four per thread in flight, reads clamped so they batch
+            for (uint32_t sb = 0; sb < total; sb += 4 * kTile) {
+                uint4 rec[4];
+                uint32_t base[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) rec[k] = stage[min(sb + tid + k * kTile, total - 1u)];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) base[k] = __shfl(queue_base, (int)(rec[k].x >> kChunkLog2), dg::kWave);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t s = sb + tid + k * kTile;
+                    if (s < total) {
+                        const size_t dst = (size_t)(base[k] + s);
+                        q_idx[dst] = (uint16_t)(rec[k].x & (kChunk - 1u));
+                        q_vx[dst] = __uint_as_float(rec[k].y);
+                        q_vy[dst] = __uint_as_float(rec[k].z);
+                    }
+                }
+            }
+        }
+    }
+}
+
 // rows[b][k] (per-workgroup counts) -> exclusive prefix over workgroups; totals[k]
 __global__ void __launch_bounds__(256)
 scan_rows_kernel(uint32_t *__restrict__ rows, uint32_t n_rows, uint32_t n_keys, uint32_t *__restrict__ totals)
@@ -420,6 +582,9 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
         const int fill_lds = (3 * kMaxBins + 16 + 4 * kRecords + (int)kLdsKeys) * 4;      // the most a launch may ask for
         hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(&bin_kernel<true>),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds);
+        if (e1 == hipSuccess)
+            e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(&fill64_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (128 + 16 * 64 + 4 * kRecords) * 4);
         if (e1 != hipSuccess) return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot reserve %d bytes of LDS: %s", fill_lds,
                                           hipGetErrorString(e1));
         const int acc_lds = 2 * kChunk * (int)sizeof(double);
@@ -458,14 +623,21 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     const size_t n_rows_words = (size_t)kBinGrid * p.n_keys;
     const int keys_lds = p.n_keys <= kLdsKeys ? (int)p.n_keys : 0;
     const int count_lds = (3 * (int)p.max_bins + 16 + keys_lds) * 4, fill_lds = (3 * (int)p.max_bins + 16 + 4 * kRecords + keys_lds) * 4;
+    const int fill64_lds = (128 + ((int)p.n_keys + 3) / 4 * 4 + 4 * kRecords) * 4;
 
     for (uint64_t n0 = 0; n0 < N; n0 += batch) {
         const uint64_t nb = N - n0 < batch ? N - n0 : batch;
         zero_u32_kernel<<<(uint32_t)((n_rows_words + 255) / 256), 256, 0, st>>>(rows, n_rows_words);
-        bin_kernel<false><<<kBinGrid, kTile, count_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
+        if (keys_lds)
+            count_lds_kernel<<<kBinGrid, kTile, keys_lds * 4, st>>>(*d, p, u, n0, nb, rows);
+        else
+            bin_kernel<false><<<kBinGrid, kTile, count_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
         scan_rows_kernel<<<(p.n_keys + 255) / 256, 256, 0, st>>>(rows, kBinGrid, p.n_keys, totals);
         scan_totals_kernel<<<1, 1024, 0, st>>>(totals, p.n_keys, binbase, blkbase);
-        bin_kernel<true><<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
+        if (p.max_bins <= 64)
+            fill64_kernel<<<kBinGrid, kTile, fill64_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
+        else
+            bin_kernel<true><<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
         const uint64_t records = nb * 8ull * (d->n_levels - p.first_level);
         const uint32_t acc_grid = (uint32_t)(records / kAccRecords) + p.n_keys;       // upper bound of the workgroups needed
         accumulate_kernel<<<acc_grid, kAccBlock, 2 * kChunk * sizeof(double), st>>>(*d, p, binbase, blkbase, q_idx, q_vx, q_vy, dtable);
