@@ -24,11 +24,12 @@ constexpr int kChunkLog2 = 13;
 constexpr uint32_t kChunk = 1u << kChunkLog2;      // entries per bin
 constexpr int kMaxBins = 2048;                     // per level: 2^24 entries / 8192
 constexpr int kTile = 512;                         // samples per tile == threads per binning workgroup
-constexpr int kRecords = kTile * 8;
-constexpr uint32_t kLdsKeys = 4096;                // (level, bin) cursors kept in LDS when there are at most this many
-constexpr int kBinGrid = 512;                      // persistent binning workgroups (two per compute unit)
+constexpr int kPairs = kTile * 4;                  // records staged per (tile, level): one per pair of corners along x
+constexpr uint32_t kLdsKeys = 4096;                // count sweep: (level, bin) counters kept in LDS when there are at most this many
+constexpr int kBinGrid = 768;                      // persistent binning workgroups (three per compute unit)
 constexpr int kAccBlock = 1024;
-constexpr uint32_t kAccRecords = 1u << 18;          // records one accumulate workgroup sums
+constexpr int kAccDepth = 4;                       // records in flight per accumulate thread
+constexpr uint32_t kAccRecords = 1u << 17;          // records one accumulate workgroup sums
 constexpr int kCoarseBlock = 1024;
 constexpr int kCoarseGrid = 256;
 
@@ -99,152 +100,16 @@ coarse_kernel(dg_grid_desc g, uint32_t first_level, const float *__restrict__ u,
 }
 
 // ------------------------------------------------------------------ binning sweeps
-// exclusive scan of cnt[0, n) into start[0, n) by the whole workgroup, 2 * kTile counters per round
-__device__ __forceinline__ void block_exclusive_scan(const uint32_t *cnt, uint32_t *start, uint32_t n, uint32_t *wave_tot)
-{
-    const uint32_t t = threadIdx.x, lane = t % dg::kWave, wave = t / dg::kWave;
-    uint32_t carry = 0;
-    for (uint32_t lo = 0; lo < n; lo += 2 * kTile) {
-        const uint32_t i0 = lo + 2 * t, i1 = i0 + 1;
-        const uint32_t a = i0 < n ? cnt[i0] : 0u, b = i1 < n ? cnt[i1] : 0u;
-        uint32_t incl = a + b;
-#pragma unroll
-        for (int off = 1; off < dg::kWave; off <<= 1) {
-            const uint32_t up = __shfl_up(incl, off, dg::kWave);
-            if ((int)lane >= off) incl += up;
-        }
-        if (lane == dg::kWave - 1) wave_tot[wave] = incl;
-        __syncthreads();
-        uint32_t base = carry, all = 0;
-        for (uint32_t w = 0; w < kTile / dg::kWave; ++w) { if (w < wave) base += wave_tot[w]; all += wave_tot[w]; }
-        const uint32_t excl = base + incl - (a + b);
-        if (i0 < n) start[i0] = excl;
-        if (i1 < n) start[i1] = excl + a;
-        carry += all;
-        __syncthreads();
-    }
-}
+// One record serves a pair of corners along x: (entry of corner 0 within the bin, entry of corner 1
+// within the bin, 4 values).  The two entries of a pair are neighbours in a dense level and differ only
+// in their low index bits in a hashed one, so they share a bin -- except where the pair straddles a bin
+// boundary (one pair in 8192 of a dense level).  Then the record carries corner 0 alone and corner 1 is
+// added to the table directly with global atomics; both sweeps see exactly four records per emitting
+// sample and level.
 
-template <bool FILL>
-__global__ void __launch_bounds__(kTile)
-bin_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
-           uint64_t n0, uint64_t nb, uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
-           uint16_t *__restrict__ q_idx, float *__restrict__ q_vx, float *__restrict__ q_vy)
-{
-    extern __shared__ uint32_t smem[];
-    const uint32_t cap = plan.max_bins;                 // largest bin count of any level
-    uint32_t *cnt = smem;                               // [cap]
-    uint32_t *start = cnt + cap;                        // [cap]
-    uint32_t *gbase = start + cap;                      // [cap]
-    uint32_t *wave_tot = gbase + cap;                   // [16]
-    // staged records, 16 bytes each (entry, value bits, pad) so that one LDS access moves a record  (FILL only)
-    uint4 *stage = reinterpret_cast<uint4 *>(wave_tot + 16);
-    uint32_t *stage_end = reinterpret_cast<uint32_t *>(stage + (FILL ? kRecords : 0));     // [kLdsKeys]
-
-    const uint32_t tid = threadIdx.x;
-    const uint32_t mask = (1u << g.log2_T) - 1u;
-    // this workgroup's counters (count sweep) / queue cursors (fill sweep), one per (level, bin): kept in LDS for
-    // the whole sweep when they fit, so the per-tile bookkeeping never waits on global memory
-    uint32_t *row_global = rows + (size_t)blockIdx.x * plan.n_keys;
-    const bool row_in_lds = plan.n_keys <= kLdsKeys;
-    uint32_t *row = row_in_lds ? stage_end : row_global;
-    if (row_in_lds) {
-        for (uint32_t i = tid; i < plan.n_keys; i += kTile) row[i] = FILL ? binbase[i] + row_global[i] : 0u;
-        __syncthreads();
-    }
-    const uint64_t n_tiles = (nb + kTile - 1) / kTile;
-    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const uint64_t rel = tile * kTile + tid;
-        const bool live = rel < nb;
-        const uint64_t n = n0 + (live ? rel : nb - 1);
-        const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
-        for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
-            const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
-            float2 gfe = make_float2(0.0f, 0.0f);
-            if (FILL && live) gfe = dfeat[(size_t)l * N + n];      // issued early: needed only after the two barriers below
-            for (uint32_t i = tid; i < n_bins; i += kTile) cnt[i] = 0u;
-            __syncthreads();
-            const LevelGeom lv = level_of(g, l);
-            uint32_t cell[3], e[8], rank[8];
-            float frac[3], w[8];
-            locate(lv, uu, cell, frac);
-            corner_entries(lv, mask, cell, e);
-            // A wavefront holds 64 consecutive samples of a ray; lanes that share a cell form a run whose
-            // 16 values are summed into the run's last lane, which alone emits records (both sweeps take
-            // the same decision from the same data).  Skipped where runs are short.
-            const int lane = tid % dg::kWave;
-            bool head = lane == 0 || !live;
-#pragma unroll
-            for (int a = 0; a < 3; ++a) head |= __shfl_up(cell[a], 1, dg::kWave) != cell[a];
-            const unsigned long long heads = __ballot(head);
-            const bool merge = __popcll(heads) <= 44;
-            const bool tail = lane == dg::kWave - 1 || ((heads >> ((lane + 1) & 63)) & 1ull);
-            const bool emit = live && (!merge || tail);
-            if (emit) {
-#pragma unroll
-                for (int c = 0; c < 8; ++c) rank[c] = atomicAdd(&cnt[e[c] >> kChunkLog2], 1u);
-            }
-            __syncthreads();
-            if (!FILL) {
-                for (uint32_t i = tid; i < n_bins; i += kTile) row[key0 + i] += cnt[i];
-                __syncthreads();
-                continue;
-            }
-            block_exclusive_scan(cnt, start, n_bins, wave_tot);
-            for (uint32_t i = tid; i < n_bins; i += kTile) {
-                const uint32_t mine = row[key0 + i] + (row_in_lds ? 0u : binbase[key0 + i]);
-                gbase[i] = mine - start[i];                          // queue position of staged slot s is gbase[bin] + s
-                row[key0 + i] += cnt[i];
-            }
-            {
-                corner_weights(frac, w);
-                float vx[8], vy[8];
-#pragma unroll
-                for (int c = 0; c < 8; ++c) { vx[c] = w[c] * gfe.x; vy[c] = w[c] * gfe.y; }
-                if (merge) segmented_sum(vx, vy, head, heads);
-                if (emit) {
-                    uint32_t slot[8];
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) slot[c] = start[e[c] >> kChunkLog2];
-#pragma unroll
-                    for (int c = 0; c < 8; ++c)
-                        stage[slot[c] + rank[c]] = make_uint4(e[c], __float_as_uint(vx[c]), __float_as_uint(vy[c]), 0u);
-                }
-            }
-            __syncthreads();
-            const uint32_t total = start[n_bins - 1] + cnt[n_bins - 1];
-            // copy the staged, bin-sorted records out; four per thread in flight, reads clamped so they batch
-            if (total > 0) {
-                for (uint32_t s0 = tid; s0 < total; s0 += 4 * kTile) {
-                    uint4 rec[4];
-                    uint32_t base[4];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) rec[k] = stage[min(s0 + k * kTile, total - 1u)];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) base[k] = gbase[rec[k].x >> kChunkLog2];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const uint32_t s = s0 + k * kTile;
-                        if (s < total) {
-                            const size_t dst = (size_t)(base[k] + s);
-                            q_idx[dst] = (uint16_t)(rec[k].x & (kChunk - 1u));
-                            q_vx[dst] = __uint_as_float(rec[k].y);
-                            q_vy[dst] = __uint_as_float(rec[k].z);
-                        }
-                    }
-                }
-            }
-            __syncthreads();
-        }
-    }
-    if (!FILL && row_in_lds)
-        for (uint32_t i = tid; i < plan.n_keys; i += kTile) row_global[i] = row[i];
-}
-
-// ---- sweeps for grids whose levels all have at most 64 bins: the bookkeeping of a level fits one register per lane
-// Which records a sample emits at a level (both sweeps take the same decision from the same data).  A wavefront
-// holds 64 consecutive samples of a ray; lanes that share a cell form a run whose 16 values are summed into the
-// run's last lane, which alone emits records.  Skipped where runs are short.
+// Which records a sample emits at a level (both sweeps take the same decision from the same data).  A
+// wavefront holds 64 consecutive samples of a ray; lanes that share a cell form a run whose 16 values are
+// summed into the run's last lane, which alone emits records.  Skipped where runs are short.
 struct Emission {
     uint32_t e[8];
     float frac[3];
@@ -290,13 +155,72 @@ count_lds_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, uint64_
             if (em.emit) {
                 uint32_t *c = row + plan.key_base[l];
 #pragma unroll
-                for (int k = 0; k < 8; ++k) atomicAdd(&c[em.e[k] >> kChunkLog2], 1u);
+                for (int p = 0; p < 4; ++p) atomicAdd(&c[em.e[2 * p] >> kChunkLog2], 1u);
             }
         }
     }
     __syncthreads();
     uint32_t *row_global = rows + (size_t)blockIdx.x * plan.n_keys;
     for (uint32_t i = tid; i < plan.n_keys; i += kTile) row_global[i] = row[i];
+}
+
+// count sweep with the counters of one level in LDS and this workgroup's row of all (level, bin) counters in
+// global memory (grids with too many bins for LDS)
+__global__ void __launch_bounds__(kTile)
+count_global_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, uint64_t n0, uint64_t nb, uint32_t *__restrict__ rows)
+{
+    extern __shared__ uint32_t smem[];
+    uint32_t *cnt = smem;                                // [max_bins]
+    const uint32_t tid = threadIdx.x;
+    const int lane = tid % dg::kWave;
+    const uint32_t mask = (1u << g.log2_T) - 1u;
+    uint32_t *row = rows + (size_t)blockIdx.x * plan.n_keys;
+    const uint64_t n_tiles = (nb + kTile - 1) / kTile;
+    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint64_t rel = tile * kTile + tid;
+        const bool live = rel < nb;
+        const uint64_t n = n0 + (live ? rel : nb - 1);
+        const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
+        for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
+            const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
+            for (uint32_t i = tid; i < n_bins; i += kTile) cnt[i] = 0u;
+            __syncthreads();
+            const Emission em = classify(level_of(g, l), mask, uu, live, lane);
+            if (em.emit) {
+#pragma unroll
+                for (int p = 0; p < 4; ++p) atomicAdd(&cnt[em.e[2 * p] >> kChunkLog2], 1u);
+            }
+            __syncthreads();
+            for (uint32_t i = tid; i < n_bins; i += kTile) row[key0 + i] += cnt[i];
+            __syncthreads();
+        }
+    }
+}
+
+// exclusive scan of cnt[0, n) into start[0, n) by the whole workgroup, 2 * kTile counters per round
+__device__ __forceinline__ void block_exclusive_scan(const uint32_t *cnt, uint32_t *start, uint32_t n, uint32_t *wave_tot)
+{
+    const uint32_t t = threadIdx.x, lane = t % dg::kWave, wave = t / dg::kWave;
+    uint32_t carry = 0;
+    for (uint32_t lo = 0; lo < n; lo += 2 * kTile) {
+        const uint32_t i0 = lo + 2 * t, i1 = i0 + 1;
+        const uint32_t a = i0 < n ? cnt[i0] : 0u, b = i1 < n ? cnt[i1] : 0u;
+        uint32_t incl = a + b;
+#pragma unroll
+        for (int off = 1; off < dg::kWave; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off, dg::kWave);
+            if ((int)lane >= off) incl += up;
+        }
+        if (lane == dg::kWave - 1) wave_tot[wave] = incl;
+        __syncthreads();
+        uint32_t base = carry, all = 0;
+        for (uint32_t w = 0; w < kTile / dg::kWave; ++w) { if (w < wave) base += wave_tot[w]; all += wave_tot[w]; }
+        const uint32_t excl = base + incl - (a + b);
+        if (i0 < n) start[i0] = excl;
+        if (i1 < n) start[i1] = excl + a;
+        carry += all;
+        __syncthreads();
+    }
 }
 
 template <int CTRL, int ROW_MASK>
@@ -317,26 +241,38 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
     return v;
 }
 
-// Fill sweep for at most 64 bins per level.  Every wavefront reads the 64 tile counters of the level and scans them
-// itself, so staging offsets and queue positions sit in one register per lane (lane == bin) and are fetched with
-// wavefront shuffles: two barriers per (tile, level) instead of six.  The tile counters are double-buffered so that
-// the buffer of the next level is cleared while this level is staged.
+// Fill sweep.  Per (tile, level): every emitting lane takes a rank in its records' bins (LDS counters), the
+// counters are scanned into staging offsets, the records are staged in LDS sorted by bin and then copied to
+// the queues, so that every bin receives contiguous runs.
+//   kWide == false (at most 64 bins in every level): every wavefront reads the 64 tile counters and scans them
+//     itself, so staging offsets and queue positions sit in one register per lane (lane == bin) and are fetched
+//     with wavefront shuffles -- two barriers per (tile, level); the tile counters are double-buffered so that
+//     the buffer of the next level is cleared while this level is staged; the queue cursors live in LDS.
+//   kWide == true: counters, offsets and positions in LDS arrays, workgroup-wide scan, cursors in global memory.
+template <bool kWide>
 __global__ void __launch_bounds__(kTile)
-fill64_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
-              uint64_t n0, uint64_t nb, const uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
-              uint16_t *__restrict__ q_idx, float *__restrict__ q_vx, float *__restrict__ q_vy)
+fill_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
+            uint64_t n0, uint64_t nb, uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
+            uint32_t *__restrict__ q_idx, float4 *__restrict__ q_val, float *__restrict__ dtable)
 {
     extern __shared__ uint32_t smem[];
-    uint32_t *cnt = smem;                                // [2][64]
-    uint32_t *row = cnt + 128;                           // [n_keys] this workgroup's queue cursors
-    uint4 *stage = reinterpret_cast<uint4 *>(row + (plan.n_keys + 3) / 4 * 4);      // [kRecords]
+    const uint32_t cap = plan.max_bins;
+    uint32_t *cnt = smem;                                             // narrow [2][64], wide [cap]
+    uint32_t *start = cnt + (kWide ? cap : 128u);                     // wide [cap]
+    uint32_t *gbase = start + (kWide ? cap : 0u);                     // wide [cap]
+    uint32_t *wave_tot = gbase + (kWide ? cap : 0u);                  // wide [16]
+    uint32_t *row = wave_tot + (kWide ? 16u : 0u);                    // narrow [n_keys]: this workgroup's queue cursors
+    uint4 *stage0 = reinterpret_cast<uint4 *>(row + (kWide ? 0u : (plan.n_keys + 3u) / 4u * 4u));   // [kPairs] entry, entry, 2 values
+    uint2 *stage1 = reinterpret_cast<uint2 *>(stage0 + kPairs);                                    // [kPairs] 2 values
     const uint32_t tid = threadIdx.x;
     const int lane = tid % dg::kWave;
     const uint32_t mask = (1u << g.log2_T) - 1u;
-    const uint32_t *row_global = rows + (size_t)blockIdx.x * plan.n_keys;
-    for (uint32_t i = tid; i < plan.n_keys; i += kTile) row[i] = binbase[i] + row_global[i];
-    if (tid < 128) cnt[tid] = 0u;
-    __syncthreads();
+    uint32_t *row_global = rows + (size_t)blockIdx.x * plan.n_keys;
+    if (!kWide) {
+        for (uint32_t i = tid; i < plan.n_keys; i += kTile) row[i] = binbase[i] + row_global[i];
+        if (tid < 128) cnt[tid] = 0u;
+        __syncthreads();
+    }
     uint32_t parity = 0;
     const uint64_t n_tiles = (nb + kTile - 1) / kTile;
     for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -345,60 +281,97 @@ fill64_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const floa
         const uint64_t n = n0 + (live ? rel : nb - 1);
         const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
         for (uint32_t l = plan.first_level; l < g.n_levels; ++l, parity ^= 1u) {
-            uint32_t *c_cur = cnt + 64 * parity, *c_next = cnt + 64 * (parity ^ 1u);
+            uint32_t *c_cur = kWide ? cnt : cnt + 64u * parity;
             const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
             float2 gfe = dfeat[(size_t)l * N + n];                   // issued early: needed only after the barrier
             if (!live) gfe = make_float2(0.0f, 0.0f);
-            const Emission em = classify(level_of(g, l), mask, uu, live, lane);
-            uint32_t rank[8];
+            if (kWide) {
+                for (uint32_t i = tid; i < n_bins; i += kTile) cnt[i] = 0u;
+                __syncthreads();
+            }
+            const LevelGeom lv = level_of(g, l);
+            const Emission em = classify(lv, mask, uu, live, lane);
+            uint32_t rank[4];
             if (em.emit) {
 #pragma unroll
-                for (int c = 0; c < 8; ++c) rank[c] = atomicAdd(&c_cur[em.e[c] >> kChunkLog2], 1u);
+                for (int p = 0; p < 4; ++p) rank[p] = atomicAdd(&c_cur[em.e[2 * p] >> kChunkLog2], 1u);
             }
             __syncthreads();
-            // lane b: records of bin b in this tile, their first staging slot, and where staged slot s of the bin
-            // goes in the queue (queue_base + s)
-            const uint32_t in_bin = c_cur[lane];
-            const uint32_t incl = wave_inclusive_scan(in_bin);
-            const uint32_t first_slot = incl - in_bin;
-            const uint32_t total = __shfl(incl, dg::kWave - 1, dg::kWave);
-            const uint32_t cursor = (uint32_t)lane < n_bins ? row[key0 + lane] : 0u;
-            const uint32_t queue_base = cursor - first_slot;
-            if (tid < dg::kWave) c_next[tid] = 0u;                   // last read two barriers ago
+            uint32_t total, first_slot = 0, queue_base = 0, cursor = 0, in_bin = 0;
+            if (kWide) {
+                block_exclusive_scan(cnt, start, n_bins, wave_tot);
+                for (uint32_t i = tid; i < n_bins; i += kTile) {
+                    gbase[i] = row_global[key0 + i] + binbase[key0 + i] - start[i];     // queue position of staged slot s: gbase[bin] + s
+                    row_global[key0 + i] += cnt[i];
+                }
+                total = start[n_bins - 1] + cnt[n_bins - 1];
+            } else {
+                // lane b: records of bin b in this tile, their first staging slot, and where staged slot s of the
+                // bin goes in the queue (queue_base + s)
+                in_bin = c_cur[lane];
+                const uint32_t incl = wave_inclusive_scan(in_bin);
+                first_slot = incl - in_bin;
+                total = __shfl(incl, dg::kWave - 1, dg::kWave);
+                cursor = (uint32_t)lane < n_bins ? row[key0 + lane] : 0u;
+                queue_base = cursor - first_slot;
+                if (tid < dg::kWave) cnt[64u * (parity ^ 1u) + tid] = 0u;       // the other buffer: last read two barriers ago
+            }
             float w[8], vx[8], vy[8];
             corner_weights(em.frac, w);
 #pragma unroll
             for (int c = 0; c < 8; ++c) { vx[c] = w[c] * gfe.x; vy[c] = w[c] * gfe.y; }
             if (em.merge) segmented_sum(vx, vy, em.head, em.heads);
-            uint32_t slot[8];
+            uint32_t slot[4];
 #pragma unroll
-            for (int c = 0; c < 8; ++c) slot[c] = __shfl(first_slot, (int)(em.e[c] >> kChunkLog2), dg::kWave);
+            for (int p = 0; p < 4; ++p) {
+                const uint32_t bin = em.e[2 * p] >> kChunkLog2;
+                slot[p] = kWide ? (em.emit ? start[bin] : 0u) : __shfl(first_slot, (int)bin, dg::kWave);
+            }
             if (em.emit) {
 #pragma unroll
-                for (int c = 0; c < 8; ++c)
-                    stage[slot[c] + rank[c]] = make_uint4(em.e[c], __float_as_uint(vx[c]), __float_as_uint(vy[c]), 0u);
+                for (int p = 0; p < 4; ++p) {
+                    const uint32_t ea = em.e[2 * p], eb = em.e[2 * p + 1];
+                    const bool together = (ea >> kChunkLog2) == (eb >> kChunkLog2);
+                    const uint32_t s = slot[p] + rank[p];
+                    stage0[s] = make_uint4(ea, (together ? eb : ea) & (kChunk - 1u), __float_as_uint(vx[2 * p]), __float_as_uint(vy[2 * p]));
+                    stage1[s] = together ? make_uint2(__float_as_uint(vx[2 * p + 1]), __float_as_uint(vy[2 * p + 1])) : make_uint2(0u, 0u);
+                    if (!together) {           // the pair straddles a bin boundary: corner 1 goes to the table directly
+                        float *dst = dtable + 2 * ((size_t)lv.offset + eb);
+                        if (vx[2 * p + 1] != 0.0f) unsafeAtomicAdd(dst, vx[2 * p + 1]);
+                        if (vy[2 * p + 1] != 0.0f) unsafeAtomicAdd(dst + 1, vy[2 * p + 1]);
+                    }
+                }
             }
             __syncthreads();
-            if (tid < n_bins) row[key0 + tid] = cursor + in_bin;     // every wavefront read its copy before the barrier
+            if (!kWide && tid < n_bins) row[key0 + tid] = cursor + in_bin;     // every wavefront read its copy before the barrier
             // copy the staged, bin-sorted records out; four per thread in flight, reads clamped so they batch
             for (uint32_t sb = 0; sb < total; sb += 4 * kTile) {
-                uint4 rec[4];
+                uint4 r0[4];
+                uint2 r1[4];
                 uint32_t base[4];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) rec[k] = stage[min(sb + tid + k * kTile, total - 1u)];
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t s = min(sb + tid + k * kTile, total - 1u);
+                    r0[k] = stage0[s];
+                    r1[k] = stage1[s];
+                }
 #pragma unroll
-                for (int k = 0; k < 4; ++k) base[k] = __shfl(queue_base, (int)(rec[k].x >> kChunkLog2), dg::kWave);
+                for (int k = 0; k < 4; ++k) {
+                    const uint32_t bin = r0[k].x >> kChunkLog2;
+                    base[k] = kWide ? gbase[bin] : __shfl(queue_base, (int)bin, dg::kWave);
+                }
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const uint32_t s = sb + tid + k * kTile;
                     if (s < total) {
                         const size_t dst = (size_t)(base[k] + s);
-                        q_idx[dst] = (uint16_t)(rec[k].x & (kChunk - 1u));
-                        q_vx[dst] = __uint_as_float(rec[k].y);
-                        q_vy[dst] = __uint_as_float(rec[k].z);
+                        q_idx[dst] = (r0[k].x & (kChunk - 1u)) | (r0[k].y << 16);
+                        q_val[dst] = make_float4(__uint_as_float(r0[k].z), __uint_as_float(r0[k].w), __uint_as_float(r1[k].x),
+                                                 __uint_as_float(r1[k].y));
                     }
                 }
             }
+            if (kWide) __syncthreads();
         }
     }
 }
@@ -453,8 +426,7 @@ scan_totals_kernel(const uint32_t *__restrict__ totals, uint32_t n_keys, uint32_
 // ------------------------------------------------------------------ accumulate one (bin, split)
 __global__ void __launch_bounds__(kAccBlock)
 accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbase, const uint32_t *__restrict__ blkbase,
-                  const uint16_t *__restrict__ q_idx, const float *__restrict__ q_vx, const float *__restrict__ q_vy,
-                  float *__restrict__ dtable)
+                  const uint32_t *__restrict__ q_idx, const float4 *__restrict__ q_val, float *__restrict__ dtable)
 {
     extern __shared__ double acc_tab[];      // [2 * kChunk] fp64 sums (fast LDS atomics, and exact enough to be order-independent)
     double *tab = acc_tab;
@@ -470,25 +442,27 @@ accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbas
     const size_t end = min(begin + (size_t)kAccRecords, (size_t)binbase[key + 1]);
     for (uint32_t i = threadIdx.x; i < 2 * kChunk; i += kAccBlock) tab[i] = 0.0;
     __syncthreads();
-    // eight records in flight per thread so that the queue streams at memory speed: the loads are unconditional
+    // several records in flight per thread so that the queue streams at memory speed: the loads are unconditional
     // (index clamped into the range) so that they issue back to back; a clamped duplicate adds 0
     if (begin < end) {
         const size_t last = end - 1;
-        for (size_t i0 = begin + threadIdx.x; i0 < end; i0 += 8 * kAccBlock) {
-            uint32_t e[8];
-            float x[8], y[8];
+        for (size_t i0 = begin + threadIdx.x; i0 < end; i0 += kAccDepth * kAccBlock) {
+            uint32_t e[kAccDepth];
+            float4 v[kAccDepth];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < kAccDepth; ++k) {
                 const size_t want = i0 + (size_t)k * kAccBlock, i = want < last ? want : last;
                 e[k] = q_idx[i];
-                x[k] = q_vx[i];
-                y[k] = q_vy[i];
+                v[k] = q_val[i];
             }
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < kAccDepth; ++k) {
                 const bool ok = i0 + (size_t)k * kAccBlock < end;
-                __hip_atomic_fetch_add(&tab[2 * e[k]], ok ? (double)x[k] : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                __hip_atomic_fetch_add(&tab[2 * e[k] + 1], ok ? (double)y[k] : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                const uint32_t ea = e[k] & 0xffffu, eb = e[k] >> 16;
+                __hip_atomic_fetch_add(&tab[2 * ea], ok ? (double)v[k].x : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(&tab[2 * ea + 1], ok ? (double)v[k].y : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(&tab[2 * eb], ok ? (double)v[k].z : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(&tab[2 * eb + 1], ok ? (double)v[k].w : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
     }
@@ -527,7 +501,7 @@ Plan make_plan(const dg_grid_desc *d)
 inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct Layout {
-    size_t rows, totals, binbase, blkbase, q_idx, q_vx, q_vy, total;
+    size_t rows, totals, binbase, blkbase, q_idx, q_val, total;
     uint64_t batch;      // samples per batch
 };
 
@@ -535,15 +509,14 @@ struct Layout {
 Layout make_layout(const dg_grid_desc *d, const Plan &p, uint64_t batch)
 {
     Layout L{};
-    const uint64_t records = batch * 8ull * (d->n_levels - p.first_level);
+    const uint64_t records = batch * 4ull * (d->n_levels - p.first_level);
     size_t off = 0;
     L.rows = off; off = align256(off + (size_t)kBinGrid * p.n_keys * 4);
     L.totals = off; off = align256(off + (size_t)p.n_keys * 4);
     L.binbase = off; off = align256(off + (size_t)(p.n_keys + 1) * 4);
     L.blkbase = off; off = align256(off + (size_t)(p.n_keys + 1) * 4);
-    L.q_idx = off; off = align256(off + records * 2);
-    L.q_vx = off; off = align256(off + records * 4);
-    L.q_vy = off; off = align256(off + records * 4);
+    L.q_idx = off; off = align256(off + records * 4);
+    L.q_val = off; off = align256(off + records * 16);
     L.total = off;
     L.batch = batch;
     return L;
@@ -551,7 +524,7 @@ Layout make_layout(const dg_grid_desc *d, const Plan &p, uint64_t batch)
 
 uint64_t max_batch(const dg_grid_desc *d, const Plan &p)
 {
-    const uint64_t per_sample = 8ull * (d->n_levels - p.first_level);
+    const uint64_t per_sample = 4ull * (d->n_levels - p.first_level);
     if (per_sample == 0) return ~0ull;
     return (0xffffffffull / per_sample) / kTile * kTile;           // record offsets stay below 2^32
 }
@@ -579,21 +552,15 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     const Plan p = make_plan(d);
     static bool lds_opt_in = false;
     if (!lds_opt_in) {
-        const int fill_lds = (3 * kMaxBins + 16 + 4 * kRecords + (int)kLdsKeys) * 4;      // the most a launch may ask for
-        hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(&bin_kernel<true>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds);
-        if (e1 == hipSuccess)
-            e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(&fill64_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (128 + 16 * 64 + 4 * kRecords) * 4);
-        if (e1 != hipSuccess) return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot reserve %d bytes of LDS: %s", fill_lds,
-                                          hipGetErrorString(e1));
+        const int fill_lds = (3 * kMaxBins + 16) * 4 + kPairs * 24;      // the most a launch may ask for
         const int acc_lds = 2 * kChunk * (int)sizeof(double);
-        hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(&accumulate_kernel),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, acc_lds);
-        hipError_t e3 = hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_kernel),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, acc_lds);
-        if (e2 != hipSuccess || e3 != hipSuccess)
-            return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot reserve %d bytes of LDS", acc_lds);
+        const hipError_t e[4] = {
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds),
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds),
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&accumulate_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, acc_lds),
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, acc_lds)};
+        for (const hipError_t x : e)
+            if (x != hipSuccess) return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot reserve LDS: %s", hipGetErrorString(x));
         lds_opt_in = true;
     }
     if (p.first_level > 0) {
@@ -617,30 +584,30 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     uint32_t *totals = reinterpret_cast<uint32_t *>(base + L.totals);
     uint32_t *binbase = reinterpret_cast<uint32_t *>(base + L.binbase);
     uint32_t *blkbase = reinterpret_cast<uint32_t *>(base + L.blkbase);
-    uint16_t *q_idx = reinterpret_cast<uint16_t *>(base + L.q_idx);
-    float *q_vx = reinterpret_cast<float *>(base + L.q_vx);
-    float *q_vy = reinterpret_cast<float *>(base + L.q_vy);
+    uint32_t *q_idx = reinterpret_cast<uint32_t *>(base + L.q_idx);
+    float4 *q_val = reinterpret_cast<float4 *>(base + L.q_val);
     const size_t n_rows_words = (size_t)kBinGrid * p.n_keys;
-    const int keys_lds = p.n_keys <= kLdsKeys ? (int)p.n_keys : 0;
-    const int count_lds = (3 * (int)p.max_bins + 16 + keys_lds) * 4, fill_lds = (3 * (int)p.max_bins + 16 + 4 * kRecords + keys_lds) * 4;
-    const int fill64_lds = (128 + ((int)p.n_keys + 3) / 4 * 4 + 4 * kRecords) * 4;
+    const bool narrow = p.max_bins <= 64;                 // then n_keys <= 64 * DG_MAX_LEVELS
+    const bool count_in_lds = p.n_keys <= kLdsKeys;
+    const int fill_lds = (narrow ? 128 + ((int)p.n_keys + 3) / 4 * 4 : 3 * (int)p.max_bins + 16) * 4 + kPairs * 24;
 
     for (uint64_t n0 = 0; n0 < N; n0 += batch) {
         const uint64_t nb = N - n0 < batch ? N - n0 : batch;
-        zero_u32_kernel<<<(uint32_t)((n_rows_words + 255) / 256), 256, 0, st>>>(rows, n_rows_words);
-        if (keys_lds)
-            count_lds_kernel<<<kBinGrid, kTile, keys_lds * 4, st>>>(*d, p, u, n0, nb, rows);
-        else
-            bin_kernel<false><<<kBinGrid, kTile, count_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
+        if (count_in_lds) {
+            count_lds_kernel<<<kBinGrid, kTile, p.n_keys * 4, st>>>(*d, p, u, n0, nb, rows);
+        } else {
+            zero_u32_kernel<<<(uint32_t)((n_rows_words + 255) / 256), 256, 0, st>>>(rows, n_rows_words);
+            count_global_kernel<<<kBinGrid, kTile, p.max_bins * 4, st>>>(*d, p, u, n0, nb, rows);
+        }
         scan_rows_kernel<<<(p.n_keys + 255) / 256, 256, 0, st>>>(rows, kBinGrid, p.n_keys, totals);
         scan_totals_kernel<<<1, 1024, 0, st>>>(totals, p.n_keys, binbase, blkbase);
-        if (p.max_bins <= 64)
-            fill64_kernel<<<kBinGrid, kTile, fill64_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
+        if (narrow)
+            fill_kernel<false><<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_val, dtable);
         else
-            bin_kernel<true><<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_vx, q_vy);
-        const uint64_t records = nb * 8ull * (d->n_levels - p.first_level);
+            fill_kernel<true><<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_val, dtable);
+        const uint64_t records = nb * 4ull * (d->n_levels - p.first_level);
         const uint32_t acc_grid = (uint32_t)(records / kAccRecords) + p.n_keys;       // upper bound of the workgroups needed
-        accumulate_kernel<<<acc_grid, kAccBlock, 2 * kChunk * sizeof(double), st>>>(*d, p, binbase, blkbase, q_idx, q_vx, q_vy, dtable);
+        accumulate_kernel<<<acc_grid, kAccBlock, 2 * kChunk * sizeof(double), st>>>(*d, p, binbase, blkbase, q_idx, q_val, dtable);
     }
     return launch_status("dg_hashgrid_encode_bwd");
 }

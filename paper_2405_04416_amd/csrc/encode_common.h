@@ -86,12 +86,13 @@ template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ void seg_step(float (&vx)[8], float (&vy)[8], int &f)
 {
     const int fs = __builtin_amdgcn_update_dpp(0, f, CTRL, ROW_MASK, 0xF, true);
+    const float take = f ? 0.0f : 1.0f;      // v + 1 * t is exact, so one multiply-add (which can carry the DPP move) does the step
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
         const float tx = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(vx[c]), CTRL, ROW_MASK, 0xF, true));
         const float ty = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(vy[c]), CTRL, ROW_MASK, 0xF, true));
-        vx[c] += f ? 0.0f : tx;
-        vy[c] += f ? 0.0f : ty;
+        vx[c] = __builtin_fmaf(tx, take, vx[c]);
+        vy[c] = __builtin_fmaf(ty, take, vy[c]);
     }
     f |= fs;
 }

@@ -123,7 +123,25 @@ GRIDS = {
     "c2": lambda: (di.config("c2_ngp"), None),
     "mixed_small": lambda: (None, dict(L=6, F=2, log2_T=10, n_min=4, growth=1.7, extent=[1.0, 2.0, 0.5])),
     "one_level_dense": lambda: (None, dict(L=1, F=2, log2_T=12, n_min=15, growth=1.0, extent=[1.0, 1.0, 1.0])),
+    # 37^3 vertices in one dense level: 7 bins of 8192 entries, odd row length, so x-pairs straddle bin boundaries
+    "dense_odd": lambda: (None, dict(L=1, F=2, log2_T=16, n_min=36, growth=1.0, extent=[1.0, 1.0, 1.0])),
+    # T = 2^21: a dense level of 34 bins and hashed levels of 256 bins (more than one wavefront's worth)
+    "wide": lambda: (None, dict(L=4, F=2, log2_T=21, n_min=64, growth=2.0, extent=[1.0, 1.0, 1.0])),
+    # T = 2^24, three hashed levels: 6144 (level, bin) pairs, too many for the counters to sit in LDS
+    "huge": lambda: (None, dict(L=3, F=2, log2_T=24, n_min=512, growth=2.0, extent=[1.0, 1.0, 1.0])),
 }
+
+
+def _coords(N, flavour, seed):
+    """independent points, or stretches of 64 consecutive samples along short segments (as a ray gives them)"""
+    if flavour == "points":
+        return di.make_unit_coords(N, seed=seed)
+    rng = np.random.default_rng(seed)
+    n_seg = -(-N // 64)
+    a = rng.random((n_seg, 1, 3))
+    step = rng.standard_normal((n_seg, 1, 3)) * rng.choice([1e-4, 2e-3, 1e-2], size=(n_seg, 1, 1))
+    u = a + step * np.arange(64).reshape(1, 64, 1)
+    return np.clip(u, 0.0, 1.0).reshape(-1, 3)[:N].astype(np.float32)
 
 
 def _both_grids(key):
@@ -166,12 +184,15 @@ def test_encode_fwd_and_indices(key, N):
 
 
 @pytest.mark.parametrize("mode", ["atomic", "binned", "binned_batched"])
-@pytest.mark.parametrize("key,N", [("c1", 32768), ("c2", 10007), ("mixed_small", 3333), ("one_level_dense", 700)])
-def test_encode_bwd(key, N, mode):
-    say("encode bwd %s N=%d %s" % (key, N, mode))
+@pytest.mark.parametrize("key,N,flavour", [("c1", 32768, "points"), ("c2", 10007, "points"), ("mixed_small", 3333, "points"),
+                                           ("one_level_dense", 700, "points"), ("c2", 20011, "rays"),
+                                           ("dense_odd", 150001, "points"), ("dense_odd", 30000, "rays"),
+                                           ("wide", 20011, "points"), ("wide", 9000, "rays"), ("huge", 20011, "points")])
+def test_encode_bwd(key, N, flavour, mode):
+    say("encode bwd %s N=%d %s %s" % (key, N, flavour, mode))
     g, r, _ = _both_grids(key)
     L = g.n_levels
-    u = di.make_unit_coords(N, seed=5)
+    u = _coords(N, flavour, seed=5)
     dfeat = (np.random.default_rng(6).standard_normal((N, 2 * L)) * 1e-3).astype(np.float32)
     dfeat[::7] = 0.0
     dtable = torch.zeros(r.n_entries, 2, device=DEV)
