@@ -376,19 +376,31 @@ fill_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2
     }
 }
 
-// rows[b][k] (per-workgroup counts) -> exclusive prefix over workgroups; totals[k]
-__global__ void __launch_bounds__(256)
+// rows[b][k] (per-workgroup counts) -> exclusive prefix over workgroups; totals[k].  A workgroup serves 32
+// keys; 32 groups of threads each take a contiguous stretch of the rows.
+constexpr int kScanKeys = 32, kScanGroups = 32;
+__global__ void __launch_bounds__(kScanKeys * kScanGroups)
 scan_rows_kernel(uint32_t *__restrict__ rows, uint32_t n_rows, uint32_t n_keys, uint32_t *__restrict__ totals)
 {
-    const uint32_t k = blockIdx.x * 256 + threadIdx.x;
+    __shared__ uint32_t part[kScanGroups][kScanKeys];
+    const uint32_t col = threadIdx.x % kScanKeys, group = threadIdx.x / kScanKeys;
+    const uint32_t k = blockIdx.x * kScanKeys + col;
+    const uint32_t per = (n_rows + kScanGroups - 1) / kScanGroups;
+    const uint32_t lo = min(group * per, n_rows), hi = min(lo + per, n_rows);
+    uint32_t sum = 0;
+    if (k < n_keys)
+        for (uint32_t b = lo; b < hi; ++b) sum += rows[(size_t)b * n_keys + k];
+    part[group][col] = sum;
+    __syncthreads();
     if (k >= n_keys) return;
     uint32_t run = 0;
-    for (uint32_t b = 0; b < n_rows; ++b) {
+    for (uint32_t g = 0; g < group; ++g) run += part[g][col];
+    for (uint32_t b = lo; b < hi; ++b) {
         const uint32_t t = rows[(size_t)b * n_keys + k];
         rows[(size_t)b * n_keys + k] = run;
         run += t;
     }
-    totals[k] = run;
+    if (group == kScanGroups - 1) totals[k] = run;
 }
 
 // binbase = exclusive scan of totals; blkbase = exclusive scan of the number of accumulate workgroups each
@@ -599,7 +611,7 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
             zero_u32_kernel<<<(uint32_t)((n_rows_words + 255) / 256), 256, 0, st>>>(rows, n_rows_words);
             count_global_kernel<<<kBinGrid, kTile, p.max_bins * 4, st>>>(*d, p, u, n0, nb, rows);
         }
-        scan_rows_kernel<<<(p.n_keys + 255) / 256, 256, 0, st>>>(rows, kBinGrid, p.n_keys, totals);
+        scan_rows_kernel<<<(p.n_keys + kScanKeys - 1) / kScanKeys, kScanKeys * kScanGroups, 0, st>>>(rows, kBinGrid, p.n_keys, totals);
         scan_totals_kernel<<<1, 1024, 0, st>>>(totals, p.n_keys, binbase, blkbase);
         if (narrow)
             fill_kernel<false><<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_val, dtable);

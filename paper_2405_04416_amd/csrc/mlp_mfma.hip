@@ -97,6 +97,14 @@ __device__ __forceinline__ h8 image(const __half *lds, int chunk, int lane)
     return reinterpret_cast<const h8 *>(lds)[chunk * 64 + lane];
 }
 
+// Returns its argument, in a way the compiler cannot see through: LDS reads indexed with the result are
+// issued where they are used, not hoisted out of the tile loop and held in registers for its whole length.
+__device__ __forceinline__ int opaque(int x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
 __device__ __forceinline__ f16v mma(h8 a, h8 b, f16v c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
 
 __device__ __forceinline__ f16v zero16()
@@ -200,7 +208,7 @@ __device__ __forceinline__ void load_inputs(const __half *feat, const __half *di
     }
 }
 
-__global__ void __launch_bounds__(kBlock, 2)
+__global__ void __launch_bounds__(kBlock, 4)
 fwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, const __half *__restrict__ dir_enc,
            uint32_t S, uint64_t n_samples, uint32_t act_c, float *__restrict__ sigma, float *__restrict__ rgb)
 {
@@ -216,7 +224,7 @@ fwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, 
         const bool valid = n < n_samples;
         Tile t;
         load_inputs(feat, dir_enc, S, n_samples, n, valid, h, t);
-        forward_tile(lds, lane, act_c, t);
+        forward_tile(lds, opaque(lane), act_c, t);
         if (valid && h == 0) {
             sigma[n] = t.sigma;
             rgb[3 * n] = t.rgb[0]; rgb[3 * n + 1] = t.rgb[1]; rgb[3 * n + 2] = t.rgb[2];
@@ -271,11 +279,13 @@ __device__ __forceinline__ void store_share(float *dst, int n_in, int rows_real,
 // The backward pass runs as two kernels so that neither has to hold all twelve dW tiles (192
 // accumulator registers) next to the activations:
 //   colour_bwd : recomputes the whole forward, back-propagates the colour net, accumulates dWc1..3
-//                and leaves delta_geo (gradient of the 16 density outputs, sigma term included,
+//                (8 tiles = 128 registers; the weight images are re-read from LDS tile by tile so that
+//                the rest fits the 256 registers of two wavefronts per SIMD, which keeps every MFMA
+//                result in ordinary registers) and leaves delta_geo (gradient of the 16 density outputs, sigma term included,
 //                already scaled and rounded to fp16, in operand order) in the workspace;
 //   density_bwd: recomputes the density hidden layer, back-propagates it from delta_geo, accumulates
 //                dWd1..2 and writes the feature gradient planes.
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kBlock, 2)
 colour_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, const __half *__restrict__ dir_enc,
                   uint32_t S, uint64_t n_samples, uint32_t act_c, const float *__restrict__ dsigma,
                   const float *__restrict__ drgb, float loss_scale, h8 *__restrict__ dgeo, float *__restrict__ shares)
@@ -284,7 +294,7 @@ colour_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__
     build_forward_images(lds, weights);
     build_backward_images(lds, weights);
     __syncthreads();
-    const int lane = threadIdx.x & 63, h = lane >> 5;
+    const int lane_fixed = threadIdx.x & 63, h = lane_fixed >> 5;
     const uint64_t n_tiles = (n_samples + 31) / 32;
     const uint64_t wave = (uint64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
@@ -295,8 +305,9 @@ colour_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__
     for (int a = 0; a < 2; ++a) { gWc3[a] = zero16(); gWc1[a] = zero16(); gWc2[a][0] = zero16(); gWc2[a][1] = zero16(); }
 
     for (uint64_t tile = wave; tile < n_tiles; tile += n_waves) {
-        const uint64_t n = tile * 32 + (lane & 31);
+        const uint64_t n = tile * 32 + (lane_fixed & 31);
         const bool valid = n < n_samples;
+        const int lane = opaque(lane_fixed);
         Tile t;
         load_inputs(feat, dir_enc, S, n_samples, n, valid, h, t);
         float ds = 0.0f, dc[3] = {0.0f, 0.0f, 0.0f};
@@ -372,6 +383,7 @@ colour_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__
     }
 
     float *mine = shares + wave * (kTotal - oWc1) - oWc1;       // colour shares hold elements [oWc1, kTotal)
+    const int lane = lane_fixed;
     store_share(mine + oWc3, HC, 3, 0, 0, lane, gWc3[0]);
     store_share(mine + oWc3, HC, 3, 0, 1, lane, gWc3[1]);
 #pragma unroll
@@ -480,26 +492,40 @@ density_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict_
 
 // dW[e] += (sum of the wavefronts' shares of element e) / loss_scale, in a fixed order.  Elements below
 // oWc1 (density net) come from density_shares [n_d][oWc1], the rest from colour_shares [n_c][kTotal - oWc1].
-__global__ void __launch_bounds__(256)
+// A workgroup serves 64 consecutive elements; 16 groups of threads each sum every 16th share, then the 16
+// partial sums are added in a fixed order.
+constexpr int kFoldElems = 64, kFoldGroups = 16;
+static_assert(oWc1 % kFoldElems == 0, "a fold workgroup must not span both share regions");
+__global__ void __launch_bounds__(kFoldElems * kFoldGroups)
 fold_shares_kernel(const float *__restrict__ density_shares, uint32_t n_d, const float *__restrict__ colour_shares,
                    uint32_t n_c, float inv_scale, float *__restrict__ dW)
 {
-    const uint32_t e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= (uint32_t)kTotal) return;
-    const bool dens = e < (uint32_t)oWc1;
-    const float *src = dens ? density_shares + e : colour_shares + (e - oWc1);
-    const uint32_t stride = dens ? oWc1 : kTotal - oWc1, n = dens ? n_d : n_c;
-    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
-    uint32_t b = 0;
-    for (; b + 4 <= n; b += 4) {
-        s0 += src[(size_t)b * stride]; s1 += src[(size_t)(b + 1) * stride];
-        s2 += src[(size_t)(b + 2) * stride]; s3 += src[(size_t)(b + 3) * stride];
+    __shared__ float part[kFoldGroups][kFoldElems];
+    const uint32_t col = threadIdx.x % kFoldElems, group = threadIdx.x / kFoldElems;
+    const uint32_t e = blockIdx.x * kFoldElems + col;
+    float s0 = 0.0f, s1 = 0.0f;
+    if (e < (uint32_t)kTotal) {
+        const bool dens = e < (uint32_t)oWc1;
+        const float *src = dens ? density_shares + e : colour_shares + (e - oWc1);
+        const uint32_t stride = dens ? oWc1 : kTotal - oWc1, n = dens ? n_d : n_c;
+        uint32_t b = group;
+        for (; b + kFoldGroups < n; b += 2 * kFoldGroups) {
+            s0 += src[(size_t)b * stride];
+            s1 += src[(size_t)(b + kFoldGroups) * stride];
+        }
+        if (b < n) s0 += src[(size_t)b * stride];
     }
-    for (; b < n; ++b) s0 += src[(size_t)b * stride];
-    dW[e] += ((s0 + s1) + (s2 + s3)) * inv_scale;
+    part[group][col] = s0 + s1;
+    __syncthreads();
+    if (group == 0 && e < (uint32_t)kTotal) {
+        float s = 0.0f;
+#pragma unroll
+        for (int k = 0; k < kFoldGroups; ++k) s += part[k][col];
+        dW[e] += s * inv_scale;
+    }
 }
 
-constexpr uint32_t kGridColour = 256;      // persistent workgroups: one per compute unit of MI355X
+constexpr uint32_t kGridColour = 512;      // persistent workgroups: two per compute unit of MI355X
 constexpr uint32_t kGridDensity = 512;     // the lighter kernel fits two workgroups per compute unit
 
 inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
@@ -542,8 +568,8 @@ void mlp_mfma_bwd(const void *weights, const void *feat, const void *dir_enc, ui
                                                  act_c, dsigma, drgb, loss_scale, dgeo, colour_shares);
     density_bwd_kernel<<<grid_d, kBlock, 0, st>>>((const __half *)weights, (const __half *)feat, N, dgeo, loss_scale, dfeat,
                                                   density_shares);
-    fold_shares_kernel<<<(kTotal + 255) / 256, 256, 0, st>>>(density_shares, grid_d * kWavesPerBlock, colour_shares,
-                                                             grid_c * kWavesPerBlock, 1.0f / loss_scale, dW);
+    fold_shares_kernel<<<(kTotal + kFoldElems - 1) / kFoldElems, kFoldElems * kFoldGroups, 0, st>>>(
+        density_shares, grid_d * kWavesPerBlock, colour_shares, grid_c * kWavesPerBlock, 1.0f / loss_scale, dW);
 }
 
 }  // namespace dg
