@@ -76,7 +76,7 @@ encode_bwd_kernel(dg_grid_desc g, const float *__restrict__ u, const float2 *__r
         // runs of lanes that share a cell
         bool head = lane == 0;
 #pragma unroll
-        for (int a = 0; a < 3; ++a) head |= __shfl_up(cell[a], 1, dg::kWave) != cell[a];
+        for (int a = 0; a < 3; ++a) head |= from_lane_below(cell[a]) != cell[a];
         const unsigned long long heads = __ballot(head);
         float vx[8], vy[8];
 #pragma unroll

@@ -24,6 +24,7 @@ constexpr int kChunkLog2 = 13;
 constexpr uint32_t kChunk = 1u << kChunkLog2;      // entries per bin
 constexpr int kMaxBins = 2048;                     // per level: 2^24 entries / 8192
 constexpr int kTile = 512;                         // samples per tile == threads per binning workgroup
+constexpr int kWriters = 128;                      // narrow fill sweep: threads that only copy staged records to the queues
 constexpr int kPairs = kTile * 4;                  // records staged per (tile, level): one per pair of corners along x
 constexpr uint32_t kLdsKeys = 4096;                // count sweep: (level, bin) counters kept in LDS when there are at most this many
 constexpr int kBinGrid = 768;                      // persistent binning workgroups (three per compute unit)
@@ -75,7 +76,7 @@ coarse_kernel(dg_grid_desc g, uint32_t first_level, const float *__restrict__ u,
             if (!live) gfe = make_float2(0.0f, 0.0f);
             bool head = lane == 0;
 #pragma unroll
-            for (int a = 0; a < 3; ++a) head |= __shfl_up(cell[a], 1, dg::kWave) != cell[a];
+            for (int a = 0; a < 3; ++a) head |= from_lane_below(cell[a]) != cell[a];
             const unsigned long long heads = __ballot(head);
             float vx[8], vy[8];
 #pragma unroll
@@ -107,6 +108,13 @@ coarse_kernel(dg_grid_desc g, uint32_t first_level, const float *__restrict__ u,
 // added to the table directly with global atomics; both sweeps see exactly four records per emitting
 // sample and level.
 
+// A queue record: 5 words, (entry of corner 0 | entry of corner 1 << 16, both within the bin), then the 4 values.
+// One array of 20-byte records: a record is one 16-byte and one 4-byte access to the same cache line, and a run
+// of records is one contiguous piece of memory.
+constexpr int kRecordWords = 5;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 __attribute__((aligned(4))) u32x4_unaligned;
+
 // Which records a sample emits at a level (both sweeps take the same decision from the same data).  A
 // wavefront holds 64 consecutive samples of a ray; lanes that share a cell form a run whose 16 values are
 // summed into the run's last lane, which alone emits records.  Skipped where runs are short.
@@ -125,7 +133,7 @@ __device__ __forceinline__ Emission classify(const LevelGeom &lv, uint32_t mask,
     corner_entries(lv, mask, cell, o.e);
     o.head = lane == 0 || !live;
 #pragma unroll
-    for (int a = 0; a < 3; ++a) o.head |= __shfl_up(cell[a], 1, dg::kWave) != cell[a];
+    for (int a = 0; a < 3; ++a) o.head |= from_lane_below(cell[a]) != cell[a];
     o.heads = __ballot(o.head);
     o.merge = __popcll(o.heads) <= 44;
     const bool tail = lane == dg::kWave - 1 || ((o.heads >> ((lane + 1) & 63)) & 1ull);
@@ -241,55 +249,122 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
     return v;
 }
 
-// Fill sweep.  Per (tile, level): every emitting lane takes a rank in its records' bins (LDS counters), the
-// counters are scanned into staging offsets, the records are staged in LDS sorted by bin and then copied to
-// the queues, so that every bin receives contiguous runs.
-//   kWide == false (at most 64 bins in every level): every wavefront reads the 64 tile counters and scans them
-//     itself, so staging offsets and queue positions sit in one register per lane (lane == bin) and are fetched
-//     with wavefront shuffles -- two barriers per (tile, level); the tile counters are double-buffered so that
-//     the buffer of the next level is cleared while this level is staged; the queue cursors live in LDS.
-//   kWide == true: counters, offsets and positions in LDS arrays, workgroup-wide scan, cursors in global memory.
-template <bool kWide>
-__global__ void __launch_bounds__(kTile)
-fill_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
-            uint64_t n0, uint64_t nb, uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
-            uint32_t *__restrict__ q_idx, float4 *__restrict__ q_val, float *__restrict__ dtable)
+// Fill sweep.  Per step (one tile at one level): every emitting lane takes a rank in its records' bins (LDS
+// counters), the counters are scanned into staging offsets, the records are staged in LDS sorted by bin and then
+// copied to the queues, so that every bin receives contiguous runs.  A workgroup goes level after level, and
+// within a level tile after tile: it then appends to the same queue slices step after step, so the partly written
+// cache lines at their ends are completed while they still sit in L2.
+// Loads are requested one step ahead: memory operations of a wavefront retire in order, so a load issued right
+// after queue stores could only be awaited together with their acknowledgements.
+
+struct StepAhead {
+    float u[3];
+    float2 g;
+};
+
+__device__ __forceinline__ void load_ahead(StepAhead &a, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
+                                           uint64_t n0, uint64_t nb, uint64_t tile, uint32_t l, uint32_t tid)
+{
+    const uint64_t rel = tile * kTile + tid, n = n0 + (rel < nb ? rel : nb - 1);
+    a.u[0] = u[3 * n]; a.u[1] = u[3 * n + 1]; a.u[2] = u[3 * n + 2];
+    a.g = dfeat[(size_t)l * N + n];
+}
+
+// values of the 8 corners of one sample at one level, runs merged where the emission says so
+__device__ __forceinline__ void corner_values(const Emission &em, float2 gfe, float (&vx)[8], float (&vy)[8])
+{
+    float w[8];
+    corner_weights(em.frac, w);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) { vx[c] = w[c] * gfe.x; vy[c] = w[c] * gfe.y; }
+    if (em.merge) segmented_sum(vx, vy, em.head, em.heads);
+}
+
+// stage the record of pair p in slot s; it will go to queue position qpos
+__device__ __forceinline__ void stage_pair(uint4 *stage0, uint2 *stage1, uint32_t s, uint32_t qpos, const Emission &em, int p,
+                                           const float (&vx)[8], const float (&vy)[8], uint32_t level_offset, float *__restrict__ dtable)
+{
+    const uint32_t ea = em.e[2 * p], eb = em.e[2 * p + 1];
+    const bool together = (ea >> kChunkLog2) == (eb >> kChunkLog2);
+    const uint32_t pair = (ea & (kChunk - 1u)) | (((together ? eb : ea) & (kChunk - 1u)) << 16);
+    stage0[s] = make_uint4(qpos, pair, __float_as_uint(vx[2 * p]), __float_as_uint(vy[2 * p]));
+    stage1[s] = together ? make_uint2(__float_as_uint(vx[2 * p + 1]), __float_as_uint(vy[2 * p + 1])) : make_uint2(0u, 0u);
+    if (!together) {           // the pair straddles a bin boundary: corner 1 goes to the table directly
+        float *dst = dtable + 2 * ((size_t)level_offset + eb);
+        if (vx[2 * p + 1] != 0.0f) unsafeAtomicAdd(dst, vx[2 * p + 1]);
+        if (vy[2 * p + 1] != 0.0f) unsafeAtomicAdd(dst + 1, vy[2 * p + 1]);
+    }
+}
+
+// copy staged records [0, total) to their queue positions; `n_threads` threads (this one is `t`) share the work,
+// four records per thread in flight, reads clamped so they batch
+__device__ __forceinline__ void copy_out(const uint4 *stage0, const uint2 *stage1, uint32_t total, uint32_t t, uint32_t n_threads,
+                                         uint32_t *__restrict__ queue)
+{
+    for (uint32_t sb = 0; sb < total; sb += 4 * n_threads) {
+        uint4 r0[4];
+        uint2 r1[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t s = min(sb + t + k * n_threads, total - 1u);
+            r0[k] = stage0[s];
+            r1[k] = stage1[s];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (sb + t + k * n_threads < total) {
+                uint32_t *rec = queue + (size_t)r0[k].x * kRecordWords;
+                *reinterpret_cast<u32x4_unaligned *>(rec) = u32x4{r0[k].y, r0[k].z, r0[k].w, r1[k].x};
+                rec[4] = r1[k].y;
+            }
+        }
+    }
+}
+
+// Fill sweep for grids with at most 64 bins in every level.  kTile threads bin the samples; every one of their
+// wavefronts reads the 64 step counters and scans them itself, so staging offsets and queue cursors sit in one
+// register per lane (lane == bin) and are fetched with wavefront shuffles: two barriers per step.  The counters are
+// double-buffered so that the buffer of the next step is cleared while this step is staged; the queue cursors live
+// in LDS.  kWriters more threads do nothing but copy each staged step to the queues while the others already bin
+// the next step: they never wait for a load, so their stores drain in the background instead of stalling the
+// wavefronts that compute (a wavefront that mixes both waits for its stores whenever it waits for a load).
+__global__ void __launch_bounds__(kTile + kWriters)
+fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
+                   uint64_t n0, uint64_t nb, const uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
+                   uint32_t *__restrict__ queue, float *__restrict__ dtable)
 {
     extern __shared__ uint32_t smem[];
-    const uint32_t cap = plan.max_bins;
-    uint32_t *cnt = smem;                                             // narrow [2][64], wide [cap]
-    uint32_t *start = cnt + (kWide ? cap : 128u);                     // wide [cap]
-    uint32_t *gbase = start + (kWide ? cap : 0u);                     // wide [cap]
-    uint32_t *wave_tot = gbase + (kWide ? cap : 0u);                  // wide [16]
-    uint32_t *row = wave_tot + (kWide ? 16u : 0u);                    // narrow [n_keys]: this workgroup's queue cursors
-    uint4 *stage0 = reinterpret_cast<uint4 *>(row + (kWide ? 0u : (plan.n_keys + 3u) / 4u * 4u));   // [kPairs] entry, entry, 2 values
-    uint2 *stage1 = reinterpret_cast<uint2 *>(stage0 + kPairs);                                    // [kPairs] 2 values
+    uint32_t *cnt = smem;                                             // [2][64] records per bin of the step
+    uint32_t *staged = cnt + 128;                                     // [2] records of the step (+ 2 words of padding)
+    uint32_t *row = staged + 4;                                       // [n_keys] this workgroup's queue cursors
+    uint4 *stage0 = reinterpret_cast<uint4 *>(row + (plan.n_keys + 3u) / 4u * 4u);      // [kPairs] queue position, entry pair, 2 values
+    uint2 *stage1 = reinterpret_cast<uint2 *>(stage0 + kPairs);                         // [kPairs] 2 values
     const uint32_t tid = threadIdx.x;
+    const bool writer = tid >= (uint32_t)kTile;                       // whole wavefronts: kTile is a multiple of 64
     const int lane = tid % dg::kWave;
     const uint32_t mask = (1u << g.log2_T) - 1u;
-    uint32_t *row_global = rows + (size_t)blockIdx.x * plan.n_keys;
-    if (!kWide) {
-        for (uint32_t i = tid; i < plan.n_keys; i += kTile) row[i] = binbase[i] + row_global[i];
-        if (tid < 128) cnt[tid] = 0u;
-        __syncthreads();
-    }
+    const uint32_t *row_global = rows + (size_t)blockIdx.x * plan.n_keys;
+    for (uint32_t i = tid; i < plan.n_keys; i += kTile + kWriters) row[i] = binbase[i] + row_global[i];
+    if (tid < 128) cnt[tid] = 0u;
+    __syncthreads();
     uint32_t parity = 0;
     const uint64_t n_tiles = (nb + kTile - 1) / kTile;
-    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const uint64_t rel = tile * kTile + tid;
-        const bool live = rel < nb;
-        const uint64_t n = n0 + (live ? rel : nb - 1);
-        const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
-        for (uint32_t l = plan.first_level; l < g.n_levels; ++l, parity ^= 1u) {
-            uint32_t *c_cur = kWide ? cnt : cnt + 64u * parity;
-            const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
-            float2 gfe = dfeat[(size_t)l * N + n];                   // issued early: needed only after the barrier
-            if (!live) gfe = make_float2(0.0f, 0.0f);
-            if (kWide) {
-                for (uint32_t i = tid; i < n_bins; i += kTile) cnt[i] = 0u;
-                __syncthreads();
+    StepAhead ahead = {{0.0f, 0.0f, 0.0f}, make_float2(0.0f, 0.0f)};
+    if (!writer && blockIdx.x < n_tiles) load_ahead(ahead, u, dfeat, N, n0, nb, blockIdx.x, plan.first_level, tid);
+    for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
+        const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
+        const LevelGeom lv = level_of(g, l);
+        for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x, parity ^= 1u) {
+            uint32_t *c_cur = cnt + 64u * parity;
+            if (writer) {
+                __syncthreads();                                     // ranks taken
+                __syncthreads();                                     // step staged
+                copy_out(stage0, stage1, staged[parity], tid - kTile, kWriters, queue);
+                continue;                                            // the LDS reads are complete before the next barrier
             }
-            const LevelGeom lv = level_of(g, l);
+            const bool live = tile * kTile + tid < nb;
+            const float uu[3] = {ahead.u[0], ahead.u[1], ahead.u[2]};
+            const float2 gfe = live ? ahead.g : make_float2(0.0f, 0.0f);
             const Emission em = classify(lv, mask, uu, live, lane);
             uint32_t rank[4];
             if (em.emit) {
@@ -297,81 +372,101 @@ fill_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2
                 for (int p = 0; p < 4; ++p) rank[p] = atomicAdd(&c_cur[em.e[2 * p] >> kChunkLog2], 1u);
             }
             __syncthreads();
-            uint32_t total, first_slot = 0, queue_base = 0, cursor = 0, in_bin = 0;
-            if (kWide) {
-                block_exclusive_scan(cnt, start, n_bins, wave_tot);
-                for (uint32_t i = tid; i < n_bins; i += kTile) {
-                    gbase[i] = row_global[key0 + i] + binbase[key0 + i] - start[i];     // queue position of staged slot s: gbase[bin] + s
-                    row_global[key0 + i] += cnt[i];
-                }
-                total = start[n_bins - 1] + cnt[n_bins - 1];
-            } else {
-                // lane b: records of bin b in this tile, their first staging slot, and where staged slot s of the
-                // bin goes in the queue (queue_base + s)
-                in_bin = c_cur[lane];
-                const uint32_t incl = wave_inclusive_scan(in_bin);
-                first_slot = incl - in_bin;
-                total = __shfl(incl, dg::kWave - 1, dg::kWave);
-                cursor = (uint32_t)lane < n_bins ? row[key0 + lane] : 0u;
-                queue_base = cursor - first_slot;
-                if (tid < dg::kWave) cnt[64u * (parity ^ 1u) + tid] = 0u;       // the other buffer: last read two barriers ago
+            // lane b: records of bin b in this step, their first staging slot, and the queue position of the first
+            const uint32_t in_bin = c_cur[lane];
+            const uint32_t incl = wave_inclusive_scan(in_bin);
+            const uint32_t first_slot = incl - in_bin;
+            const uint32_t cursor = (uint32_t)lane < n_bins ? row[key0 + lane] : 0u;
+            if (tid < dg::kWave) {
+                cnt[64u * (parity ^ 1u) + tid] = 0u;                 // the other buffer: last read two barriers ago
+                if (tid == dg::kWave - 1) staged[parity] = incl;     // read by the writers after the next barrier
             }
-            float w[8], vx[8], vy[8];
-            corner_weights(em.frac, w);
-#pragma unroll
-            for (int c = 0; c < 8; ++c) { vx[c] = w[c] * gfe.x; vy[c] = w[c] * gfe.y; }
-            if (em.merge) segmented_sum(vx, vy, em.head, em.heads);
-            uint32_t slot[4];
+            float vx[8], vy[8];
+            corner_values(em, gfe, vx, vy);
+            uint32_t slot[4], qpos[4];        // staging slot and queue position of each record: (first of the bin) + rank
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                const uint32_t bin = em.e[2 * p] >> kChunkLog2;
-                slot[p] = kWide ? (em.emit ? start[bin] : 0u) : __shfl(first_slot, (int)bin, dg::kWave);
+                const int bin = (int)(em.e[2 * p] >> kChunkLog2);
+                slot[p] = __shfl(first_slot, bin, dg::kWave);
+                qpos[p] = __shfl(cursor, bin, dg::kWave);
             }
             if (em.emit) {
 #pragma unroll
+                for (int p = 0; p < 4; ++p) stage_pair(stage0, stage1, slot[p] + rank[p], qpos[p] + rank[p], em, p, vx, vy, lv.offset, dtable);
+            }
+            __syncthreads();
+            {
+                const bool same_level = tile + gridDim.x < n_tiles;
+                const uint32_t l_next = same_level ? l : l + 1;
+                if (l_next < g.n_levels) load_ahead(ahead, u, dfeat, N, n0, nb, same_level ? tile + gridDim.x : blockIdx.x, l_next, tid);
+            }
+            if (tid < n_bins) row[key0 + tid] = cursor + in_bin;    // every wavefront read its copy before the barrier
+        }
+    }
+}
+
+// Fill sweep for any number of bins: counters, staging offsets and queue cursors of the step in LDS arrays,
+// workgroup-wide scan, this workgroup's cursors of all (level, bin) pairs in global memory.
+__global__ void __launch_bounds__(kTile)
+fill_wide_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
+                 uint64_t n0, uint64_t nb, uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
+                 uint32_t *__restrict__ queue, float *__restrict__ dtable)
+{
+    extern __shared__ uint32_t smem[];
+    const uint32_t cap = plan.max_bins;
+    uint32_t *cnt = smem;                                             // [cap]
+    uint32_t *start = cnt + cap;                                      // [cap] first staging slot of each bin
+    uint32_t *cursor = start + cap;                                   // [cap] queue position of each bin's first record
+    uint32_t *wave_tot = cursor + cap;                                // [16]
+    uint4 *stage0 = reinterpret_cast<uint4 *>(wave_tot + 16);         // [kPairs] queue position, entry pair, 2 values
+    uint2 *stage1 = reinterpret_cast<uint2 *>(stage0 + kPairs);       // [kPairs] 2 values
+    const uint32_t tid = threadIdx.x;
+    const int lane = tid % dg::kWave;
+    const uint32_t mask = (1u << g.log2_T) - 1u;
+    uint32_t *row = rows + (size_t)blockIdx.x * plan.n_keys;
+    const uint64_t n_tiles = (nb + kTile - 1) / kTile;
+    StepAhead ahead = {{0.0f, 0.0f, 0.0f}, make_float2(0.0f, 0.0f)};
+    if (blockIdx.x < n_tiles) load_ahead(ahead, u, dfeat, N, n0, nb, blockIdx.x, plan.first_level, tid);
+    for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
+        const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
+        const LevelGeom lv = level_of(g, l);
+        for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+            const bool live = tile * kTile + tid < nb;
+            const float uu[3] = {ahead.u[0], ahead.u[1], ahead.u[2]};
+            const float2 gfe = live ? ahead.g : make_float2(0.0f, 0.0f);
+            for (uint32_t i = tid; i < n_bins; i += kTile) cnt[i] = 0u;
+            __syncthreads();
+            const Emission em = classify(lv, mask, uu, live, lane);
+            uint32_t rank[4];
+            if (em.emit) {
+#pragma unroll
+                for (int p = 0; p < 4; ++p) rank[p] = atomicAdd(&cnt[em.e[2 * p] >> kChunkLog2], 1u);
+            }
+            __syncthreads();
+            block_exclusive_scan(cnt, start, n_bins, wave_tot);
+            for (uint32_t i = tid; i < n_bins; i += kTile) {
+                cursor[i] = row[key0 + i] + binbase[key0 + i];
+                row[key0 + i] += cnt[i];
+            }
+            const uint32_t total = start[n_bins - 1] + cnt[n_bins - 1];
+            __syncthreads();
+            float vx[8], vy[8];
+            corner_values(em, gfe, vx, vy);
+            if (em.emit) {
+#pragma unroll
                 for (int p = 0; p < 4; ++p) {
-                    const uint32_t ea = em.e[2 * p], eb = em.e[2 * p + 1];
-                    const bool together = (ea >> kChunkLog2) == (eb >> kChunkLog2);
-                    const uint32_t s = slot[p] + rank[p];
-                    stage0[s] = make_uint4(ea, (together ? eb : ea) & (kChunk - 1u), __float_as_uint(vx[2 * p]), __float_as_uint(vy[2 * p]));
-                    stage1[s] = together ? make_uint2(__float_as_uint(vx[2 * p + 1]), __float_as_uint(vy[2 * p + 1])) : make_uint2(0u, 0u);
-                    if (!together) {           // the pair straddles a bin boundary: corner 1 goes to the table directly
-                        float *dst = dtable + 2 * ((size_t)lv.offset + eb);
-                        if (vx[2 * p + 1] != 0.0f) unsafeAtomicAdd(dst, vx[2 * p + 1]);
-                        if (vy[2 * p + 1] != 0.0f) unsafeAtomicAdd(dst + 1, vy[2 * p + 1]);
-                    }
+                    const uint32_t bin = em.e[2 * p] >> kChunkLog2;
+                    stage_pair(stage0, stage1, start[bin] + rank[p], cursor[bin] + rank[p], em, p, vx, vy, lv.offset, dtable);
                 }
             }
             __syncthreads();
-            if (!kWide && tid < n_bins) row[key0 + tid] = cursor + in_bin;     // every wavefront read its copy before the barrier
-            // copy the staged, bin-sorted records out; four per thread in flight, reads clamped so they batch
-            for (uint32_t sb = 0; sb < total; sb += 4 * kTile) {
-                uint4 r0[4];
-                uint2 r1[4];
-                uint32_t base[4];
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const uint32_t s = min(sb + tid + k * kTile, total - 1u);
-                    r0[k] = stage0[s];
-                    r1[k] = stage1[s];
-                }
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const uint32_t bin = r0[k].x >> kChunkLog2;
-                    base[k] = kWide ? gbase[bin] : __shfl(queue_base, (int)bin, dg::kWave);
-                }
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const uint32_t s = sb + tid + k * kTile;
-                    if (s < total) {
-                        const size_t dst = (size_t)(base[k] + s);
-                        q_idx[dst] = (r0[k].x & (kChunk - 1u)) | (r0[k].y << 16);
-                        q_val[dst] = make_float4(__uint_as_float(r0[k].z), __uint_as_float(r0[k].w), __uint_as_float(r1[k].x),
-                                                 __uint_as_float(r1[k].y));
-                    }
-                }
+            {
+                const bool same_level = tile + gridDim.x < n_tiles;
+                const uint32_t l_next = same_level ? l : l + 1;
+                if (l_next < g.n_levels) load_ahead(ahead, u, dfeat, N, n0, nb, same_level ? tile + gridDim.x : blockIdx.x, l_next, tid);
             }
-            if (kWide) __syncthreads();
+            copy_out(stage0, stage1, total, tid, kTile, queue);
+            __syncthreads();
         }
     }
 }
@@ -438,7 +533,7 @@ scan_totals_kernel(const uint32_t *__restrict__ totals, uint32_t n_keys, uint32_
 // ------------------------------------------------------------------ accumulate one (bin, split)
 __global__ void __launch_bounds__(kAccBlock)
 accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbase, const uint32_t *__restrict__ blkbase,
-                  const uint32_t *__restrict__ q_idx, const float4 *__restrict__ q_val, float *__restrict__ dtable)
+                  const uint32_t *__restrict__ queue, float *__restrict__ dtable)
 {
     extern __shared__ double acc_tab[];      // [2 * kChunk] fp64 sums (fast LDS atomics, and exact enough to be order-independent)
     double *tab = acc_tab;
@@ -459,22 +554,25 @@ accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbas
     if (begin < end) {
         const size_t last = end - 1;
         for (size_t i0 = begin + threadIdx.x; i0 < end; i0 += kAccDepth * kAccBlock) {
-            uint32_t e[kAccDepth];
-            float4 v[kAccDepth];
+            u32x4 head[kAccDepth];       // entry pair, 3 values
+            uint32_t tail[kAccDepth];    // 4th value
 #pragma unroll
             for (int k = 0; k < kAccDepth; ++k) {
                 const size_t want = i0 + (size_t)k * kAccBlock, i = want < last ? want : last;
-                e[k] = q_idx[i];
-                v[k] = q_val[i];
+                const uint32_t *rec = queue + i * kRecordWords;
+                head[k] = *reinterpret_cast<const u32x4_unaligned *>(rec);
+                tail[k] = rec[4];
             }
 #pragma unroll
             for (int k = 0; k < kAccDepth; ++k) {
                 const bool ok = i0 + (size_t)k * kAccBlock < end;
-                const uint32_t ea = e[k] & 0xffffu, eb = e[k] >> 16;
-                __hip_atomic_fetch_add(&tab[2 * ea], ok ? (double)v[k].x : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                __hip_atomic_fetch_add(&tab[2 * ea + 1], ok ? (double)v[k].y : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                __hip_atomic_fetch_add(&tab[2 * eb], ok ? (double)v[k].z : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                __hip_atomic_fetch_add(&tab[2 * eb + 1], ok ? (double)v[k].w : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                const uint32_t ea = head[k].x & 0xffffu, eb = head[k].x >> 16;
+                const float v0 = __uint_as_float(head[k].y), v1 = __uint_as_float(head[k].z), v2 = __uint_as_float(head[k].w),
+                            v3 = __uint_as_float(tail[k]);
+                __hip_atomic_fetch_add(&tab[2 * ea], ok ? (double)v0 : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(&tab[2 * ea + 1], ok ? (double)v1 : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(&tab[2 * eb], ok ? (double)v2 : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(&tab[2 * eb + 1], ok ? (double)v3 : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
     }
@@ -513,7 +611,7 @@ Plan make_plan(const dg_grid_desc *d)
 inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct Layout {
-    size_t rows, totals, binbase, blkbase, q_idx, q_val, total;
+    size_t rows, totals, binbase, blkbase, queue, total;
     uint64_t batch;      // samples per batch
 };
 
@@ -527,8 +625,7 @@ Layout make_layout(const dg_grid_desc *d, const Plan &p, uint64_t batch)
     L.totals = off; off = align256(off + (size_t)p.n_keys * 4);
     L.binbase = off; off = align256(off + (size_t)(p.n_keys + 1) * 4);
     L.blkbase = off; off = align256(off + (size_t)(p.n_keys + 1) * 4);
-    L.q_idx = off; off = align256(off + records * 4);
-    L.q_val = off; off = align256(off + records * 16);
+    L.queue = off; off = align256(off + records * kRecordWords * 4);
     L.total = off;
     L.batch = batch;
     return L;
@@ -567,8 +664,8 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
         const int fill_lds = (3 * kMaxBins + 16) * 4 + kPairs * 24;      // the most a launch may ask for
         const int acc_lds = 2 * kChunk * (int)sizeof(double);
         const hipError_t e[4] = {
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds),
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds),
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_wide_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds),
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_narrow_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds),
             hipFuncSetAttribute(reinterpret_cast<const void *>(&accumulate_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, acc_lds),
             hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, acc_lds)};
         for (const hipError_t x : e)
@@ -596,12 +693,11 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     uint32_t *totals = reinterpret_cast<uint32_t *>(base + L.totals);
     uint32_t *binbase = reinterpret_cast<uint32_t *>(base + L.binbase);
     uint32_t *blkbase = reinterpret_cast<uint32_t *>(base + L.blkbase);
-    uint32_t *q_idx = reinterpret_cast<uint32_t *>(base + L.q_idx);
-    float4 *q_val = reinterpret_cast<float4 *>(base + L.q_val);
+    uint32_t *queue = reinterpret_cast<uint32_t *>(base + L.queue);
     const size_t n_rows_words = (size_t)kBinGrid * p.n_keys;
     const bool narrow = p.max_bins <= 64;                 // then n_keys <= 64 * DG_MAX_LEVELS
     const bool count_in_lds = p.n_keys <= kLdsKeys;
-    const int fill_lds = (narrow ? 128 + ((int)p.n_keys + 3) / 4 * 4 : 3 * (int)p.max_bins + 16) * 4 + kPairs * 24;
+    const int fill_lds = (narrow ? 132 + ((int)p.n_keys + 3) / 4 * 4 : 3 * (int)p.max_bins + 16) * 4 + kPairs * 24;
 
     for (uint64_t n0 = 0; n0 < N; n0 += batch) {
         const uint64_t nb = N - n0 < batch ? N - n0 : batch;
@@ -614,12 +710,12 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
         scan_rows_kernel<<<(p.n_keys + kScanKeys - 1) / kScanKeys, kScanKeys * kScanGroups, 0, st>>>(rows, kBinGrid, p.n_keys, totals);
         scan_totals_kernel<<<1, 1024, 0, st>>>(totals, p.n_keys, binbase, blkbase);
         if (narrow)
-            fill_kernel<false><<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_val, dtable);
+            fill_narrow_kernel<<<kBinGrid, kTile + kWriters, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, queue, dtable);
         else
-            fill_kernel<true><<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, q_idx, q_val, dtable);
+            fill_wide_kernel<<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, queue, dtable);
         const uint64_t records = nb * 4ull * (d->n_levels - p.first_level);
         const uint32_t acc_grid = (uint32_t)(records / kAccRecords) + p.n_keys;       // upper bound of the workgroups needed
-        accumulate_kernel<<<acc_grid, kAccBlock, 2 * kChunk * sizeof(double), st>>>(*d, p, binbase, blkbase, q_idx, q_val, dtable);
+        accumulate_kernel<<<acc_grid, kAccBlock, 2 * kChunk * sizeof(double), st>>>(*d, p, binbase, blkbase, queue, dtable);
     }
     return launch_status("dg_hashgrid_encode_bwd");
 }

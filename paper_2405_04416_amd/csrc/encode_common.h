@@ -67,6 +67,12 @@ __device__ __forceinline__ void corner_weights(const float frac[3], float w[8])
 }
 
 
+// value of the lane below (lane - 1) in the wavefront; lane 0 gets its own.  A DPP move: no LDS traffic, no wait.
+__device__ __forceinline__ uint32_t from_lane_below(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x138 /* wave_shr:1 */, 0xF, 0xF, false);
+}
+
 // length of the longest run of lanes that share a cell, from the mask of run heads (wavefront-uniform)
 __device__ __forceinline__ int longest_run(unsigned long long heads)
 {
