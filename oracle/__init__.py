@@ -73,6 +73,9 @@ def lib():
         _lib.dgo_mlp_weight_count.restype = C.c_uint64
         _lib.dgo_mlp_weight_count.argtypes = [C.POINTER(Mlp)]
         _lib.dgo_loss.restype = C.c_double
+        _lib.dgo_adam_step.restype = None
+        _lib.dgo_cosine_lr.restype = C.c_double
+        _lib.dgo_cosine_lr.argtypes = [C.c_double, C.c_double, C.c_uint64, C.c_uint64]
         for name in ("dgo_encode_fwd", "dgo_encode_bwd", "dgo_ray_aabb_segments", "dgo_bucket_segments",
                      "dgo_sample_segments", "dgo_sh", "dgo_mlp_fwd", "dgo_mlp_bwd", "dgo_composite_fwd",
                      "dgo_composite_bwd", "dgo_merge_fwd", "dgo_merge_bwd"):
@@ -290,3 +293,18 @@ def loss(Cc, T, Cgt, lambda1=0.0, want_grad=True):
     gT = np.zeros(R, np.float64) if want_grad else None
     val = lib().dgo_loss(_p(Cc), _p(T), _p(Cgt), C.c_uint32(R), C.c_double(lambda1), _p(gC), _p(gT))
     return (val, gC, gT) if want_grad else val
+
+
+# ---------------------------------------------------------------- optimiser
+def adam_step(theta, grad, m, v, lr, step, beta1=0.9, beta2=0.99, eps=1e-15, l2=0.0, skip_zero=False):
+    """In place on float64 arrays theta, m, v (Sec. 5.1: Adam); returns them."""
+    for a in (theta, m, v):
+        assert a.dtype == np.float64 and a.flags["C_CONTIGUOUS"]
+    g = _arr(grad, np.float64)
+    lib().dgo_adam_step(_p(theta), _p(g), _p(m), _p(v), C.c_uint64(theta.size), C.c_double(lr), C.c_double(beta1),
+                        C.c_double(beta2), C.c_double(eps), C.c_uint32(step), C.c_double(l2), C.c_int(1 if skip_zero else 0))
+    return theta, m, v
+
+
+def cosine_lr(lr0, lr1, iteration, total):
+    return lib().dgo_cosine_lr(lr0, lr1, iteration, total)

@@ -574,3 +574,24 @@ double dgo_loss(const double *C, const double *T, const double *Cgt, uint32_t R,
     }
     return loss;
 }
+
+void dgo_adam_step(double *theta, const double *grad, double *m, double *v, uint64_t n, double lr,
+                   double beta1, double beta2, double eps, uint32_t step, double l2, int skip_zero)
+{
+    const double c1 = 1.0 - pow(beta1, (double)step), c2 = 1.0 - pow(beta2, (double)step);
+    for (uint64_t i = 0; i < n; ++i) {
+        if (skip_zero && grad[i] == 0.0) continue;
+        const double g = grad[i] + l2 * theta[i];
+        m[i] = beta1 * m[i] + (1.0 - beta1) * g;
+        v[i] = beta2 * v[i] + (1.0 - beta2) * g * g;
+        const double m_hat = m[i] / c1, v_hat = v[i] / c2;
+        theta[i] -= lr * m_hat / (sqrt(v_hat) + eps);
+    }
+}
+
+double dgo_cosine_lr(double lr0, double lr1, uint64_t iteration, uint64_t total)
+{
+    const double pi = 3.14159265358979323846;
+    const double x = iteration >= total ? 1.0 : (double)iteration / (double)total;
+    return lr1 + 0.5 * (lr0 - lr1) * (1.0 + cos(pi * x));
+}

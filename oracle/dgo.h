@@ -117,6 +117,17 @@ void dgo_merge_bwd(const double *Ck, const double *Tk, const uint32_t *seg_count
 double dgo_loss(const double *C, const double *T, const double *Cgt, uint32_t R, double lambda1,
                 double *gC, double *gT);
 
+/* One Adam step (Kingma & Ba 2015, Algorithm 1; optimiser named in Sec. 5.1) on n parameters, in place:
+ * g' = g + l2 * theta;  m = b1 m + (1-b1) g';  v = b2 v + (1-b2) g'^2;
+ * theta -= lr * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps),   t = step >= 1.
+ * skip_zero != 0: a parameter whose gradient is exactly 0 is left alone altogether (value and both moments), the
+ * rule of the system whose unnamed hyper-parameters Sec. 5.1 inherits, for sparsely touched hash tables. */
+void dgo_adam_step(double *theta, const double *grad, double *m, double *v, uint64_t n, double lr,
+                   double beta1, double beta2, double eps, uint32_t step, double l2, int skip_zero);
+
+/* Learning rate of Sec. 5.1: from lr0 down to lr1 along half a cosine over `total` iterations. */
+double dgo_cosine_lr(double lr0, double lr1, uint64_t iteration, uint64_t total);
+
 #ifdef __cplusplus
 }
 #endif
