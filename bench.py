@@ -6,7 +6,7 @@ all their backward passes, including zeroing the gradient buffers) over one batc
 rays that is already resident in HBM.  The workload is the Instant-NGP-scale single-partition
 configuration (2^18 rays x 64 samples, L=16, F=2, T=2^19).  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_ngp] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_ngp] [--no-cpu-baseline] [--no-optimizer]
 """
 import argparse
 import json
@@ -56,6 +56,7 @@ def main():
     ap.add_argument("--workload", default="c2_ngp")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rays", type=int, default=16384)
+    ap.add_argument("--no-optimizer", action="store_true", help="skip the separate timing of the Adam sweep")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, stream 1 GiB through one elementwise kernel (known traffic, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -131,6 +132,23 @@ def main():
     n_samples = n_seg * S
     per_call = step.timing_summary()           # HIP events on the launch stream, inside the timed region
 
+    # the optimiser sweep (Sec. 5.1: Adam), measured apart from the metric: `value` stays the forward+backward rate
+    optimiser = None
+    if not args.no_optimizer:
+        n_param = sum(models[p].table.numel() for p in resident)
+        touched = sum(int(torch.count_nonzero(models[p].dtable)) for p in resident)
+        step.timings = {}
+        for k in range(3):
+            if k:
+                step.step(od, dd, Cd, None, foreign)       # fresh gradients for every sweep
+            step.optimiser_step(k)
+        calls, total_ms = step.timing_summary()["dg_adam_step"]
+        ms = total_ms / 3
+        moved = touched * 32 + (n_param - touched) * 4     # touched: value, gradient, 2 moments read and written; else the gradient read
+        optimiser = {"entry": "dg_adam_step", "ms_per_step": round(ms, 4), "parameters": n_param,
+                     "touched_fraction": round(touched / n_param, 4), "algorithmic_bytes": moved,
+                     "GB/s": round(moved / (ms * 1e-3) / 1e9, 1), "frac_hbm": round(moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -190,7 +208,7 @@ def main():
                    "samples": n_samples, "levels": g["L"], "features": g["F"], "log2_T": g["log2_T"],
                    "partitions_resident": len(resident), "mlp_operands": "f16, f32 accumulate"},
         "samples_per_s": round(n_samples / (ms_per_step * 1e-3), 1),
-        "roofline": roofline, "kernels": others, "ms_per_call": breakdown, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": others, "ms_per_call": breakdown, "optimiser": optimiser, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 

@@ -208,6 +208,24 @@ int dg_merge_segments_bwd(const float *Ck, const float *Tk, const uint32_t *seg_
 int dg_loss_seed(const float *C, const float *T, const float *Cgt, uint32_t R,
                  float lambda1, float *gC, float *gT, float *loss, void *stream);
 
+/* One Adam step (Sec. 5.1 names the optimiser; the update is Algorithm 1 of Kingma & Ba) on n fp32 values, in place:
+ *   g' = g + l2 * p;  m = beta1 m + (1 - beta1) g';  v = beta2 v + (1 - beta2) g'^2;
+ *   p -= lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps),      step = 1, 2, ...
+ * param, grad, m, v: device arrays of n floats, 16-byte aligned, owned by the caller.  grad is consumed: every
+ * gradient that was used is set to 0, so the next backward pass can accumulate without a separate clearing pass.
+ * skip_zero_grad != 0 (for the hash tables): a value whose gradient is exactly 0 is left alone altogether -- value
+ * and both moments unchanged -- and the sweep does not fetch them (the rule of the system whose unnamed
+ * hyper-parameters Sec. 5.1 inherits: beta1 0.9, beta2 0.99, eps 1e-15, l2 1e-6 on the MLP weights only).
+ * param_half: NULL, or a device array of n fp16 values (8-byte aligned) that receives the rounded new values of
+ * every value that was updated (the MLP kernels read fp16 weights).  Errors: DG_ERR_ARG for null / misaligned
+ * pointers, step == 0, beta outside [0, 1), eps < 0; DG_ERR_UNSUPPORTED for n >= 2^41. */
+int dg_adam_step(float *param, float *grad, float *m, float *v, uint64_t n, float lr, float beta1, float beta2,
+                 float eps, uint32_t step, float l2, uint32_t skip_zero_grad, void *param_half, void *stream);
+
+/* Learning rate of Sec. 5.1 (host function): lr0 at iteration 0 down to lr1 at `total` along half a cosine,
+ * lr1 afterwards (the paper: 0.05 -> 0.005 over 300 000 iterations). */
+float dg_cosine_lr(float lr0, float lr1, uint64_t iteration, uint64_t total);
+
 #ifdef __cplusplus
 }
 #endif

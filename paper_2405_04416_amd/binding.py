@@ -70,6 +70,8 @@ _SIGNATURES = {
     "dg_merge_segments": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32] + [C.c_void_p] * 3),
     "dg_merge_segments_bwd": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32] + [C.c_void_p] * 5),
     "dg_loss_seed": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_float] + [C.c_void_p] * 4),
+    "dg_adam_step": (C.c_int, [C.c_void_p] * 4 + [C.c_uint64] + [C.c_float] * 4 + [C.c_uint32, C.c_float, C.c_uint32] + [C.c_void_p] * 2),
+    "dg_cosine_lr": (C.c_float, [C.c_float, C.c_float, C.c_uint64, C.c_uint64]),
 }
 
 EXPORTS = tuple(_SIGNATURES)
@@ -225,3 +227,15 @@ def dg_merge_segments_bwd(Ck, Tk, seg_count, R, k_max, gC, gT, gCk, gTk):
 def dg_loss_seed(Cin, Tin, Cgt, R, lambda1, gC, gT, loss=None):
     _check(lib().dg_loss_seed(_ptr(Cin, torch.float32), _ptr(Tin, torch.float32), _ptr(Cgt, torch.float32), R, lambda1,
                               _ptr(gC, torch.float32), _ptr(gT, torch.float32), _ptr(loss, torch.float32, True), _stream()))
+
+
+def dg_adam_step(param, grad, m, v, lr, step, beta1=0.9, beta2=0.99, eps=1e-15, l2=0.0, skip_zero_grad=False, param_half=None):
+    n = param.numel()
+    assert grad.numel() == n and m.numel() == n and v.numel() == n and (param_half is None or param_half.numel() == n)
+    _check(lib().dg_adam_step(_ptr(param, torch.float32), _ptr(grad, torch.float32), _ptr(m, torch.float32), _ptr(v, torch.float32),
+                              n, lr, beta1, beta2, eps, step, l2, 1 if skip_zero_grad else 0,
+                              _ptr(param_half, torch.float16, True), _stream()))
+
+
+def dg_cosine_lr(lr0, lr1, iteration, total):
+    return float(lib().dg_cosine_lr(lr0, lr1, iteration, total))

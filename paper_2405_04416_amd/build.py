@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libdistgrid.so")
 
-SOURCES = ["host.hip", "segments.hip", "encode.hip", "encode_bwd_binned.hip", "mlp.hip", "mlp_mfma.hip", "render.hip"]
+SOURCES = ["host.hip", "segments.hip", "encode.hip", "encode_bwd_binned.hip", "mlp.hip", "mlp_mfma.hip", "render.hip", "optim.hip"]
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           # packed fp32 instructions are kept out of every kernel of this library
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -21,6 +21,15 @@ class SubModel:
         self.table, self.weights = table, weights
         self.dtable = torch.zeros_like(table)
         self.dW = torch.zeros(weights.numel(), dtype=torch.float32, device=weights.device)
+        self.opt = None     # optimiser state, allocated by the first optimiser step
+
+    def optimiser_state(self):
+        """Adam moments of the table and of the weights, and the fp32 master copy of the fp16 weights."""
+        if self.opt is None:
+            self.opt = {"table_m": torch.zeros_like(self.table), "table_v": torch.zeros_like(self.table),
+                        "w_master": self.weights.float().reshape(-1).contiguous(), "w_m": torch.zeros_like(self.dW),
+                        "w_v": torch.zeros_like(self.dW)}
+        return self.opt
 
 
 class TrainStep:
@@ -151,3 +160,18 @@ class TrainStep:
     def step(self, o, d, Cgt, jitter=None, foreign=None):
         self.forward(o, d, Cgt, jitter, foreign)
         self.backward()
+
+    # -- optimiser (Sec. 5.1) -----------------------------------------------------------------
+    def optimiser_step(self, iteration, total_iterations=300000, lr0=0.05, lr1=0.005, l2_weights=1e-6):
+        """Adam on every resident sub-model, learning rate from the cosine schedule; consumes (clears) the gradients.
+        iteration counts from 0."""
+        lr = B.dg_cosine_lr(lr0, lr1, iteration, total_iterations)
+        for p in self.resident:
+            m = self.models[p]
+            st = m.optimiser_state()
+            with self._timed("dg_adam_step"):
+                B.dg_adam_step(m.table.reshape(-1), m.dtable.reshape(-1), st["table_m"].reshape(-1), st["table_v"].reshape(-1), lr,
+                               iteration + 1, skip_zero_grad=True)
+                B.dg_adam_step(st["w_master"], m.dW, st["w_m"], st["w_v"], lr, iteration + 1, l2=l2_weights,
+                               param_half=m.weights.reshape(-1))
+        return lr

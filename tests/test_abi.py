@@ -75,3 +75,15 @@ def test_argument_validation_on_host():
     assert B.lib().dg_hashgrid_encode_fwd(C.byref(desc), None, None, 5, None, 0, None) == -1
     bad = B.dg_mlp_desc(24, 64, 16, 16, 64, 2)
     assert B.lib().dg_mlp_fwd(C.byref(bad), None, None, None, 4, 0, None, None, None) == -2
+
+
+def test_optimiser_host_side():
+    # the schedule is a host function: same values as the oracle's (fp32 result of a double computation)
+    for it in (0, 1, 1234, 150000, 299999, 300000, 10 ** 6):
+        assert B.dg_cosine_lr(0.05, 0.005, it, 300000) == pytest.approx(oracle.cosine_lr(0.05, 0.005, it, 300000), rel=2e-7)
+    L = B.lib()
+    f = C.c_float
+    args = lambda n, step, b1=0.9, eps=1e-15: (None, None, None, None, C.c_uint64(n), f(0.01), f(b1), f(0.99), f(eps), step, f(0.0), 1, None, None)
+    assert L.dg_adam_step(*args(0, 1)) == 0                 # nothing to do
+    assert L.dg_adam_step(*args(8, 1)) == -1                # null pointers
+    assert b"null" in L.dg_last_error()

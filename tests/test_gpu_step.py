@@ -15,6 +15,7 @@ import oracle
 import oracle.step as ostep
 from paper_2405_04416_amd import binding as B
 
+import oracle
 from gpu_util import (DEV, TOL_F16, TOL_F32, assert_close_robust, dev, from_planes, gpu_models, have_gpu, host, make_step,
                       rel_err)
 
@@ -220,3 +221,36 @@ def test_step_full_size_bench_configuration():
     # merged transmittance of a single segment is that segment's, untouched rays stay (0, 1)
     miss = torch.nonzero(step.seg_count == 0).flatten()
     assert bool((step.T[miss] == 1).all()) and bool((step.C[miss] == 0).all())
+
+
+def test_optimiser_step_after_a_training_step():
+    """Sec. 5.1: Adam over the table (untouched entries left alone) and the weights (fp32 master, fp16 working copy)
+    after one forward+backward pass of c1; the oracle's update is driven with the gradients the GPU pass produced."""
+    say("c1 optimiser step")
+    cfg = di.config("c1_tiny")
+    R = 512
+    o, d = di.make_rays(cfg, seed=3, R=R)
+    Cgt = di.make_targets(R, seed=3)
+    gm = gpu_models(cfg, ostep.make_models(cfg, seed=3))
+    step = make_step(cfg, gm, R, loss_scale=1024.0, seed=3)
+    m = gm[0]
+    f32 = lambda x: float(np.float32(x))
+    table = host(m.table).astype(np.float64).reshape(-1)
+    w = host(m.weights).astype(np.float64).reshape(-1)
+    tm, tv, wm, wv = np.zeros_like(table), np.zeros_like(table), np.zeros_like(w), np.zeros_like(w)
+    for it in range(2):
+        step.step(dev(o), dev(d), dev(Cgt))
+        g_table, g_w = host(m.dtable).astype(np.float64).reshape(-1), host(m.dW).astype(np.float64)
+        assert np.count_nonzero(g_table) > 0 and np.count_nonzero(g_table) < g_table.size
+        before = host(m.table).reshape(-1).copy()
+        lr = step.optimiser_step(it, total_iterations=10)
+        assert lr == pytest.approx(oracle.cosine_lr(0.05, 0.005, it, 10), rel=2e-7)
+        oracle.adam_step(table, g_table, tm, tv, lr=f32(lr), step=it + 1, beta1=f32(0.9), beta2=f32(0.99), eps=f32(1e-15), skip_zero=True)
+        oracle.adam_step(w, g_w, wm, wv, lr=f32(lr), step=it + 1, beta1=f32(0.9), beta2=f32(0.99), eps=f32(1e-15), l2=f32(1e-6))
+        got = host(m.table).reshape(-1)
+        assert np.array_equal(got[g_table == 0.0], before[g_table == 0.0])           # untouched entries: bit-identical
+        np.testing.assert_allclose(got, table, rtol=0, atol=2e-6 * (it + 1) * 0.05 + 2e-7)
+        st = m.optimiser_state()
+        np.testing.assert_allclose(host(st["w_master"]), w, rtol=0, atol=2e-6 * (it + 1) * 0.05 + 2e-7)
+        np.testing.assert_array_equal(host(m.weights).reshape(-1), host(st["w_master"]).astype(np.float16))
+        assert torch.count_nonzero(m.dtable).item() == 0 and torch.count_nonzero(m.dW).item() == 0
