@@ -53,8 +53,10 @@ __global__ void __launch_bounds__(kCoarseBlock)
 coarse_kernel(dg_grid_desc g, uint32_t first_level, const float *__restrict__ u, const float2 *__restrict__ dfeat,
               uint64_t N, float *__restrict__ dtable)
 {
-    extern __shared__ double tab[];         // 2 sums per entry of levels [0, first_level); fp64 LDS atomics run ~7x faster than fp32 ones
-    const uint32_t n_floats = 2u * g.offset[first_level];
+    // 2 sums per entry of levels [0, first_level), one plane per feature (an add instruction then spreads over all LDS
+    // banks); fp64 LDS atomics run ~7x faster than fp32 ones
+    extern __shared__ double tab[];
+    const uint32_t n_entries = g.offset[first_level], n_floats = 2u * n_entries;
     for (uint32_t i = threadIdx.x; i < n_floats; i += kCoarseBlock) tab[i] = 0.0;
     __syncthreads();
     const int lane = threadIdx.x % dg::kWave;
@@ -86,16 +88,16 @@ coarse_kernel(dg_grid_desc g, uint32_t first_level, const float *__restrict__ u,
             if (tail) {
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {
-                    const uint32_t slot = 2u * (lv.offset + e[c]);
+                    const uint32_t slot = lv.offset + e[c];
                     if (vx[c] != 0.0f) __hip_atomic_fetch_add(&tab[slot], (double)vx[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    if (vy[c] != 0.0f) __hip_atomic_fetch_add(&tab[slot + 1], (double)vy[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    if (vy[c] != 0.0f) __hip_atomic_fetch_add(&tab[n_entries + slot], (double)vy[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
         }
     }
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < n_floats; i += kCoarseBlock) {
-        const float v = (float)tab[i];
+        const float v = (float)tab[(i & 1u) * n_entries + (i >> 1)];
         if (v != 0.0f) unsafeAtomicAdd(dtable + i, v);
     }
 }
@@ -535,7 +537,9 @@ __global__ void __launch_bounds__(kAccBlock)
 accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbase, const uint32_t *__restrict__ blkbase,
                   const uint32_t *__restrict__ queue, float *__restrict__ dtable)
 {
-    extern __shared__ double acc_tab[];      // [2 * kChunk] fp64 sums (fast LDS atomics, and exact enough to be order-independent)
+    // [2][kChunk] fp64 sums (fast LDS atomics, and exact enough to be order-independent), one plane per feature: an add
+    // instruction then spreads over all LDS banks instead of every other pair
+    extern __shared__ double acc_tab[];
     double *tab = acc_tab;
     if (blockIdx.x >= blkbase[plan.n_keys]) return;
     // the bin this workgroup serves: last key whose first workgroup is <= blockIdx.x
@@ -569,10 +573,10 @@ accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbas
                 const uint32_t ea = head[k].x & 0xffffu, eb = head[k].x >> 16;
                 const float v0 = __uint_as_float(head[k].y), v1 = __uint_as_float(head[k].z), v2 = __uint_as_float(head[k].w),
                             v3 = __uint_as_float(tail[k]);
-                __hip_atomic_fetch_add(&tab[2 * ea], ok ? (double)v0 : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                __hip_atomic_fetch_add(&tab[2 * ea + 1], ok ? (double)v1 : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                __hip_atomic_fetch_add(&tab[2 * eb], ok ? (double)v2 : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                __hip_atomic_fetch_add(&tab[2 * eb + 1], ok ? (double)v3 : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(&tab[ea], ok ? (double)v0 : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(&tab[kChunk + ea], ok ? (double)v1 : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(&tab[eb], ok ? (double)v2 : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(&tab[kChunk + eb], ok ? (double)v3 : 0.0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
     }
@@ -584,7 +588,7 @@ accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbas
     const uint32_t first = bin * kChunk, n_valid = min(kChunk, level_len - first);
     float *dst = dtable + 2 * ((size_t)g.offset[l] + first);
     for (uint32_t i = threadIdx.x; i < 2 * n_valid; i += kAccBlock) {
-        const float v = (float)tab[i];
+        const float v = (float)tab[(i & 1u) * kChunk + (i >> 1)];
         if (v != 0.0f) unsafeAtomicAdd(dst + i, v);
     }
 }
