@@ -291,6 +291,7 @@ colour_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__
                   const float *__restrict__ drgb, float loss_scale, h8 *__restrict__ dgeo, float *__restrict__ shares)
 {
     __shared__ __attribute__((aligned(16))) __half lds[kAllChunks * 512];
+    __shared__ float acc3[kWavesPerBlock * 2 * 3 * 32];
     build_forward_images(lds, weights);
     build_backward_images(lds, weights);
     __syncthreads();
@@ -300,9 +301,17 @@ colour_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__
     const uint64_t n_waves = (uint64_t)gridDim.x * kWavesPerBlock;
     const h8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 
-    f16v gWc3[2], gWc2[2][2], gWc1[2];      // [output tile][input tile]
+    f16v gWc2[2][2], gWc1[2];               // [output tile][input tile]
 #pragma unroll
-    for (int a = 0; a < 2; ++a) { gWc3[a] = zero16(); gWc1[a] = zero16(); gWc2[a][0] = zero16(); gWc2[a][1] = zero16(); }
+    for (int a = 0; a < 2; ++a) { gWc1[a] = zero16(); gWc2[a][0] = zero16(); gWc2[a][1] = zero16(); }
+    // The output layer has 3 rows: its gradient tiles are 3 real rows of 32, too little to deserve 32 accumulator
+    // registers next to the others.  Each wavefront keeps those 3 x 64 sums in LDS words of its own (one owner lane
+    // per word, plain read-add-write, so the order of the additions is fixed).
+    float *gWc3 = acc3 + (threadIdx.x >> 6) * (2 * 3 * 32);      // [input tile][row][column]
+    if (h == 0) {
+#pragma unroll
+        for (int k = 0; k < 6; ++k) gWc3[k * 32 + (lane_fixed & 31)] = 0.0f;
+    }
 
     for (uint64_t tile = wave; tile < n_tiles; tile += n_waves) {
         const uint64_t n = tile * 32 + (lane_fixed & 31);
@@ -332,9 +341,14 @@ colour_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__
         transpose_tile(t.c2[0], t.c2[1], selT0, selT1, ta[0]);
         transpose_tile(t.c2[2], t.c2[3], selT0, selT1, ta[1]);
 #pragma unroll
-        for (int it = 0; it < 2; ++it)
+        for (int it = 0; it < 2; ++it) {
+            f16v part = mma(td[0][0], ta[it][0], zero16());
+            part = mma(td[0][1], ta[it][1], part);
+            if (h == 0) {                  // rows 0..2 of the tile are registers 0..2 of the lower half's lanes
 #pragma unroll
-            for (int p = 0; p < 2; ++p) gWc3[it] = mma(td[0][p], ta[it][p], gWc3[it]);
+                for (int o = 0; o < 3; ++o) gWc3[(it * 3 + o) * 32 + (lane_fixed & 31)] += part[o];
+            }
+        }
         f16v g[2];
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) g[mt] = mma(image(lds, cC3T + mt, lane), d3, zero16());
@@ -384,8 +398,12 @@ colour_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__
 
     float *mine = shares + wave * (kTotal - oWc1) - oWc1;       // colour shares hold elements [oWc1, kTotal)
     const int lane = lane_fixed;
-    store_share(mine + oWc3, HC, 3, 0, 0, lane, gWc3[0]);
-    store_share(mine + oWc3, HC, 3, 0, 1, lane, gWc3[1]);
+    if (h == 0) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it)
+#pragma unroll
+            for (int o = 0; o < 3; ++o) mine[oWc3 + o * HC + 32 * it + (lane & 31)] = gWc3[(it * 3 + o) * 32 + (lane & 31)];
+    }
 #pragma unroll
     for (int ot = 0; ot < 2; ++ot) {
         store_share(mine + oWc2, HC, HC, ot, 0, lane, gWc2[ot][0]);
