@@ -47,7 +47,21 @@ CONFIGS = {
         cam_height=1.5, R=1 << 20, S=64, k_max=4, extra_fraction=0.6,
         grid=dict(L=16, F=2, log2_T=24, n_min=16, n_max=8192), table_range=1e-4,
         mlp=dict(n_hidden_d=64, n_geo=16, sh_degree=4, n_hidden_c=64, n_layers_c=2)),
+    # Two-level cascade of Sec. 4.2.2: fine sub-models tile the inner box, coarse sub-models (T = 2^19) tile the outer
+    # box with the same split planes and cover it minus the inner box ("holes": the box subtracted from each partition).
+    "c6_cascade": dict(
+        parts=np.concatenate([_tile([-1, 0, 1], [-1, 0, 1], 0, 0.25), _tile([-3, 0, 3], [-3, 0, 3], 0, 0.5)]),
+        holes=np.concatenate([np.zeros((4, 6), np.float32), _tile([-1, 0, 1], [-1, 0, 1], 0, 0.25)]),
+        rays="oblique", r_max=4.0, cam_height=1.5, R=1 << 18, S=64, k_max=10,
+        grid=dict(L=16, F=2, log2_T=22, n_min=16, n_max=2048), grid_coarse=dict(L=16, F=2, log2_T=19, n_min=16, n_max=2048),
+        coarse_from=4, table_range=1e-4,
+        mlp=dict(n_hidden_d=64, n_geo=16, sh_degree=4, n_hidden_c=64, n_layers_c=2)),
 }
+
+
+def grid_params(cfg, p):
+    """Hash-grid hyper-parameters of partition p (the coarse level of a cascade has its own)."""
+    return cfg["grid_coarse"] if "coarse_from" in cfg and p >= cfg["coarse_from"] else cfg["grid"]
 
 
 def config(name, **overrides):

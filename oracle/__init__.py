@@ -136,16 +136,19 @@ def encode_bwd(g, u, dfeat):
 
 
 # ---------------------------------------------------------------- rays and segments
-def ray_aabb_segments(o, d, aabb, t_min, k_max):
+def ray_aabb_segments(o, d, aabb, t_min, k_max, holes=None):
     o = _arr(o, np.float32).reshape(-1, 3)
     d = _arr(d, np.float32).reshape(-1, 3)
     aabb = _arr(aabb, np.float32).reshape(-1, 6)
     R, P = o.shape[0], aabb.shape[0]
+    if holes is not None:
+        holes = _arr(holes, np.float32).reshape(-1, 6)
+        assert holes.shape[0] == P
     cnt = np.zeros(R, np.uint32)
     seg_t = np.zeros((R, k_max, 2), np.float32)
     seg_part = np.zeros((R, k_max), np.int32)
     status = np.zeros(1, np.uint32)
-    lib().dgo_ray_aabb_segments(_p(o), _p(d), C.c_uint32(R), _p(aabb), C.c_uint32(P), C.c_float(t_min),
+    lib().dgo_ray_aabb_segments(_p(o), _p(d), C.c_uint32(R), _p(aabb), _p(holes), C.c_uint32(P), C.c_float(t_min),
                                 C.c_uint32(k_max), _p(cnt), _p(seg_t), _p(seg_part), _p(status))
     return cnt, seg_t, seg_part, int(status[0])
 

@@ -145,8 +145,47 @@ void dgo_encode_bwd(const dgo_grid *g, const float *u, const double *dfeat, uint
 /* Rays, boxes, segments (Sec. 4.2.1, Sec. 4.4.2, Fig. 2 steps 2-3)    */
 /* ------------------------------------------------------------------ */
 
-void dgo_ray_aabb_segments(const float *o, const float *d, uint32_t R, const float *aabb, uint32_t P,
-                           float t_min, uint32_t k_max, uint32_t *seg_count, float *seg_t,
+/* slab test of one ray against one box; 0 = miss.  One rounding per operation; a ray parallel to a slab is inside
+ * iff lo <= o < hi (half-open, so a ray lying in a shared face belongs to the higher box). */
+static int slab_interval(const float *o, const float *d, const float *lo, const float *hi, float t_min,
+                         float *t_in, float *t_out)
+{
+    float tn = -INFINITY, tf = INFINITY;
+    for (int a = 0; a < 3; ++a) {
+        float oa = o[a], da = d[a];
+        if (da == 0.0f) {
+            if (!(lo[a] <= oa && oa < hi[a])) return 0;
+            continue;
+        }
+        float inv = 1.0f / da;
+        float t1 = (lo[a] - oa) * inv;
+        float t2 = (hi[a] - oa) * inv;
+        tn = fmaxf(tn, fminf(t1, t2));
+        tf = fminf(tf, fmaxf(t1, t2));
+    }
+    *t_in = fmaxf(tn, t_min);
+    *t_out = tf;
+    return *t_out > *t_in;
+}
+
+/* insert a segment in front-to-back order: ascending entry time, ties keep the order of insertion */
+static void insert_segment(float *st, int32_t *sp, uint32_t *cnt, uint32_t k_max, uint32_t *status,
+                           float t_in, float t_out, int32_t p)
+{
+    uint32_t pos = *cnt < k_max ? *cnt : k_max;
+    while (pos > 0 && st[2 * (pos - 1)] > t_in) --pos;
+    if (pos >= k_max) { if (status) *status |= 1u; return; }
+    if (*cnt >= k_max && status) *status |= 1u;
+    uint32_t last = *cnt < k_max ? *cnt : k_max - 1;
+    for (uint32_t k = last; k > pos; --k) {
+        st[2 * k] = st[2 * (k - 1)]; st[2 * k + 1] = st[2 * (k - 1) + 1]; sp[k] = sp[k - 1];
+    }
+    st[2 * pos] = t_in; st[2 * pos + 1] = t_out; sp[pos] = p;
+    if (*cnt < k_max) ++*cnt;
+}
+
+void dgo_ray_aabb_segments(const float *o, const float *d, uint32_t R, const float *aabb, const float *holes,
+                           uint32_t P, float t_min, uint32_t k_max, uint32_t *seg_count, float *seg_t,
                            int32_t *seg_part, uint32_t *status)
 {
     for (uint32_t r = 0; r < R; ++r) {
@@ -156,34 +195,19 @@ void dgo_ray_aabb_segments(const float *o, const float *d, uint32_t R, const flo
         for (uint32_t k = 0; k < k_max; ++k) { st[2 * k] = 0.0f; st[2 * k + 1] = 0.0f; sp[k] = -1; }
         for (uint32_t p = 0; p < P; ++p) {
             const float *lo = aabb + 6 * p, *hi = lo + 3;
-            float tn = -INFINITY, tf = INFINITY;
-            int miss = 0;
-            for (int a = 0; a < 3; ++a) {
-                float oa = o[3 * r + a], da = d[3 * r + a];
-                if (da == 0.0f) {
-                    /* parallel to this slab: inside iff lo <= o < hi (half-open) */
-                    if (!(lo[a] <= oa && oa < hi[a])) miss = 1;
-                    continue;
-                }
-                float inv = 1.0f / da;
-                float t1 = (lo[a] - oa) * inv;
-                float t2 = (hi[a] - oa) * inv;
-                tn = fmaxf(tn, fminf(t1, t2));
-                tf = fminf(tf, fmaxf(t1, t2));
+            float t_in, t_out;
+            if (!slab_interval(o + 3 * r, d + 3 * r, lo, hi, t_min, &t_in, &t_out)) continue;
+            /* the region of partition p is its box minus its hole (Sec. 4.2.2: the coarse level covers the outer box
+             * around the inner one); a hole with no volume is no hole */
+            const float *hlo = holes ? holes + 6 * p : NULL, *hhi = hlo ? hlo + 3 : NULL;
+            float h_in, h_out;
+            if (hlo && hhi[0] > hlo[0] && hhi[1] > hlo[1] && hhi[2] > hlo[2] &&
+                slab_interval(o + 3 * r, d + 3 * r, hlo, hhi, t_min, &h_in, &h_out)) {
+                if (h_in > t_in) insert_segment(st, sp, &cnt, k_max, status, t_in, h_in, (int32_t)p);
+                if (t_out > h_out) insert_segment(st, sp, &cnt, k_max, status, h_out, t_out, (int32_t)p);
+            } else {
+                insert_segment(st, sp, &cnt, k_max, status, t_in, t_out, (int32_t)p);
             }
-            float t_in = fmaxf(tn, t_min), t_out = tf;
-            if (miss || !(t_out > t_in)) continue;
-            /* insert in front-to-back order: ascending entry time, ties by box index */
-            uint32_t pos = cnt < k_max ? cnt : k_max;
-            while (pos > 0 && st[2 * (pos - 1)] > t_in) --pos;
-            if (pos >= k_max) { if (status) *status |= 1u; continue; }
-            if (cnt >= k_max && status) *status |= 1u;
-            uint32_t last = cnt < k_max ? cnt : k_max - 1;
-            for (uint32_t k = last; k > pos; --k) {
-                st[2 * k] = st[2 * (k - 1)]; st[2 * k + 1] = st[2 * (k - 1) + 1]; sp[k] = sp[k - 1];
-            }
-            st[2 * pos] = t_in; st[2 * pos + 1] = t_out; sp[pos] = (int32_t)p;
-            if (cnt < k_max) ++cnt;
         }
         seg_count[r] = cnt;
     }

@@ -62,9 +62,11 @@ void dgo_encode_fwd(const dgo_grid *g, const float *table, const float *u, uint6
 void dgo_encode_bwd(const dgo_grid *g, const float *u, const double *dfeat, uint64_t n,
                     double *dtable);
 
-/* Ray / AABB slab test against P boxes; ordered segment list per ray (Sec. 4.2.1, Fig. 2 step 2). */
-void dgo_ray_aabb_segments(const float *o, const float *d, uint32_t R, const float *aabb, uint32_t P,
-                           float t_min, uint32_t k_max, uint32_t *seg_count, float *seg_t,
+/* Ray / AABB slab test against P boxes; ordered segment list per ray (Sec. 4.2.1, Fig. 2 step 2).
+ * holes: NULL, or P boxes; partition p then covers its box minus holes[p] (the coarse level of the two-level
+ * cascade of Sec. 4.2.2 covers the outer box around the inner one), which a ray meets in up to two segments. */
+void dgo_ray_aabb_segments(const float *o, const float *d, uint32_t R, const float *aabb, const float *holes,
+                           uint32_t P, float t_min, uint32_t k_max, uint32_t *seg_count, float *seg_t,
                            int32_t *seg_part, uint32_t *status);
 /* Stable distribution of (ray, slot) pairs to partitions (Fig. 2 step 3). */
 void dgo_bucket_segments(const uint32_t *seg_count, const int32_t *seg_part, uint32_t R, uint32_t k_max,

@@ -200,3 +200,89 @@ def test_spherical_harmonics():
         np.testing.assert_allclose((Y[:, l * l:(l + 1) ** 2] ** 2).sum(1), (2 * l + 1) / (4 * np.pi), rtol=1e-12)
     # degree 2 is the prefix of degree 4
     np.testing.assert_array_equal(oracle.sh(rnd, 2), Y[:, :4])
+
+
+# ---------------------------------------------------------------------------- partitions with a hole (Sec. 4.2.2)
+def _cascade():
+    cfg = di.config("c6_cascade")
+    return cfg, cfg["parts"], cfg["holes"]
+
+
+def test_cascade_segments_pave_the_outer_box():
+    cfg, parts, holes = _cascade()
+    R = 500
+    o, d = di.make_rays(cfg, seed=2, R=R)
+    cnt, seg_t, part, status = oracle.ray_aabb_segments(o, d, parts, 0.0, 10, holes=holes)
+    assert status == 0
+    scene = np.concatenate([parts[:, :3].min(0), parts[:, 3:].max(0)])[None]
+    wcnt, wt, _, _ = oracle.ray_aabb_segments(o, d, scene, 0.0, 1)
+    seen_two = 0
+    for r in range(R):
+        K = cnt[r]
+        assert (K > 0) == (wcnt[r] > 0)
+        if K == 0:
+            continue
+        t = seg_t[r, :K]
+        assert np.all(t[:, 1] > t[:, 0])
+        np.testing.assert_array_equal(t[1:, 0], t[:-1, 1])          # fine and coarse pieces share bit-identical boundaries
+        assert abs(t[0, 0] - wt[r, 0, 0]) <= 1e-5 * max(1.0, abs(wt[r, 0, 0]))
+        assert abs(t[-1, 1] - wt[r, 0, 1]) <= 1e-5 * max(1.0, abs(wt[r, 0, 1]))
+        ids = list(part[r, :K])
+        seen_two += any(ids.count(p) == 2 for p in ids)
+        assert all(ids.count(p) <= (2 if p >= 4 else 1) for p in ids)     # only a region with a hole is met twice
+        for k in range(K):
+            p = part[r, k]
+            for frac in (0.02, 0.5, 0.98):
+                x = o[r].astype(np.float64) + (t[k, 0] + frac * (float(t[k, 1]) - float(t[k, 0]))) * d[r].astype(np.float64)
+                assert np.all(x >= parts[p, :3] - 1e-5) and np.all(x <= parts[p, 3:] + 1e-5)
+                if p >= 4:      # not strictly inside the hole
+                    assert not (np.all(x > holes[p, :3] + 1e-5) and np.all(x < holes[p, 3:] - 1e-5))
+    assert seen_two > 20        # the recipe does produce rays that enter a coarse region twice
+
+
+def test_cascade_brute_force_labels():
+    cfg, parts, holes = _cascade()
+    o, d = di.make_rays(cfg, seed=7, R=40)
+    cnt, seg_t, part, _ = oracle.ray_aabb_segments(o, d, parts, 0.0, 10, holes=holes)
+    P64, H64 = parts.astype(np.float64), holes.astype(np.float64)
+    for r in range(40):
+        ts = np.linspace(0.0, 30.0, 120001)
+        x = o[r].astype(np.float64)[None] + ts[:, None] * d[r].astype(np.float64)[None]
+        label = np.full(ts.size, -1)
+        for p in range(8):
+            inside = np.all((x >= P64[p, :3]) & (x < P64[p, 3:]), axis=1)
+            if p >= 4:
+                inside &= ~np.all((x >= H64[p, :3]) & (x < H64[p, 3:]), axis=1)
+            label[inside] = p
+        order = [int(label[i]) for i in range(ts.size) if label[i] >= 0 and (i == 0 or label[i] != label[i - 1])]
+        mine = [int(part[r, k]) for k in range(cnt[r]) if seg_t[r, k, 1] - seg_t[r, k, 0] > 2e-3]
+        kept, it = [], iter(order)
+        assert all(any(q == p for q in it) for p in mine), (r, order, mine)       # `mine` is a subsequence of the brute-force order
+
+
+def test_hole_without_volume_or_out_of_reach_changes_nothing():
+    cfg, parts, holes = _cascade()
+    o, d = di.make_rays(cfg, seed=3, R=300)
+    ref = oracle.ray_aabb_segments(o, d, parts, 0.0, 10)
+    flat = np.zeros_like(holes)
+    flat[:, 3:5] = 1.0                                  # zero height: no volume
+    got = oracle.ray_aabb_segments(o, d, parts, 0.0, 10, holes=flat)
+    for a, b in zip(ref[:3], got[:3]):
+        np.testing.assert_array_equal(a, b)
+    far = np.tile(np.array([50, 50, 50, 51, 51, 51], np.float32), (8, 1))    # a hole no ray reaches
+    got = oracle.ray_aabb_segments(o, d, parts, 0.0, 10, holes=far)
+    for a, b in zip(ref[:3], got[:3]):
+        np.testing.assert_array_equal(a, b)
+
+
+def test_single_box_with_a_centred_hole():
+    # textbook case: unit cube with a cube hole in the middle, ray along x through the centre
+    box = np.array([[0, 0, 0, 4, 4, 4]], np.float32)
+    hole = np.array([[1, 1, 1, 3, 3, 3]], np.float32)
+    o = np.array([[-1, 2, 2], [-1, 0.5, 2], [2, 2, 2]], np.float32)
+    d = np.array([[1, 0, 0], [1, 0, 0], [1, 0, 0]], np.float32)
+    cnt, t, part, _ = oracle.ray_aabb_segments(o, d, box, 0.0, 4, holes=hole)
+    assert list(cnt) == [2, 1, 1]
+    np.testing.assert_array_equal(t[0, :2], [[1, 2], [4, 5]])
+    np.testing.assert_array_equal(t[1, 0], [1, 5])                        # passes beside the hole
+    np.testing.assert_array_equal(t[2, 0], [1, 2])                        # starts inside the hole (t_min = 0): only the far piece
