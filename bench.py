@@ -103,18 +103,20 @@ def main():
     # seeded synthetic inputs, moved to HBM before anything is timed
     o, d = di.make_rays(cfg, seed=0)
     Cgt = di.make_targets(R, seed=0)
-    growth = g.get("growth") or B.dg_growth_factor(g["n_min"], g["n_max"], g["L"])
     n_feat = g["L"] * g["F"]
     models = {}
     for p in resident:
-        grid = B.dg_grid_desc_init(g["L"], g["F"], g["log2_T"], g["n_min"], growth, di.box_extent(cfg["parts"][p]))
+        gp = di.grid_params(cfg, p)            # the coarse level of a cascade has its own table length
+        growth = gp.get("growth") or B.dg_growth_factor(gp["n_min"], gp["n_max"], gp["L"])
+        grid = B.dg_grid_desc_init(gp["L"], gp["F"], gp["log2_T"], gp["n_min"], growth, di.box_extent(cfg["parts"][p]))
         mlp = B.dg_mlp_desc(n_feat, m["n_hidden_d"], m["n_geo"], m["sh_degree"] ** 2, m["n_hidden_c"], m["n_layers_c"], 1)
-        table = to_dev(di.make_table(grid.n_entries, g["F"], cfg["table_range"], seed=1000 * p))
+        table = to_dev(di.make_table(grid.n_entries, gp["F"], cfg["table_range"], seed=1000 * p))
         weights = to_dev(di.make_mlp_weights(n_feat, m, seed=1000 * p))
         models[p] = SubModel(grid, mlp, table, weights)
     od, dd, Cd = to_dev(o), to_dev(d), to_dev(Cgt)
     step = TrainStep(to_dev(cfg["parts"]), models, resident, R, S, k_max, m["sh_degree"], loss_scale=65536.0,
-                     lambda1=1e-3, seed=0)
+                     lambda1=1e-3, seed=0, holes=to_dev(cfg["holes"]) if "holes" in cfg else None,
+                     max_segments=R * min(k_max, 4))         # rays of these recipes average well under four segments
 
     for w in range(args.warmup):
         step.seed = w

@@ -52,7 +52,7 @@ CONFIGS = {
     "c6_cascade": dict(
         parts=np.concatenate([_tile([-1, 0, 1], [-1, 0, 1], 0, 0.25), _tile([-3, 0, 3], [-3, 0, 3], 0, 0.5)]),
         holes=np.concatenate([np.zeros((4, 6), np.float32), _tile([-1, 0, 1], [-1, 0, 1], 0, 0.25)]),
-        rays="oblique", r_max=4.0, cam_height=1.5, R=1 << 18, S=64, k_max=10,
+        rays="through_inner", r_max=2.5, cam_height=1.5, R=1 << 18, S=64, k_max=10,
         grid=dict(L=16, F=2, log2_T=22, n_min=16, n_max=2048), grid_coarse=dict(L=16, F=2, log2_T=19, n_min=16, n_max=2048),
         coarse_from=4, table_range=1e-4,
         mlp=dict(n_hidden_d=64, n_geo=16, sh_degree=4, n_hidden_c=64, n_layers_c=2)),
@@ -147,6 +147,9 @@ def make_rays(cfg, seed=0, R=None):
         return rays_aerial(R, scene, cfg["cam_height"], cfg["tilt_deg"], rng)
     if kind == "oblique":
         return rays_oblique(R, scene, cfg["cam_height"], cfg["r_max"], rng)
+    if kind == "through_inner":       # cameras look at the inner (fine) area of a cascade: entry points above it
+        fine = parts[:cfg["coarse_from"]]
+        return rays_oblique(R, scene, cfg["cam_height"], cfg["r_max"], rng, through=np.concatenate([fine[:, :3].min(0), fine[:, 3:].max(0)]))
     if kind == "through_resident":
         return rays_oblique(R, scene, cfg["cam_height"], cfg["r_max"], rng, through=parts[cfg["resident"]])
     raise ValueError(kind)

@@ -86,11 +86,18 @@ int dg_grid_desc_init(dg_grid_desc *desc, uint32_t L, uint32_t F, uint32_t log2_
  * a stable counting sort: part_offset [P+1], seg_ray / seg_slot [R*k_max capacity] hold
  * box p's segments at [part_offset[p], part_offset[p+1]) in ascending (ray,slot) order.
  * That step needs dg_segments_workspace_bytes(R,P) bytes of device workspace.
- * P <= DG_MAX_PARTITIONS, 1 <= k_max <= 8.
+ * holes: NULL, or [P,6] fp32 device boxes: partition p then covers parts[p] minus holes[p]
+ * (Sec. 4.2.2: the coarse sub-models of the two-level cascade cover the outer box around the
+ * inner one, split by the same planes).  The hole's interval on the ray comes from the same
+ * slab expressions; the region is met in up to two pieces, [t_in, hole entry] and [hole exit,
+ * t_out], each kept if it has positive length and listed under box index p.  A hole with no
+ * volume (hi <= lo on some axis) is no hole.  Faces that a hole shares with another box give
+ * bit-identical times, so fine and coarse pieces pave the ray as plain boxes do.
+ * P <= DG_MAX_PARTITIONS, 1 <= k_max <= 12.
  * ---------------------------------------------------------------------------------- */
 size_t dg_segments_workspace_bytes(uint32_t R, uint32_t P);
 int dg_ray_aabb_segments(const float *o, const float *d, uint32_t R,
-                         const float *parts, uint32_t P, float t_min, uint32_t k_max,
+                         const float *parts, const float *holes, uint32_t P, float t_min, uint32_t k_max,
                          uint32_t *seg_count, float *seg_t, int32_t *seg_part,
                          uint32_t *part_offset, uint32_t *seg_ray, uint32_t *seg_slot,
                          uint32_t *status, void *ws, size_t ws_bytes, void *stream);

@@ -11,9 +11,10 @@ import oracle as O
 def make_models(cfg, seed=0):
     """Grid geometry, MLP descriptor and seeded parameters for every partition of a configuration."""
     import dg_inputs as di
-    g, m = cfg["grid"], cfg["mlp"]
+    m = cfg["mlp"]
     models = {}
     for p in cfg.get("resident_list", range(cfg["parts"].shape[0])):
+        g = di.grid_params(cfg, p)
         growth = g.get("growth") or O.growth_factor(g["n_min"], g["n_max"], g["L"])
         grid = O.grid_init(g["L"], g["F"], g["log2_T"], g["n_min"], growth, di.box_extent(cfg["parts"][p]))
         n_feat = g["L"] * g["F"]
@@ -32,7 +33,7 @@ def run_step(cfg, models, o, d, Cgt, jitter=None, seed=0, lambda1=0.0, loss_scal
     deg = cfg["mlp"]["sh_degree"]
     resident = list(range(P)) if resident is None else list(resident)
     out = {}
-    cnt, seg_t, seg_part, status = O.ray_aabb_segments(o, d, parts, 0.0, k_max)
+    cnt, seg_t, seg_part, status = O.ray_aabb_segments(o, d, parts, 0.0, k_max, holes=cfg.get("holes"))
     off, seg_ray, seg_slot = O.bucket_segments(cnt, seg_part, P)
     out.update(seg_count=cnt, seg_t=seg_t, seg_part=seg_part, status=status, part_offset=off, seg_ray=seg_ray,
                seg_slot=seg_slot)

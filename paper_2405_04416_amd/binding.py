@@ -45,7 +45,7 @@ _SIGNATURES = {
     "dg_grid_desc_init": (C.c_int, [C.POINTER(GridDesc), C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_double,
                                     C.POINTER(C.c_double)]),
     "dg_segments_workspace_bytes": (C.c_size_t, [C.c_uint32, C.c_uint32]),
-    "dg_ray_aabb_segments": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_float, C.c_uint32,
+    "dg_ray_aabb_segments": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32, C.c_float, C.c_uint32,
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_size_t, C.c_void_p]),
     "dg_sample_segments": (C.c_int, [C.c_void_p] * 5 + [C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.c_uint32,
@@ -144,10 +144,11 @@ def dg_mlp_bwd_workspace_bytes(desc, N):
 
 # ------------------------------------------------------------------ device entry points
 def dg_ray_aabb_segments(o, d, parts, t_min, k_max, seg_count, seg_t, seg_part, status, part_offset=None, seg_ray=None,
-                         seg_slot=None, ws=None):
+                         seg_slot=None, ws=None, holes=None):
     R, P = o.shape[0], parts.shape[0]
+    assert holes is None or tuple(holes.shape) == tuple(parts.shape)
     _check(lib().dg_ray_aabb_segments(
-        _ptr(o, torch.float32), _ptr(d, torch.float32), R, _ptr(parts, torch.float32), P, t_min, k_max,
+        _ptr(o, torch.float32), _ptr(d, torch.float32), R, _ptr(parts, torch.float32), _ptr(holes, torch.float32, True), P, t_min, k_max,
         _ptr(seg_count, torch.int32), _ptr(seg_t, torch.float32), _ptr(seg_part, torch.int32),
         _ptr(part_offset, torch.int32, True), _ptr(seg_ray, torch.int32, True), _ptr(seg_slot, torch.int32, True),
         _ptr(status, torch.int32), _ptr(ws, None, True), 0 if ws is None else ws.numel() * ws.element_size(), _stream()))

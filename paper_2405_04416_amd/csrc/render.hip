@@ -134,7 +134,7 @@ composite_bwd_kernel(const float *__restrict__ sigma, const float *__restrict__ 
     }
 }
 
-constexpr uint32_t kMaxK = 8;
+constexpr uint32_t kMaxK = 12;
 
 __global__ void __launch_bounds__(kBlock)
 merge_fwd_kernel(const float *__restrict__ Ck, const float *__restrict__ Tk, const uint32_t *__restrict__ seg_count,

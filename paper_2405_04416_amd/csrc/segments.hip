@@ -11,69 +11,95 @@
 namespace {
 
 constexpr int kBlock = 256;
-constexpr uint32_t kMaxK = 8;
+constexpr uint32_t kMaxK = 12;
 
 // ---------------------------------------------------------------- ray / box slab test
+// interval of the ray inside one box, clipped to t >= t_min; false = miss
+__device__ __forceinline__ bool slab_interval(const float (&oo)[3], const float (&dd)[3], const float (&inv)[3], const float *lo,
+                                              const float *hi, float t_min, float &t_in, float &t_out)
+{
+    float tn = -INFINITY, tf = INFINITY;
+    bool miss = false;
+    for (int a = 0; a < 3; ++a) {
+        if (dd[a] == 0.0f) {
+            if (!(lo[a] <= oo[a] && oo[a] < hi[a])) miss = true;   // half-open: shared faces go up
+            continue;
+        }
+        const float t1 = (lo[a] - oo[a]) * inv[a];
+        const float t2 = (hi[a] - oo[a]) * inv[a];
+        tn = fmaxf(tn, fminf(t1, t2));
+        tf = fminf(tf, fmaxf(t1, t2));
+    }
+    t_in = fmaxf(tn, t_min);
+    t_out = tf;
+    return !miss && t_out > t_in;
+}
+
+struct SegmentList {
+    float tin[kMaxK], tout[kMaxK];
+    int32_t pid[kMaxK];
+    uint32_t cnt;
+    bool overflow;
+};
+
+// sorted insert, front to back; equal entry times keep the order of insertion
+__device__ __forceinline__ void insert_segment(SegmentList &L, uint32_t k_max, float t_in, float t_out, int32_t p)
+{
+    uint32_t pos = L.cnt;
+    while (pos > 0 && L.tin[pos - 1] > t_in) --pos;
+    if (L.cnt >= k_max) L.overflow = true;
+    if (pos >= k_max) return;
+    const uint32_t last = L.cnt < k_max ? L.cnt : k_max - 1;
+    for (uint32_t k = last; k > pos; --k) { L.tin[k] = L.tin[k - 1]; L.tout[k] = L.tout[k - 1]; L.pid[k] = L.pid[k - 1]; }
+    L.tin[pos] = t_in; L.tout[pos] = t_out; L.pid[pos] = p;
+    if (L.cnt < k_max) ++L.cnt;
+}
+
+// A partition covers its box minus its hole (Sec. 4.2.2: coarse sub-models cover the outer box around the inner one);
+// a ray meets such a region in up to two pieces, [t_in, hole entry] and [hole exit, t_out].
 __global__ void __launch_bounds__(kBlock)
 ray_aabb_kernel(const float *__restrict__ o, const float *__restrict__ d, uint32_t R,
-                const float *__restrict__ parts, uint32_t P, float t_min, uint32_t k_max,
+                const float *__restrict__ parts, const float *__restrict__ holes, uint32_t P, float t_min, uint32_t k_max,
                 uint32_t *__restrict__ seg_count, float *__restrict__ seg_t, int32_t *__restrict__ seg_part,
                 uint32_t *__restrict__ status)
 {
-    __shared__ float boxes[DG_MAX_PARTITIONS * 6];
-    for (uint32_t i = threadIdx.x; i < P * 6; i += kBlock) boxes[i] = parts[i];
+    __shared__ float boxes[DG_MAX_PARTITIONS * 6], hboxes[DG_MAX_PARTITIONS * 6];
+    for (uint32_t i = threadIdx.x; i < P * 6; i += kBlock) { boxes[i] = parts[i]; hboxes[i] = holes ? holes[i] : 0.0f; }
     __syncthreads();
     const uint32_t r = blockIdx.x * kBlock + threadIdx.x;
     if (r >= R) return;
-    const float ox = o[3 * r], oy = o[3 * r + 1], oz = o[3 * r + 2];
-    const float dx = d[3 * r], dy = d[3 * r + 1], dz = d[3 * r + 2];
-    const float oo[3] = {ox, oy, oz}, dd[3] = {dx, dy, dz};
+    const float oo[3] = {o[3 * r], o[3 * r + 1], o[3 * r + 2]}, dd[3] = {d[3 * r], d[3 * r + 1], d[3 * r + 2]};
     float inv[3];
     for (int a = 0; a < 3; ++a) inv[a] = dd[a] != 0.0f ? 1.0f / dd[a] : 0.0f;
 
-    float tin[kMaxK], tout[kMaxK];
-    int32_t pid[kMaxK];
-    uint32_t cnt = 0;
-    bool overflow = false;
+    SegmentList L;
+    L.cnt = 0;
+    L.overflow = false;
     for (uint32_t p = 0; p < P; ++p) {
-        const float *lo = boxes + 6 * p, *hi = lo + 3;
-        float tn = -INFINITY, tf = INFINITY;
-        bool miss = false;
-        for (int a = 0; a < 3; ++a) {
-            if (dd[a] == 0.0f) {
-                if (!(lo[a] <= oo[a] && oo[a] < hi[a])) miss = true;   // half-open: shared faces go up
-                continue;
-            }
-            const float t1 = (lo[a] - oo[a]) * inv[a];
-            const float t2 = (hi[a] - oo[a]) * inv[a];
-            tn = fmaxf(tn, fminf(t1, t2));
-            tf = fminf(tf, fmaxf(t1, t2));
+        const float *lo = boxes + 6 * p, *hi = lo + 3, *hlo = hboxes + 6 * p, *hhi = hlo + 3;
+        float t_in, t_out, h_in, h_out;
+        if (!slab_interval(oo, dd, inv, lo, hi, t_min, t_in, t_out)) continue;
+        const bool has_hole = hhi[0] > hlo[0] && hhi[1] > hlo[1] && hhi[2] > hlo[2];      // a hole with no volume is no hole
+        if (has_hole && slab_interval(oo, dd, inv, hlo, hhi, t_min, h_in, h_out)) {
+            if (h_in > t_in) insert_segment(L, k_max, t_in, h_in, (int32_t)p);
+            if (t_out > h_out) insert_segment(L, k_max, h_out, t_out, (int32_t)p);
+        } else {
+            insert_segment(L, k_max, t_in, t_out, (int32_t)p);
         }
-        const float t_in = fmaxf(tn, t_min), t_out = tf;
-        if (miss || !(t_out > t_in)) continue;
-        // sorted insert, front to back; boxes are visited in index order so ties keep that order
-        uint32_t pos = cnt;
-        while (pos > 0 && tin[pos - 1] > t_in) --pos;
-        if (cnt >= k_max) overflow = true;
-        if (pos >= k_max) continue;
-        const uint32_t last = cnt < k_max ? cnt : k_max - 1;
-        for (uint32_t k = last; k > pos; --k) { tin[k] = tin[k - 1]; tout[k] = tout[k - 1]; pid[k] = pid[k - 1]; }
-        tin[pos] = t_in; tout[pos] = t_out; pid[pos] = (int32_t)p;
-        if (cnt < k_max) ++cnt;
     }
-    seg_count[r] = cnt;
+    seg_count[r] = L.cnt;
     for (uint32_t k = 0; k < k_max; ++k) {
-        const bool used = k < cnt;
-        seg_t[((size_t)r * k_max + k) * 2] = used ? tin[k] : 0.0f;
-        seg_t[((size_t)r * k_max + k) * 2 + 1] = used ? tout[k] : 0.0f;
-        seg_part[(size_t)r * k_max + k] = used ? pid[k] : -1;
+        const bool used = k < L.cnt;
+        seg_t[((size_t)r * k_max + k) * 2] = used ? L.tin[k] : 0.0f;
+        seg_t[((size_t)r * k_max + k) * 2 + 1] = used ? L.tout[k] : 0.0f;
+        seg_part[(size_t)r * k_max + k] = used ? L.pid[k] : -1;
     }
-    if (overflow) atomicOr(status, 1u);
+    if (L.overflow) atomicOr(status, 1u);
 }
 
 // ---------------------------------------------------------------- stable distribution to boxes
 // Three passes: per-block histogram, scan over blocks, scatter with in-block stable ranks.
-// A convex box is crossed at most once by a ray, so a ray holds at most one segment per box.
+// A ray holds at most two segments per partition (a convex box is crossed once; a box with a hole in up to two pieces).
 __global__ void __launch_bounds__(kBlock)
 bucket_count_kernel(const uint32_t *__restrict__ seg_count, const int32_t *__restrict__ seg_part, uint32_t R,
                     uint32_t k_max, uint32_t P, uint32_t n_blocks, uint32_t *__restrict__ block_hist)
@@ -138,19 +164,22 @@ bucket_scatter_kernel(const uint32_t *__restrict__ seg_count, const int32_t *__r
         for (uint32_t k = 0; k < kMaxK; ++k) mine[k] = (k < cnt && k < k_max) ? seg_part[(size_t)r * k_max + k] : -1;
     }
     for (uint32_t p = 0; p < P; ++p) {
-        int slot = -1;
-        for (uint32_t k = 0; k < kMaxK; ++k) if (k < cnt && mine[k] == (int32_t)p) slot = (int)k;
-        const unsigned long long vote = __ballot(slot >= 0);
-        const uint32_t before = __popcll(vote & ((1ull << lane) - 1ull));
-        if (lane == 0) wave_count[wave] = __popcll(vote);
+        int first = -1, second = -1;          // this ray's slots in box p, front to back
+        for (uint32_t k = 0; k < kMaxK; ++k)
+            if (k < cnt && mine[k] == (int32_t)p) { if (first < 0) first = (int)k; else second = (int)k; }
+        const unsigned long long vote1 = __ballot(first >= 0), vote2 = __ballot(second >= 0);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        const uint32_t before = __popcll(vote1 & below) + __popcll(vote2 & below);
+        if (lane == 0) wave_count[wave] = __popcll(vote1) + __popcll(vote2);
         __syncthreads();
         uint32_t base = 0;
         for (uint32_t w = 0; w < wave; ++w) base += wave_count[w];
         __syncthreads();
-        if (slot >= 0) {
+        if (first >= 0) {
             const uint32_t dst = part_offset[p] + block_hist[(size_t)p * n_blocks + blockIdx.x] + base + before;
             seg_ray[dst] = r;
-            seg_slot[dst] = (uint32_t)slot;
+            seg_slot[dst] = (uint32_t)first;
+            if (second >= 0) { seg_ray[dst + 1] = r; seg_slot[dst + 1] = (uint32_t)second; }
         }
     }
 }
@@ -231,8 +260,8 @@ extern "C" size_t dg_segments_workspace_bytes(uint32_t R, uint32_t P)
     return (n_blocks ? n_blocks : 1) * (size_t)P * sizeof(uint32_t);
 }
 
-extern "C" int dg_ray_aabb_segments(const float *o, const float *d, uint32_t R, const float *parts, uint32_t P,
-                                    float t_min, uint32_t k_max, uint32_t *seg_count, float *seg_t,
+extern "C" int dg_ray_aabb_segments(const float *o, const float *d, uint32_t R, const float *parts, const float *holes,
+                                    uint32_t P, float t_min, uint32_t k_max, uint32_t *seg_count, float *seg_t,
                                     int32_t *seg_part, uint32_t *part_offset, uint32_t *seg_ray,
                                     uint32_t *seg_slot, uint32_t *status, void *ws, size_t ws_bytes, void *stream)
 {
@@ -248,7 +277,7 @@ extern "C" int dg_ray_aabb_segments(const float *o, const float *d, uint32_t R, 
                    "dg_ray_aabb_segments: workspace %zu < %zu bytes", ws_bytes, dg_segments_workspace_bytes(R, P));
     }
     if (R > 0) {
-        ray_aabb_kernel<<<n_blocks, kBlock, 0, st>>>(o, d, R, parts, P, t_min, k_max, seg_count, seg_t, seg_part, status);
+        ray_aabb_kernel<<<n_blocks, kBlock, 0, st>>>(o, d, R, parts, holes, P, t_min, k_max, seg_count, seg_t, seg_part, status);
     }
     if (part_offset) {
         uint32_t *hist = (uint32_t *)ws;

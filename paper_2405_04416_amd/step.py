@@ -34,10 +34,11 @@ class SubModel:
 
 class TrainStep:
     def __init__(self, parts, models, resident, R, S, k_max, sh_degree, loss_scale=65536.0, lambda1=0.0, seed=0,
-                 device="cuda:0", max_segments=None, binned_backward=True, encode_ws_cap=48 << 30):
-        """parts: [P,6] float tensor (device); models: {partition index: SubModel}; resident: partition indices served."""
+                 device="cuda:0", max_segments=None, binned_backward=True, encode_ws_cap=48 << 30, holes=None):
+        """parts: [P,6] float tensor (device); models: {partition index: SubModel}; resident: partition indices served;
+        holes: None or [P,6] (device): the box subtracted from each partition (coarse level of the cascade, Sec. 4.2.2)."""
         self.dev = torch.device(device)
-        self.parts, self.models, self.resident = parts, models, list(resident)
+        self.parts, self.models, self.resident, self.holes = parts, models, list(resident), holes
         self.parts_host = parts.cpu().tolist()
         self.P, self.R, self.S, self.k_max, self.deg = parts.shape[0], R, S, k_max, sh_degree
         self.loss_scale, self.lambda1, self.seed = float(loss_scale), float(lambda1), seed
@@ -91,7 +92,7 @@ class TrainStep:
         self.status.zero_()
         with self._timed("dg_ray_aabb_segments"):
             B.dg_ray_aabb_segments(o, d, self.parts, t_min, self.k_max, self.seg_count, self.seg_t, self.seg_part,
-                                   self.status, self.part_offset, self.seg_ray, self.seg_slot, self.ws_seg)
+                                   self.status, self.part_offset, self.seg_ray, self.seg_slot, self.ws_seg, holes=self.holes)
         self.offsets = self.part_offset.cpu().tolist()      # P+1 integers: how many segments each sub-model got
         if self.offsets[-1] > self.cap:
             raise B.DistGridError("segment capacity %d exceeded (%d)" % (self.cap, self.offsets[-1]))

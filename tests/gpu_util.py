@@ -55,7 +55,7 @@ def rel_err(got, ref, floor=None):
 
 
 def gpu_grid(cfg, part=0):
-    g = cfg["grid"]
+    g = di.grid_params(cfg, part)
     growth = g.get("growth") or B.dg_growth_factor(g["n_min"], g["n_max"], g["L"])
     return B.dg_grid_desc_init(g["L"], g["F"], g["log2_T"], g["n_min"], growth, di.box_extent(cfg["parts"][part]))
 
@@ -77,8 +77,9 @@ def gpu_models(cfg, host_models):
 def make_step(cfg, models, R, resident=None, **kw):
     P = cfg["parts"].shape[0]
     resident = list(range(P)) if resident is None else resident
+    holes = dev(cfg["holes"]) if "holes" in cfg else None
     return TrainStep(dev(cfg["parts"]), models, resident, R, cfg["S"], cfg["k_max"], cfg["mlp"]["sh_degree"],
-                     device=DEV, **kw)
+                     device=DEV, holes=holes, **kw)
 
 
 def assert_close_robust(got, ref, tol, what="", outlier_frac=1e-3, min_outliers=3):

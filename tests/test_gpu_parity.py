@@ -33,7 +33,7 @@ def ora_grid(cfg, part=0):
 
 
 # ---------------------------------------------------------------------------- segments
-def _run_segments(o, d, parts, k_max, t_min=0.0):
+def _run_segments(o, d, parts, k_max, t_min=0.0, holes=None):
     R, P = o.shape[0], parts.shape[0]
     i32 = torch.int32
     cnt = torch.zeros(max(R, 1), dtype=i32, device=DEV)
@@ -45,13 +45,15 @@ def _run_segments(o, d, parts, k_max, t_min=0.0):
     status = torch.zeros(1, dtype=i32, device=DEV)
     ws = torch.zeros(max(B.dg_segments_workspace_bytes(R, P) // 4, 1), dtype=i32, device=DEV)
     od, dd = (dev(o), dev(d)) if R else (torch.zeros(1, 3, device=DEV), torch.zeros(1, 3, device=DEV))
-    B.dg_ray_aabb_segments(od[:R], dd[:R], dev(parts), t_min, k_max, cnt, seg_t, part, status, off, ray, slot, ws)
+    B.dg_ray_aabb_segments(od[:R], dd[:R], dev(parts), t_min, k_max, cnt, seg_t, part, status, off, ray, slot, ws,
+                           holes=None if holes is None else dev(holes))
     torch.cuda.synchronize()
     return host(cnt)[:R], host(seg_t)[:R], host(part)[:R], int(host(status)[0]), host(off), host(ray), host(slot)
 
 
 @pytest.mark.parametrize("name,R,k_max", [("c3_2x2", 5000, 4), ("c5_share", 3001, 6), ("c2_ngp", 1000, 1),
-                                          ("c1_tiny", 1024, 1), ("c5_share", 2000, 2)])
+                                          ("c1_tiny", 1024, 1), ("c5_share", 2000, 2), ("c6_cascade", 6001, 10),
+                                          ("c6_cascade", 2500, 3), ("c6_cascade", 999, 12)])
 def test_segments_bit_exact(name, R, k_max):
     say("segments %s R=%d k_max=%d" % (name, R, k_max))
     cfg = di.config(name)
@@ -60,8 +62,8 @@ def test_segments_bit_exact(name, R, k_max):
     o[:3] = [[0.0, -3.0, 0.1], [0.5, 0.5, 5.0], [50.0, 50.0, 50.0]]
     d[:3] = [[0.0, 1.0, 0.0], [0.0, 0.0, -1.0], [0.0, 0.0, 1.0]]
     P = cfg["parts"].shape[0]
-    cnt, seg_t, part, status, off, ray, slot = _run_segments(o, d, cfg["parts"], k_max)
-    rc, rt, rp, rs = oracle.ray_aabb_segments(o, d, cfg["parts"], 0.0, k_max)
+    cnt, seg_t, part, status, off, ray, slot = _run_segments(o, d, cfg["parts"], k_max, holes=cfg.get("holes"))
+    rc, rt, rp, rs = oracle.ray_aabb_segments(o, d, cfg["parts"], 0.0, k_max, holes=cfg.get("holes"))
     np.testing.assert_array_equal(cnt, rc)
     np.testing.assert_array_equal(seg_t.view(np.uint32), rt.view(np.uint32))      # bit for bit
     np.testing.assert_array_equal(part, rp)

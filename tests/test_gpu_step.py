@@ -111,6 +111,19 @@ def test_step_c3_segmented_2x2():
     assert np.mean(ref["seg_count"] >= 2) >= 0.4
 
 
+def test_step_c6_two_level_cascade():
+    say("step c6_cascade, 1000 rays, four fine (T = 2^16) and four coarse (T = 2^14) sub-models, coarse regions with holes")
+    cfg = di.config("c6_cascade")
+    cfg["grid"] = dict(cfg["grid"], log2_T=16)
+    cfg["grid_coarse"] = dict(cfg["grid_coarse"], log2_T=14)
+    step, ref = _compare_step(cfg, 1000, seed=6, lambda1=1e-3, loss_scale=2.0 ** 14, use_jitter_array=False,
+                              table_gain=3000.0)
+    cnt = ref["seg_count"]
+    assert cnt.max() >= 4 and np.mean(cnt >= 3) >= 0.3          # coarse piece, fine piece(s), coarse piece
+    part = ref["seg_part"]
+    assert np.any((part >= 4).sum(axis=1) >= 2) and np.any((part >= 0) & (part < 4))
+
+
 def test_step_c5_one_share_with_foreign_partials():
     say("step c5_share: one resident sub-model, foreign partials from the generator")
     cfg = di.config("c5_share")
