@@ -8,12 +8,12 @@
 //   * levels whose tables fit LDS together (the coarse prefix) are accumulated directly: persistent
 //     workgroups sweep the samples, merge runs of lanes that share a cell, add into an LDS copy of
 //     those tables and flush it once;
-//   * every other level is cut into bins of 8192 entries (64 KB of float2).  A counting sweep and a
-//     filling sweep over the samples (same persistent tiling, so each workgroup owns a private, pre-
-//     computed slice of every bin's queue: no global atomics, no overflow) write one record
-//     (entry within bin, w*g.x, w*g.y) per corner, staged through LDS so that each bin receives
-//     contiguous runs.  Then one workgroup per (bin, split) streams its queue, accumulates in LDS and
-//     adds the finished bin into dtable with coalesced atomics.
+//   * every other level is cut into bins of 8192 entries (128 KB of fp64 sums in LDS).  A counting sweep
+//     and a filling sweep over the samples (same persistent tiling, so each workgroup owns a private,
+//     pre-computed slice of every bin's queue: no global atomics, no overflow) write one 20-byte record
+//     (two entries within the bin, 4 values) per pair of corners along x, staged through LDS so that each
+//     bin receives contiguous runs.  Then workgroups balanced by record count stream the queues,
+//     accumulate in LDS and add the finished bin into dtable with coalesced atomics.
 #include "encode_common.h"
 
 namespace dg_encode_binned {
@@ -28,10 +28,10 @@ constexpr int kWriters = 128;                      // narrow fill sweep: threads
 constexpr int kPairs = kTile * 4;                  // records staged per (tile, level): one per pair of corners along x
 constexpr uint32_t kLdsKeys = 4096;                // count sweep: (level, bin) counters kept in LDS when there are at most this many
 constexpr int kBinGrid = 768;                      // persistent binning workgroups (three per compute unit)
-constexpr int kAccBlock = 1024;
+constexpr int kAccBlock = 1024;                    // threads of an accumulate workgroup (one per compute unit: its table fills LDS)
 constexpr int kAccDepth = 4;                       // records in flight per accumulate thread
 constexpr uint32_t kAccRecords = 1u << 17;          // records one accumulate workgroup sums
-constexpr int kCoarseBlock = 1024;
+constexpr int kCoarseBlock = 1024;                 // coarse prefix: threads per workgroup, persistent workgroups (one per compute unit)
 constexpr int kCoarseGrid = 256;
 
 struct Plan {
