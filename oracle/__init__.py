@@ -78,7 +78,7 @@ def lib():
         _lib.dgo_cosine_lr.argtypes = [C.c_double, C.c_double, C.c_uint64, C.c_uint64]
         for name in ("dgo_encode_fwd", "dgo_encode_bwd", "dgo_ray_aabb_segments", "dgo_bucket_segments",
                      "dgo_sample_segments", "dgo_sh", "dgo_mlp_fwd", "dgo_mlp_bwd", "dgo_composite_fwd",
-                     "dgo_composite_bwd", "dgo_merge_fwd", "dgo_merge_bwd"):
+                     "dgo_composite_bwd", "dgo_merge_fwd", "dgo_merge_bwd", "dgo_composite_depth", "dgo_merge_depth"):
             getattr(_lib, name).restype = None
     return _lib
 
@@ -170,7 +170,7 @@ def jitter(seed, ray, slot, s):
     return float(lib().dgo_jitter(C.c_uint64(seed), ray, slot, s))
 
 
-def sample_segments(o, d, seg_t, seg_ray, seg_slot, seg_begin, seg_end, aabb6, S, seed=0, jitter_arr=None):
+def sample_segments(o, d, seg_t, seg_ray, seg_slot, seg_begin, seg_end, aabb6, S, seed=0, jitter_arr=None, want_t=False):
     o = _arr(o, np.float32)
     d = _arr(d, np.float32)
     seg_t = _arr(seg_t, np.float32)
@@ -181,13 +181,14 @@ def sample_segments(o, d, seg_t, seg_ray, seg_slot, seg_begin, seg_end, aabb6, S
     n = (seg_end - seg_begin) * S
     u = np.zeros((n, 3), np.float32)
     delta = np.zeros(n, np.float32)
+    t = np.zeros(n, np.float32) if want_t else None
     if jitter_arr is not None:
         jitter_arr = _arr(jitter_arr, np.float32)
         assert jitter_arr.size >= n
     lib().dgo_sample_segments(_p(o), _p(d), _p(seg_t), _p(seg_ray), _p(seg_slot), C.c_uint32(seg_begin),
                               C.c_uint32(seg_end), C.c_uint32(k_max), _p(aabb6), C.c_uint32(S),
-                              C.c_uint64(seed), _p(jitter_arr), _p(u), _p(delta))
-    return u, delta
+                              C.c_uint64(seed), _p(jitter_arr), _p(u), _p(delta), _p(t))
+    return (u, delta, t) if want_t else (u, delta)
 
 
 def sh(d, degree):
@@ -260,6 +261,24 @@ def composite_bwd(sigma, rgb, delta, S, gC, gT):
     lib().dgo_composite_bwd(_p(sigma), _p(rgb), _p(delta), C.c_uint32(n_seg), C.c_uint32(S), _p(gC), _p(gT),
                             _p(dsigma), _p(drgb))
     return dsigma, drgb
+
+
+def composite_depth(sigma, delta, t, S):
+    """Per-segment expected distance sum_i T_i alpha_i t_i (evaluation rendering, Sec. 4.4.2)."""
+    sigma, delta, t = _arr(sigma, np.float64), _arr(delta, np.float64), _arr(t, np.float64)
+    n_seg = sigma.size // S
+    D = np.zeros(n_seg, np.float64)
+    lib().dgo_composite_depth(_p(sigma), _p(delta), _p(t), C.c_uint32(n_seg), C.c_uint32(S), _p(D))
+    return D
+
+
+def merge_depth(Dk, Tk, seg_count):
+    Dk, Tk = _arr(Dk, np.float64), _arr(Tk, np.float64)
+    seg_count = _arr(seg_count, np.uint32)
+    R, k_max = Tk.shape
+    D = np.zeros(R, np.float64)
+    lib().dgo_merge_depth(_p(Dk), _p(Tk), _p(seg_count), C.c_uint32(R), C.c_uint32(k_max), _p(D))
+    return D
 
 
 def merge_fwd(Ck, Tk, seg_count):

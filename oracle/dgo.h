@@ -77,7 +77,7 @@ float dgo_jitter(uint64_t seed, uint32_t ray, uint32_t slot, uint32_t s);
 void dgo_sample_segments(const float *o, const float *d, const float *seg_t, const uint32_t *seg_ray,
                          const uint32_t *seg_slot, uint32_t seg_begin, uint32_t seg_end, uint32_t k_max,
                          const float *aabb6, uint32_t S, uint64_t seed, const float *jitter,
-                         float *u, float *delta);
+                         float *u, float *delta, float *t /* nullable: sample distances */);
 
 /* Real spherical harmonics, bands l = 0..degree-1, on normalised d: out [n, degree^2]. */
 void dgo_sh(const float *d, uint64_t n, uint32_t degree, double *out);
@@ -118,6 +118,13 @@ void dgo_merge_bwd(const double *Ck, const double *Tk, const uint32_t *seg_count
 /* Loss (Eq. 9 as a mean, plus lambda1 * Eq. 10) and its gradient seeds. */
 double dgo_loss(const double *C, const double *T, const double *Cgt, uint32_t R, double lambda1,
                 double *gC, double *gT);
+
+/* Depth for evaluation rendering (Sec. 4.4.2: "final color, depth, and transmittance"): per segment
+ * D_k = sum_i T_i alpha_i t_i, merged as D = sum_k (prod_{j<k} T_j) D_k, i.e. like colour under Eq. 5. */
+void dgo_composite_depth(const double *sigma, const double *delta, const double *t, uint32_t n_seg, uint32_t S,
+                         double *D);
+void dgo_merge_depth(const double *Dk, const double *Tk, const uint32_t *seg_count, uint32_t R, uint32_t k_max,
+                     double *D);
 
 /* One Adam step (Kingma & Ba 2015, Algorithm 1; optimiser named in Sec. 5.1) on n parameters, in place:
  * g' = g + l2 * theta;  m = b1 m + (1-b1) g';  v = b2 v + (1-b2) g'^2;

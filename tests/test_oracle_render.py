@@ -277,3 +277,69 @@ def test_loss_and_seeds():
     # fully transparent rays (T = 1) sit on the clamp: finite loss, zero gradient
     val1, _, gT1 = oracle.loss(Cc, np.ones(R), Cgt, lambda1=1e-3)
     assert np.isfinite(val1) and np.all(gT1 == 0)
+
+
+# ---------------------------------------------------------------------------- depth (evaluation rendering, Sec. 4.4.2)
+def test_depth_is_the_colour_rule_applied_to_distances():
+    # D_k = sum T_i alpha_i t_i is the composite of a "colour" whose value is the distance: the pinned colour routine
+    # must give the same number in each channel
+    rng = np.random.default_rng(31)
+    S, n_seg = 24, 17
+    sigma = rng.random(n_seg * S) * 30.0
+    delta = rng.random(n_seg * S) * 0.05
+    t = np.sort(rng.random((n_seg, S)) * 5.0, axis=1).reshape(-1)
+    D = oracle.composite_depth(sigma, delta, t, S)
+    C, _ = oracle.composite_fwd(sigma, np.repeat(t[:, None], 3, axis=1), delta, S)
+    np.testing.assert_allclose(D, C[:, 0], rtol=1e-13)
+
+
+def test_depth_closed_forms():
+    S = 32
+    delta = np.full(S, 0.01)
+    t = 1.0 + (np.arange(S) + 0.5) * 0.01
+    # all the distances equal c: D = c (1 - T)
+    sigma = np.random.default_rng(32).random(S) * 50.0
+    D = oracle.composite_depth(sigma, delta, np.full(S, 2.5), S)
+    _, T = oracle.composite_fwd(sigma, np.zeros((S, 3)), delta, S)
+    assert D[0] == pytest.approx(2.5 * (1.0 - T[0]), rel=1e-13)
+    # an opaque sheet at sample 9 behind empty space: the depth is that sample's distance
+    sigma = np.zeros(S)
+    sigma[9] = 1e9
+    assert oracle.composite_depth(sigma, delta, t, S)[0] == pytest.approx(t[9], rel=1e-13)
+    # uniform medium: geometric weights T_i alpha_i = q^i (1 - q), q = exp(-sigma delta)
+    sigma = np.full(S, 7.0)
+    q = np.exp(-0.07)
+    assert oracle.composite_depth(sigma, delta, t, S)[0] == pytest.approx(np.sum(q ** np.arange(S) * (1 - q) * t), rel=1e-12)
+
+
+def test_depth_of_merged_segments_equals_depth_of_the_whole_ray():
+    # the property that makes Eq. 5 exact for the discrete sums holds for the depth channel too
+    rng = np.random.default_rng(33)
+    S, K, R = 16, 4, 9
+    sigma = rng.random((R, K * S)) * 20.0
+    delta = rng.random((R, K * S)) * 0.05
+    t = np.sort(rng.random((R, K * S)) * 4.0, axis=1)
+    whole = oracle.composite_depth(sigma.reshape(-1), delta.reshape(-1), t.reshape(-1), K * S)
+    Dk = oracle.composite_depth(sigma.reshape(-1), delta.reshape(-1), t.reshape(-1), S).reshape(R, K)
+    _, Tk = oracle.composite_fwd(sigma.reshape(-1), np.zeros((R * K * S, 3)), delta.reshape(-1), S)
+    merged = oracle.merge_depth(Dk, Tk.reshape(R, K), np.full(R, K, np.uint32))
+    np.testing.assert_allclose(merged, whole, rtol=1e-12)
+    # fewer segments than slots: unused slots are ignored
+    merged2 = oracle.merge_depth(Dk, Tk.reshape(R, K), np.full(R, 2, np.uint32))
+    np.testing.assert_allclose(merged2, Dk[:, 0] + Tk.reshape(R, K)[:, 0] * Dk[:, 1], rtol=1e-13)
+
+
+def test_sample_distances_match_the_positions():
+    cfg = di.config("c3_2x2")
+    o, d = di.make_rays(cfg, seed=4, R=50)
+    cnt, seg_t, part, _ = oracle.ray_aabb_segments(o, d, cfg["parts"], 0.0, 4)
+    off, ray, slot = oracle.bucket_segments(cnt, part, 4)
+    p = 0
+    u, delta, t = oracle.sample_segments(o, d, seg_t, ray, slot, int(off[p]), int(off[p + 1]), cfg["parts"][p], 8, seed=3, want_t=True)
+    lo, ext = cfg["parts"][p][:3].astype(np.float64), di.box_extent(cfg["parts"][p])
+    x = lo + u.astype(np.float64) * ext
+    rr = np.repeat(ray[int(off[p]):int(off[p + 1])], 8)
+    expect = o[rr].astype(np.float64) + t[:, None].astype(np.float64) * d[rr].astype(np.float64)
+    np.testing.assert_allclose(x, expect, atol=2e-6)
+    tt = t.reshape(-1, 8)
+    assert np.all(np.diff(tt, axis=1) > 0)
