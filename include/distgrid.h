@@ -109,11 +109,12 @@ int dg_ray_aabb_segments(const float *o, const float *d, uint32_t R,
  * if jitter != NULL, else a counter-based generator keyed by (seed, ray, slot, s):
  * splitmix64 output mix of seed + 0x9E3779B97F4A7C15*(ctr+1), ctr = ray<<32|slot<<16|s,
  * top 24 bits scaled by 2^-24.
- * Outputs (device): u [n_seg*S,3] fp32 unit coordinates, delta [n_seg*S] stratum widths. */
+ * Outputs (device): u [n_seg*S,3] fp32 unit coordinates, delta [n_seg*S] stratum widths,
+ * t [n_seg*S] the sample distances along the ray (NULL: not wanted; the depth channel needs them). */
 int dg_sample_segments(const float *o, const float *d, const float *seg_t,
                        const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t n_seg,
                        uint32_t k_max, const float *box, uint32_t S, uint64_t seed,
-                       const float *jitter, float *u, float *delta, void *stream);
+                       const float *jitter, float *u, float *delta, float *t, void *stream);
 
 /* Direction encoding: real spherical harmonics of bands 0..degree-1 (degree 1..4) of the
  * normalised direction of ray index[i] (index NULL: i itself); out [n, degree^2] fp16.
@@ -195,6 +196,12 @@ int dg_composite_segment_fwd(const float *sigma, const float *rgb, const float *
                              uint32_t n_seg, uint32_t S, const uint32_t *seg_ray,
                              const uint32_t *seg_slot, uint32_t k_max, float *Ck, float *Tk,
                              void *stream);
+/* Depth for evaluation rendering (Sec. 4.4.2: the partial results are merged into "the final color, depth, and
+ * transmittance"): D_k = sum_i T_i alpha_i t_i with the weights above, t [n_seg*S] the sample distances from
+ * dg_sample_segments; written to Dk [R,k_max] at the segment's (ray, slot). */
+int dg_composite_segment_depth(const float *sigma, const float *delta, const float *t, uint32_t n_seg, uint32_t S,
+                               const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t k_max, float *Dk,
+                               void *stream);
 /* Backward: from gCk [R,k_max,3], gTk [R,k_max] to dsigma [n_seg*S], drgb [n_seg*S,3]. */
 int dg_composite_segment_bwd(const float *sigma, const float *rgb, const float *delta,
                              uint32_t n_seg, uint32_t S, const uint32_t *seg_ray,
@@ -205,6 +212,10 @@ int dg_composite_segment_bwd(const float *sigma, const float *rgb, const float *
  * T = prod_k T_k over the first seg_count[r] slots; a ray with no segment gives C=0, T=1. */
 int dg_merge_segments(const float *Ck, const float *Tk, const uint32_t *seg_count,
                       uint32_t R, uint32_t k_max, float *C, float *T, void *stream);
+/* Depth merges like a colour channel under Eq. 5: D = sum_k (prod_{j<k} T_j) D_k; D [R] (0 for a ray with no
+ * segment). */
+int dg_merge_depth(const float *Dk, const float *Tk, const uint32_t *seg_count, uint32_t R, uint32_t k_max,
+                   float *D, void *stream);
 /* Its backward (Eq. 7, 8), evaluated without dividing by any T_k; unused slots get 0. */
 int dg_merge_segments_bwd(const float *Ck, const float *Tk, const uint32_t *seg_count,
                           uint32_t R, uint32_t k_max, const float *gC, const float *gT,

@@ -49,7 +49,7 @@ _SIGNATURES = {
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_size_t, C.c_void_p]),
     "dg_sample_segments": (C.c_int, [C.c_void_p] * 5 + [C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.c_uint32,
-                                                        C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+                                                        C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dg_dir_encode": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p]),
     "dg_hashgrid_encode_fwd": (C.c_int, [C.POINTER(GridDesc), C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32,
                                          C.c_void_p]),
@@ -70,6 +70,8 @@ _SIGNATURES = {
     "dg_merge_segments": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32] + [C.c_void_p] * 3),
     "dg_merge_segments_bwd": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32] + [C.c_void_p] * 5),
     "dg_loss_seed": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_float] + [C.c_void_p] * 4),
+    "dg_composite_segment_depth": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]),
+    "dg_merge_depth": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p]),
     "dg_adam_step": (C.c_int, [C.c_void_p] * 4 + [C.c_uint64] + [C.c_float] * 4 + [C.c_uint32, C.c_float, C.c_uint32] + [C.c_void_p] * 2),
     "dg_cosine_lr": (C.c_float, [C.c_float, C.c_float, C.c_uint64, C.c_uint64]),
 }
@@ -154,12 +156,12 @@ def dg_ray_aabb_segments(o, d, parts, t_min, k_max, seg_count, seg_t, seg_part, 
         _ptr(status, torch.int32), _ptr(ws, None, True), 0 if ws is None else ws.numel() * ws.element_size(), _stream()))
 
 
-def dg_sample_segments(o, d, seg_t, seg_ray, seg_slot, n_seg, k_max, box, S, seed, jitter, u, delta):
+def dg_sample_segments(o, d, seg_t, seg_ray, seg_slot, n_seg, k_max, box, S, seed, jitter, u, delta, t=None):
     box_c = (C.c_float * 6)(*[float(b) for b in box])
     _check(lib().dg_sample_segments(
         _ptr(o, torch.float32), _ptr(d, torch.float32), _ptr(seg_t, torch.float32), _ptr(seg_ray, torch.int32),
         _ptr(seg_slot, torch.int32), n_seg, k_max, box_c, S, seed, _ptr(jitter, torch.float32, True),
-        _ptr(u, torch.float32), _ptr(delta, torch.float32), _stream()))
+        _ptr(u, torch.float32), _ptr(delta, torch.float32), _ptr(t, torch.float32, True), _stream()))
 
 
 def dg_dir_encode(d, index, n, degree, out):
@@ -240,3 +242,16 @@ def dg_adam_step(param, grad, m, v, lr, step, beta1=0.9, beta2=0.99, eps=1e-15, 
 
 def dg_cosine_lr(lr0, lr1, iteration, total):
     return float(lib().dg_cosine_lr(lr0, lr1, iteration, total))
+
+
+def dg_composite_segment_depth(sigma, delta, t, n_seg, S, seg_ray, seg_slot, k_max, Dk):
+    assert min(sigma.numel(), delta.numel(), t.numel()) >= n_seg * S and min(seg_ray.numel(), seg_slot.numel()) >= n_seg
+    _check(lib().dg_composite_segment_depth(_ptr(sigma, torch.float32), _ptr(delta, torch.float32), _ptr(t, torch.float32), n_seg, S,
+                                            _ptr(seg_ray, torch.int32), _ptr(seg_slot, torch.int32), k_max, _ptr(Dk, torch.float32),
+                                            _stream()))
+
+
+def dg_merge_depth(Dk, Tk, seg_count, R, k_max, D):
+    assert min(Dk.numel(), Tk.numel()) >= R * k_max and min(seg_count.numel(), D.numel()) >= R
+    _check(lib().dg_merge_depth(_ptr(Dk, torch.float32), _ptr(Tk, torch.float32), _ptr(seg_count, torch.int32), R, k_max,
+                                _ptr(D, torch.float32), _stream()))

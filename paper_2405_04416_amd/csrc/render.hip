@@ -71,6 +71,31 @@ composite_fwd_kernel(const float *__restrict__ sigma, const float *__restrict__ 
     }
 }
 
+// Depth of evaluation rendering (Sec. 4.4.2): D_k = sum_i T_i alpha_i t_i, the colour rule applied to the sample distances
+__global__ void __launch_bounds__(kBlock)
+composite_depth_kernel(const float *__restrict__ sigma, const float *__restrict__ delta, const float *__restrict__ t,
+                       uint32_t n_seg, uint32_t S, const uint32_t *__restrict__ seg_ray,
+                       const uint32_t *__restrict__ seg_slot, uint32_t k_max, float *__restrict__ Dk)
+{
+    const uint32_t j = blockIdx.x * kWavesPerBlock + threadIdx.x / dg::kWave;
+    const int lane = threadIdx.x % dg::kWave;
+    if (j >= n_seg) return;
+    float trans = 1.0f, depth = 0.0f;
+    for (uint32_t base = 0; base < S; base += dg::kWave) {
+        const uint32_t s = base + lane;
+        const bool live = s < S;
+        const size_t n = (size_t)j * S + (live ? s : 0);
+        const float x = live ? sigma[n] * delta[n] : 0.0f;
+        const float incl = wave_inclusive_product(expf(-x), lane);
+        float before = __shfl_up(incl, 1, dg::kWave);
+        if (lane == 0) before = 1.0f;
+        depth += live ? trans * before * -expm1f(-x) * t[n] : 0.0f;
+        trans *= __shfl(incl, dg::kWave - 1, dg::kWave);
+    }
+    depth = wave_sum(depth);
+    if (lane == 0) Dk[(size_t)seg_ray[j] * k_max + seg_slot[j]] = depth;
+}
+
 // d sigma_i = delta_i [ gC.(T_{i+1} c_i) - sum_{j>i} w_j gC.c_j - gT T_k ],  d c_i = w_i gC
 __global__ void __launch_bounds__(kBlock)
 composite_bwd_kernel(const float *__restrict__ sigma, const float *__restrict__ rgb, const float *__restrict__ delta,
@@ -151,6 +176,23 @@ merge_fwd_kernel(const float *__restrict__ Ck, const float *__restrict__ Tk, con
     }
     C[3 * r] = c0; C[3 * r + 1] = c1; C[3 * r + 2] = c2;
     T[r] = front;
+}
+
+// depth merges like a colour channel under Eq. 5
+__global__ void __launch_bounds__(kBlock)
+merge_depth_kernel(const float *__restrict__ Dk, const float *__restrict__ Tk, const uint32_t *__restrict__ seg_count,
+                   uint32_t R, uint32_t k_max, float *__restrict__ D)
+{
+    const uint32_t r = blockIdx.x * kBlock + threadIdx.x;
+    if (r >= R) return;
+    const uint32_t K = min(seg_count[r], k_max);
+    float front = 1.0f, depth = 0.0f;
+    for (uint32_t k = 0; k < K; ++k) {
+        const size_t i = (size_t)r * k_max + k;
+        depth += front * Dk[i];
+        front *= Tk[i];
+    }
+    D[r] = depth;
 }
 
 // Eq. 7: gC_k = gC P_k with P_k = prod_{j<k} T_j.
@@ -239,6 +281,18 @@ extern "C" int dg_composite_segment_fwd(const float *sigma, const float *rgb, co
     return dg::launch_status("dg_composite_segment_fwd");
 }
 
+extern "C" int dg_composite_segment_depth(const float *sigma, const float *delta, const float *t, uint32_t n_seg, uint32_t S,
+                                          const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t k_max, float *Dk,
+                                          void *stream)
+{
+    if (int rc = seg_args_ok(n_seg, S, k_max, "dg_composite_segment_depth")) return rc;
+    if (n_seg == 0) return DG_OK;
+    DG_REQUIRE(sigma && delta && t && seg_ray && seg_slot && Dk, DG_ERR_ARG, "dg_composite_segment_depth: null pointer");
+    const uint32_t n_blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
+    composite_depth_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, delta, t, n_seg, S, seg_ray, seg_slot, k_max, Dk);
+    return dg::launch_status("dg_composite_segment_depth");
+}
+
 extern "C" int dg_composite_segment_bwd(const float *sigma, const float *rgb, const float *delta, uint32_t n_seg,
                                         uint32_t S, const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t k_max,
                                         const float *gCk, const float *gTk, float *dsigma, float *drgb, void *stream)
@@ -261,6 +315,16 @@ extern "C" int dg_merge_segments(const float *Ck, const float *Tk, const uint32_
     DG_REQUIRE(Ck && Tk && seg_count && C && T, DG_ERR_ARG, "dg_merge_segments: null pointer");
     merge_fwd_kernel<<<(R + kBlock - 1) / kBlock, kBlock, 0, (hipStream_t)stream>>>(Ck, Tk, seg_count, R, k_max, C, T);
     return dg::launch_status("dg_merge_segments");
+}
+
+extern "C" int dg_merge_depth(const float *Dk, const float *Tk, const uint32_t *seg_count, uint32_t R, uint32_t k_max,
+                              float *D, void *stream)
+{
+    DG_REQUIRE(k_max >= 1 && k_max <= kMaxK, DG_ERR_UNSUPPORTED, "dg_merge_depth: k_max=%u outside 1..%u", k_max, kMaxK);
+    if (R == 0) return DG_OK;
+    DG_REQUIRE(Dk && Tk && seg_count && D, DG_ERR_ARG, "dg_merge_depth: null pointer");
+    merge_depth_kernel<<<(R + kBlock - 1) / kBlock, kBlock, 0, (hipStream_t)stream>>>(Dk, Tk, seg_count, R, k_max, D);
+    return dg::launch_status("dg_merge_depth");
 }
 
 extern "C" int dg_merge_segments_bwd(const float *Ck, const float *Tk, const uint32_t *seg_count, uint32_t R,

@@ -201,7 +201,7 @@ __global__ void __launch_bounds__(kBlock)
 sample_kernel(const float *__restrict__ o, const float *__restrict__ d, const float *__restrict__ seg_t,
               const uint32_t *__restrict__ seg_ray, const uint32_t *__restrict__ seg_slot, uint64_t n_samples,
               uint32_t k_max, BoxArgs box, uint32_t S, uint64_t seed, const float *__restrict__ jitter,
-              float *__restrict__ u, float *__restrict__ delta)
+              float *__restrict__ u, float *__restrict__ delta, float *__restrict__ t_samples)
 {
     const uint64_t n = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
     if (n >= n_samples) return;
@@ -216,6 +216,7 @@ sample_kernel(const float *__restrict__ o, const float *__restrict__ d, const fl
         u[3 * n + a] = (x - box.lo[a]) * box.inv_ext[a];
     }
     delta[n] = dt;
+    if (t_samples) t_samples[n] = t;
 }
 
 // ---------------------------------------------------------------- real spherical harmonics
@@ -294,7 +295,7 @@ extern "C" int dg_ray_aabb_segments(const float *o, const float *d, uint32_t R, 
 extern "C" int dg_sample_segments(const float *o, const float *d, const float *seg_t, const uint32_t *seg_ray,
                                   const uint32_t *seg_slot, uint32_t n_seg, uint32_t k_max, const float *box,
                                   uint32_t S, uint64_t seed, const float *jitter, float *u, float *delta,
-                                  void *stream)
+                                  float *t_samples, void *stream)
 {
     DG_REQUIRE(box && S >= 1 && S <= 65535 && k_max >= 1, DG_ERR_ARG, "dg_sample_segments: bad box/S/k_max");
     if (n_seg == 0) return DG_OK;
@@ -309,7 +310,7 @@ extern "C" int dg_sample_segments(const float *o, const float *d, const float *s
     const uint64_t n_blocks = (n + kBlock - 1) / kBlock;
     DG_REQUIRE(n_blocks <= 0x7fffffffull, DG_ERR_UNSUPPORTED, "dg_sample_segments: too many samples");
     sample_kernel<<<(uint32_t)n_blocks, kBlock, 0, (hipStream_t)stream>>>(o, d, seg_t, seg_ray, seg_slot, n, k_max, b, S,
-                                                                          seed, jitter, u, delta);
+                                                                          seed, jitter, u, delta, t_samples);
     return dg::launch_status("dg_sample_segments");
 }
 

@@ -96,12 +96,14 @@ def test_sampling_bit_exact(use_array):
         b, e = int(off[p]), int(off[p + 1])
         n = (e - b) * S
         jit = di.make_jitter(n, seed=p) if use_array else None
-        u = torch.zeros(n, 3, device=DEV); delta = torch.zeros(n, device=DEV)
+        u = torch.zeros(n, 3, device=DEV); delta = torch.zeros(n, device=DEV); t = torch.zeros(n, device=DEV)
         B.dg_sample_segments(od, dd, td, rayd[b:e], slotd[b:e], e - b, k_max, parts[p], S, 99,
-                             None if jit is None else dev(jit), u, delta)
-        ru, rdelta = oracle.sample_segments(o, d, rt, ray, slot, b, e, parts[p], S, seed=99, jitter_arr=jit)
+                             None if jit is None else dev(jit), u, delta, t if p % 2 == 0 else None)
+        ru, rdelta, rt_s = oracle.sample_segments(o, d, rt, ray, slot, b, e, parts[p], S, seed=99, jitter_arr=jit, want_t=True)
         np.testing.assert_array_equal(host(u).view(np.uint32), ru.view(np.uint32))
         np.testing.assert_array_equal(host(delta).view(np.uint32), rdelta.view(np.uint32))
+        if p % 2 == 0:
+            np.testing.assert_array_equal(host(t).view(np.uint32), rt_s.view(np.uint32))      # sample distances, bit for bit
 
 
 @pytest.mark.parametrize("degree", [1, 2, 3, 4])
@@ -212,6 +214,35 @@ def test_encode_bwd(key, N, flavour, mode):
         sl = slice(r.first[l], r.first[l + 1])
         assert rel_err(got[sl], ref[sl]) <= TOL_F16, l
     assert np.all(got[ref == 0] == 0)                                 # untouched entries stay untouched
+
+
+@pytest.mark.parametrize("S,n_seg,k_max", [(64, 501, 4), (32, 77, 1), (100, 33, 3), (7, 1000, 12)])
+def test_depth_channel(S, n_seg, k_max):
+    """Evaluation depth (Sec. 4.4.2): per-segment expected distance and its merge, against the oracle."""
+    say("depth S=%d n_seg=%d k_max=%d" % (S, n_seg, k_max))
+    rng = np.random.default_rng(S * 1000 + n_seg)
+    R = n_seg                                   # R * k_max >= n_seg distinct (ray, slot) pairs exist
+    pairs = rng.permutation(R * k_max)[:n_seg]
+    assert pairs.size == n_seg
+    ray, slot = (pairs // k_max).astype(np.int32), (pairs % k_max).astype(np.int32)
+    sigma = (rng.random(n_seg * S) * 40.0).astype(np.float32)
+    sigma[rng.random(n_seg * S) < 0.3] = 0.0
+    delta = (rng.random(n_seg * S) * 0.05).astype(np.float32)
+    t = np.sort(rng.random((n_seg, S)) * 6.0, axis=1).reshape(-1).astype(np.float32)
+    Dk = torch.zeros(R, k_max, device=DEV)
+    B.dg_composite_segment_depth(dev(sigma), dev(delta), dev(t), n_seg, S, dev(ray), dev(slot), k_max, Dk)
+    ref = oracle.composite_depth(sigma, delta, t, S)
+    got = host(Dk)[ray, slot]
+    assert np.all(np.abs(got - ref) <= TOL_F32 * np.maximum(np.abs(ref), 1e-3))
+    # merge over random partials
+    cnt = rng.integers(0, k_max + 1, R).astype(np.int32)
+    Dk_h = (rng.random((R, k_max)) * 5.0).astype(np.float32)
+    Tk_h = rng.random((R, k_max)).astype(np.float32)
+    D = torch.full((R,), -1.0, device=DEV)
+    B.dg_merge_depth(dev(Dk_h), dev(Tk_h), dev(cnt), R, k_max, D)
+    refD = oracle.merge_depth(Dk_h, Tk_h, cnt.astype(np.uint32))
+    assert np.all(np.abs(host(D) - refD) <= TOL_F32 * np.maximum(np.abs(refD), 1e-3))
+    assert np.all(host(D)[cnt == 0] == 0.0)
 
 
 # ---------------------------------------------------------------------------- MLPs
