@@ -213,3 +213,45 @@ def make_extra_partials(R, k_max, fraction, seed=0):
     Ck = rng.random((R, k_max, 3), dtype=np.float32)
     Tk = rng.random((R, k_max), dtype=np.float32)
     return before.astype(np.uint32), (extra - before).astype(np.uint32), Ck, Tk
+
+
+# ---------------------------------------------------------------------------
+# Occupancy (for occupancy-guided sampling)
+# ---------------------------------------------------------------------------
+
+
+def make_cell_densities(shape, seed=0, shell=0.08, n_blocks=40, level=100.0, skin=3):
+    """Per-cell densities of a scene shaped like an aerial capture, [shape_z, shape_y, shape_x] flattened (x fastest).
+
+    A rolling ground surface (a few random sinusoids) of relative thickness `shell`, plus `n_blocks` box-shaped
+    "buildings" standing on it; the surface cells of that solid get a density around `level` (log-uniform over two
+    decades), all other cells 0.  These are stand-in numbers for the densities a trained field would report.
+    """
+    rng = np.random.default_rng([seed, 83])
+    nx, ny, nz = (int(v) for v in shape)
+    x = (np.arange(nx) + 0.5) / nx
+    y = (np.arange(ny) + 0.5) / ny
+    z = (np.arange(nz) + 0.5) / nz
+    ground = np.full((ny, nx), 0.3)
+    for _ in range(4):
+        fx, fy = rng.integers(1, 5, size=2)
+        ground += 0.06 * np.sin(2 * math.pi * (fx * x[None, :] + fy * y[:, None]) + rng.random() * 6.28)
+    top = ground.copy()
+    for _ in range(n_blocks):
+        cx, cy = rng.random(2)
+        wx, wy = 0.02 + 0.06 * rng.random(2)
+        h = 0.1 + 0.4 * rng.random()
+        inside = (np.abs(x[None, :] - cx) < wx) & (np.abs(y[:, None] - cy) < wy)
+        top = np.where(inside, np.maximum(top, ground + h), top)
+    solid = (z[:, None, None] <= top[None]) & (z[:, None, None] >= ground[None] - shell)
+    # matter that cameras see is the surface of the solid: drop what lies more than `skin` cells inside
+    deep = solid.copy()
+    for _ in range(skin):
+        core = deep.copy()
+        core[1:] &= deep[:-1]; core[:-1] &= deep[1:]
+        core[:, 1:] &= deep[:, :-1]; core[:, :-1] &= deep[:, 1:]
+        core[:, :, 1:] &= deep[:, :, :-1]; core[:, :, :-1] &= deep[:, :, 1:]
+        deep = core
+    visible = solid & ~deep
+    dens = np.where(visible, level * 10.0 ** (rng.random((nz, ny, nx)) * 2.0 - 1.0), 0.0)
+    return dens.astype(np.float32).ravel()

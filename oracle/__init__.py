@@ -330,3 +330,118 @@ def adam_step(theta, grad, m, v, lr, step, beta1=0.9, beta2=0.99, eps=1e-15, l2=
 
 def cosine_lr(lr0, lr1, iteration, total):
     return lib().dgo_cosine_lr(lr0, lr1, iteration, total)
+
+
+# ---------------------------------------------------------------- occupancy grid and marching
+class Occ(C.Structure):
+    """Deformable occupancy grid geometry (Sec. 4.1, Sec. 5.1)."""
+    _fields_ = [("shape", C.c_uint32 * 3), ("n_cells", C.c_uint32), ("gain", C.c_float * 3)]
+
+
+def occ_init(N, extent):
+    g = Occ()
+    ext = (C.c_double * 3)(*[float(e) for e in extent])
+    rc = lib().dgo_occ_init(C.byref(g), C.c_uint32(N), ext)
+    if rc != 0:
+        raise ValueError("dgo_occ_init failed")
+    return g
+
+
+def occ_cell(g, u):
+    u = _arr(u, np.float32).reshape(-1, 3)
+    f = lib().dgo_occ_cell
+    f.restype = C.c_uint32
+    return np.array([f(C.byref(g), _p(u[i])) for i in range(u.shape[0])], np.uint32)
+
+
+def occ_schedule(iteration):
+    """(update_now, warmup, decay, threshold) at a training iteration (Sec. 5.1)."""
+    a, b, c, d = C.c_int(), C.c_int(), C.c_float(), C.c_float()
+    lib().dgo_occ_schedule(C.c_uint64(iteration), C.byref(a), C.byref(b), C.byref(c), C.byref(d))
+    return bool(a.value), bool(b.value), c.value, d.value
+
+
+def rand64(seed, counter):
+    f = lib().dgo_rand64
+    f.restype = C.c_uint64
+    return int(f(C.c_uint64(seed), C.c_uint64(counter)))
+
+
+def occ_candidates(g, bits, M, n_uniform, warmup, seed, iteration, tries=32):
+    bits = _arr(bits, np.uint32)
+    cell = np.zeros(M, np.uint32)
+    u = np.zeros((M, 3), np.float32)
+    lib().dgo_occ_candidates(C.byref(g), _p(bits), C.c_uint32(M), C.c_uint32(n_uniform), C.c_int(1 if warmup else 0),
+                             C.c_uint64(seed), C.c_uint32(iteration), C.c_uint32(tries), _p(cell), _p(u))
+    return cell, u
+
+
+def occ_decay(density, factor):
+    assert density.dtype == np.float32 and density.flags["C_CONTIGUOUS"]
+    lib().dgo_occ_decay(_p(density), C.c_uint32(density.size), C.c_float(factor))
+    return density
+
+
+def occ_update(density, cell, sigma):
+    assert density.dtype == np.float32 and density.flags["C_CONTIGUOUS"]
+    cell, sigma = _arr(cell, np.uint32), _arr(sigma, np.float32)
+    lib().dgo_occ_update(_p(density), _p(cell), _p(sigma), C.c_uint32(cell.size))
+    return density
+
+
+def occ_bits(density, threshold):
+    density = _arr(density, np.float32)
+    bits = np.zeros((density.size + 31) // 32, np.uint32)
+    f = lib().dgo_occ_bits
+    f.restype = C.c_uint32
+    n_set = f(_p(density), C.c_uint32(density.size), C.c_float(threshold), _p(bits))
+    return bits, int(n_set)
+
+
+def march_segments(o, d, seg_t, seg_ray, seg_slot, seg_begin, seg_end, aabb6, g, bits, dt, max_steps=4096, seed=0):
+    """Occupancy-guided samples of one box's segments: (first [n_seg+1], u, delta, t, sample_ray)."""
+    o, d, seg_t = _arr(o, np.float32), _arr(d, np.float32), _arr(seg_t, np.float32)
+    k_max = seg_t.shape[1]
+    seg_ray, seg_slot = _arr(seg_ray, np.uint32), _arr(seg_slot, np.uint32)
+    aabb6, bits = _arr(aabb6, np.float32), _arr(bits, np.uint32)
+    first = np.zeros(seg_end - seg_begin + 1, np.uint32)
+    f = lib().dgo_march_segments
+    f.restype = C.c_uint32
+
+    def call(u, delta, t, ray):
+        return f(_p(o), _p(d), _p(seg_t), _p(seg_ray), _p(seg_slot), C.c_uint32(seg_begin), C.c_uint32(seg_end),
+                 C.c_uint32(k_max), _p(aabb6), C.byref(g), _p(bits), C.c_float(dt), C.c_uint32(max_steps),
+                 C.c_uint64(seed), _p(first), _p(u), _p(delta), _p(t), _p(ray))
+
+    n = call(None, None, None, None)
+    u, delta, t = np.zeros((n, 3), np.float32), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    ray = np.zeros(n, np.uint32)
+    assert call(u, delta, t, ray) == n
+    return first, u, delta, t, ray
+
+
+def composite_fwd_ragged(sigma, rgb, delta, first):
+    sigma, rgb, delta = _arr(sigma, np.float64), _arr(rgb, np.float64), _arr(delta, np.float64)
+    first = _arr(first, np.uint32)
+    n_seg = first.size - 1
+    Cc, T = np.zeros((n_seg, 3), np.float64), np.zeros(n_seg, np.float64)
+    lib().dgo_composite_fwd_ragged(_p(sigma), _p(rgb), _p(delta), C.c_uint32(n_seg), _p(first), _p(Cc), _p(T))
+    return Cc, T
+
+
+def composite_bwd_ragged(sigma, rgb, delta, first, gC, gT):
+    sigma, rgb, delta = _arr(sigma, np.float64), _arr(rgb, np.float64), _arr(delta, np.float64)
+    gC, gT, first = _arr(gC, np.float64), _arr(gT, np.float64), _arr(first, np.uint32)
+    n_seg = first.size - 1
+    dsigma, drgb = np.zeros(sigma.size, np.float64), np.zeros((sigma.size, 3), np.float64)
+    lib().dgo_composite_bwd_ragged(_p(sigma), _p(rgb), _p(delta), C.c_uint32(n_seg), _p(first), _p(gC), _p(gT),
+                                   _p(dsigma), _p(drgb))
+    return dsigma, drgb
+
+
+def composite_depth_ragged(sigma, delta, t, first):
+    sigma, delta, t = _arr(sigma, np.float64), _arr(delta, np.float64), _arr(t, np.float64)
+    first = _arr(first, np.uint32)
+    D = np.zeros(first.size - 1, np.float64)
+    lib().dgo_composite_depth_ragged(_p(sigma), _p(delta), _p(t), C.c_uint32(first.size - 1), _p(first), _p(D))
+    return D

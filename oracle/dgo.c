@@ -650,3 +650,174 @@ void dgo_merge_depth(const double *Dk, const double *Tk, const uint32_t *seg_cou
         D[r] = sum;
     }
 }
+
+/* ------------------------------------------------------------------ */
+/* Occupancy grid and occupancy-guided sampling                        */
+/* (Sec. 3.2, Sec. 4.1, Sec. 5.1; update rule: Instant-NGP App. E.2)   */
+/* ------------------------------------------------------------------ */
+
+int dgo_occ_init(dgo_occ *g, uint32_t N, const double extent[3])
+{
+    if (!g || N == 0) return -1;
+    double s = extent[0];
+    if (extent[1] > s) s = extent[1];
+    if (extent[2] > s) s = extent[2];
+    if (!(s > 0.0)) return -1;
+    uint64_t cells = 1;
+    for (int a = 0; a < 3; ++a) {
+        if (!(extent[a] > 0.0)) return -1;
+        double along = extent[a] / s * (double)N;       /* the hash grid's rule (Sec. 4.1) at one resolution */
+        g->shape[a] = (uint32_t)ceil(along);
+        if (g->shape[a] == 0) g->shape[a] = 1;
+        g->gain[a] = (float)along;
+        cells *= g->shape[a];
+    }
+    if (cells > 0xffffffffull) return -1;
+    g->n_cells = (uint32_t)cells;
+    return 0;
+}
+
+uint32_t dgo_occ_cell(const dgo_occ *g, const float *u3)
+{
+    uint32_t c[3];
+    for (int a = 0; a < 3; ++a) {
+        float v = u3[a];
+        v = v >= 0.0f ? v : 0.0f;
+        v = v > 1.0f ? 1.0f : v;
+        float pos = v * g->gain[a];
+        uint32_t i = (uint32_t)floorf(pos);
+        if (i > g->shape[a] - 1) i = g->shape[a] - 1;
+        c[a] = i;
+    }
+    return c[0] + g->shape[0] * (c[1] + g->shape[1] * c[2]);
+}
+
+void dgo_occ_schedule(uint64_t iteration, int *update_now, int *warmup, float *decay, float *threshold)
+{
+    *update_now = iteration % 16 == 0;          /* refreshed every 16 training iterations */
+    *warmup = iteration < 4096;                 /* all cells are candidates during warm-up */
+    *decay = 0.99f;
+    *threshold = iteration < 10000 ? 0.6f : 60.0f;
+}
+
+uint64_t dgo_rand64(uint64_t seed, uint64_t counter)
+{
+    uint64_t z = seed + 0x9E3779B97F4A7C15ull * (counter + 1);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+static uint64_t candidate_counter(uint32_t iteration, uint32_t i, uint32_t attempt, uint32_t q)
+{
+    return ((uint64_t)iteration << 36) | ((uint64_t)i << 8) | ((uint64_t)attempt << 2) | q;
+}
+
+void dgo_occ_candidates(const dgo_occ *g, const uint32_t *bits, uint32_t M, uint32_t n_uniform, int warmup,
+                        uint64_t seed, uint32_t iteration, uint32_t tries, uint32_t *cell, float *u)
+{
+    for (uint32_t i = 0; i < M; ++i) {
+        uint32_t c = i, attempt = 0;
+        if (!warmup) {
+            uint32_t allowed = i < n_uniform ? 1 : tries;
+            for (attempt = 0; attempt < allowed; ++attempt) {
+                uint64_t z = dgo_rand64(seed, candidate_counter(iteration, i, attempt, 0));
+                c = (uint32_t)(((z >> 32) * (uint64_t)g->n_cells) >> 32);
+                if (i < n_uniform || ((bits[c >> 5] >> (c & 31)) & 1u)) break;
+            }
+            if (attempt == allowed) attempt = allowed - 1;      /* no occupied cell met: keep the last draw */
+        }
+        cell[i] = c;
+        uint32_t idx[3] = {c % g->shape[0], (c / g->shape[0]) % g->shape[1], c / (g->shape[0] * g->shape[1])};
+        for (uint32_t a = 0; a < 3; ++a) {
+            uint64_t z = dgo_rand64(seed, candidate_counter(iteration, i, attempt, a + 1));
+            float xi = (float)(z >> 40) * (1.0f / 16777216.0f);
+            u[3 * (uint64_t)i + a] = ((float)idx[a] + xi) / g->gain[a];
+        }
+    }
+}
+
+void dgo_occ_decay(float *density, uint32_t n_cells, float factor)
+{
+    for (uint32_t c = 0; c < n_cells; ++c) density[c] = density[c] * factor;
+}
+
+void dgo_occ_update(float *density, const uint32_t *cell, const float *sigma, uint32_t M)
+{
+    for (uint32_t i = 0; i < M; ++i)
+        if (sigma[i] > density[cell[i]]) density[cell[i]] = sigma[i];
+}
+
+uint32_t dgo_occ_bits(const float *density, uint32_t n_cells, float threshold, uint32_t *bits)
+{
+    uint32_t set = 0;
+    for (uint32_t w = 0; w < (n_cells + 31) / 32; ++w) bits[w] = 0;
+    for (uint32_t c = 0; c < n_cells; ++c)
+        if (density[c] > threshold) { bits[c >> 5] |= 1u << (c & 31); ++set; }
+    return set;
+}
+
+uint32_t dgo_march_segments(const float *o, const float *d, const float *seg_t, const uint32_t *seg_ray,
+                            const uint32_t *seg_slot, uint32_t seg_begin, uint32_t seg_end, uint32_t k_max,
+                            const float *aabb6, const dgo_occ *g, const uint32_t *bits, float dt,
+                            uint32_t max_steps, uint64_t seed, uint32_t *first, float *u, float *delta,
+                            float *t_samples, uint32_t *sample_ray)
+{
+    float inv_ext[3];
+    for (int a = 0; a < 3; ++a) inv_ext[a] = 1.0f / (aabb6[3 + a] - aabb6[a]);
+    uint32_t kept = 0;
+    for (uint32_t j = seg_begin; j < seg_end; ++j) {
+        first[j - seg_begin] = kept;
+        uint32_t r = seg_ray[j], k = seg_slot[j];
+        float t_in = seg_t[((uint64_t)r * k_max + k) * 2], t_out = seg_t[((uint64_t)r * k_max + k) * 2 + 1];
+        float len = t_out - t_in;
+        float wanted = ceilf(len / dt);                 /* strata no wider than the marching step */
+        uint32_t n = wanted >= (float)max_steps ? max_steps : (wanted >= 1.0f ? (uint32_t)wanted : 1u);
+        float width = len / (float)n;
+        for (uint32_t s = 0; s < n; ++s) {
+            float xi = dgo_jitter(seed, r, k, s);
+            float t = t_in + ((float)s + xi) * width;
+            float u3[3];
+            for (int a = 0; a < 3; ++a) {
+                float x = fmaf(t, d[3 * r + a], o[3 * r + a]);
+                u3[a] = (x - aabb6[a]) * inv_ext[a];
+            }
+            uint32_t c = dgo_occ_cell(g, u3);
+            if (!((bits[c >> 5] >> (c & 31)) & 1u)) continue;      /* empty space is skipped */
+            if (u) {
+                for (int a = 0; a < 3; ++a) u[3 * (uint64_t)kept + a] = u3[a];
+                delta[kept] = width;
+                t_samples[kept] = t;
+                sample_ray[kept] = r;
+            }
+            ++kept;
+        }
+    }
+    first[seg_end - seg_begin] = kept;
+    return kept;
+}
+
+void dgo_composite_fwd_ragged(const double *sigma, const double *rgb, const double *delta, uint32_t n_seg,
+                              const uint32_t *first, double *C, double *T)
+{
+    for (uint32_t j = 0; j < n_seg; ++j)
+        dgo_composite_fwd(sigma + first[j], rgb + 3 * (uint64_t)first[j], delta + first[j], 1,
+                          first[j + 1] - first[j], C + 3 * (uint64_t)j, T + j);
+}
+
+void dgo_composite_bwd_ragged(const double *sigma, const double *rgb, const double *delta, uint32_t n_seg,
+                              const uint32_t *first, const double *gC, const double *gT, double *dsigma,
+                              double *drgb)
+{
+    for (uint32_t j = 0; j < n_seg; ++j)
+        dgo_composite_bwd(sigma + first[j], rgb + 3 * (uint64_t)first[j], delta + first[j], 1,
+                          first[j + 1] - first[j], gC + 3 * (uint64_t)j, gT + j, dsigma + first[j],
+                          drgb + 3 * (uint64_t)first[j]);
+}
+
+void dgo_composite_depth_ragged(const double *sigma, const double *delta, const double *t, uint32_t n_seg,
+                                const uint32_t *first, double *D)
+{
+    for (uint32_t j = 0; j < n_seg; ++j)
+        dgo_composite_depth(sigma + first[j], delta + first[j], t + first[j], 1, first[j + 1] - first[j], D + j);
+}

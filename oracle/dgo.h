@@ -137,6 +137,57 @@ void dgo_adam_step(double *theta, const double *grad, double *m, double *v, uint
 /* Learning rate of Sec. 5.1: from lr0 down to lr1 along half a cosine over `total` iterations. */
 double dgo_cosine_lr(double lr0, double lr1, uint64_t iteration, uint64_t total);
 
+/* ------------------------------------------------------------------------------------------------
+ * Occupancy grid and occupancy-guided sampling (Sec. 3.2: a grid of per-voxel densities lets ray
+ * marching skip empty space; Sec. 4.1: it is deformable like the hash grid; Sec. 5.1: one scale, plain
+ * x-fastest storage, resolution 512, decay 0.99 every 16 iterations, warm-up 4096 iterations, bit
+ * threshold 0.6 before iteration 10 000 and 60 after; the update rule itself is Instant-NGP App. E.2).
+ * Everything that decides an integer (a cell, a bit, a sample count) is computed in fp32 / integers.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+    uint32_t shape[3];      /* cells per axis: ceil(a_d/s * N)                  */
+    uint32_t n_cells;
+    float    gain[3];       /* grid position of unit coordinate u_d: u_d * gain */
+} dgo_occ;
+int dgo_occ_init(dgo_occ *g, uint32_t N, const double extent[3]);
+/* cell of a point with unit coordinates u (clamped to [0,1]): x + shape_x (y + shape_y z) */
+uint32_t dgo_occ_cell(const dgo_occ *g, const float *u3);
+/* when and how the grid is refreshed at a training iteration (Sec. 5.1) */
+void dgo_occ_schedule(uint64_t iteration, int *update_now, int *warmup, float *decay, float *threshold);
+/* 64 random bits for (seed, counter): splitmix64 output mix of seed + golden * (counter + 1) */
+uint64_t dgo_rand64(uint64_t seed, uint64_t counter);
+/* Candidate cells of one refresh (Instant-NGP App. E.2) and a random point inside each.
+ * warmup: M must be n_cells and candidate i is cell i.  Otherwise the first n_uniform candidates are
+ * uniform draws over all cells and the others are drawn among the occupied cells by rejection: up to
+ * `tries` uniform draws, the first whose bit is set wins, the last one is taken if none is.
+ * Draw q (0 = cell, 1..3 = position) of try a of candidate i uses counter (iteration<<36)|(i<<8)|(a<<2)|q;
+ * cell = (top 32 bits * n_cells) >> 32; position u_d = (c_d + xi_d) / gain_d, xi from the top 24 bits. */
+void dgo_occ_candidates(const dgo_occ *g, const uint32_t *bits, uint32_t M, uint32_t n_uniform, int warmup,
+                        uint64_t seed, uint32_t iteration, uint32_t tries, uint32_t *cell, float *u);
+void dgo_occ_decay(float *density, uint32_t n_cells, float factor);
+/* density[cell[i]] = max(density[cell[i]], sigma[i]) */
+void dgo_occ_update(float *density, const uint32_t *cell, const float *sigma, uint32_t M);
+/* bit (c % 32) of word c / 32 = density[c] > threshold; returns the number of set bits */
+uint32_t dgo_occ_bits(const float *density, uint32_t n_cells, float threshold, uint32_t *bits);
+/* Marching of the segments [seg_begin, seg_end) of one box: a segment of length len = t_out - t_in is cut
+ * into n = clamp(ceil(len / dt), 1, max_steps) equal strata, stratum s is sampled at t_in + (s + xi) len/n
+ * (xi as in dgo_sample_segments) and the sample is kept iff the bit of its cell is set.  first[j - seg_begin]
+ * receives the number of samples kept before segment j (n_seg + 1 values).  The sample arrays may be NULL
+ * (counting only).  Returns the total. */
+uint32_t dgo_march_segments(const float *o, const float *d, const float *seg_t, const uint32_t *seg_ray,
+                            const uint32_t *seg_slot, uint32_t seg_begin, uint32_t seg_end, uint32_t k_max,
+                            const float *aabb6, const dgo_occ *g, const uint32_t *bits, float dt,
+                            uint32_t max_steps, uint64_t seed, uint32_t *first, float *u, float *delta,
+                            float *t, uint32_t *sample_ray);
+/* Eq. 3 on segments of different lengths: segment j owns samples [first[j], first[j+1]) */
+void dgo_composite_fwd_ragged(const double *sigma, const double *rgb, const double *delta, uint32_t n_seg,
+                              const uint32_t *first, double *C, double *T);
+void dgo_composite_bwd_ragged(const double *sigma, const double *rgb, const double *delta, uint32_t n_seg,
+                              const uint32_t *first, const double *gC, const double *gT, double *dsigma,
+                              double *drgb);
+void dgo_composite_depth_ragged(const double *sigma, const double *delta, const double *t, uint32_t n_seg,
+                                const uint32_t *first, double *D);
+
 #ifdef __cplusplus
 }
 #endif
