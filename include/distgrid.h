@@ -14,8 +14,9 @@
  *  - arrays are row-major, innermost dimension last; fp16 means IEEE binary16;
  *  - outputs documented as "+=" accumulate into what the buffer holds (the caller zeroes
  *    it); all other outputs are overwritten;
- *  - data-dependent overflow (more than k_max segments on a ray) is reported through a
- *    device-side status word, not through the return code.
+ *  - data-dependent overflow (more than k_max segments on a ray, more samples than the
+ *    caller's capacity) is reported through a device-side status word, not through the
+ *    return code.
  */
 #ifndef DISTGRID_H
 #define DISTGRID_H
@@ -244,6 +245,73 @@ int dg_adam_step(float *param, float *grad, float *m, float *v, uint64_t n, floa
 /* Learning rate of Sec. 5.1 (host function): lr0 at iteration 0 down to lr1 at `total` along half a cosine,
  * lr1 afterwards (the paper: 0.05 -> 0.005 over 300 000 iterations). */
 float dg_cosine_lr(float lr0, float lr1, uint64_t iteration, uint64_t total);
+
+/* ------------------------------------------------------------------------------------
+ * Occupancy grid and occupancy-guided sampling (Sec. 3.2: per-voxel densities let ray
+ * marching skip empty space; Sec. 4.1: the grid is deformable like the hash grid; Sec. 5.1:
+ * one scale, plain x-fastest storage, resolution 512, decay 0.99 every 16 iterations,
+ * warm-up of 4096 iterations, bit threshold 0.6 before iteration 10 000 and 60 after; the
+ * refresh rule -- decay, candidate cells, maximum, threshold -- is Instant-NGP App. E.2).
+ * The grid has res[d] = ceil(a_d/s * N) cubic cells of side s/N; a point with unit
+ * coordinates u (clamped to [0,1]) lies in cell min(floor(u_d * scale[d]), res[d]-1) per
+ * axis, linear index x + res_x (y + res_y z).  density: n_cells fp32 (device);
+ * bits: ceil(n_cells/32) uint32 words (device), bit c%32 of word c/32 belongs to cell c.
+ * ---------------------------------------------------------------------------------- */
+typedef struct dg_occ_desc {
+    uint32_t res[3];
+    uint32_t n_cells;
+    float    scale[3];
+} dg_occ_desc;
+/* Host.  DG_ERR_ARG for null pointers, N == 0 or non-positive extents, DG_ERR_UNSUPPORTED for more than 2^31 cells. */
+int dg_occ_desc_init(dg_occ_desc *desc, uint32_t N, const double extent[3]);
+/* Host: what Sec. 5.1 prescribes at a training iteration -- whether the grid is refreshed now (every 16th),
+ * whether the warm-up rule for candidates applies (< 4096), the decay factor and the bit threshold. */
+void dg_occ_schedule(uint64_t iteration, int *update_now, int *warmup, float *decay, float *threshold);
+/* Candidate cells of one refresh and a random point in each: cell [M] uint32, u [M,3] fp32 (device).
+ * warmup != 0: M must equal n_cells, candidate i is cell i.  Otherwise candidates [0, n_uniform) are uniform draws
+ * over all cells and the rest are drawn among occupied cells by rejection: up to `tries` (1..64) uniform draws, the
+ * first one whose bit is set, else the last.  Random numbers: splitmix64 output mix of
+ * seed + 0x9E3779B97F4A7C15*(ctr+1), ctr = iteration<<36 | i<<8 | try<<2 | q (q = 0 cell, 1..3 position);
+ * cell = (top 32 bits * n_cells) >> 32; u_d = (c_d + xi_d) / scale[d], xi = top 24 bits * 2^-24.
+ * M < 2^28, iteration < 2^28. */
+int dg_occ_candidates(const dg_occ_desc *desc, const uint32_t *bits, uint32_t M, uint32_t n_uniform, int warmup,
+                      uint64_t seed, uint32_t iteration, uint32_t tries, uint32_t *cell, float *u, void *stream);
+/* density[c] *= factor */
+int dg_occ_decay(float *density, uint32_t n_cells, float factor, void *stream);
+/* density[cell[i]] = max(density[cell[i]], sigma[i]); densities are >= 0, a sigma that is negative or NaN is ignored,
+ * and so is a cell index >= n_cells */
+int dg_occ_update(float *density, uint32_t n_cells, const uint32_t *cell, const float *sigma, uint32_t M,
+                  void *stream);
+/* bit of cell c = density[c] > threshold; *n_set (device, may be NULL) "+=" the number of set bits */
+int dg_occ_bits(const float *density, uint32_t n_cells, float threshold, uint32_t *bits, uint32_t *n_set,
+                void *stream);
+/* Marching of the n_seg segments listed in seg_ray/seg_slot (as for dg_sample_segments) through box `box` (host,
+ * 6 floats) with the occupancy bits of that box's sub-model.  A segment of length len = t_out - t_in is cut into
+ * n = clamp(ceil(len / dt), 1, max_steps) equal strata (max_steps <= 65535), stratum s is sampled at
+ * t = t_in + (s + xi) * (len / n) with the jitter generator of dg_sample_segments, and the sample is kept iff the
+ * bit of its cell is set (fp32 throughout, one rounding per operation).
+ * Outputs (device): first [n_seg + 1] -- the samples of segment j are [first[j], first[j+1]), first[n_seg] is the
+ * total; u [capacity,3], delta [capacity] (stratum width), t [capacity], sample_ray [capacity] (ray of each sample,
+ * the index for dg_dir_encode).  Samples at positions >= capacity are not written and bit 1 of *status is set: the
+ * caller reads first[n_seg] back and must not use more than it has room for.
+ * ws: dg_march_workspace_bytes(n_seg) bytes of device memory. */
+size_t dg_march_workspace_bytes(uint32_t n_seg);
+int dg_march_segments(const float *o, const float *d, const float *seg_t, const uint32_t *seg_ray,
+                      const uint32_t *seg_slot, uint32_t n_seg, uint32_t k_max, const float *box,
+                      const dg_occ_desc *occ, const uint32_t *bits, float dt, uint32_t max_steps, uint64_t seed,
+                      uint32_t capacity, uint32_t *first, float *u, float *delta, float *t, uint32_t *sample_ray,
+                      uint32_t *status, void *ws, size_t ws_bytes, void *stream);
+/* Local volume rendering (Eq. 3) of segments of different lengths: as dg_composite_segment_fwd / _depth / _bwd, with
+ * segment j owning samples [first[j], first[j+1]); a segment without samples gives C_k = 0, T_k = 1, D_k = 0. */
+int dg_composite_ragged_fwd(const float *sigma, const float *rgb, const float *delta, uint32_t n_seg,
+                            const uint32_t *first, const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t k_max,
+                            float *Ck, float *Tk, void *stream);
+int dg_composite_ragged_depth(const float *sigma, const float *delta, const float *t, uint32_t n_seg,
+                              const uint32_t *first, const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t k_max,
+                              float *Dk, void *stream);
+int dg_composite_ragged_bwd(const float *sigma, const float *rgb, const float *delta, uint32_t n_seg,
+                            const uint32_t *first, const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t k_max,
+                            const float *gCk, const float *gTk, float *dsigma, float *drgb, void *stream);
 
 #ifdef __cplusplus
 }

@@ -33,6 +33,10 @@ class MlpDesc(C.Structure):
                                           "act_c")]
 
 
+class OccDesc(C.Structure):
+    _fields_ = [("res", C.c_uint32 * 3), ("n_cells", C.c_uint32), ("scale", C.c_float * 3)]
+
+
 class DistGridError(RuntimeError):
     pass
 
@@ -74,6 +78,22 @@ _SIGNATURES = {
     "dg_merge_depth": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p]),
     "dg_adam_step": (C.c_int, [C.c_void_p] * 4 + [C.c_uint64] + [C.c_float] * 4 + [C.c_uint32, C.c_float, C.c_uint32] + [C.c_void_p] * 2),
     "dg_cosine_lr": (C.c_float, [C.c_float, C.c_float, C.c_uint64, C.c_uint64]),
+    "dg_occ_desc_init": (C.c_int, [C.POINTER(OccDesc), C.c_uint32, C.POINTER(C.c_double)]),
+    "dg_occ_schedule": (None, [C.c_uint64, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_float), C.POINTER(C.c_float)]),
+    "dg_occ_candidates": (C.c_int, [C.POINTER(OccDesc), C.c_void_p, C.c_uint32, C.c_uint32, C.c_int, C.c_uint64, C.c_uint32, C.c_uint32,
+                                    C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dg_occ_decay": (C.c_int, [C.c_void_p, C.c_uint32, C.c_float, C.c_void_p]),
+    "dg_occ_update": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]),
+    "dg_occ_bits": (C.c_int, [C.c_void_p, C.c_uint32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dg_march_workspace_bytes": (C.c_size_t, [C.c_uint32]),
+    "dg_march_segments": (C.c_int, [C.c_void_p] * 5 + [C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.POINTER(OccDesc), C.c_void_p, C.c_float,
+                                                       C.c_uint32, C.c_uint64, C.c_uint32] + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]),
+    "dg_composite_ragged_fwd": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
+                                                             C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dg_composite_ragged_depth": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
+                                                               C.c_void_p, C.c_void_p]),
+    "dg_composite_ragged_bwd": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32]
+                                + [C.c_void_p] * 5),
 }
 
 EXPORTS = tuple(_SIGNATURES)
@@ -255,3 +275,79 @@ def dg_merge_depth(Dk, Tk, seg_count, R, k_max, D):
     assert min(Dk.numel(), Tk.numel()) >= R * k_max and min(seg_count.numel(), D.numel()) >= R
     _check(lib().dg_merge_depth(_ptr(Dk, torch.float32), _ptr(Tk, torch.float32), _ptr(seg_count, torch.int32), R, k_max,
                                 _ptr(D, torch.float32), _stream()))
+
+
+# ------------------------------------------------------------------ occupancy grid and occupancy-guided sampling
+def dg_occ_desc_init(N, extent):
+    desc = OccDesc()
+    ext = (C.c_double * 3)(*[float(e) for e in extent])
+    _check(lib().dg_occ_desc_init(C.byref(desc), N, ext))
+    return desc
+
+
+def dg_occ_schedule(iteration):
+    """(update_now, warmup, decay, threshold) at a training iteration."""
+    a, b, c, d = C.c_int(), C.c_int(), C.c_float(), C.c_float()
+    lib().dg_occ_schedule(iteration, C.byref(a), C.byref(b), C.byref(c), C.byref(d))
+    return bool(a.value), bool(b.value), c.value, d.value
+
+
+def dg_occ_candidates(desc, bits, M, n_uniform, warmup, seed, iteration, tries, cell, u):
+    assert cell.numel() >= M and u.numel() >= 3 * M and (bits is None or bits.numel() >= (desc.n_cells + 31) // 32)
+    _check(lib().dg_occ_candidates(C.byref(desc), _ptr(bits, torch.int32, True), M, n_uniform, 1 if warmup else 0, seed, iteration,
+                                   tries, _ptr(cell, torch.int32), _ptr(u, torch.float32), _stream()))
+
+
+def dg_occ_decay(density, factor):
+    _check(lib().dg_occ_decay(_ptr(density, torch.float32), density.numel(), factor, _stream()))
+
+
+def dg_occ_update(density, cell, sigma, M):
+    assert cell.numel() >= M and sigma.numel() >= M
+    _check(lib().dg_occ_update(_ptr(density, torch.float32), density.numel(), _ptr(cell, torch.int32), _ptr(sigma, torch.float32), M,
+                               _stream()))
+
+
+def dg_occ_bits(density, threshold, bits, n_set=None):
+    assert bits.numel() >= (density.numel() + 31) // 32
+    _check(lib().dg_occ_bits(_ptr(density, torch.float32), density.numel(), threshold, _ptr(bits, torch.int32),
+                             _ptr(n_set, torch.int32, True), _stream()))
+
+
+def dg_march_workspace_bytes(n_seg):
+    return int(lib().dg_march_workspace_bytes(n_seg))
+
+
+def dg_march_segments(o, d, seg_t, seg_ray, seg_slot, n_seg, k_max, box, occ, bits, dt, max_steps, seed, capacity, first, u, delta, t,
+                      sample_ray, status, ws):
+    assert first.numel() >= n_seg + 1 and bits.numel() >= (occ.n_cells + 31) // 32
+    assert min(seg_ray.numel(), seg_slot.numel()) >= n_seg
+    assert u.numel() >= 3 * capacity and min(delta.numel(), t.numel(), sample_ray.numel()) >= capacity
+    box_c = (C.c_float * 6)(*[float(b) for b in box])
+    _check(lib().dg_march_segments(
+        _ptr(o, torch.float32), _ptr(d, torch.float32), _ptr(seg_t, torch.float32), _ptr(seg_ray, torch.int32),
+        _ptr(seg_slot, torch.int32), n_seg, k_max, box_c, C.byref(occ), _ptr(bits, torch.int32), dt, max_steps, seed, capacity,
+        _ptr(first, torch.int32), _ptr(u, torch.float32), _ptr(delta, torch.float32), _ptr(t, torch.float32),
+        _ptr(sample_ray, torch.int32), _ptr(status, torch.int32), _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+def dg_composite_ragged_fwd(sigma, rgb, delta, n_seg, first, seg_ray, seg_slot, k_max, Ck, Tk):
+    assert first.numel() >= n_seg + 1 and min(seg_ray.numel(), seg_slot.numel()) >= n_seg
+    _check(lib().dg_composite_ragged_fwd(
+        _ptr(sigma, torch.float32), _ptr(rgb, torch.float32), _ptr(delta, torch.float32), n_seg, _ptr(first, torch.int32),
+        _ptr(seg_ray, torch.int32), _ptr(seg_slot, torch.int32), k_max, _ptr(Ck, torch.float32), _ptr(Tk, torch.float32), _stream()))
+
+
+def dg_composite_ragged_depth(sigma, delta, t, n_seg, first, seg_ray, seg_slot, k_max, Dk):
+    assert first.numel() >= n_seg + 1 and min(seg_ray.numel(), seg_slot.numel()) >= n_seg
+    _check(lib().dg_composite_ragged_depth(
+        _ptr(sigma, torch.float32), _ptr(delta, torch.float32), _ptr(t, torch.float32), n_seg, _ptr(first, torch.int32),
+        _ptr(seg_ray, torch.int32), _ptr(seg_slot, torch.int32), k_max, _ptr(Dk, torch.float32), _stream()))
+
+
+def dg_composite_ragged_bwd(sigma, rgb, delta, n_seg, first, seg_ray, seg_slot, k_max, gCk, gTk, dsigma, drgb):
+    assert first.numel() >= n_seg + 1 and min(seg_ray.numel(), seg_slot.numel()) >= n_seg
+    _check(lib().dg_composite_ragged_bwd(
+        _ptr(sigma, torch.float32), _ptr(rgb, torch.float32), _ptr(delta, torch.float32), n_seg, _ptr(first, torch.int32),
+        _ptr(seg_ray, torch.int32), _ptr(seg_slot, torch.int32), k_max, _ptr(gCk, torch.float32), _ptr(gTk, torch.float32),
+        _ptr(dsigma, torch.float32), _ptr(drgb, torch.float32), _stream()))

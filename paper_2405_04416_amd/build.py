@@ -10,12 +10,12 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libdistgrid.so")
 
-SOURCES = ["host.hip", "segments.hip", "encode.hip", "encode_bwd_binned.hip", "mlp.hip", "mlp_mfma.hip", "render.hip", "optim.hip"]
+SOURCES = ["host.hip", "segments.hip", "encode.hip", "encode_bwd_binned.hip", "mlp.hip", "mlp_mfma.hip", "render.hip", "optim.hip", "occupancy.hip"]
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           # packed fp32 instructions are kept out of every kernel of this library
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
-PER_FILE = {"segments.hip": ["-ffp-contract=off"]}   # bit-exact fp32 bookkeeping: no fused multiply-add
+PER_FILE = {"segments.hip": ["-ffp-contract=off"], "occupancy.hip": ["-ffp-contract=off"]}   # bit-exact fp32 bookkeeping: no fused multiply-add
 
 
 def hipcc():

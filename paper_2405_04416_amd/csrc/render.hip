@@ -39,18 +39,20 @@ __device__ __forceinline__ float wave_sum(float v)
 
 __global__ void __launch_bounds__(kBlock)
 composite_fwd_kernel(const float *__restrict__ sigma, const float *__restrict__ rgb, const float *__restrict__ delta,
-                     uint32_t n_seg, uint32_t S, const uint32_t *__restrict__ seg_ray,
+                     uint32_t n_seg, uint32_t S_fixed, const uint32_t *__restrict__ first, const uint32_t *__restrict__ seg_ray,
                      const uint32_t *__restrict__ seg_slot, uint32_t k_max, float *__restrict__ Ck,
                      float *__restrict__ Tk)
 {
     const uint32_t j = blockIdx.x * kWavesPerBlock + threadIdx.x / dg::kWave;
     const int lane = threadIdx.x % dg::kWave;
     if (j >= n_seg) return;
+    const size_t begin = first ? (size_t)first[j] : (size_t)j * S_fixed;      // segments of different lengths bring their offsets
+    const uint32_t S = first ? first[j + 1] - first[j] : S_fixed;
     float trans = 1.0f, c0 = 0.0f, c1 = 0.0f, c2 = 0.0f;
     for (uint32_t base = 0; base < S; base += dg::kWave) {
         const uint32_t s = base + lane;
         const bool live = s < S;
-        const size_t n = (size_t)j * S + (live ? s : 0);
+        const size_t n = begin + (live ? s : 0);
         const float x = live ? sigma[n] * delta[n] : 0.0f;
         const float keep = expf(-x);                        // 1 - alpha
         const float alpha = -expm1f(-x);
@@ -74,17 +76,19 @@ composite_fwd_kernel(const float *__restrict__ sigma, const float *__restrict__ 
 // Depth of evaluation rendering (Sec. 4.4.2): D_k = sum_i T_i alpha_i t_i, the colour rule applied to the sample distances
 __global__ void __launch_bounds__(kBlock)
 composite_depth_kernel(const float *__restrict__ sigma, const float *__restrict__ delta, const float *__restrict__ t,
-                       uint32_t n_seg, uint32_t S, const uint32_t *__restrict__ seg_ray,
+                       uint32_t n_seg, uint32_t S_fixed, const uint32_t *__restrict__ first, const uint32_t *__restrict__ seg_ray,
                        const uint32_t *__restrict__ seg_slot, uint32_t k_max, float *__restrict__ Dk)
 {
     const uint32_t j = blockIdx.x * kWavesPerBlock + threadIdx.x / dg::kWave;
     const int lane = threadIdx.x % dg::kWave;
     if (j >= n_seg) return;
+    const size_t begin = first ? (size_t)first[j] : (size_t)j * S_fixed;      // segments of different lengths bring their offsets
+    const uint32_t S = first ? first[j + 1] - first[j] : S_fixed;
     float trans = 1.0f, depth = 0.0f;
     for (uint32_t base = 0; base < S; base += dg::kWave) {
         const uint32_t s = base + lane;
         const bool live = s < S;
-        const size_t n = (size_t)j * S + (live ? s : 0);
+        const size_t n = begin + (live ? s : 0);
         const float x = live ? sigma[n] * delta[n] : 0.0f;
         const float incl = wave_inclusive_product(expf(-x), lane);
         float before = __shfl_up(incl, 1, dg::kWave);
@@ -99,13 +103,15 @@ composite_depth_kernel(const float *__restrict__ sigma, const float *__restrict_
 // d sigma_i = delta_i [ gC.(T_{i+1} c_i) - sum_{j>i} w_j gC.c_j - gT T_k ],  d c_i = w_i gC
 __global__ void __launch_bounds__(kBlock)
 composite_bwd_kernel(const float *__restrict__ sigma, const float *__restrict__ rgb, const float *__restrict__ delta,
-                     uint32_t n_seg, uint32_t S, const uint32_t *__restrict__ seg_ray,
+                     uint32_t n_seg, uint32_t S_fixed, const uint32_t *__restrict__ first, const uint32_t *__restrict__ seg_ray,
                      const uint32_t *__restrict__ seg_slot, uint32_t k_max, const float *__restrict__ gCk,
                      const float *__restrict__ gTk, float *__restrict__ dsigma, float *__restrict__ drgb)
 {
     const uint32_t j = blockIdx.x * kWavesPerBlock + threadIdx.x / dg::kWave;
     const int lane = threadIdx.x % dg::kWave;
     if (j >= n_seg) return;
+    const size_t begin = first ? (size_t)first[j] : (size_t)j * S_fixed;      // segments of different lengths bring their offsets
+    const uint32_t S = first ? first[j + 1] - first[j] : S_fixed;
     const size_t src = (size_t)seg_ray[j] * k_max + seg_slot[j];
     const float g0 = gCk[3 * src], g1 = gCk[3 * src + 1], g2 = gCk[3 * src + 2], gt = gTk[src];
 
@@ -116,7 +122,7 @@ composite_bwd_kernel(const float *__restrict__ sigma, const float *__restrict__ 
         for (uint32_t base = 0; base < S; base += dg::kWave) {
             const uint32_t s = base + lane;
             const bool live = s < S;
-            const size_t n = (size_t)j * S + (live ? s : 0);
+            const size_t n = begin + (live ? s : 0);
             const float x = live ? sigma[n] * delta[n] : 0.0f;
             const float incl = wave_inclusive_product(expf(-x), lane);
             float before = __shfl_up(incl, 1, dg::kWave);
@@ -133,7 +139,7 @@ composite_bwd_kernel(const float *__restrict__ sigma, const float *__restrict__ 
     for (uint32_t base = 0; base < S; base += dg::kWave) {
         const uint32_t s = base + lane;
         const bool live = s < S;
-        const size_t n = (size_t)j * S + (live ? s : 0);
+        const size_t n = begin + (live ? s : 0);
         const float dl = live ? delta[n] : 0.0f;
         const float x = live ? sigma[n] * dl : 0.0f;
         const float keep = expf(-x);
@@ -276,8 +282,8 @@ extern "C" int dg_composite_segment_fwd(const float *sigma, const float *rgb, co
     if (n_seg == 0) return DG_OK;
     DG_REQUIRE(sigma && rgb && delta && seg_ray && seg_slot && Ck && Tk, DG_ERR_ARG, "dg_composite_segment_fwd: null pointer");
     const uint32_t n_blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
-    composite_fwd_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, S, seg_ray, seg_slot,
-                                                                       k_max, Ck, Tk);
+    composite_fwd_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, S, nullptr, seg_ray,
+                                                                       seg_slot, k_max, Ck, Tk);
     return dg::launch_status("dg_composite_segment_fwd");
 }
 
@@ -289,7 +295,8 @@ extern "C" int dg_composite_segment_depth(const float *sigma, const float *delta
     if (n_seg == 0) return DG_OK;
     DG_REQUIRE(sigma && delta && t && seg_ray && seg_slot && Dk, DG_ERR_ARG, "dg_composite_segment_depth: null pointer");
     const uint32_t n_blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
-    composite_depth_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, delta, t, n_seg, S, seg_ray, seg_slot, k_max, Dk);
+    composite_depth_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, delta, t, n_seg, S, nullptr, seg_ray, seg_slot,
+                                                                         k_max, Dk);
     return dg::launch_status("dg_composite_segment_depth");
 }
 
@@ -302,9 +309,50 @@ extern "C" int dg_composite_segment_bwd(const float *sigma, const float *rgb, co
     DG_REQUIRE(sigma && rgb && delta && seg_ray && seg_slot && gCk && gTk && dsigma && drgb, DG_ERR_ARG,
                "dg_composite_segment_bwd: null pointer");
     const uint32_t n_blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
-    composite_bwd_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, S, seg_ray, seg_slot,
-                                                                       k_max, gCk, gTk, dsigma, drgb);
+    composite_bwd_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, S, nullptr, seg_ray,
+                                                                       seg_slot, k_max, gCk, gTk, dsigma, drgb);
     return dg::launch_status("dg_composite_segment_bwd");
+}
+
+// ---- the same three on segments of different lengths (occupancy-guided sampling, Sec. 3.2 / Sec. 5.1)
+extern "C" int dg_composite_ragged_fwd(const float *sigma, const float *rgb, const float *delta, uint32_t n_seg,
+                                       const uint32_t *first, const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t k_max,
+                                       float *Ck, float *Tk, void *stream)
+{
+    if (int rc = seg_args_ok(n_seg, 1, k_max, "dg_composite_ragged_fwd")) return rc;
+    if (n_seg == 0) return DG_OK;
+    DG_REQUIRE(sigma && rgb && delta && first && seg_ray && seg_slot && Ck && Tk, DG_ERR_ARG, "dg_composite_ragged_fwd: null pointer");
+    const uint32_t n_blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
+    composite_fwd_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, 0, first, seg_ray, seg_slot,
+                                                                       k_max, Ck, Tk);
+    return dg::launch_status("dg_composite_ragged_fwd");
+}
+
+extern "C" int dg_composite_ragged_depth(const float *sigma, const float *delta, const float *t, uint32_t n_seg,
+                                         const uint32_t *first, const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t k_max,
+                                         float *Dk, void *stream)
+{
+    if (int rc = seg_args_ok(n_seg, 1, k_max, "dg_composite_ragged_depth")) return rc;
+    if (n_seg == 0) return DG_OK;
+    DG_REQUIRE(sigma && delta && t && first && seg_ray && seg_slot && Dk, DG_ERR_ARG, "dg_composite_ragged_depth: null pointer");
+    const uint32_t n_blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
+    composite_depth_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, delta, t, n_seg, 0, first, seg_ray, seg_slot,
+                                                                         k_max, Dk);
+    return dg::launch_status("dg_composite_ragged_depth");
+}
+
+extern "C" int dg_composite_ragged_bwd(const float *sigma, const float *rgb, const float *delta, uint32_t n_seg,
+                                       const uint32_t *first, const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t k_max,
+                                       const float *gCk, const float *gTk, float *dsigma, float *drgb, void *stream)
+{
+    if (int rc = seg_args_ok(n_seg, 1, k_max, "dg_composite_ragged_bwd")) return rc;
+    if (n_seg == 0) return DG_OK;
+    DG_REQUIRE(sigma && rgb && delta && first && seg_ray && seg_slot && gCk && gTk && dsigma && drgb, DG_ERR_ARG,
+               "dg_composite_ragged_bwd: null pointer");
+    const uint32_t n_blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
+    composite_bwd_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, 0, first, seg_ray, seg_slot,
+                                                                       k_max, gCk, gTk, dsigma, drgb);
+    return dg::launch_status("dg_composite_ragged_bwd");
 }
 
 extern "C" int dg_merge_segments(const float *Ck, const float *Tk, const uint32_t *seg_count, uint32_t R,

@@ -5,6 +5,7 @@
 // The fp32 bookkeeping here must round after every operation (segment times are compared bit
 // for bit between boxes), so this file is built with -ffp-contract=off.
 #include "dg_internal.h"
+#include "sample_common.h"
 
 #pragma clang fp contract(off)
 
@@ -185,17 +186,8 @@ bucket_scatter_kernel(const uint32_t *__restrict__ seg_count, const int32_t *__r
 }
 
 // ---------------------------------------------------------------- stratified samples
-__device__ __forceinline__ float counter_jitter(uint64_t seed, uint32_t ray, uint32_t slot, uint32_t s)
-{
-    const uint64_t ctr = ((uint64_t)ray << 32) | ((uint64_t)(slot & 0xffffu) << 16) | (uint64_t)(s & 0xffffu);
-    uint64_t z = seed + 0x9E3779B97F4A7C15ull * (ctr + 1ull);
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    z ^= z >> 31;
-    return (float)(uint32_t)(z >> 40) * (1.0f / 16777216.0f);
-}
-
-struct BoxArgs { float lo[3], inv_ext[3]; };
+using dg_sample::counter_jitter;
+using dg_sample::BoxArgs;
 
 __global__ void __launch_bounds__(kBlock)
 sample_kernel(const float *__restrict__ o, const float *__restrict__ d, const float *__restrict__ seg_t,

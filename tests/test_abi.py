@@ -77,6 +77,34 @@ def test_argument_validation_on_host():
     assert B.lib().dg_mlp_fwd(C.byref(bad), None, None, None, 4, 0, None, None, None) == -2
 
 
+def test_occupancy_host_side():
+    for N, ext in [(512, (2.0, 2.0, 0.25)), (8, (4.0, 2.0, 1.0)), (10, (1.0, 1.0, 0.25)), (33, (0.7, 3.1, 1.9))]:
+        desc, ref = B.dg_occ_desc_init(N, ext), oracle.occ_init(N, ext)
+        assert tuple(desc.res) == tuple(ref.shape) and desc.n_cells == ref.n_cells
+        assert tuple(desc.scale) == tuple(ref.gain)                     # bit-identical fp32
+    for it in list(range(0, 40)) + [4095, 4096, 9999, 10000, 10016, 299999]:
+        assert B.dg_occ_schedule(it) == oracle.occ_schedule(it)
+    with pytest.raises(B.DistGridError):
+        B.dg_occ_desc_init(0, [1, 1, 1])
+    with pytest.raises(B.DistGridError):
+        B.dg_occ_desc_init(8, [1, -1, 1])
+    with pytest.raises(B.DistGridError):
+        B.dg_occ_desc_init(2048, [1, 1, 1])                             # 2^33 cells
+    desc = B.dg_occ_desc_init(8, [1, 1, 1])
+    lib = B.lib()
+    assert lib.dg_occ_candidates(C.byref(desc), None, 0, 0, 0, 0, 0, 32, None, None, None) == 0
+    assert lib.dg_occ_candidates(C.byref(desc), None, 5, 0, 1, 0, 0, 32, None, None, None) == -1       # warm-up visits all cells
+    assert lib.dg_occ_candidates(C.byref(desc), None, 5, 0, 0, 0, 0, 65, None, None, None) == -1
+    assert lib.dg_march_workspace_bytes(0) >= 4 and lib.dg_march_workspace_bytes(1 << 20) >= 4 * 513
+    box = (C.c_float * 6)(0, 0, 0, 1, 1, 1)
+    assert lib.dg_march_segments(None, None, None, None, None, 0, 1, box, C.byref(desc), None, 0.0, 10, 0, 0, None, None, None, None,
+                                 None, None, None, 0, None) == -1          # dt must be positive
+    assert lib.dg_march_segments(None, None, None, None, None, 0, 1, box, C.byref(desc), None, 0.1, 70000, 0, 0, None, None, None,
+                                 None, None, None, None, 0, None) == -1    # the jitter counter has 16 bits for the stratum
+    assert lib.dg_composite_ragged_fwd(None, None, None, 0, None, None, None, 1, None, None, None) == 0
+    assert lib.dg_composite_ragged_fwd(None, None, None, 3, None, None, None, 1, None, None, None) == -1
+
+
 def test_optimiser_host_side():
     # the schedule is a host function: same values as the oracle's (fp32 result of a double computation)
     for it in (0, 1, 1234, 150000, 299999, 300000, 10 ** 6):
