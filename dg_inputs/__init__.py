@@ -2,7 +2,7 @@
 
 Shared by the tests, the benchmark and the smoke check.  This module holds none
 of the method's arithmetic: it only draws random rays, boxes, table values,
-weights, targets and jitter, and names the five workload configurations.  The
+weights, targets, jitter and stand-in cell densities, and names the workload configurations.  The
 paper trains on drone oblique photography of flat scenes, rays drawn uniformly
 at random over all images (DistGrid Sec. 4.4.1, Sec. 5.1); those datasets are
 not available here, so the generators below stand in for them.
@@ -55,6 +55,13 @@ CONFIGS = {
         rays="through_inner", r_max=2.5, cam_height=1.5, R=1 << 18, S=64, k_max=10,
         grid=dict(L=16, F=2, log2_T=22, n_min=16, n_max=2048), grid_coarse=dict(L=16, F=2, log2_T=19, n_min=16, n_max=2048),
         coarse_from=4, table_range=1e-4,
+        mlp=dict(n_hidden_d=64, n_geo=16, sh_degree=4, n_hidden_c=64, n_layers_c=2)),
+    # Occupancy-guided sampling (Sec. 3.2, Sec. 5.1): the c2 scene and rays with an occupancy grid of resolution 512 along
+    # the longest side; segments are cut into strata of Instant-NGP's marching step and only occupied cells are sampled.
+    "c7_occ": dict(
+        parts=_tile([-1, 1], [-1, 1], 0, 0.25), rays="aerial", cam_height=1.5, tilt_deg=30.0, R=1 << 18, S=64,
+        k_max=1, grid=dict(L=16, F=2, log2_T=19, n_min=16, n_max=2048), table_range=1e-4,
+        occ=dict(res=512, max_steps=1024),
         mlp=dict(n_hidden_d=64, n_geo=16, sh_degree=4, n_hidden_c=64, n_layers_c=2)),
 }
 

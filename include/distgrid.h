@@ -267,15 +267,18 @@ int dg_occ_desc_init(dg_occ_desc *desc, uint32_t N, const double extent[3]);
 /* Host: what Sec. 5.1 prescribes at a training iteration -- whether the grid is refreshed now (every 16th),
  * whether the warm-up rule for candidates applies (< 4096), the decay factor and the bit threshold. */
 void dg_occ_schedule(uint64_t iteration, int *update_now, int *warmup, float *decay, float *threshold);
-/* Candidate cells of one refresh and a random point in each: cell [M] uint32, u [M,3] fp32 (device).
- * warmup != 0: M must equal n_cells, candidate i is cell i.  Otherwise candidates [0, n_uniform) are uniform draws
- * over all cells and the rest are drawn among occupied cells by rejection: up to `tries` (1..64) uniform draws, the
+/* Candidate cells [i0, i0 + M) of one refresh and a random point in each (a refresh may be produced in several
+ * calls): cell [M] uint32, u [M,3] fp32 (device).  A refresh has all n_cells cells as candidates during warm-up and
+ * n_cells/2 afterwards, half of them uniform (Instant-NGP App. E.2).
+ * warmup != 0: candidate i is cell i (i0 + M <= n_cells).  Otherwise candidates i < n_uniform are uniform draws over
+ * all cells and the others are drawn among occupied cells by rejection: up to `tries` (1..64) uniform draws, the
  * first one whose bit is set, else the last.  Random numbers: splitmix64 output mix of
  * seed + 0x9E3779B97F4A7C15*(ctr+1), ctr = iteration<<36 | i<<8 | try<<2 | q (q = 0 cell, 1..3 position);
  * cell = (top 32 bits * n_cells) >> 32; u_d = (c_d + xi_d) / scale[d], xi = top 24 bits * 2^-24.
- * M < 2^28, iteration < 2^28. */
-int dg_occ_candidates(const dg_occ_desc *desc, const uint32_t *bits, uint32_t M, uint32_t n_uniform, int warmup,
-                      uint64_t seed, uint32_t iteration, uint32_t tries, uint32_t *cell, float *u, void *stream);
+ * i0 + M <= 2^28, iteration < 2^28. */
+int dg_occ_candidates(const dg_occ_desc *desc, const uint32_t *bits, uint32_t i0, uint32_t M, uint32_t n_uniform,
+                      int warmup, uint64_t seed, uint32_t iteration, uint32_t tries, uint32_t *cell, float *u,
+                      void *stream);
 /* density[c] *= factor */
 int dg_occ_decay(float *density, uint32_t n_cells, float factor, void *stream);
 /* density[cell[i]] = max(density[cell[i]], sigma[i]); densities are >= 0, a sigma that is negative or NaN is ignored,

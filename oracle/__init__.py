@@ -367,11 +367,11 @@ def rand64(seed, counter):
     return int(f(C.c_uint64(seed), C.c_uint64(counter)))
 
 
-def occ_candidates(g, bits, M, n_uniform, warmup, seed, iteration, tries=32):
+def occ_candidates(g, bits, M, n_uniform, warmup, seed, iteration, tries=32, i0=0):
     bits = _arr(bits, np.uint32)
     cell = np.zeros(M, np.uint32)
     u = np.zeros((M, 3), np.float32)
-    lib().dgo_occ_candidates(C.byref(g), _p(bits), C.c_uint32(M), C.c_uint32(n_uniform), C.c_int(1 if warmup else 0),
+    lib().dgo_occ_candidates(C.byref(g), _p(bits), C.c_uint32(i0), C.c_uint32(M), C.c_uint32(n_uniform), C.c_int(1 if warmup else 0),
                              C.c_uint64(seed), C.c_uint32(iteration), C.c_uint32(tries), _p(cell), _p(u))
     return cell, u
 

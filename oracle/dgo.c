@@ -713,10 +713,10 @@ static uint64_t candidate_counter(uint32_t iteration, uint32_t i, uint32_t attem
     return ((uint64_t)iteration << 36) | ((uint64_t)i << 8) | ((uint64_t)attempt << 2) | q;
 }
 
-void dgo_occ_candidates(const dgo_occ *g, const uint32_t *bits, uint32_t M, uint32_t n_uniform, int warmup,
+void dgo_occ_candidates(const dgo_occ *g, const uint32_t *bits, uint32_t i0, uint32_t M, uint32_t n_uniform, int warmup,
                         uint64_t seed, uint32_t iteration, uint32_t tries, uint32_t *cell, float *u)
 {
-    for (uint32_t i = 0; i < M; ++i) {
+    for (uint32_t i = i0; i < i0 + M; ++i) {
         uint32_t c = i, attempt = 0;
         if (!warmup) {
             uint32_t allowed = i < n_uniform ? 1 : tries;
@@ -727,12 +727,12 @@ void dgo_occ_candidates(const dgo_occ *g, const uint32_t *bits, uint32_t M, uint
             }
             if (attempt == allowed) attempt = allowed - 1;      /* no occupied cell met: keep the last draw */
         }
-        cell[i] = c;
+        cell[i - i0] = c;
         uint32_t idx[3] = {c % g->shape[0], (c / g->shape[0]) % g->shape[1], c / (g->shape[0] * g->shape[1])};
         for (uint32_t a = 0; a < 3; ++a) {
             uint64_t z = dgo_rand64(seed, candidate_counter(iteration, i, attempt, a + 1));
             float xi = (float)(z >> 40) * (1.0f / 16777216.0f);
-            u[3 * (uint64_t)i + a] = ((float)idx[a] + xi) / g->gain[a];
+            u[3 * (uint64_t)(i - i0) + a] = ((float)idx[a] + xi) / g->gain[a];
         }
     }
 }

@@ -156,13 +156,13 @@ uint32_t dgo_occ_cell(const dgo_occ *g, const float *u3);
 void dgo_occ_schedule(uint64_t iteration, int *update_now, int *warmup, float *decay, float *threshold);
 /* 64 random bits for (seed, counter): splitmix64 output mix of seed + golden * (counter + 1) */
 uint64_t dgo_rand64(uint64_t seed, uint64_t counter);
-/* Candidate cells of one refresh (Instant-NGP App. E.2) and a random point inside each.
- * warmup: M must be n_cells and candidate i is cell i.  Otherwise the first n_uniform candidates are
+/* Candidate cells [i0, i0 + M) of one refresh (Instant-NGP App. E.2) and a random point inside each (a refresh may be
+ * produced in several pieces).  warmup: candidate i is cell i (i0 + M <= n_cells).  Otherwise the first n_uniform candidates are
  * uniform draws over all cells and the others are drawn among the occupied cells by rejection: up to
  * `tries` uniform draws, the first whose bit is set wins, the last one is taken if none is.
  * Draw q (0 = cell, 1..3 = position) of try a of candidate i uses counter (iteration<<36)|(i<<8)|(a<<2)|q;
  * cell = (top 32 bits * n_cells) >> 32; position u_d = (c_d + xi_d) / gain_d, xi from the top 24 bits. */
-void dgo_occ_candidates(const dgo_occ *g, const uint32_t *bits, uint32_t M, uint32_t n_uniform, int warmup,
+void dgo_occ_candidates(const dgo_occ *g, const uint32_t *bits, uint32_t i0, uint32_t M, uint32_t n_uniform, int warmup,
                         uint64_t seed, uint32_t iteration, uint32_t tries, uint32_t *cell, float *u);
 void dgo_occ_decay(float *density, uint32_t n_cells, float factor);
 /* density[cell[i]] = max(density[cell[i]], sigma[i]) */

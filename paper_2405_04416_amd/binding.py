@@ -80,7 +80,7 @@ _SIGNATURES = {
     "dg_cosine_lr": (C.c_float, [C.c_float, C.c_float, C.c_uint64, C.c_uint64]),
     "dg_occ_desc_init": (C.c_int, [C.POINTER(OccDesc), C.c_uint32, C.POINTER(C.c_double)]),
     "dg_occ_schedule": (None, [C.c_uint64, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_float), C.POINTER(C.c_float)]),
-    "dg_occ_candidates": (C.c_int, [C.POINTER(OccDesc), C.c_void_p, C.c_uint32, C.c_uint32, C.c_int, C.c_uint64, C.c_uint32, C.c_uint32,
+    "dg_occ_candidates": (C.c_int, [C.POINTER(OccDesc), C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, C.c_uint64, C.c_uint32, C.c_uint32,
                                     C.c_void_p, C.c_void_p, C.c_void_p]),
     "dg_occ_decay": (C.c_int, [C.c_void_p, C.c_uint32, C.c_float, C.c_void_p]),
     "dg_occ_update": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]),
@@ -292,9 +292,9 @@ def dg_occ_schedule(iteration):
     return bool(a.value), bool(b.value), c.value, d.value
 
 
-def dg_occ_candidates(desc, bits, M, n_uniform, warmup, seed, iteration, tries, cell, u):
+def dg_occ_candidates(desc, bits, M, n_uniform, warmup, seed, iteration, tries, cell, u, i0=0):
     assert cell.numel() >= M and u.numel() >= 3 * M and (bits is None or bits.numel() >= (desc.n_cells + 31) // 32)
-    _check(lib().dg_occ_candidates(C.byref(desc), _ptr(bits, torch.int32, True), M, n_uniform, 1 if warmup else 0, seed, iteration,
+    _check(lib().dg_occ_candidates(C.byref(desc), _ptr(bits, torch.int32, True), i0, M, n_uniform, 1 if warmup else 0, seed, iteration,
                                    tries, _ptr(cell, torch.int32), _ptr(u, torch.float32), _stream()))
 
 

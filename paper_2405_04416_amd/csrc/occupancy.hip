@@ -56,11 +56,12 @@ __device__ __forceinline__ uint64_t candidate_counter(uint32_t iteration, uint32
 }
 
 __global__ void __launch_bounds__(kBlock)
-candidates_kernel(OccArgs g, const uint32_t *__restrict__ bits, uint32_t M, uint32_t n_uniform, int warmup, uint64_t seed,
-                  uint32_t iteration, uint32_t tries, uint32_t *__restrict__ cell, float *__restrict__ u)
+candidates_kernel(OccArgs g, const uint32_t *__restrict__ bits, uint32_t i0, uint32_t M, uint32_t n_uniform, int warmup,
+                  uint64_t seed, uint32_t iteration, uint32_t tries, uint32_t *__restrict__ cell, float *__restrict__ u)
 {
-    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
-    if (i >= M) return;
+    const uint32_t j = blockIdx.x * kBlock + threadIdx.x;       // position in this call's output
+    if (j >= M) return;
+    const uint32_t i = i0 + j;                                   // index of the candidate within the refresh
     uint32_t c = i, attempt = 0;
     if (!warmup) {
         const uint32_t allowed = i < n_uniform ? 1u : tries;
@@ -71,12 +72,12 @@ candidates_kernel(OccArgs g, const uint32_t *__restrict__ bits, uint32_t M, uint
         }
         if (attempt == allowed) attempt = allowed - 1u;     // no occupied cell met: the last draw stands
     }
-    cell[i] = c;
+    cell[j] = c;
     const uint32_t idx[3] = {c % g.res[0], (c / g.res[0]) % g.res[1], c / (g.res[0] * g.res[1])};
 #pragma unroll
     for (uint32_t a = 0; a < 3; ++a) {
         const float xi = unit_float(mix64(seed, candidate_counter(iteration, i, attempt, a + 1u)));
-        u[3 * (size_t)i + a] = ((float)idx[a] + xi) / g.scale[a];
+        u[3 * (size_t)j + a] = ((float)idx[a] + xi) / g.scale[a];
     }
 }
 
@@ -293,17 +294,19 @@ extern "C" void dg_occ_schedule(uint64_t iteration, int *update_now, int *warmup
     if (threshold) *threshold = iteration < 10000 ? 0.6f : 60.0f;
 }
 
-extern "C" int dg_occ_candidates(const dg_occ_desc *desc, const uint32_t *bits, uint32_t M, uint32_t n_uniform, int warmup,
-                                 uint64_t seed, uint32_t iteration, uint32_t tries, uint32_t *cell, float *u, void *stream)
+extern "C" int dg_occ_candidates(const dg_occ_desc *desc, const uint32_t *bits, uint32_t i0, uint32_t M, uint32_t n_uniform,
+                                 int warmup, uint64_t seed, uint32_t iteration, uint32_t tries, uint32_t *cell, float *u,
+                                 void *stream)
 {
     if (int rc = occ_desc_ok(desc, "dg_occ_candidates")) return rc;
-    DG_REQUIRE(M < (1u << 28) && iteration < (1u << 28), DG_ERR_UNSUPPORTED, "dg_occ_candidates: M and iteration must be below 2^28");
+    DG_REQUIRE((uint64_t)i0 + M <= (1u << 28) && iteration < (1u << 28), DG_ERR_UNSUPPORTED,
+               "dg_occ_candidates: candidate indices and iteration must be below 2^28");
     DG_REQUIRE(tries >= 1 && tries <= 64, DG_ERR_ARG, "dg_occ_candidates: tries=%u outside 1..64", tries);
-    DG_REQUIRE(!warmup || M == desc->n_cells, DG_ERR_ARG, "dg_occ_candidates: the warm-up rule visits every cell, M must be n_cells");
+    DG_REQUIRE(!warmup || (uint64_t)i0 + M <= desc->n_cells, DG_ERR_ARG, "dg_occ_candidates: the warm-up rule visits cell i, i0 + M exceeds n_cells");
     if (M == 0) return DG_OK;
-    DG_REQUIRE(cell && u && (warmup || n_uniform >= M || bits), DG_ERR_ARG, "dg_occ_candidates: null pointer");
-    candidates_kernel<<<(M + kBlock - 1) / kBlock, kBlock, 0, (hipStream_t)stream>>>(occ_args(desc), bits, M, n_uniform, warmup, seed,
-                                                                                    iteration, tries, cell, u);
+    DG_REQUIRE(cell && u && (warmup || n_uniform >= i0 + M || bits), DG_ERR_ARG, "dg_occ_candidates: null pointer");
+    candidates_kernel<<<(M + kBlock - 1) / kBlock, kBlock, 0, (hipStream_t)stream>>>(occ_args(desc), bits, i0, M, n_uniform, warmup,
+                                                                                    seed, iteration, tries, cell, u);
     return dg::launch_status("dg_occ_candidates");
 }
 

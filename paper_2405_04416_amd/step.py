@@ -32,11 +32,22 @@ class SubModel:
         return self.opt
 
 
+class Occupancy:
+    """Occupancy grid of one sub-model (Sec. 3.2, Sec. 5.1): geometry, per-cell densities, bit field, marching step."""
+
+    def __init__(self, desc, density, bits, dt, max_steps):
+        self.desc, self.density, self.bits, self.dt, self.max_steps = desc, density, bits, float(dt), int(max_steps)
+        self.n_set = torch.zeros(1, dtype=torch.int32, device=density.device)
+
+
 class TrainStep:
     def __init__(self, parts, models, resident, R, S, k_max, sh_degree, loss_scale=65536.0, lambda1=0.0, seed=0,
-                 device="cuda:0", max_segments=None, binned_backward=True, encode_ws_cap=48 << 30, holes=None):
+                 device="cuda:0", max_segments=None, binned_backward=True, encode_ws_cap=48 << 30, holes=None,
+                 occupancy=None, max_samples=None):
         """parts: [P,6] float tensor (device); models: {partition index: SubModel}; resident: partition indices served;
-        holes: None or [P,6] (device): the box subtracted from each partition (coarse level of the cascade, Sec. 4.2.2)."""
+        holes: None or [P,6] (device): the box subtracted from each partition (coarse level of the cascade, Sec. 4.2.2);
+        occupancy: None (S stratified samples per segment) or {partition index: Occupancy}: occupancy-guided sampling
+        (Sec. 3.2, Sec. 5.1), at most max_samples samples per step over all resident partitions (S is then unused)."""
         self.dev = torch.device(device)
         self.parts, self.models, self.resident, self.holes = parts, models, list(resident), holes
         self.parts_host = parts.cpu().tolist()
@@ -50,11 +61,18 @@ class TrainStep:
         self.part_offset, self.status = z(self.P + 1, dt=i32), z(1, dt=i32)
         self.seg_ray, self.seg_slot = z(R * k_max, dt=i32), z(R * k_max, dt=i32)
         self.ws_seg = z(max(B.dg_segments_workspace_bytes(R, self.P) // 4, 1), dt=i32)
-        n = cap * S
+        self.occ = occupancy
+        n = cap * S if occupancy is None else int(max_samples)
+        self.max_samples = n
         any_model = next(iter(models.values()))
         self.n_feat = any_model.grid.n_levels * any_model.grid.n_features
         self.u, self.delta = z(n, 3), z(n)
-        self.dir_enc = z(cap, sh_degree * sh_degree, dt=f16)
+        self.dir_enc = z(cap if occupancy is None else n, sh_degree * sh_degree, dt=f16)
+        if occupancy is not None:
+            self.first = z(cap + self.P + 1, dt=i32)       # per partition: n_seg + 1 sample offsets, at [b + p, e + p]
+            self.t, self.sample_ray = z(n), z(n, dt=i32)
+            self.ws_march = z(B.dg_march_workspace_bytes(cap) // 4, dt=i32)
+            self.samples = {}                               # partition -> (first sample, number of samples) of this step
         self.feat = z(n, self.n_feat, dt=f16)
         self.sigma, self.rgb = z(n), z(n, 3)
         self.dsigma, self.drgb = z(n), z(n, 3)
@@ -105,7 +123,9 @@ class TrainStep:
         """foreign: optional callable(self) that fills partials of non-resident partitions into Ck/Tk."""
         S = self.S
         self.segments(o, d)
-        for p in self.resident:
+        if self.occ is not None:
+            self._forward_marched(o, d)
+        for p in self.resident if self.occ is None else ():
             b, e, sl = self._slices(p)
             n_seg = e - b
             if n_seg == 0:
@@ -133,12 +153,114 @@ class TrainStep:
         with self._timed("dg_loss_seed"):
             B.dg_loss_seed(self.C, self.T, Cgt, self.R, self.lambda1, self.gC, self.gT, self.loss)
 
+    def _forward_marched(self, o, d):
+        """Per sub-model forward with occupancy-guided sampling (Sec. 3.2, Sec. 5.1): segments of different lengths,
+        one direction row per sample."""
+        self.samples = {}
+        s0 = 0
+        for p in self.resident:
+            b, e = self.offsets[p], self.offsets[p + 1]
+            n_seg = e - b
+            if n_seg == 0:
+                continue
+            m, q = self.models[p], self.occ[p]
+            first = self.first[b + p:e + p + 1]
+            ray, slot = self.seg_ray[b:e], self.seg_slot[b:e]
+            room = self.max_samples - s0
+            with self._timed("dg_march_segments"):
+                B.dg_march_segments(o, d, self.seg_t, ray, slot, n_seg, self.k_max, self.parts_host[p], q.desc, q.bits, q.dt,
+                                    q.max_steps, self.seed, room, first, self.u[s0:], self.delta[s0:], self.t[s0:],
+                                    self.sample_ray[s0:], self.status, self.ws_march)
+            N = int(first[n_seg].item())                    # the one number the host needs: how many samples were kept
+            if N > room:
+                raise B.DistGridError("sample capacity %d exceeded (%d more wanted by partition %d)" % (self.max_samples, N - room, p))
+            sl = slice(s0, s0 + N)
+            self.samples[p] = (s0, N)
+            s0 += N
+            if N:
+                with self._timed("dg_dir_encode"):
+                    B.dg_dir_encode(d, self.sample_ray[sl], N, self.deg, self.dir_enc[sl])
+                with self._timed("dg_hashgrid_encode_fwd"):
+                    B.dg_hashgrid_encode_fwd(m.grid, m.table, self.u[sl], N, self.feat[sl])
+                with self._timed("dg_mlp_fwd"):
+                    B.dg_mlp_fwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[sl], 1, N, self.sigma[sl], self.rgb[sl])
+            with self._timed("dg_composite_ragged_fwd"):        # also writes C_k = 0, T_k = 1 for segments that saw nothing
+                B.dg_composite_ragged_fwd(self.sigma[s0 - N:], self.rgb[s0 - N:], self.delta[s0 - N:], n_seg, first, ray, slot,
+                                          self.k_max, self.Ck, self.Tk)
+
+    def depth(self):
+        """Depth channel of evaluation rendering (Sec. 4.4.2) for the samples of the last forward pass with
+        occupancy-guided sampling; returns D [R]."""
+        Dk = torch.zeros(self.R, self.k_max, device=self.dev)
+        D = torch.zeros(self.R, device=self.dev)
+        for p, (s0, N) in self.samples.items():
+            b, e = self.offsets[p], self.offsets[p + 1]
+            B.dg_composite_ragged_depth(self.sigma[s0:], self.delta[s0:], self.t[s0:], e - b, self.first[b + p:e + p + 1],
+                                        self.seg_ray[b:e], self.seg_slot[b:e], self.k_max, Dk)
+        B.dg_merge_depth(Dk, self.Tk, self.seg_count, self.R, self.k_max, D)
+        return D
+
+    def _backward_marched(self):
+        for p in self.resident:
+            m = self.models[p]
+            with self._timed("zero_gradients"):
+                m.dtable.zero_()
+                m.dW.zero_()
+            if p not in self.samples or self.samples[p][1] == 0:
+                continue
+            s0, N = self.samples[p]
+            b, e = self.offsets[p], self.offsets[p + 1]
+            sl = slice(s0, s0 + N)
+            with self._timed("dg_composite_ragged_bwd"):
+                B.dg_composite_ragged_bwd(self.sigma[s0:], self.rgb[s0:], self.delta[s0:], e - b, self.first[b + p:e + p + 1],
+                                          self.seg_ray[b:e], self.seg_slot[b:e], self.k_max, self.gCk, self.gTk, self.dsigma[s0:],
+                                          self.drgb[s0:])
+            with self._timed("dg_mlp_bwd"):
+                B.dg_mlp_bwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[sl], 1, N, self.dsigma[sl], self.drgb[sl],
+                             self.loss_scale, self.dfeat[sl], m.dW, self.ws_mlp)
+            with self._timed("dg_hashgrid_encode_bwd"):
+                B.dg_hashgrid_encode_bwd(m.grid, self.u[sl], self.dfeat[sl], N, m.dtable, self.ws_enc)
+
+    # -- occupancy refresh (Sec. 5.1; Instant-NGP App. E.2) -------------------------------------
+    def refresh_occupancy(self, iteration, tries=32):
+        """Decay, candidate cells, the field's density at a random point of each, maximum, new bits -- when the
+        schedule asks for it at this iteration.  Candidates are produced in pieces that fit the sample buffers."""
+        update_now, warmup, decay, threshold = B.dg_occ_schedule(iteration)
+        if not update_now:
+            return False
+        for p in self.resident:
+            m, q = self.models[p], self.occ[p]
+            n_cells = q.desc.n_cells
+            with self._timed("dg_occ_decay"):
+                B.dg_occ_decay(q.density, decay)
+            M = n_cells if warmup else n_cells // 2
+            n_uniform = 0 if warmup else M // 2
+            piece = self.max_samples
+            for i0 in range(0, M, piece):
+                n = min(piece, M - i0)
+                cell = self.sample_ray[:n]                      # the step's sample buffers serve as scratch
+                with self._timed("dg_occ_candidates"):
+                    B.dg_occ_candidates(q.desc, q.bits, n, n_uniform, warmup, self.seed, iteration, tries, cell, self.u[:n], i0=i0)
+                with self._timed("dg_hashgrid_encode_fwd"):
+                    B.dg_hashgrid_encode_fwd(m.grid, m.table, self.u[:n], n, self.feat[:n])
+                self.dir_enc[:1].zero_()                        # the density does not depend on the direction: one zero row
+                with self._timed("dg_mlp_fwd"):
+                    B.dg_mlp_fwd(m.mlp, m.weights, self.feat[:n], self.dir_enc[:1], max(n, 1), n, self.sigma[:n], self.rgb[:n])
+                with self._timed("dg_occ_update"):
+                    B.dg_occ_update(q.density, cell, self.sigma[:n], n)
+            q.n_set.zero_()
+            with self._timed("dg_occ_bits"):
+                B.dg_occ_bits(q.density, threshold, q.bits, q.n_set)
+        return True
+
     # -- backward --------------------------------------------------------------------------
     def backward(self):
         S = self.S
         with self._timed("dg_merge_segments_bwd"):
             B.dg_merge_segments_bwd(self.Ck, self.Tk, self.seg_count, self.R, self.k_max, self.gC, self.gT, self.gCk,
                                     self.gTk)
+        if self.occ is not None:
+            return self._backward_marched()
         for p in self.resident:
             b, e, sl = self._slices(p)
             n_seg = e - b

@@ -92,9 +92,9 @@ def test_occupancy_host_side():
         B.dg_occ_desc_init(2048, [1, 1, 1])                             # 2^33 cells
     desc = B.dg_occ_desc_init(8, [1, 1, 1])
     lib = B.lib()
-    assert lib.dg_occ_candidates(C.byref(desc), None, 0, 0, 0, 0, 0, 32, None, None, None) == 0
-    assert lib.dg_occ_candidates(C.byref(desc), None, 5, 0, 1, 0, 0, 32, None, None, None) == -1       # warm-up visits all cells
-    assert lib.dg_occ_candidates(C.byref(desc), None, 5, 0, 0, 0, 0, 65, None, None, None) == -1
+    assert lib.dg_occ_candidates(C.byref(desc), None, 0, 0, 0, 0, 0, 0, 32, None, None, None) == 0
+    assert lib.dg_occ_candidates(C.byref(desc), None, 510, 5, 0, 1, 0, 0, 32, None, None, None) == -1    # warm-up: candidate i is cell i
+    assert lib.dg_occ_candidates(C.byref(desc), None, 0, 5, 0, 0, 0, 0, 65, None, None, None) == -1
     assert lib.dg_march_workspace_bytes(0) >= 4 and lib.dg_march_workspace_bytes(1 << 20) >= 4 * 513
     box = (C.c_float * 6)(0, 0, 0, 1, 1, 1)
     assert lib.dg_march_segments(None, None, None, None, None, 0, 1, box, C.byref(desc), None, 0.0, 10, 0, 0, None, None, None, None,

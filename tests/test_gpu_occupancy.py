@@ -45,6 +45,10 @@ def test_candidates_bit_exact(N, ext):
         rc, ru = oracle.occ_candidates(g_ref, bits, M, n_uniform, warmup, 77, it, tries)
         np.testing.assert_array_equal(host(cell).view(np.uint32), rc)
         np.testing.assert_array_equal(host(u), ru)
+        i0, m = M // 3, M - M // 3 - 1                                       # a piece of the same refresh
+        B.dg_occ_candidates(g, _bits_dev(bits), m, n_uniform, warmup, 77, it, tries, cell, u, i0=i0)
+        np.testing.assert_array_equal(host(cell).view(np.uint32)[:m], rc[i0:i0 + m])
+        np.testing.assert_array_equal(host(u)[:m], ru[i0:i0 + m])
 
 
 @pytest.mark.parametrize("n", [1, 63, 64, 1000, 100003])

@@ -100,6 +100,10 @@ def test_later_candidates_half_uniform_half_occupied():
     # with nothing occupied the rejection half still returns valid cells (the last draw)
     cell3, _ = oracle.occ_candidates(g, np.zeros_like(bits), 1000, 500, False, seed=4, iteration=4112)
     assert cell3.max() < g.n_cells and len(set(cell3[500:])) > 200
+    # a refresh produced in pieces is the same refresh
+    a, ua = oracle.occ_candidates(g, bits, 300, M // 2, False, seed=4, iteration=4112, i0=M // 2 - 100)
+    np.testing.assert_array_equal(a, cell[M // 2 - 100:M // 2 + 200])
+    np.testing.assert_array_equal(ua, u[M // 2 - 100:M // 2 + 200])
     # one try: the rejection half degenerates to uniform draws
     cell4, _ = oracle.occ_candidates(g, bits, 4000, 0, False, seed=4, iteration=4112, tries=1)
     assert 0.4 < occupied[cell4].mean() < 0.6
