@@ -7,6 +7,9 @@ rays that is already resident in HBM.  The workload is the Instant-NGP-scale sin
 configuration (2^18 rays x 64 samples, L=16, F=2, T=2^19).  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_ngp] [--no-cpu-baseline] [--no-optimizer]
+
+--workload c7_occ runs the same scene with occupancy-guided sampling (Sec. 3.2, Sec. 5.1) instead of 64 stratified
+samples per segment, and also times the occupancy refresh.
 """
 import argparse
 import json
@@ -69,7 +72,7 @@ def main():
     import torch
     import dg_inputs as di
     from paper_2405_04416_amd import binding as B
-    from paper_2405_04416_amd.step import SubModel, TrainStep
+    from paper_2405_04416_amd.step import Occupancy, SubModel, TrainStep
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
@@ -114,9 +117,21 @@ def main():
         weights = to_dev(di.make_mlp_weights(n_feat, m, seed=1000 * p))
         models[p] = SubModel(grid, mlp, table, weights)
     od, dd, Cd = to_dev(o), to_dev(d), to_dev(Cgt)
+    occupancy, extra = None, {}
+    if "occ" in cfg:
+        # occupancy-guided sampling: seeded stand-in densities per cell, thresholded by the library into the bit field
+        occupancy = {}
+        for p in resident:
+            ext = di.box_extent(cfg["parts"][p])
+            desc = B.dg_occ_desc_init(cfg["occ"]["res"], ext)
+            density = to_dev(di.make_cell_densities(list(desc.res), seed=1000 * p))
+            bits = torch.zeros((desc.n_cells + 31) // 32, dtype=torch.int32, device=dev)
+            occupancy[p] = Occupancy(desc, density, bits, np.float32(float(ext.max()) * np.sqrt(3.0) / 1024), cfg["occ"]["max_steps"])
+            B.dg_occ_bits(density, 0.6, bits, occupancy[p].n_set)
+        extra = dict(occupancy=occupancy, max_samples=R * 32)
     step = TrainStep(to_dev(cfg["parts"]), models, resident, R, S, k_max, m["sh_degree"], loss_scale=65536.0,
                      lambda1=1e-3, seed=0, holes=to_dev(cfg["holes"]) if "holes" in cfg else None,
-                     max_segments=R * min(k_max, 4))         # rays of these recipes average well under four segments
+                     max_segments=R * min(k_max, 4), **extra)  # rays of these recipes average well under four segments
 
     for w in range(args.warmup):
         step.seed = w
@@ -131,8 +146,25 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = 1e3 * wall / args.steps
     n_seg = sum(step.offsets[p + 1] - step.offsets[p] for p in resident)
-    n_samples = n_seg * S
+    n_samples = n_seg * S if occupancy is None else sum(n for _, n in step.samples.values())
     per_call = step.timing_summary()           # HIP events on the launch stream, inside the timed region
+
+    # the occupancy refresh (every 16th iteration, Sec. 5.1), measured apart from the metric, in both of its forms
+    refresh = None
+    if occupancy is not None:
+        cells = sum(q.desc.n_cells for q in occupancy.values())
+        refresh = {"cells": cells, "occupied_fraction": round(sum(int(q.n_set.item()) for q in occupancy.values()) / cells, 4)}
+        for name, it in (("warmup_all_cells", 16), ("half_uniform_half_occupied", 4112)):
+            saved = {p: (q.density.clone(), q.bits.clone()) for p, q in occupancy.items()}
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            step.timings = None
+            step.refresh_occupancy(it)
+            torch.cuda.synchronize()
+            refresh[name] = {"ms": round(1e3 * (time.perf_counter() - t1), 3),
+                             "candidates": sum(q.desc.n_cells // (1 if it < 4096 else 2) for q in occupancy.values())}
+            for p, q in occupancy.items():         # the random-weight field is no scene: put the stand-in grid back
+                q.density.copy_(saved[p][0]); q.bits.copy_(saved[p][1])
 
     # the optimiser sweep (Sec. 5.1: Adam), measured apart from the metric: `value` stays the forward+backward rate
     optimiser = None
@@ -195,8 +227,9 @@ def main():
         import oracle.step as ostep            # the oracle, as it stands, on the host cores of this machine
         Rc = min(args.cpu_rays, R)
         hm = ostep.make_models(dict(cfg, resident_list=resident), seed=0)
+        ho = ostep.make_occupancy(cfg, seed=0) if occupancy is not None else None     # built outside the timed call, like the tables
         t1 = time.perf_counter()
-        ostep.run_step(cfg, hm, o[:Rc], d[:Rc], Cgt[:Rc], seed=0, lambda1=1e-3, loss_scale=65536.0, resident=resident)   # (without the synthetic foreign partials)
+        ostep.run_step(cfg, hm, o[:Rc], d[:Rc], Cgt[:Rc], seed=0, lambda1=1e-3, loss_scale=65536.0, resident=resident, occ=ho)   # (without the synthetic foreign partials)
         cpu_s = time.perf_counter() - t1
         cpu = {"value": round(Rc / cpu_s, 2), "unit": "rays/s", "cores": 1, "kind": "oracle",
                "sample": "first %d rays of the same batch, full-size tables, one fwd+bwd pass, %.1f s" % (Rc, cpu_s)}
@@ -206,11 +239,14 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": args.workload, "rays": R, "samples_per_segment": S, "segments": n_seg,
+        "config": {"workload": args.workload, "rays": R,
+                   "samples_per_segment": S if occupancy is None else round(n_samples / max(n_seg, 1), 2), "segments": n_seg,
+                   "sampling": "stratified" if occupancy is None else "occupancy-guided, resolution %d" % cfg["occ"]["res"],
                    "samples": n_samples, "levels": g["L"], "features": g["F"], "log2_T": g["log2_T"],
                    "partitions_resident": len(resident), "mlp_operands": "f16, f32 accumulate"},
         "samples_per_s": round(n_samples / (ms_per_step * 1e-3), 1),
-        "roofline": roofline, "kernels": others, "ms_per_call": breakdown, "optimiser": optimiser, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": others, "ms_per_call": breakdown, "optimiser": optimiser, "occupancy_refresh": refresh,
+        "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 

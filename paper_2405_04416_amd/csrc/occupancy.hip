@@ -100,18 +100,37 @@ update_kernel(float *__restrict__ density, uint32_t n_cells, const uint32_t *__r
     if (c < n_cells && s > 0.0f) atomicMax(reinterpret_cast<unsigned int *>(density) + c, __float_as_uint(s));
 }
 
+constexpr int kBitsRounds = 16;                        // cells per thread of the bit-field pass
+
+// one workgroup thresholds kBlock * kBitsRounds consecutive cells; set bits are counted per workgroup, so the shared
+// counter takes one atomic per 4096 cells (same-address atomics serialise)
 __global__ void __launch_bounds__(kBlock)
 bits_kernel(const float *__restrict__ density, uint32_t n_cells, float threshold, uint32_t *__restrict__ bits,
             uint32_t *__restrict__ n_set)
 {
-    const uint32_t c = blockIdx.x * kBlock + threadIdx.x;               // n_cells <= 2^31: no wrap
-    const bool on = c < n_cells && density[c] > threshold;
-    const unsigned long long mask = __ballot(on);
-    if (threadIdx.x % dg::kWave == 0 && c < n_cells) {
-        const uint32_t w = c >> 5, n_words = (n_cells + 31u) >> 5;
-        bits[w] = (uint32_t)mask;
-        if (w + 1u < n_words) bits[w + 1u] = (uint32_t)(mask >> 32);
-        if (n_set && mask) atomicAdd(n_set, (uint32_t)__popcll(mask));
+    __shared__ uint32_t wave_count[kWavesPerBlock];
+    const uint32_t n_words = (n_cells + 31u) >> 5;
+    uint32_t mine = 0;
+#pragma unroll 4
+    for (int round = 0; round < kBitsRounds; ++round) {
+        // n_cells <= 2^31 and the grid covers it once: no wrap
+        const uint32_t c = (blockIdx.x * kBitsRounds + round) * kBlock + threadIdx.x;
+        const bool on = c < n_cells && density[c] > threshold;
+        const unsigned long long mask = __ballot(on);
+        if (threadIdx.x % dg::kWave == 0 && c < n_cells) {
+            const uint32_t w = c >> 5;
+            bits[w] = (uint32_t)mask;
+            if (w + 1u < n_words) bits[w + 1u] = (uint32_t)(mask >> 32);
+            mine += (uint32_t)__popcll(mask);
+        }
+    }
+    if (!n_set) return;
+    if (threadIdx.x % dg::kWave == 0) wave_count[threadIdx.x / dg::kWave] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t total = 0;
+        for (int w = 0; w < kWavesPerBlock; ++w) total += wave_count[w];
+        if (total) atomicAdd(n_set, total);
     }
 }
 
@@ -332,7 +351,8 @@ extern "C" int dg_occ_bits(const float *density, uint32_t n_cells, float thresho
 {
     if (n_cells == 0) return DG_OK;
     DG_REQUIRE(density && bits, DG_ERR_ARG, "dg_occ_bits: null pointer");
-    const uint32_t n_blocks = (uint32_t)(((uint64_t)n_cells + kBlock - 1) / kBlock);
+    const uint64_t per_block = (uint64_t)kBlock * kBitsRounds;
+    const uint32_t n_blocks = (uint32_t)(((uint64_t)n_cells + per_block - 1) / per_block);
     bits_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(density, n_cells, threshold, bits, n_set);
     return dg::launch_status("dg_occ_bits");
 }
