@@ -63,6 +63,11 @@ CONFIGS = {
         k_max=1, grid=dict(L=16, F=2, log2_T=19, n_min=16, n_max=2048), table_range=1e-4,
         occ=dict(res=512, max_steps=1024),
         mlp=dict(n_hidden_d=64, n_geo=16, sh_degree=4, n_hidden_c=64, n_layers_c=2)),
+    # Appearance features (Sec. 4.4.3): c2 with 48 further colour-net inputs, one fixed vector per image, 1000 images.
+    "c8_app": dict(
+        parts=_tile([-1, 1], [-1, 1], 0, 0.25), rays="aerial", cam_height=1.5, tilt_deg=30.0, R=1 << 18, S=64,
+        k_max=1, grid=dict(L=16, F=2, log2_T=19, n_min=16, n_max=2048), table_range=1e-4, n_images=1000,
+        mlp=dict(n_hidden_d=64, n_geo=16, sh_degree=4, n_hidden_c=64, n_layers_c=2, n_app=48)),
 }
 
 
@@ -176,8 +181,9 @@ def make_table(n_entries, F, value_range, seed=0):
 
 
 def mlp_layer_shapes(n_feat, mlp):
-    """[(out, in)] of the five (or four) weight matrices in packing order."""
-    n_dir = mlp["sh_degree"] ** 2
+    """[(out, in)] of the five (or four) weight matrices in packing order.  Appearance features (mlp["n_app"]) are
+    further inputs of the first colour layer, after the direction encoding."""
+    n_dir = mlp["sh_degree"] ** 2 + mlp.get("n_app", 0)
     shapes = [(mlp["n_hidden_d"], n_feat), (mlp["n_geo"], mlp["n_hidden_d"]),
               (mlp["n_hidden_c"], mlp["n_geo"] + n_dir)]
     if mlp["n_layers_c"] == 2:
@@ -194,6 +200,15 @@ def make_mlp_weights(n_feat, mlp, seed=0, gain=1.0):
         a = gain * math.sqrt(6.0 / (n_in + n_out))
         chunks.append(((rng.random((n_out, n_in)) * 2.0 - 1.0) * a).astype(np.float16).ravel())
     return np.concatenate(chunks)
+
+
+def make_appearance(n_images, n_app, R, seed=0):
+    """Per-image appearance vectors (fp16, N(0,1): stand-ins for the PCA-reduced Gram features of Sec. 4.4.3) and the
+    image every ray belongs to (rays are drawn uniformly over all images)."""
+    rng = np.random.default_rng([seed, 97])
+    table = rng.standard_normal((n_images, n_app)).astype(np.float16)
+    image_of_ray = rng.integers(0, n_images, R).astype(np.uint32)
+    return table, image_of_ray
 
 
 def make_targets(R, seed=0):

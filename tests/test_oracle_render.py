@@ -33,13 +33,16 @@ def _mlp_case(name, n, seed, S=4, round_f16=1, gain=1.0):
     cfg = di.config(name)
     m = cfg["mlp"]
     n_feat = cfg["grid"]["L"] * cfg["grid"]["F"]
-    n_dir = m["sh_degree"] ** 2
+    n_dir = m["sh_degree"] ** 2 + m.get("n_app", 0)       # appearance features (Sec. 4.4.3) follow the direction encoding
     desc = oracle.mlp_desc(n_feat, m["n_hidden_d"], m["n_geo"], n_dir, m["n_hidden_c"], m["n_layers_c"], 1, round_f16)
     w = di.make_mlp_weights(n_feat, m, seed=seed, gain=gain).astype(np.float64)
     rng = np.random.default_rng(seed + 100)
     feat = rng.standard_normal((n, n_feat)).astype(np.float16).astype(np.float64)
     dirs = rng.standard_normal((-(-n // S), 3)).astype(np.float32)
     dir_enc = oracle.sh(dirs, m["sh_degree"])
+    if m.get("n_app"):
+        table, image = di.make_appearance(7, m["n_app"], dirs.shape[0], seed=seed)
+        dir_enc = np.concatenate([dir_enc, table[image].astype(np.float64)], axis=1)
     return cfg, desc, w, feat, dir_enc, S
 
 
@@ -63,7 +66,7 @@ def _numpy_mlp(cfg, w, feat, dir_enc, S, half):
     return sigma, rgb
 
 
-@pytest.mark.parametrize("name", ["c1_tiny", "c2_ngp"])
+@pytest.mark.parametrize("name", ["c1_tiny", "c2_ngp", "c8_app"])
 @pytest.mark.parametrize("half", [0, 1])
 def test_mlp_fwd_against_numpy(name, half):
     cfg, desc, w, feat, dir_enc, S = _mlp_case(name, 300, seed=1, round_f16=half)
@@ -89,7 +92,37 @@ def test_mlp_output_clip():
     assert np.all(dfeat == 0) and np.all(dw == 0)
 
 
-@pytest.mark.parametrize("name", ["c1_tiny", "c2_ngp"])
+def test_appearance_inputs_with_zero_weights_change_nothing():
+    # Sec. 4.4.3: appearance features are further inputs of the colour net; with their weight columns at zero the
+    # network is the one without them, and the density never depends on them
+    cfg, desc, w, feat, dir_enc, S = _mlp_case("c8_app", 100, seed=9)
+    m = cfg["mlp"]
+    shapes = di.mlp_layer_shapes(feat.shape[1], m)
+    pos = sum(no * ni for no, ni in shapes[:2])
+    no, ni = shapes[2]
+    Wc1 = w[pos:pos + no * ni].reshape(no, ni).copy()
+    n_narrow = ni - m["n_app"]
+    sigma_full, rgb_full = oracle.mlp_fwd(desc, w, feat, dir_enc, S)
+    Wc1[:, n_narrow:] = 0.0
+    w0 = w.copy(); w0[pos:pos + no * ni] = Wc1.ravel()
+    sigma0, rgb0 = oracle.mlp_fwd(desc, w0, feat, dir_enc, S)
+    narrow = oracle.mlp_desc(desc.n_feat, desc.n_hidden_d, desc.n_geo, n_narrow - desc.n_geo, desc.n_hidden_c, desc.n_layers_c, 1, 1)
+    w_narrow = np.concatenate([w[:pos], Wc1[:, :n_narrow].ravel(), w[pos + no * ni:]])
+    sigma_n, rgb_n = oracle.mlp_fwd(narrow, w_narrow, feat, dir_enc[:, :n_narrow - desc.n_geo], S)
+    np.testing.assert_array_equal(sigma0, sigma_n)
+    np.testing.assert_array_equal(rgb0, rgb_n)
+    np.testing.assert_array_equal(sigma_full, sigma_n)
+    assert np.abs(rgb_full - rgb_n).max() > 1e-3
+    # and their weight columns receive gradient, the others' gradient is that of the narrow net when they are zero
+    gs, gr = np.zeros(100), np.ones((100, 3))
+    _, dw0 = oracle.mlp_bwd(desc, w0, feat, dir_enc, S, gs, gr)
+    _, dwn = oracle.mlp_bwd(narrow, w_narrow, feat, dir_enc[:, :n_narrow - desc.n_geo], S, gs, gr)
+    g = dw0[pos:pos + no * ni].reshape(no, ni)
+    np.testing.assert_allclose(g[:, :n_narrow].ravel(), dwn[pos:pos + no * n_narrow], rtol=1e-12, atol=1e-18)
+    assert np.abs(g[:, n_narrow:]).max() > 0
+
+
+@pytest.mark.parametrize("name", ["c1_tiny", "c2_ngp", "c8_app"])
 def test_mlp_bwd_finite_differences(name):
     cfg, desc, w, feat, dir_enc, S = _mlp_case(name, 24, seed=3, round_f16=0)
     rng = np.random.default_rng(5)
