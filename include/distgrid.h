@@ -169,6 +169,7 @@ int dg_hashgrid_corner_indices(const dg_grid_desc *desc, const float *u, uint64_
 typedef struct dg_mlp_desc {
     uint32_t n_feat, n_hidden_d, n_geo, n_dir, n_hidden_c, n_layers_c;
     uint32_t act_c;                       /* 0 ReLU, 1 sigmoid */
+    uint32_t n_app;                       /* appearance inputs of the colour net: 0, 16 or 48 (Sec. 4.4.3) */
 } dg_mlp_desc;
 size_t dg_mlp_weight_count(const dg_mlp_desc *desc);
 int dg_mlp_fwd(const dg_mlp_desc *desc, const void *weights, const void *feat,
@@ -227,6 +228,25 @@ int dg_merge_segments_bwd(const float *Ck, const float *Tk, const uint32_t *seg_
  * *loss (device scalar, "+=", may be NULL) accumulates the loss value. */
 int dg_loss_seed(const float *C, const float *T, const float *Cgt, uint32_t R,
                  float lambda1, float *gC, float *gT, float *loss, void *stream);
+
+/* The same networks with appearance features (Sec. 4.4.3: a fixed vector per image, 16 or 48 values, as additional
+ * inputs of the colour net): colour input = [geo | dir_enc row | app row], desc->n_app = 16 or 48 (0: app is ignored and
+ * may be NULL; only the 32-64-16 / 64-64-3 shape takes appearance inputs).  app [ceil(N/S), n_app] fp16 device, 16-byte
+ * aligned, row n/S serves sample n like dir_enc.  Weight packing: the five matrices as above, Wc1 [n_hidden_c, n_geo+n_dir]
+ * included, then Wapp [n_hidden_c, n_app] -- the columns of the first colour layer that multiply the appearance
+ * features, kept last so that the packing of the other matrices does not depend on n_app; dW likewise.  The appearance
+ * features get no gradient (they are fixed).  Workspace: dg_mlp_bwd_app_workspace_bytes(desc, N, S) bytes (it holds
+ * 256 bytes per ROW of samples on top of what dg_mlp_bwd needs). */
+int dg_mlp_fwd_app(const dg_mlp_desc *desc, const void *weights, const void *feat, const void *dir_enc,
+                   const void *app, uint32_t S, uint64_t N, float *sigma, float *rgb, void *stream);
+size_t dg_mlp_bwd_app_workspace_bytes(const dg_mlp_desc *desc, uint64_t N, uint32_t S);
+int dg_mlp_bwd_app(const dg_mlp_desc *desc, const void *weights, const void *feat, const void *dir_enc,
+                   const void *app, uint32_t S, uint64_t N, const float *dsigma, const float *drgb,
+                   float loss_scale, float *dfeat, float *dW, void *ws, size_t ws_bytes, void *stream);
+/* Row table for the two calls above: out[i, :] = table[image_of_ray[index[i]], :] (index NULL: i itself);
+ * table [n_images, n_app] fp16, image_of_ray [R] uint32, out [n, n_app] fp16; n_app a multiple of 8. */
+int dg_appearance_rows(const void *table, const uint32_t *image_of_ray, const uint32_t *index, uint64_t n,
+                       uint32_t n_app, void *out, void *stream);
 
 /* One Adam step (Sec. 5.1 names the optimiser; the update is Algorithm 1 of Kingma & Ba) on n fp32 values, in place:
  *   g' = g + l2 * p;  m = beta1 m + (1 - beta1) g';  v = beta2 v + (1 - beta2) g'^2;

@@ -30,7 +30,7 @@ class GridDesc(C.Structure):
 
 class MlpDesc(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in ("n_feat", "n_hidden_d", "n_geo", "n_dir", "n_hidden_c", "n_layers_c",
-                                          "act_c")]
+                                          "act_c", "n_app")]
 
 
 class OccDesc(C.Structure):
@@ -67,6 +67,12 @@ _SIGNATURES = {
     "dg_mlp_bwd_workspace_bytes": (C.c_size_t, [C.POINTER(MlpDesc), C.c_uint64]),
     "dg_mlp_bwd": (C.c_int, [C.POINTER(MlpDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p,
                              C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "dg_mlp_fwd_app": (C.c_int, [C.POINTER(MlpDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64,
+                                 C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dg_mlp_bwd_app_workspace_bytes": (C.c_size_t, [C.POINTER(MlpDesc), C.c_uint64, C.c_uint32]),
+    "dg_mlp_bwd_app": (C.c_int, [C.POINTER(MlpDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64,
+                                 C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "dg_appearance_rows": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p]),
     "dg_composite_segment_fwd": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32,
                                                               C.c_void_p, C.c_void_p, C.c_void_p]),
     "dg_composite_segment_bwd": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32]
@@ -148,8 +154,8 @@ def dg_grid_desc_init(L, F, log2_T, n_min, growth, extent):
     return desc
 
 
-def dg_mlp_desc(n_feat, n_hidden_d, n_geo, n_dir, n_hidden_c, n_layers_c, act_c=1):
-    return MlpDesc(n_feat, n_hidden_d, n_geo, n_dir, n_hidden_c, n_layers_c, act_c)
+def dg_mlp_desc(n_feat, n_hidden_d, n_geo, n_dir, n_hidden_c, n_layers_c, act_c=1, n_app=0):
+    return MlpDesc(n_feat, n_hidden_d, n_geo, n_dir, n_hidden_c, n_layers_c, act_c, n_app)
 
 
 def dg_mlp_weight_count(desc):
@@ -162,6 +168,10 @@ def dg_segments_workspace_bytes(R, P):
 
 def dg_mlp_bwd_workspace_bytes(desc, N):
     return int(lib().dg_mlp_bwd_workspace_bytes(C.byref(desc), N))
+
+
+def dg_mlp_bwd_app_workspace_bytes(desc, N, S):
+    return int(lib().dg_mlp_bwd_app_workspace_bytes(C.byref(desc), N, S))
 
 
 # ------------------------------------------------------------------ device entry points
@@ -351,3 +361,28 @@ def dg_composite_ragged_bwd(sigma, rgb, delta, n_seg, first, seg_ray, seg_slot, 
         _ptr(sigma, torch.float32), _ptr(rgb, torch.float32), _ptr(delta, torch.float32), n_seg, _ptr(first, torch.int32),
         _ptr(seg_ray, torch.int32), _ptr(seg_slot, torch.int32), k_max, _ptr(gCk, torch.float32), _ptr(gTk, torch.float32),
         _ptr(dsigma, torch.float32), _ptr(drgb, torch.float32), _stream()))
+
+
+# ------------------------------------------------------------------ appearance features as colour-net inputs
+def dg_appearance_rows(table, image_of_ray, index, n, out):
+    n_app = table.shape[-1]
+    assert out.numel() >= n * n_app and (index is None or index.numel() >= n)
+    _check(lib().dg_appearance_rows(_ptr(table, torch.float16), _ptr(image_of_ray, torch.int32), _ptr(index, torch.int32, True), n,
+                                    n_app, _ptr(out, torch.float16), _stream()))
+
+
+def dg_mlp_fwd_app(desc, weights, feat, dir_enc, app, S, N, sigma, rgb):
+    rows = -(-N // S)
+    assert dir_enc.numel() >= rows * desc.n_dir and (app is None or app.numel() >= rows * desc.n_app)
+    _check(lib().dg_mlp_fwd_app(C.byref(desc), _ptr(weights, torch.float16), _ptr(feat, torch.float16), _ptr(dir_enc, torch.float16),
+                                _ptr(app, torch.float16, True), S, N, _ptr(sigma, torch.float32), _ptr(rgb, torch.float32), _stream()))
+
+
+def dg_mlp_bwd_app(desc, weights, feat, dir_enc, app, S, N, dsigma, drgb, loss_scale, dfeat, dW, ws):
+    rows = -(-N // S)
+    assert dir_enc.numel() >= rows * desc.n_dir and (app is None or app.numel() >= rows * desc.n_app)
+    assert dW.numel() >= dg_mlp_weight_count(desc)
+    _check(lib().dg_mlp_bwd_app(C.byref(desc), _ptr(weights, torch.float16), _ptr(feat, torch.float16), _ptr(dir_enc, torch.float16),
+                                _ptr(app, torch.float16, True), S, N, _ptr(dsigma, torch.float32), _ptr(drgb, torch.float32),
+                                loss_scale, _ptr(dfeat, torch.float32), _ptr(dW, torch.float32), _ptr(ws),
+                                ws.numel() * ws.element_size(), _stream()))

@@ -38,13 +38,14 @@ size_t encode_bwd_binned_workspace_bytes(const dg_grid_desc *d, uint64_t N);
 int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat, uint64_t N, float *dtable, void *ws,
                       size_t ws_bytes, hipStream_t st);
 
-// matrix-core path of the 32-64-16 / 32-64-64-3 field MLPs (mlp_mfma.hip)
-size_t mlp_mfma_workspace_bytes(uint64_t N);
-void mlp_mfma_fwd(const void *weights, const void *feat, const void *dir_enc, uint32_t S, uint64_t N, uint32_t act_c,
-                  float *sigma, float *rgb, hipStream_t st);
-void mlp_mfma_bwd(const void *weights, const void *feat, const void *dir_enc, uint32_t S, uint64_t N, uint32_t act_c,
-                  const float *dsigma, const float *drgb, float loss_scale, float *dfeat, float *dW, void *ws,
-                  hipStream_t st);
+// matrix-core path of the 32-64-16 / (32 + n_app)-64-64-3 field MLPs (mlp_mfma.hip); n_app = 0, 16 or 48
+size_t mlp_mfma_workspace_bytes(uint64_t N, uint32_t n_app, uint32_t S);
+size_t mlp_mfma_weight_count(uint32_t n_app);
+void mlp_mfma_fwd(const void *weights, const void *feat, const void *dir_enc, const void *app, uint32_t n_app, uint32_t S,
+                  uint64_t N, uint32_t act_c, float *sigma, float *rgb, hipStream_t st);
+void mlp_mfma_bwd(const void *weights, const void *feat, const void *dir_enc, const void *app, uint32_t n_app, uint32_t S,
+                  uint64_t N, uint32_t act_c, const float *dsigma, const float *drgb, float loss_scale, float *dfeat, float *dW,
+                  void *ws, hipStream_t st);
 
 }  // namespace dg
 

@@ -66,5 +66,6 @@ extern "C" size_t dg_mlp_weight_count(const dg_mlp_desc *m)
     size_t c = (size_t)m->n_hidden_d * m->n_feat + (size_t)m->n_geo * m->n_hidden_d +
                (size_t)m->n_hidden_c * (m->n_geo + m->n_dir) + 3u * (size_t)m->n_hidden_c;
     if (m->n_layers_c == 2) c += (size_t)m->n_hidden_c * m->n_hidden_c;
+    c += (size_t)m->n_hidden_c * m->n_app;      // the appearance columns of the first colour layer, packed last
     return c;
 }

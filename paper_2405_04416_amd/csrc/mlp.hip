@@ -227,10 +227,14 @@ int which_net(const dg_mlp_desc *m, const char *who)
 {
     DG_REQUIRE(m, DG_ERR_ARG, "%s: null descriptor", who);
     DG_REQUIRE(m->act_c <= 1, DG_ERR_ARG, "%s: act_c must be 0 or 1", who);
-    if (m->n_feat == 32 && m->n_hidden_d == 64 && m->n_geo == 16 && m->n_dir == 16 && m->n_hidden_c == 64 && m->n_layers_c == 2) return 1;
-    if (m->n_feat == 8 && m->n_hidden_d == 32 && m->n_geo == 16 && m->n_dir == 4 && m->n_hidden_c == 32 && m->n_layers_c == 1) return 2;
-    return dg::fail(DG_ERR_UNSUPPORTED, "%s: unsupported MLP shape (%u,%u,%u,%u,%u,%u)", who, m->n_feat, m->n_hidden_d,
-                    m->n_geo, m->n_dir, m->n_hidden_c, m->n_layers_c);
+    if (m->n_feat == 32 && m->n_hidden_d == 64 && m->n_geo == 16 && m->n_dir == 16 && m->n_hidden_c == 64 && m->n_layers_c == 2 &&
+        (m->n_app == 0 || m->n_app == 16 || m->n_app == 48))
+        return 1;
+    if (m->n_feat == 8 && m->n_hidden_d == 32 && m->n_geo == 16 && m->n_dir == 4 && m->n_hidden_c == 32 && m->n_layers_c == 1 &&
+        m->n_app == 0)
+        return 2;
+    return dg::fail(DG_ERR_UNSUPPORTED, "%s: unsupported MLP shape (%u,%u,%u,%u,%u,%u) with %u appearance inputs", who, m->n_feat,
+                    m->n_hidden_d, m->n_geo, m->n_dir, m->n_hidden_c, m->n_layers_c, m->n_app);
 }
 
 }  // namespace
@@ -238,17 +242,25 @@ int which_net(const dg_mlp_desc *m, const char *who)
 extern "C" int dg_mlp_fwd(const dg_mlp_desc *desc, const void *weights, const void *feat, const void *dir_enc,
                           uint32_t S, uint64_t N, float *sigma, float *rgb, void *stream)
 {
+    DG_REQUIRE(!desc || desc->n_app == 0, DG_ERR_ARG, "dg_mlp_fwd: a network with appearance inputs needs dg_mlp_fwd_app");
+    return dg_mlp_fwd_app(desc, weights, feat, dir_enc, nullptr, S, N, sigma, rgb, stream);
+}
+
+extern "C" int dg_mlp_fwd_app(const dg_mlp_desc *desc, const void *weights, const void *feat, const void *dir_enc,
+                              const void *app, uint32_t S, uint64_t N, float *sigma, float *rgb, void *stream)
+{
     const int net = which_net(desc, "dg_mlp_fwd");
     if (net < 0) return net;
     DG_REQUIRE(S >= 1, DG_ERR_ARG, "dg_mlp_fwd: S must be >= 1");
     if (N == 0) return DG_OK;
     DG_REQUIRE(weights && feat && dir_enc && sigma && rgb, DG_ERR_ARG, "dg_mlp_fwd: null pointer");
+    DG_REQUIRE(desc->n_app == 0 || (app && dg::aligned(app, 16)), DG_ERR_ARG, "dg_mlp_fwd: appearance rows missing or not 16-byte aligned");
     const uint64_t n_blocks = (N + kFwdBlock - 1) / kFwdBlock;
     DG_REQUIRE(n_blocks <= 0x7fffffffull, DG_ERR_UNSUPPORTED, "dg_mlp_fwd: N too large");
     hipStream_t st = (hipStream_t)stream;
     if (net == 1) {
         DG_REQUIRE(dg::aligned(feat, 4) && dg::aligned(dir_enc, 16), DG_ERR_ARG, "dg_mlp_fwd: feat must be 4-byte, dir_enc 16-byte aligned");
-        dg::mlp_mfma_fwd(weights, feat, dir_enc, S, N, desc->act_c, sigma, rgb, st);
+        dg::mlp_mfma_fwd(weights, feat, dir_enc, app, desc->n_app, S, N, desc->act_c, sigma, rgb, st);
     } else
         mlp_fwd_kernel<NetTiny><<<(uint32_t)n_blocks, kFwdBlock, 0, st>>>((const __half *)weights, (const __half *)feat,
                                                                            (const __half *)dir_enc, S, N, desc->act_c, sigma, rgb);
@@ -257,24 +269,38 @@ extern "C" int dg_mlp_fwd(const dg_mlp_desc *desc, const void *weights, const vo
 
 extern "C" size_t dg_mlp_bwd_workspace_bytes(const dg_mlp_desc *desc, uint64_t N)
 {
-    if (!desc) return 0;
+    return dg_mlp_bwd_app_workspace_bytes(desc, N, 1);
+}
+
+extern "C" size_t dg_mlp_bwd_app_workspace_bytes(const dg_mlp_desc *desc, uint64_t N, uint32_t S)
+{
+    if (!desc || S == 0) return 0;
     const size_t scalar = (size_t)kBwdGrid * dg_mlp_weight_count(desc) * sizeof(float);
     const bool ngp = desc->n_feat == 32 && desc->n_hidden_d == 64 && desc->n_geo == 16 && desc->n_dir == 16 &&
                      desc->n_hidden_c == 64 && desc->n_layers_c == 2;
-    return ngp ? dg::mlp_mfma_workspace_bytes(N) : scalar;
+    return ngp ? dg::mlp_mfma_workspace_bytes(N, desc->n_app, S) : scalar;
 }
 
 extern "C" int dg_mlp_bwd(const dg_mlp_desc *desc, const void *weights, const void *feat, const void *dir_enc,
                           uint32_t S, uint64_t N, const float *dsigma, const float *drgb, float loss_scale,
                           float *dfeat, float *dW, void *ws, size_t ws_bytes, void *stream)
 {
+    DG_REQUIRE(!desc || desc->n_app == 0, DG_ERR_ARG, "dg_mlp_bwd: a network with appearance inputs needs dg_mlp_bwd_app");
+    return dg_mlp_bwd_app(desc, weights, feat, dir_enc, nullptr, S, N, dsigma, drgb, loss_scale, dfeat, dW, ws, ws_bytes, stream);
+}
+
+extern "C" int dg_mlp_bwd_app(const dg_mlp_desc *desc, const void *weights, const void *feat, const void *dir_enc,
+                              const void *app, uint32_t S, uint64_t N, const float *dsigma, const float *drgb,
+                              float loss_scale, float *dfeat, float *dW, void *ws, size_t ws_bytes, void *stream)
+{
     const int net = which_net(desc, "dg_mlp_bwd");
     if (net < 0) return net;
     DG_REQUIRE(S >= 1 && loss_scale > 0.0f, DG_ERR_ARG, "dg_mlp_bwd: S >= 1 and loss_scale > 0 required");
     if (N == 0) return DG_OK;
     DG_REQUIRE(weights && feat && dir_enc && dsigma && drgb && dfeat && dW, DG_ERR_ARG, "dg_mlp_bwd: null pointer");
-    DG_REQUIRE(ws && ws_bytes >= dg_mlp_bwd_workspace_bytes(desc, N), DG_ERR_WORKSPACE, "dg_mlp_bwd: workspace %zu < %zu bytes",
-               ws_bytes, dg_mlp_bwd_workspace_bytes(desc, N));
+    DG_REQUIRE(desc->n_app == 0 || (app && dg::aligned(app, 16)), DG_ERR_ARG, "dg_mlp_bwd: appearance rows missing or not 16-byte aligned");
+    DG_REQUIRE(ws && ws_bytes >= dg_mlp_bwd_app_workspace_bytes(desc, N, S), DG_ERR_WORKSPACE, "dg_mlp_bwd: workspace %zu < %zu bytes",
+               ws_bytes, dg_mlp_bwd_app_workspace_bytes(desc, N, S));
     DG_REQUIRE(dg::aligned(ws, 256), DG_ERR_ARG, "dg_mlp_bwd: workspace must be 256-byte aligned");
     const uint64_t n_tiles = (N + kBwdBlock - 1) / kBwdBlock;
     const uint32_t grid = (uint32_t)(n_tiles < kBwdGrid ? n_tiles : kBwdGrid);
@@ -283,7 +309,7 @@ extern "C" int dg_mlp_bwd(const dg_mlp_desc *desc, const void *weights, const vo
     if (net == 1) {
         DG_REQUIRE(dg::aligned(feat, 4) && dg::aligned(dir_enc, 16) && dg::aligned(dfeat, 8), DG_ERR_ARG,
                    "dg_mlp_bwd: feat must be 4-byte, dfeat 8-byte, dir_enc 16-byte aligned");
-        dg::mlp_mfma_bwd(weights, feat, dir_enc, S, N, desc->act_c, dsigma, drgb, loss_scale, dfeat, dW, ws, st);
+        dg::mlp_mfma_bwd(weights, feat, dir_enc, app, desc->n_app, S, N, desc->act_c, dsigma, drgb, loss_scale, dfeat, dW, ws, st);
         return dg::launch_status("dg_mlp_bwd");
     }
     mlp_bwd_kernel<NetTiny><<<grid, kBwdBlock, 0, st>>>((const __half *)weights, (const __half *)feat, (const __half *)dir_enc,

@@ -17,6 +17,13 @@
 // a 0/1 selection matrix on the matrix cores transposes a tile exactly (fp16 values times one,
 // summed with zeros).  Every wavefront accumulates its share of dW in registers over all its tiles,
 // writes it to the workspace once, and a second kernel folds the shares in a fixed order.
+//
+// Appearance features (Sec. 4.4.3: a fixed per-image vector of 16 or 48 values as extra colour-net inputs) widen the
+// first colour layer to 48 or 80 inputs.  Forward: NA / 16 more k-steps from a second row table.  Backward: the
+// features are constant along a row of samples, so the gradient of their weight columns is
+// sum_rows (sum of delta over the row's samples) x (row's features): the per-row delta sums come from one more
+// matrix-core product of the transposed delta tile with a 0/1 sample-to-row matrix and are added into a [rows, 64]
+// buffer; a small kernel contracts that buffer with the feature rows.  No accumulator registers are added.
 #include "dg_internal.h"
 
 namespace dg_mlp_mfma {
@@ -137,11 +144,13 @@ __device__ __forceinline__ h8 pack_half(const f16v &c, int p)
 }
 
 struct Tile {
-    h8 x0[2], h1[4], xc[2], c1[4], c2[4];
+    h8 x0[2], h1[4], xc[2], xa[3], c1[4], c2[4];      // xa: appearance inputs (unused without them)
     float geo0, sigma, raw[3], rgb[3];     // meaningful on lanes with h == 0
 };
 
-__device__ __forceinline__ void forward_tile(const __half *lds, int lane, uint32_t act_c, Tile &t)
+// NA: appearance inputs (0, 16 or 48); their weight images start at chunk c_app
+template <int NA>
+__device__ __forceinline__ void forward_tile(const __half *lds, int lane, uint32_t act_c, Tile &t, int c_app = 0)
 {
     f16v acc[2];
     // density layer 1: 32 -> 64, ReLU
@@ -166,6 +175,8 @@ __device__ __forceinline__ void forward_tile(const __half *lds, int lane, uint32
         acc[mt] = zero16();
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) acc[mt] = mma(image(lds, cC1 + mt * 2 + ks, lane), t.xc[ks], acc[mt]);
+#pragma unroll
+        for (int ks = 0; ks < NA / 16; ++ks) acc[mt] = mma(image(lds, c_app + mt * (NA / 16) + ks, lane), t.xa[ks], acc[mt]);
     }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) t.c1[ks] = act_c ? pack_half<2>(acc[ks >> 1], ks & 1) : pack_half<1>(acc[ks >> 1], ks & 1);
@@ -188,8 +199,9 @@ __device__ __forceinline__ void forward_tile(const __half *lds, int lane, uint32
 
 // features arrive as level-major planes [16][n_samples] of half2; slot j of k-step ks on lane half h
 // is feature 16 ks + 8 h + j, i.e. component j % 2 of level 8 ks + 4 h + j / 2
-__device__ __forceinline__ void load_inputs(const __half *feat, const __half *dir_enc, uint32_t S, uint64_t n_samples,
-                                            uint64_t n, bool valid, int h, Tile &t)
+template <int NA>
+__device__ __forceinline__ void load_inputs(const __half *feat, const __half *dir_enc, const __half *app, uint32_t S,
+                                            uint64_t n_samples, uint64_t n, bool valid, int h, Tile &t)
 {
     const h8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     if (valid) {
@@ -203,17 +215,24 @@ __device__ __forceinline__ void load_inputs(const __half *feat, const __half *di
             t.x0[ks] = __builtin_bit_cast(h8, bits);
         }
         t.xc[1] = reinterpret_cast<const h8 *>(dir_enc + (n / S) * ND)[h];
+#pragma unroll
+        for (int ks = 0; ks < NA / 16; ++ks) t.xa[ks] = reinterpret_cast<const h8 *>(app + (n / S) * NA)[2 * ks + h];
     } else {
         t.x0[0] = zero; t.x0[1] = zero; t.xc[1] = zero;
+#pragma unroll
+        for (int ks = 0; ks < NA / 16; ++ks) t.xa[ks] = zero;
     }
 }
 
+template <int NA>
 __global__ void __launch_bounds__(kBlock, 4)
 fwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, const __half *__restrict__ dir_enc,
-           uint32_t S, uint64_t n_samples, uint32_t act_c, float *__restrict__ sigma, float *__restrict__ rgb)
+           const __half *__restrict__ app, uint32_t S, uint64_t n_samples, uint32_t act_c, float *__restrict__ sigma,
+           float *__restrict__ rgb)
 {
-    __shared__ __attribute__((aligned(16))) __half lds[kFwdChunks * 512];
+    __shared__ __attribute__((aligned(16))) __half lds[(kFwdChunks + 2 * (NA / 16)) * 512];
     build_forward_images(lds, weights);
+    if (NA > 0) build_image(lds + kFwdChunks * 512, weights + kTotal, HC, NA, HC, NA, 2, NA / 16, 1, false);
     __syncthreads();
     const int lane = threadIdx.x & 63, h = lane >> 5;
     const uint64_t n_tiles = (n_samples + 31) / 32;
@@ -223,8 +242,8 @@ fwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, 
         const uint64_t n = tile * 32 + (lane & 31);
         const bool valid = n < n_samples;
         Tile t;
-        load_inputs(feat, dir_enc, S, n_samples, n, valid, h, t);
-        forward_tile(lds, opaque(lane), act_c, t);
+        load_inputs<NA>(feat, dir_enc, app, S, n_samples, n, valid, h, t);
+        forward_tile<NA>(lds, opaque(lane), act_c, t, kFwdChunks);
         if (valid && h == 0) {
             sigma[n] = t.sigma;
             rgb[3 * n] = t.rgb[0]; rgb[3 * n + 1] = t.rgb[1]; rgb[3 * n + 2] = t.rgb[2];
@@ -285,15 +304,18 @@ __device__ __forceinline__ void store_share(float *dst, int n_in, int rows_real,
 //                already scaled and rounded to fp16, in operand order) in the workspace;
 //   density_bwd: recomputes the density hidden layer, back-propagates it from delta_geo, accumulates
 //                dWd1..2 and writes the feature gradient planes.
+template <int NA>
 __global__ void __launch_bounds__(kBlock, 2)
 colour_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, const __half *__restrict__ dir_enc,
-                  uint32_t S, uint64_t n_samples, uint32_t act_c, const float *__restrict__ dsigma,
-                  const float *__restrict__ drgb, float loss_scale, h8 *__restrict__ dgeo, float *__restrict__ shares)
+                  const __half *__restrict__ app, uint32_t S, uint64_t n_samples, uint32_t act_c,
+                  const float *__restrict__ dsigma, const float *__restrict__ drgb, float loss_scale, h8 *__restrict__ dgeo,
+                  float *__restrict__ shares, float *__restrict__ row_delta)
 {
-    __shared__ __attribute__((aligned(16))) __half lds[kAllChunks * 512];
+    __shared__ __attribute__((aligned(16))) __half lds[(kAllChunks + 2 * (NA / 16)) * 512];
     __shared__ float acc3[kWavesPerBlock * 2 * 3 * 32];
     build_forward_images(lds, weights);
     build_backward_images(lds, weights);
+    if (NA > 0) build_image(lds + kAllChunks * 512, weights + kTotal, HC, NA, HC, NA, 2, NA / 16, 1, false);
     __syncthreads();
     const int lane_fixed = threadIdx.x & 63, h = lane_fixed >> 5;
     const uint64_t n_tiles = (n_samples + 31) / 32;
@@ -318,13 +340,13 @@ colour_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__
         const bool valid = n < n_samples;
         const int lane = opaque(lane_fixed);
         Tile t;
-        load_inputs(feat, dir_enc, S, n_samples, n, valid, h, t);
+        load_inputs<NA>(feat, dir_enc, app, S, n_samples, n, valid, h, t);
         float ds = 0.0f, dc[3] = {0.0f, 0.0f, 0.0f};
         if (valid && h == 0) {                 // issued before the forward so the latency hides behind it
             ds = dsigma[n];
             dc[0] = drgb[3 * n]; dc[1] = drgb[3 * n + 1]; dc[2] = drgb[3 * n + 2];
         }
-        forward_tile(lds, lane, act_c, t);
+        forward_tile<NA>(lds, lane, act_c, t, kAllChunks);
         const h8 selT0 = image(lds, cSelT, lane), selT1 = image(lds, cSelT + 1, lane);
 
         // ---- output layer of the colour net
@@ -384,6 +406,30 @@ colour_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__
         for (int ot = 0; ot < 2; ++ot)
 #pragma unroll
             for (int p = 0; p < 2; ++p) gWc1[ot] = mma(td[ot][p], ta[0][p], gWc1[ot]);
+        if (NA > 0) {
+            // per-row sums of delta for the appearance columns: delta^T (features x samples) times the 0/1 matrix
+            // "sample s lies in the tile's local row c"; column c of the result is the sum over that row's samples
+            const uint64_t n0 = tile * 32, row0 = n0 / S;
+            const uint32_t rem0 = (uint32_t)(n0 % S), c = lane_fixed & 31;
+            h8 in_row[2];
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)      // slot j of k-step p holds sample feat_tiled(p, h, j) of the tile, as in td
+                    in_row[p][j] = (_Float16)(((rem0 + (uint32_t)feat_tiled(p, h, j)) / S == c) ? 1.0f : 0.0f);
+            const uint64_t last = (n_samples - 1 - n0 < 31 ? n_samples - 1 - n0 : 31);
+            const uint32_t n_local = (uint32_t)((rem0 + last) / S) + 1u;          // rows that have samples in this tile
+#pragma unroll
+            for (int ot = 0; ot < 2; ++ot) {
+                f16v sums = mma(td[ot][0], in_row[0], zero16());
+                sums = mma(td[ot][1], in_row[1], sums);
+                if (c < n_local) {
+                    float *dst = row_delta + (row0 + c) * HC + 32 * ot + 4 * h;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) unsafeAtomicAdd(dst + 8 * (r >> 2) + (r & 3), sums[r]);
+                }
+            }
+        }
         f16v gx = zero16();
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) gx = mma(image(lds, cC1T + ks, lane), dl[ks], gx);
@@ -442,7 +488,7 @@ density_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict_
         const uint64_t n = tile * 32 + (lane & 31);
         const bool valid = n < n_samples;
         Tile t;
-        load_inputs(feat, nullptr, 1, n_samples, n, false, h, t);      // zeroes
+        load_inputs<0>(feat, nullptr, nullptr, 1, n_samples, n, false, h, t);      // zeroes
         if (valid) {
             typedef uint32_t u4 __attribute__((ext_vector_type(4)));
             const uint32_t *planes = reinterpret_cast<const uint32_t *>(feat);
@@ -543,6 +589,34 @@ fold_shares_kernel(const float *__restrict__ density_shares, uint32_t n_d, const
     }
 }
 
+// dW[kTotal + o * NA + a] += inv_scale * sum_rows row_delta[row][o] * app[row][a]: a workgroup walks rows with a grid
+// stride, thread (o, quarter q) keeps NA / 4 sums, one atomic per sum and workgroup at the end
+template <int NA>
+__global__ void __launch_bounds__(kBlock)
+appearance_wgrad_kernel(const float *__restrict__ row_delta, const __half *__restrict__ app, uint64_t n_rows, float inv_scale,
+                        float *__restrict__ dW)
+{
+    constexpr int kPer = NA / 4;
+    const int o = threadIdx.x & 63, q = threadIdx.x >> 6;
+    float acc[kPer];
+#pragma unroll
+    for (int a = 0; a < kPer; ++a) acc[a] = 0.0f;
+    for (uint64_t row = blockIdx.x; row < n_rows; row += gridDim.x) {
+        const float d = row_delta[row * HC + o];
+        const __half *x = app + row * NA + q * kPer;
+#pragma unroll
+        for (int a = 0; a < kPer; ++a) acc[a] = __builtin_fmaf(d, __half2float(x[a]), acc[a]);
+    }
+#pragma unroll
+    for (int a = 0; a < kPer; ++a) unsafeAtomicAdd(dW + kTotal + o * NA + q * kPer + a, acc[a] * inv_scale);
+}
+
+__global__ void __launch_bounds__(kBlock)
+zero_kernel(float *__restrict__ p, uint64_t n)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kBlock) p[i] = 0.0f;
+}
+
 constexpr uint32_t kGridColour = 512;      // persistent workgroups: two per compute unit of MI355X
 constexpr uint32_t kGridDensity = 512;     // the lighter kernel fits two workgroups per compute unit
 
@@ -552,26 +626,32 @@ inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
 namespace dg {
 
-size_t mlp_mfma_workspace_bytes(uint64_t N)
+size_t mlp_mfma_workspace_bytes(uint64_t N, uint32_t n_app, uint32_t S)
 {
     using namespace dg_mlp_mfma;
+    const uint64_t n_rows = n_app ? (N + S - 1) / S : 0;
     return align256((size_t)kGridDensity * kWavesPerBlock * oWc1 * sizeof(float)) +
-           align256((size_t)kGridColour * kWavesPerBlock * (kTotal - oWc1) * sizeof(float)) + align256((size_t)N * 32);
+           align256((size_t)kGridColour * kWavesPerBlock * (kTotal - oWc1) * sizeof(float)) + align256((size_t)N * 32) +
+           align256((size_t)n_rows * HC * sizeof(float));
 }
 
-void mlp_mfma_fwd(const void *weights, const void *feat, const void *dir_enc, uint32_t S, uint64_t N, uint32_t act_c,
-                  float *sigma, float *rgb, hipStream_t st)
+size_t mlp_mfma_weight_count(uint32_t n_app) { return (size_t)dg_mlp_mfma::kTotal + (size_t)dg_mlp_mfma::HC * n_app; }
+
+void mlp_mfma_fwd(const void *weights, const void *feat, const void *dir_enc, const void *app, uint32_t n_app, uint32_t S,
+                  uint64_t N, uint32_t act_c, float *sigma, float *rgb, hipStream_t st)
 {
     using namespace dg_mlp_mfma;
     const uint64_t tiles = (N + 31) / 32, blocks_needed = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
     const uint32_t grid = (uint32_t)(blocks_needed < 2048 ? blocks_needed : 2048);
-    fwd_kernel<<<grid, kBlock, 0, st>>>((const __half *)weights, (const __half *)feat, (const __half *)dir_enc, S, N, act_c,
-                                        sigma, rgb);
+    const __half *w = (const __half *)weights, *f = (const __half *)feat, *dr = (const __half *)dir_enc, *ap = (const __half *)app;
+    if (n_app == 0) fwd_kernel<0><<<grid, kBlock, 0, st>>>(w, f, dr, ap, S, N, act_c, sigma, rgb);
+    else if (n_app == 16) fwd_kernel<16><<<grid, kBlock, 0, st>>>(w, f, dr, ap, S, N, act_c, sigma, rgb);
+    else fwd_kernel<48><<<grid, kBlock, 0, st>>>(w, f, dr, ap, S, N, act_c, sigma, rgb);
 }
 
-void mlp_mfma_bwd(const void *weights, const void *feat, const void *dir_enc, uint32_t S, uint64_t N, uint32_t act_c,
-                  const float *dsigma, const float *drgb, float loss_scale, float *dfeat, float *dW, void *ws,
-                  hipStream_t st)
+void mlp_mfma_bwd(const void *weights, const void *feat, const void *dir_enc, const void *app, uint32_t n_app, uint32_t S,
+                  uint64_t N, uint32_t act_c, const float *dsigma, const float *drgb, float loss_scale, float *dfeat, float *dW,
+                  void *ws, hipStream_t st)
 {
     using namespace dg_mlp_mfma;
     const uint64_t tiles = (N + 31) / 32, blocks_needed = (tiles + kWavesPerBlock - 1) / kWavesPerBlock;
@@ -582,12 +662,27 @@ void mlp_mfma_bwd(const void *weights, const void *feat, const void *dir_enc, ui
     float *colour_shares = reinterpret_cast<float *>(base + align256((size_t)kGridDensity * kWavesPerBlock * oWc1 * sizeof(float)));
     h8 *dgeo = reinterpret_cast<h8 *>(reinterpret_cast<char *>(colour_shares) +
                                       align256((size_t)kGridColour * kWavesPerBlock * (kTotal - oWc1) * sizeof(float)));
-    colour_bwd_kernel<<<grid_c, kBlock, 0, st>>>((const __half *)weights, (const __half *)feat, (const __half *)dir_enc, S, N,
-                                                 act_c, dsigma, drgb, loss_scale, dgeo, colour_shares);
-    density_bwd_kernel<<<grid_d, kBlock, 0, st>>>((const __half *)weights, (const __half *)feat, N, dgeo, loss_scale, dfeat,
-                                                  density_shares);
+    float *row_delta = reinterpret_cast<float *>(reinterpret_cast<char *>(dgeo) + align256((size_t)N * 32));
+    const uint64_t n_rows = n_app ? (N + S - 1) / S : 0;
+    const __half *w = (const __half *)weights, *f = (const __half *)feat, *dr = (const __half *)dir_enc, *ap = (const __half *)app;
+    if (n_app) {
+        const uint64_t n = n_rows * HC, want = (n + kBlock - 1) / kBlock;
+        zero_kernel<<<(uint32_t)(want < 4096 ? want : 4096), kBlock, 0, st>>>(row_delta, n);
+    }
+    if (n_app == 0)
+        colour_bwd_kernel<0><<<grid_c, kBlock, 0, st>>>(w, f, dr, ap, S, N, act_c, dsigma, drgb, loss_scale, dgeo, colour_shares, row_delta);
+    else if (n_app == 16)
+        colour_bwd_kernel<16><<<grid_c, kBlock, 0, st>>>(w, f, dr, ap, S, N, act_c, dsigma, drgb, loss_scale, dgeo, colour_shares, row_delta);
+    else
+        colour_bwd_kernel<48><<<grid_c, kBlock, 0, st>>>(w, f, dr, ap, S, N, act_c, dsigma, drgb, loss_scale, dgeo, colour_shares, row_delta);
+    density_bwd_kernel<<<grid_d, kBlock, 0, st>>>(w, f, N, dgeo, loss_scale, dfeat, density_shares);
     fold_shares_kernel<<<(kTotal + kFoldElems - 1) / kFoldElems, kFoldElems * kFoldGroups, 0, st>>>(
         density_shares, grid_d * kWavesPerBlock, colour_shares, grid_c * kWavesPerBlock, 1.0f / loss_scale, dW);
+    if (n_app) {
+        const uint32_t grid_a = (uint32_t)(n_rows < 1024 ? n_rows : 1024);
+        if (n_app == 16) appearance_wgrad_kernel<16><<<grid_a, kBlock, 0, st>>>(row_delta, ap, n_rows, 1.0f / loss_scale, dW);
+        else appearance_wgrad_kernel<48><<<grid_a, kBlock, 0, st>>>(row_delta, ap, n_rows, 1.0f / loss_scale, dW);
+    }
 }
 
 }  // namespace dg

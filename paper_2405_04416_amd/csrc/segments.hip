@@ -245,6 +245,19 @@ dir_encode_kernel(const float *__restrict__ d, const uint32_t *__restrict__ inde
     for (uint32_t k = 0; k < nd; ++k) out[i * nd + k] = __float2half_rn(v[k]);
 }
 
+// appearance rows (Sec. 4.4.3): one 16-byte piece of a row per thread
+__global__ void __launch_bounds__(kBlock)
+appearance_rows_kernel(const uint4 *__restrict__ table, const uint32_t *__restrict__ image_of_ray, const uint32_t *__restrict__ index,
+                       uint64_t n, uint32_t pieces, uint4 *__restrict__ out)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n * pieces) return;
+    const uint64_t row = i / pieces;
+    const uint32_t piece = (uint32_t)(i % pieces);
+    const size_t ray = index ? index[row] : row;
+    out[i] = table[(size_t)image_of_ray[ray] * pieces + piece];
+}
+
 }  // namespace
 
 extern "C" size_t dg_segments_workspace_bytes(uint32_t R, uint32_t P)
@@ -316,4 +329,19 @@ extern "C" int dg_dir_encode(const float *d, const uint32_t *index, uint64_t n, 
     DG_REQUIRE(n_blocks <= 0x7fffffffull, DG_ERR_UNSUPPORTED, "dg_dir_encode: too many rows");
     dir_encode_kernel<<<(uint32_t)n_blocks, kBlock, 0, (hipStream_t)stream>>>(d, index, n, degree, (__half *)out);
     return dg::launch_status("dg_dir_encode");
+}
+
+extern "C" int dg_appearance_rows(const void *table, const uint32_t *image_of_ray, const uint32_t *index, uint64_t n,
+                                  uint32_t n_app, void *out, void *stream)
+{
+    DG_REQUIRE(n_app >= 8 && n_app % 8 == 0, DG_ERR_ARG, "dg_appearance_rows: n_app=%u is not a positive multiple of 8", n_app);
+    if (n == 0) return DG_OK;
+    DG_REQUIRE(table && image_of_ray && out, DG_ERR_ARG, "dg_appearance_rows: null pointer");
+    DG_REQUIRE(dg::aligned(table, 16) && dg::aligned(out, 16), DG_ERR_ARG, "dg_appearance_rows: table and out must be 16-byte aligned");
+    const uint32_t pieces = n_app / 8;
+    const uint64_t n_blocks = (n * pieces + kBlock - 1) / kBlock;
+    DG_REQUIRE(n_blocks <= 0x7fffffffull, DG_ERR_UNSUPPORTED, "dg_appearance_rows: too many rows");
+    appearance_rows_kernel<<<(uint32_t)n_blocks, kBlock, 0, (hipStream_t)stream>>>((const uint4 *)table, image_of_ray, index, n, pieces,
+                                                                                   (uint4 *)out);
+    return dg::launch_status("dg_appearance_rows");
 }

@@ -42,6 +42,19 @@ def from_planes(t, n, width):
     return np.ascontiguousarray(a.transpose(1, 0, 2)).reshape(n, width)
 
 
+def split_appearance_weights(w, n_feat, mlp):
+    """Packed weights (or their gradient) with one wide first colour layer [n_hidden_c, n_geo + n_dir + n_app] (the
+    oracle's view) -> the library's packing: the narrow matrices first, the appearance columns Wapp [n_hidden_c, n_app] last."""
+    n_app = mlp.get("n_app", 0)
+    if not n_app:
+        return w
+    shapes = di.mlp_layer_shapes(n_feat, mlp)
+    pos = sum(no * ni for no, ni in shapes[:2])
+    no, ni = shapes[2]
+    Wc1 = np.asarray(w[pos:pos + no * ni]).reshape(no, ni)
+    return np.concatenate([w[:pos], Wc1[:, :ni - n_app].ravel(), w[pos + no * ni:], Wc1[:, ni - n_app:].ravel()])
+
+
 def rel_err(got, ref, floor=None):
     """max |got-ref| / max(|ref|, floor); floor defaults to the mean magnitude of ref (so entries that
     cancel to ~0 are judged against the size of the tensor they live in)."""
