@@ -72,7 +72,7 @@ def main():
     import torch
     import dg_inputs as di
     from paper_2405_04416_amd import binding as B
-    from paper_2405_04416_amd.step import Occupancy, SubModel, TrainStep
+    from paper_2405_04416_amd.step import Occupancy, SubModel, TrainStep, split_appearance_columns
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
@@ -112,9 +112,10 @@ def main():
         gp = di.grid_params(cfg, p)            # the coarse level of a cascade has its own table length
         growth = gp.get("growth") or B.dg_growth_factor(gp["n_min"], gp["n_max"], gp["L"])
         grid = B.dg_grid_desc_init(gp["L"], gp["F"], gp["log2_T"], gp["n_min"], growth, di.box_extent(cfg["parts"][p]))
-        mlp = B.dg_mlp_desc(n_feat, m["n_hidden_d"], m["n_geo"], m["sh_degree"] ** 2, m["n_hidden_c"], m["n_layers_c"], 1)
+        mlp = B.dg_mlp_desc(n_feat, m["n_hidden_d"], m["n_geo"], m["sh_degree"] ** 2, m["n_hidden_c"], m["n_layers_c"], 1,
+                            m.get("n_app", 0))
         table = to_dev(di.make_table(grid.n_entries, gp["F"], cfg["table_range"], seed=1000 * p))
-        weights = to_dev(di.make_mlp_weights(n_feat, m, seed=1000 * p))
+        weights = to_dev(split_appearance_columns(di.make_mlp_weights(n_feat, m, seed=1000 * p), mlp))
         models[p] = SubModel(grid, mlp, table, weights)
     od, dd, Cd = to_dev(o), to_dev(d), to_dev(Cgt)
     occupancy, extra = None, {}
@@ -129,6 +130,11 @@ def main():
             occupancy[p] = Occupancy(desc, density, bits, np.float32(float(ext.max()) * np.sqrt(3.0) / 1024), cfg["occ"]["max_steps"])
             B.dg_occ_bits(density, 0.6, bits, occupancy[p].n_set)
         extra = dict(occupancy=occupancy, max_samples=R * 32)
+    app_host = None
+    if m.get("n_app"):
+        # appearance vectors per image as further colour-net inputs (Sec. 4.4.3): seeded stand-ins, every ray in a random image
+        app_host = di.make_appearance(cfg["n_images"], m["n_app"], R, seed=0)
+        extra["appearance"] = (to_dev(app_host[0]), to_dev(app_host[1].view(np.int32)))
     step = TrainStep(to_dev(cfg["parts"]), models, resident, R, S, k_max, m["sh_degree"], loss_scale=65536.0,
                      lambda1=1e-3, seed=0, holes=to_dev(cfg["holes"]) if "holes" in cfg else None,
                      max_segments=R * min(k_max, 4), **extra)  # rays of these recipes average well under four segments
@@ -229,7 +235,8 @@ def main():
         hm = ostep.make_models(dict(cfg, resident_list=resident), seed=0)
         ho = ostep.make_occupancy(cfg, seed=0) if occupancy is not None else None     # built outside the timed call, like the tables
         t1 = time.perf_counter()
-        ostep.run_step(cfg, hm, o[:Rc], d[:Rc], Cgt[:Rc], seed=0, lambda1=1e-3, loss_scale=65536.0, resident=resident, occ=ho)   # (without the synthetic foreign partials)
+        ostep.run_step(cfg, hm, o[:Rc], d[:Rc], Cgt[:Rc], seed=0, lambda1=1e-3, loss_scale=65536.0, resident=resident, occ=ho,
+                       appearance=None if app_host is None else (app_host[0], app_host[1][:Rc]))   # (without the synthetic foreign partials)
         cpu_s = time.perf_counter() - t1
         cpu = {"value": round(Rc / cpu_s, 2), "unit": "rays/s", "cores": 1, "kind": "oracle",
                "sample": "first %d rays of the same batch, full-size tables, one fwd+bwd pass, %.1f s" % (Rc, cpu_s)}

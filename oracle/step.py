@@ -18,7 +18,9 @@ def make_models(cfg, seed=0):
         growth = g.get("growth") or O.growth_factor(g["n_min"], g["n_max"], g["L"])
         grid = O.grid_init(g["L"], g["F"], g["log2_T"], g["n_min"], growth, di.box_extent(cfg["parts"][p]))
         n_feat = g["L"] * g["F"]
-        mlp = O.mlp_desc(n_feat, m["n_hidden_d"], m["n_geo"], m["sh_degree"] ** 2, m["n_hidden_c"], m["n_layers_c"], 1, 1)
+        # appearance features (Sec. 4.4.3) are further inputs of the colour net, after the direction encoding
+        mlp = O.mlp_desc(n_feat, m["n_hidden_d"], m["n_geo"], m["sh_degree"] ** 2 + m.get("n_app", 0), m["n_hidden_c"],
+                         m["n_layers_c"], 1, 1)
         table = di.make_table(grid.n_entries, g["F"], cfg["table_range"], seed=seed + 1000 * p)
         weights = di.make_mlp_weights(n_feat, m, seed=seed + 1000 * p)
         models[p] = dict(grid=grid, mlp=mlp, table=table, weights=weights)
@@ -41,11 +43,12 @@ def make_occupancy(cfg, seed=0, threshold=0.6):
 
 
 def run_step(cfg, models, o, d, Cgt, jitter=None, seed=0, lambda1=0.0, loss_scale=65536.0, resident=None,
-             foreign=None, want_bwd=True, occ=None):
+             foreign=None, want_bwd=True, occ=None, appearance=None):
     """Returns a dict of every intermediate the GPU path can be compared with.
 
     occ: None (fixed stratified samples per segment), or {partition: occupancy grid} from make_occupancy:
-    occupancy-guided sampling, segments of different lengths."""
+    occupancy-guided sampling, segments of different lengths.
+    appearance: None, or (table [n_images, n_app], image_of_ray [R]): per-image vectors fed to the colour net."""
     parts, S, k_max = cfg["parts"], cfg["S"], cfg["k_max"]
     P, R = parts.shape[0], o.shape[0]
     deg = cfg["mlp"]["sh_degree"]
@@ -66,12 +69,16 @@ def run_step(cfg, models, o, d, Cgt, jitter=None, seed=0, lambda1=0.0, loss_scal
             jit = None if jitter is None else jitter[b * S:e * S]
             u, delta = O.sample_segments(o, d, seg_t, seg_ray, seg_slot, b, e, parts[p], S, seed=seed, jitter_arr=jit)
             dir_enc = O.sh(d[seg_ray[b:e]], deg)
+            if appearance is not None:
+                dir_enc = np.concatenate([dir_enc, appearance[0][appearance[1][seg_ray[b:e]]].astype(np.float64)], axis=1)
             first, S_mlp = None, S
         else:
             q = occ[p]
             first, u, delta, t, sample_ray = O.march_segments(o, d, seg_t, seg_ray, seg_slot, b, e, parts[p], q["grid"], q["bits"],
                                                               q["dt"], q["max_steps"], seed=seed)
             dir_enc = O.sh(d[sample_ray], deg)            # one direction row per sample
+            if appearance is not None:
+                dir_enc = np.concatenate([dir_enc, appearance[0][appearance[1][sample_ray]].astype(np.float64)], axis=1)
             S_mlp = 1
         feat = O.encode_fwd(m["grid"], m["table"], u)
         sigma, rgb = O.mlp_fwd(m["mlp"], m["weights"].astype(np.float64), feat, dir_enc, S_mlp)

@@ -409,16 +409,25 @@ colour_bwd_kernel(const __half *__restrict__ weights, const __half *__restrict__
         if (NA > 0) {
             // per-row sums of delta for the appearance columns: delta^T (features x samples) times the 0/1 matrix
             // "sample s lies in the tile's local row c"; column c of the result is the sum over that row's samples
-            const uint64_t n0 = tile * 32, row0 = n0 / S;
-            const uint32_t rem0 = (uint32_t)(n0 % S), c = lane_fixed & 31;
+            const uint64_t n0 = tile * 32;
+            const uint64_t row0 = n0 / S;                                             // row of the tile's first sample
+            const uint32_t rem0 = (uint32_t)(n0 - row0 * S), c = lane_fixed & 31;
+            // local row of sample s of the tile: rows of 32 or more samples change at most once, at sample `turn`;
+            // shorter rows: (rem0 + s) / S on integers below 64, exact through a float reciprocal
+            const bool wide = S >= 32;
+            const uint32_t turn = S - rem0;
+            const float inv_S = 1.0f / (float)S;
+            auto local_row = [&](uint32_t smp) {
+                return wide ? (smp >= turn ? 1u : 0u) : (uint32_t)((float)(rem0 + smp) * inv_S + 1e-3f);
+            };
+            const uint32_t last = (uint32_t)(n_samples - 1 - n0 < 31 ? n_samples - 1 - n0 : 31);
+            const uint32_t n_local = local_row(last) + 1u;                            // rows with samples in this tile
             h8 in_row[2];
 #pragma unroll
             for (int p = 0; p < 2; ++p)
 #pragma unroll
                 for (int j = 0; j < 8; ++j)      // slot j of k-step p holds sample feat_tiled(p, h, j) of the tile, as in td
-                    in_row[p][j] = (_Float16)(((rem0 + (uint32_t)feat_tiled(p, h, j)) / S == c) ? 1.0f : 0.0f);
-            const uint64_t last = (n_samples - 1 - n0 < 31 ? n_samples - 1 - n0 : 31);
-            const uint32_t n_local = (uint32_t)((rem0 + last) / S) + 1u;          // rows that have samples in this tile
+                    in_row[p][j] = (_Float16)(local_row((uint32_t)feat_tiled(p, h, j)) == c ? 1.0f : 0.0f);
 #pragma unroll
             for (int ot = 0; ot < 2; ++ot) {
                 f16v sums = mma(td[ot][0], in_row[0], zero16());
@@ -589,26 +598,59 @@ fold_shares_kernel(const float *__restrict__ density_shares, uint32_t n_d, const
     }
 }
 
-// dW[kTotal + o * NA + a] += inv_scale * sum_rows row_delta[row][o] * app[row][a]: a workgroup walks rows with a grid
-// stride, thread (o, quarter q) keeps NA / 4 sums, one atomic per sum and workgroup at the end
+// dW[kTotal + o * NA + a] += inv_scale * sum_rows row_delta[row][o] * app[row][a].  A workgroup of four row groups
+// walks rows with a grid stride, eight rows in flight per thread (independent loads); thread (o, quarter q) of a row
+// group keeps NA / 4 sums; the groups' sums meet in LDS and the workgroup issues one atomic per weight (atomics on the
+// same few thousand addresses serialise, so there are few workgroups).
+constexpr int kWgradGroups = 4, kWgradBlock = kWgradGroups * 256, kWgradGrid = 256;
 template <int NA>
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kWgradBlock)
 appearance_wgrad_kernel(const float *__restrict__ row_delta, const __half *__restrict__ app, uint64_t n_rows, float inv_scale,
                         float *__restrict__ dW)
 {
-    constexpr int kPer = NA / 4;
-    const int o = threadIdx.x & 63, q = threadIdx.x >> 6;
+    constexpr int kPer = NA / 4, kBatch = 8;
+    __shared__ float part[kWgradGroups - 1][HC * NA];
+    const int o = threadIdx.x & 63, q = (threadIdx.x >> 6) & 3, group = threadIdx.x >> 8;
     float acc[kPer];
 #pragma unroll
     for (int a = 0; a < kPer; ++a) acc[a] = 0.0f;
-    for (uint64_t row = blockIdx.x; row < n_rows; row += gridDim.x) {
-        const float d = row_delta[row * HC + o];
-        const __half *x = app + row * NA + q * kPer;
+    for (uint64_t first = ((uint64_t)blockIdx.x * kWgradGroups + group) * kBatch; first < n_rows;
+         first += (uint64_t)gridDim.x * kWgradGroups * kBatch) {
+        float d[kBatch];
+        uint2 x[kBatch][kPer / 4];                          // kPer halves = kPer / 4 words of 8 bytes
 #pragma unroll
-        for (int a = 0; a < kPer; ++a) acc[a] = __builtin_fmaf(d, __half2float(x[a]), acc[a]);
+        for (int b = 0; b < kBatch; ++b) {
+            const uint64_t row = first + b < n_rows ? first + b : n_rows - 1;
+            d[b] = first + b < n_rows ? row_delta[row * HC + o] : 0.0f;
+            const uint2 *src = reinterpret_cast<const uint2 *>(app + row * NA + q * kPer);
+#pragma unroll
+            for (int w = 0; w < kPer / 4; ++w) x[b][w] = src[w];
+        }
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b)
+#pragma unroll
+            for (int w = 0; w < kPer / 4; ++w) {
+                const __half2 lo = __builtin_bit_cast(__half2, x[b][w].x), hi = __builtin_bit_cast(__half2, x[b][w].y);
+                acc[4 * w] = __builtin_fmaf(d[b], __low2float(lo), acc[4 * w]);
+                acc[4 * w + 1] = __builtin_fmaf(d[b], __high2float(lo), acc[4 * w + 1]);
+                acc[4 * w + 2] = __builtin_fmaf(d[b], __low2float(hi), acc[4 * w + 2]);
+                acc[4 * w + 3] = __builtin_fmaf(d[b], __high2float(hi), acc[4 * w + 3]);
+            }
     }
+    if (group > 0) {
 #pragma unroll
-    for (int a = 0; a < kPer; ++a) unsafeAtomicAdd(dW + kTotal + o * NA + q * kPer + a, acc[a] * inv_scale);
+        for (int a = 0; a < kPer; ++a) part[group - 1][o * NA + q * kPer + a] = acc[a];
+    }
+    __syncthreads();
+    if (group == 0) {
+#pragma unroll
+        for (int a = 0; a < kPer; ++a) {
+            float v = acc[a];
+#pragma unroll
+            for (int g = 0; g < kWgradGroups - 1; ++g) v += part[g][o * NA + q * kPer + a];
+            unsafeAtomicAdd(dW + kTotal + o * NA + q * kPer + a, v * inv_scale);
+        }
+    }
 }
 
 __global__ void __launch_bounds__(kBlock)
@@ -679,9 +721,10 @@ void mlp_mfma_bwd(const void *weights, const void *feat, const void *dir_enc, co
     fold_shares_kernel<<<(kTotal + kFoldElems - 1) / kFoldElems, kFoldElems * kFoldGroups, 0, st>>>(
         density_shares, grid_d * kWavesPerBlock, colour_shares, grid_c * kWavesPerBlock, 1.0f / loss_scale, dW);
     if (n_app) {
-        const uint32_t grid_a = (uint32_t)(n_rows < 1024 ? n_rows : 1024);
-        if (n_app == 16) appearance_wgrad_kernel<16><<<grid_a, kBlock, 0, st>>>(row_delta, ap, n_rows, 1.0f / loss_scale, dW);
-        else appearance_wgrad_kernel<48><<<grid_a, kBlock, 0, st>>>(row_delta, ap, n_rows, 1.0f / loss_scale, dW);
+        const uint64_t batches = (n_rows + 8 * kWgradGroups - 1) / (8 * kWgradGroups);
+        const uint32_t grid_a = (uint32_t)(batches < kWgradGrid ? batches : kWgradGrid);
+        if (n_app == 16) appearance_wgrad_kernel<16><<<grid_a, kWgradBlock, 0, st>>>(row_delta, ap, n_rows, 1.0f / loss_scale, dW);
+        else appearance_wgrad_kernel<48><<<grid_a, kWgradBlock, 0, st>>>(row_delta, ap, n_rows, 1.0f / loss_scale, dW);
     }
 }
 

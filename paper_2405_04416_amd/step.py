@@ -13,6 +13,19 @@ import torch
 from . import binding as B
 
 
+def split_appearance_columns(w, desc):
+    """Packed MLP weights (or their gradient; numpy) with ONE wide first colour layer [n_hidden_c, n_geo + n_dir + n_app]
+    -> the library's packing: the matrices without the appearance columns first, those columns
+    Wapp [n_hidden_c, n_app] last.  Pure re-arrangement."""
+    import numpy as np
+    if not desc.n_app:
+        return w
+    pos = desc.n_hidden_d * desc.n_feat + desc.n_geo * desc.n_hidden_d
+    no, ni = desc.n_hidden_c, desc.n_geo + desc.n_dir + desc.n_app
+    Wc1 = np.asarray(w[pos:pos + no * ni]).reshape(no, ni)
+    return np.concatenate([w[:pos], Wc1[:, :ni - desc.n_app].ravel(), w[pos + no * ni:], Wc1[:, ni - desc.n_app:].ravel()])
+
+
 class SubModel:
     """Parameters and gradient buffers of one partition's sub-NeRF (hash table + MLP weights)."""
 
@@ -43,11 +56,13 @@ class Occupancy:
 class TrainStep:
     def __init__(self, parts, models, resident, R, S, k_max, sh_degree, loss_scale=65536.0, lambda1=0.0, seed=0,
                  device="cuda:0", max_segments=None, binned_backward=True, encode_ws_cap=48 << 30, holes=None,
-                 occupancy=None, max_samples=None):
+                 occupancy=None, max_samples=None, appearance=None):
         """parts: [P,6] float tensor (device); models: {partition index: SubModel}; resident: partition indices served;
         holes: None or [P,6] (device): the box subtracted from each partition (coarse level of the cascade, Sec. 4.2.2);
         occupancy: None (S stratified samples per segment) or {partition index: Occupancy}: occupancy-guided sampling
-        (Sec. 3.2, Sec. 5.1), at most max_samples samples per step over all resident partitions (S is then unused)."""
+        (Sec. 3.2, Sec. 5.1), at most max_samples samples per step over all resident partitions (S is then unused);
+        appearance: None or (table [n_images, n_app] fp16, image_of_ray [R] int32), both on the device: per-image
+        appearance vectors as further colour-net inputs (Sec. 4.4.3; the sub-models' MLP descriptors carry n_app)."""
         self.dev = torch.device(device)
         self.parts, self.models, self.resident, self.holes = parts, models, list(resident), holes
         self.parts_host = parts.cpu().tolist()
@@ -73,6 +88,8 @@ class TrainStep:
             self.t, self.sample_ray = z(n), z(n, dt=i32)
             self.ws_march = z(B.dg_march_workspace_bytes(cap) // 4, dt=i32)
             self.samples = {}                               # partition -> (first sample, number of samples) of this step
+        self.appearance = appearance
+        self.app_rows = None if appearance is None else z(self.dir_enc.shape[0], appearance[0].shape[1], dt=f16)
         self.feat = z(n, self.n_feat, dt=f16)
         self.sigma, self.rgb = z(n), z(n, 3)
         self.dsigma, self.drgb = z(n), z(n, 3)
@@ -81,7 +98,7 @@ class TrainStep:
         self.gCk, self.gTk = z(R, k_max, 3), z(R, k_max)
         self.C, self.T, self.gC, self.gT = z(R, 3), z(R), z(R, 3), z(R)
         self.loss = z(1)
-        self.ws_mlp = z(B.dg_mlp_bwd_workspace_bytes(any_model.mlp, n) // 4 + 64)
+        self.ws_mlp = z(B.dg_mlp_bwd_app_workspace_bytes(any_model.mlp, n, S if occupancy is None else 1) // 4 + 64)
         # workspace of the binned table-gradient pass, capped (the call batches itself when it is smaller than ideal)
         want = max(B.dg_hashgrid_encode_bwd_workspace_bytes(mm.grid, n) for mm in models.values())
         self.ws_enc = torch.zeros(min(want, encode_ws_cap) // 4 + 64, dtype=f32, device=self.dev) if binned_backward else None
@@ -140,8 +157,9 @@ class TrainStep:
                 B.dg_dir_encode(d, self.seg_ray[b:e], n_seg, self.deg, self.dir_enc[b:e])
             with self._timed("dg_hashgrid_encode_fwd"):
                 B.dg_hashgrid_encode_fwd(m.grid, m.table, self.u[sl], N, self.feat[sl])
+            app = self._appearance_rows(self.seg_ray[b:e], n_seg, slice(b, e))
             with self._timed("dg_mlp_fwd"):
-                B.dg_mlp_fwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[b:e], S, N, self.sigma[sl], self.rgb[sl])
+                B.dg_mlp_fwd_app(m.mlp, m.weights, self.feat[sl], self.dir_enc[b:e], app, S, N, self.sigma[sl], self.rgb[sl])
             with self._timed("dg_composite_segment_fwd"):
                 B.dg_composite_segment_fwd(self.sigma[sl], self.rgb[sl], self.delta[sl], n_seg, S, self.seg_ray[b:e],
                                            self.seg_slot[b:e], self.k_max, self.Ck, self.Tk)
@@ -152,6 +170,14 @@ class TrainStep:
         self.loss.zero_()
         with self._timed("dg_loss_seed"):
             B.dg_loss_seed(self.C, self.T, Cgt, self.R, self.lambda1, self.gC, self.gT, self.loss)
+
+    def _appearance_rows(self, index, n, rows):
+        """Gathers the appearance vector of each row's ray (rows as for the direction encoding); None without them."""
+        if self.appearance is None:
+            return None
+        with self._timed("dg_appearance_rows"):
+            B.dg_appearance_rows(self.appearance[0], self.appearance[1], index, n, self.app_rows[rows])
+        return self.app_rows[rows]
 
     def _forward_marched(self, o, d):
         """Per sub-model forward with occupancy-guided sampling (Sec. 3.2, Sec. 5.1): segments of different lengths,
@@ -182,8 +208,9 @@ class TrainStep:
                     B.dg_dir_encode(d, self.sample_ray[sl], N, self.deg, self.dir_enc[sl])
                 with self._timed("dg_hashgrid_encode_fwd"):
                     B.dg_hashgrid_encode_fwd(m.grid, m.table, self.u[sl], N, self.feat[sl])
+                app = self._appearance_rows(self.sample_ray[sl], N, sl)
                 with self._timed("dg_mlp_fwd"):
-                    B.dg_mlp_fwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[sl], 1, N, self.sigma[sl], self.rgb[sl])
+                    B.dg_mlp_fwd_app(m.mlp, m.weights, self.feat[sl], self.dir_enc[sl], app, 1, N, self.sigma[sl], self.rgb[sl])
             with self._timed("dg_composite_ragged_fwd"):        # also writes C_k = 0, T_k = 1 for segments that saw nothing
                 B.dg_composite_ragged_fwd(self.sigma[s0 - N:], self.rgb[s0 - N:], self.delta[s0 - N:], n_seg, first, ray, slot,
                                           self.k_max, self.Ck, self.Tk)
@@ -216,8 +243,8 @@ class TrainStep:
                                           self.seg_ray[b:e], self.seg_slot[b:e], self.k_max, self.gCk, self.gTk, self.dsigma[s0:],
                                           self.drgb[s0:])
             with self._timed("dg_mlp_bwd"):
-                B.dg_mlp_bwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[sl], 1, N, self.dsigma[sl], self.drgb[sl],
-                             self.loss_scale, self.dfeat[sl], m.dW, self.ws_mlp)
+                B.dg_mlp_bwd_app(m.mlp, m.weights, self.feat[sl], self.dir_enc[sl], None if self.app_rows is None else self.app_rows[sl],
+                                 1, N, self.dsigma[sl], self.drgb[sl], self.loss_scale, self.dfeat[sl], m.dW, self.ws_mlp)
             with self._timed("dg_hashgrid_encode_bwd"):
                 B.dg_hashgrid_encode_bwd(m.grid, self.u[sl], self.dfeat[sl], N, m.dtable, self.ws_enc)
 
@@ -244,8 +271,11 @@ class TrainStep:
                 with self._timed("dg_hashgrid_encode_fwd"):
                     B.dg_hashgrid_encode_fwd(m.grid, m.table, self.u[:n], n, self.feat[:n])
                 self.dir_enc[:1].zero_()                        # the density does not depend on the direction: one zero row
+                if self.app_rows is not None:
+                    self.app_rows[:1].zero_()
                 with self._timed("dg_mlp_fwd"):
-                    B.dg_mlp_fwd(m.mlp, m.weights, self.feat[:n], self.dir_enc[:1], max(n, 1), n, self.sigma[:n], self.rgb[:n])
+                    B.dg_mlp_fwd_app(m.mlp, m.weights, self.feat[:n], self.dir_enc[:1], None if self.app_rows is None else self.app_rows[:1],
+                                     max(n, 1), n, self.sigma[:n], self.rgb[:n])
                 with self._timed("dg_occ_update"):
                     B.dg_occ_update(q.density, cell, self.sigma[:n], n)
             q.n_set.zero_()
@@ -275,8 +305,8 @@ class TrainStep:
                 B.dg_composite_segment_bwd(self.sigma[sl], self.rgb[sl], self.delta[sl], n_seg, S, self.seg_ray[b:e],
                                            self.seg_slot[b:e], self.k_max, self.gCk, self.gTk, self.dsigma[sl], self.drgb[sl])
             with self._timed("dg_mlp_bwd"):
-                B.dg_mlp_bwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[b:e], S, N, self.dsigma[sl], self.drgb[sl],
-                             self.loss_scale, self.dfeat[sl], m.dW, self.ws_mlp)
+                B.dg_mlp_bwd_app(m.mlp, m.weights, self.feat[sl], self.dir_enc[b:e], None if self.app_rows is None else self.app_rows[b:e],
+                                 S, N, self.dsigma[sl], self.drgb[sl], self.loss_scale, self.dfeat[sl], m.dW, self.ws_mlp)
             with self._timed("dg_hashgrid_encode_bwd"):
                 B.dg_hashgrid_encode_bwd(m.grid, self.u[sl], self.dfeat[sl], N, m.dtable, self.ws_enc)
 

@@ -43,16 +43,10 @@ def from_planes(t, n, width):
 
 
 def split_appearance_weights(w, n_feat, mlp):
-    """Packed weights (or their gradient) with one wide first colour layer [n_hidden_c, n_geo + n_dir + n_app] (the
-    oracle's view) -> the library's packing: the narrow matrices first, the appearance columns Wapp [n_hidden_c, n_app] last."""
-    n_app = mlp.get("n_app", 0)
-    if not n_app:
-        return w
-    shapes = di.mlp_layer_shapes(n_feat, mlp)
-    pos = sum(no * ni for no, ni in shapes[:2])
-    no, ni = shapes[2]
-    Wc1 = np.asarray(w[pos:pos + no * ni]).reshape(no, ni)
-    return np.concatenate([w[:pos], Wc1[:, :ni - n_app].ravel(), w[pos + no * ni:], Wc1[:, ni - n_app:].ravel()])
+    """The oracle's packing (one wide first colour layer) -> the library's (appearance columns last)."""
+    from paper_2405_04416_amd.step import split_appearance_columns
+    return split_appearance_columns(w, B.dg_mlp_desc(n_feat, mlp["n_hidden_d"], mlp["n_geo"], mlp["sh_degree"] ** 2, mlp["n_hidden_c"],
+                                                     mlp["n_layers_c"], 1, mlp.get("n_app", 0)))
 
 
 def rel_err(got, ref, floor=None):
@@ -76,14 +70,16 @@ def gpu_grid(cfg, part=0):
 def gpu_mlp(cfg):
     g, m = cfg["grid"], cfg["mlp"]
     return B.dg_mlp_desc(g["L"] * g["F"], m["n_hidden_d"], m["n_geo"], m["sh_degree"] ** 2, m["n_hidden_c"],
-                         m["n_layers_c"], 1)
+                         m["n_layers_c"], 1, m.get("n_app", 0))
 
 
 def gpu_models(cfg, host_models):
     """Device copies of the oracle-side seeded parameters, with the library's own descriptors."""
     out = {}
     for p, hm in host_models.items():
-        out[p] = SubModel(gpu_grid(cfg, p), gpu_mlp(cfg), dev(hm["table"]), dev(hm["weights"]))
+        g = di.grid_params(cfg, p)
+        out[p] = SubModel(gpu_grid(cfg, p), gpu_mlp(cfg), dev(hm["table"]),
+                          dev(split_appearance_weights(hm["weights"], g["L"] * g["F"], cfg["mlp"])))
     return out
 
 

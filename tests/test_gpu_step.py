@@ -17,7 +17,7 @@ from paper_2405_04416_amd import binding as B
 
 import oracle
 from gpu_util import (DEV, TOL_F16, TOL_F32, assert_close_robust, dev, from_planes, gpu_models, have_gpu, host, make_step,
-                      rel_err)
+                      rel_err, split_appearance_weights)
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not have_gpu(), reason="needs a GPU")]
 
@@ -34,11 +34,15 @@ def _compare_step(cfg, R, seed, lambda1, loss_scale, use_jitter_array, table_gai
     Cgt = di.make_targets(R, seed=seed)
     hm = ostep.make_models(cfg, seed=seed)
     gm = gpu_models(cfg, hm)
-    step = make_step(cfg, gm, R, loss_scale=loss_scale, lambda1=lambda1, seed=seed)
+    app_h = app_d = None
+    if cfg["mlp"].get("n_app"):             # appearance vectors per image (Sec. 4.4.3), every ray belongs to an image
+        table, image = di.make_appearance(cfg["n_images"], cfg["mlp"]["n_app"], R, seed=seed)
+        app_h, app_d = (table, image), (dev(table), dev(image.view(np.int32)))
+    step = make_step(cfg, gm, R, loss_scale=loss_scale, lambda1=lambda1, seed=seed, appearance=app_d)
     jit = di.make_jitter(R * cfg["k_max"] * cfg["S"], seed=seed) if use_jitter_array else None
     step.step(dev(o), dev(d), dev(Cgt), None if jit is None else dev(jit))
     torch.cuda.synchronize()
-    ref = ostep.run_step(cfg, hm, o, d, Cgt, jitter=jit, seed=seed, lambda1=lambda1, loss_scale=loss_scale)
+    ref = ostep.run_step(cfg, hm, o, d, Cgt, jitter=jit, seed=seed, lambda1=lambda1, loss_scale=loss_scale, appearance=app_h)
 
     # bookkeeping: bit-exact
     np.testing.assert_array_equal(host(step.seg_count), ref["seg_count"])
@@ -74,7 +78,7 @@ def _compare_step(cfg, R, seed, lambda1, loss_scale, use_jitter_array, table_gai
         assert_close_robust(host(step.dsigma[sl]), q["dsigma"], TOL_F16, "dsigma")
         assert_close_robust(host(step.drgb[sl]), q["drgb"], TOL_F16, "drgb")
         assert_close_robust(from_planes(step.dfeat[sl], (q["e"] - q["b"]) * S, q["dfeat"].shape[1]), q["dfeat"], TOL_F16, "dfeat")
-        assert_close_robust(host(gm[p].dW), q["dW"], TOL_F16, "dW")
+        assert_close_robust(host(gm[p].dW), split_appearance_weights(q["dW"], q["feat"].shape[1], cfg["mlp"]), TOL_F16, "dW")
         grid = hm[p]["grid"]
         got = host(gm[p].dtable).astype(np.float64)
         for l in range(grid.L):
@@ -109,6 +113,15 @@ def test_step_c3_segmented_2x2():
     step, ref = _compare_step(cfg, 1200, seed=2, lambda1=1e-3, loss_scale=2.0 ** 14, use_jitter_array=False,
                               table_gain=3000.0)
     assert np.mean(ref["seg_count"] >= 2) >= 0.4
+
+
+def test_step_c8_appearance_features():
+    say("step c8_app, 1500 rays, 48 appearance inputs of the colour net, 1000 images")
+    cfg = di.config("c8_app")
+    step, ref = _compare_step(cfg, 1500, seed=8, lambda1=1e-3, loss_scale=2.0 ** 14, use_jitter_array=False, table_gain=3000.0)
+    # the appearance columns of the first colour layer received gradient
+    n_w = step.models[0].dW.numel()
+    assert float(step.models[0].dW[n_w - 64 * 48:].abs().max()) > 0
 
 
 def test_step_c6_two_level_cascade():

@@ -12,7 +12,7 @@ import oracle
 import oracle.step as ostep
 
 from gpu_util import (DEV, TOL_F16, TOL_F32, assert_close_robust, dev, from_planes, gpu_models, gpu_occupancy, have_gpu, host,
-                      make_step, rel_err)
+                      make_step, rel_err, split_appearance_weights)
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not have_gpu(), reason="needs a GPU")]
 
@@ -30,12 +30,16 @@ def _compare(cfg, R, seed, lambda1, loss_scale, table_gain, max_samples):
     hm = ostep.make_models(cfg, seed=seed)
     ho = ostep.make_occupancy(cfg, seed=seed)
     gm = gpu_models(cfg, hm)
+    app_h = app_d = None
+    if cfg["mlp"].get("n_app"):
+        table, image = di.make_appearance(cfg["n_images"], cfg["mlp"]["n_app"], R, seed=seed)
+        app_h, app_d = (table, image), (dev(table), dev(image.view(np.int32)))
     step = make_step(cfg, gm, R, loss_scale=loss_scale, lambda1=lambda1, seed=seed, occupancy=gpu_occupancy(cfg, ho),
-                     max_samples=max_samples)
+                     max_samples=max_samples, appearance=app_d)
     step.step(dev(o), dev(d), dev(Cgt))
     D = step.depth()
     torch.cuda.synchronize()
-    ref = ostep.run_step(cfg, hm, o, d, Cgt, seed=seed, lambda1=lambda1, loss_scale=loss_scale, occ=ho)
+    ref = ostep.run_step(cfg, hm, o, d, Cgt, seed=seed, lambda1=lambda1, loss_scale=loss_scale, occ=ho, appearance=app_h)
     assert int(host(step.status)[0]) == 0
     np.testing.assert_array_equal(host(step.seg_count), ref["seg_count"])
     np.testing.assert_array_equal(host(step.part_offset), ref["part_offset"])
@@ -64,7 +68,7 @@ def _compare(cfg, R, seed, lambda1, loss_scale, table_gain, max_samples):
         assert_close_robust(host(step.dsigma[sl]), q["dsigma"], TOL_F16, "dsigma")
         assert_close_robust(host(step.drgb[sl]), q["drgb"], TOL_F16, "drgb")
         assert_close_robust(from_planes(step.dfeat[sl], N, q["dfeat"].shape[1]), q["dfeat"], TOL_F16, "dfeat")
-        assert_close_robust(host(gm[p].dW), q["dW"], TOL_F16, "dW")
+        assert_close_robust(host(gm[p].dW), split_appearance_weights(q["dW"], q["feat"].shape[1], cfg["mlp"]), TOL_F16, "dW")
         grid = hm[p]["grid"]
         got = host(gm[p].dtable).astype(np.float64)
         for l in range(grid.L):
@@ -98,6 +102,14 @@ def test_step_occupancy_four_boxes():
     cfg["occ"] = dict(res=48, max_steps=512)
     step, ref = _compare(cfg, 900, seed=2, lambda1=1e-3, loss_scale=2.0 ** 14, table_gain=3000.0, max_samples=200000)
     assert len(ref["per"]) == 4
+
+
+def test_step_occupancy_with_appearance_features():
+    say("step c8_app with an occupancy grid of resolution 64: one appearance row per sample, 16 appearance inputs")
+    cfg = di.config("c8_app")
+    cfg["mlp"] = dict(cfg["mlp"], n_app=16)
+    cfg["occ"] = dict(res=64, max_steps=1024)
+    _compare(cfg, 1000, seed=4, lambda1=1e-3, loss_scale=2.0 ** 14, table_gain=3000.0, max_samples=60000)
 
 
 def test_sample_capacity_is_enforced():
