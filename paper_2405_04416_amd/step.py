@@ -103,6 +103,7 @@ class TrainStep:
         want = max(B.dg_hashgrid_encode_bwd_workspace_bytes(mm.grid, n) for mm in models.values())
         self.ws_enc = torch.zeros(min(want, encode_ws_cap) // 4 + 64, dtype=f32, device=self.dev) if binned_backward else None
         self.offsets = None
+        self.t_fixed = None
         self.timings = None     # set to {} to collect (start, end) event pairs per entry point
 
     @contextlib.contextmanager
@@ -138,6 +139,36 @@ class TrainStep:
 
     def forward(self, o, d, Cgt, jitter=None, foreign=None):
         """foreign: optional callable(self) that fills partials of non-resident partitions into Ck/Tk."""
+        self._partials(o, d, jitter)
+        if foreign is not None:
+            foreign(self)
+        with self._timed("dg_merge_segments"):
+            B.dg_merge_segments(self.Ck, self.Tk, self.seg_count, self.R, self.k_max, self.C, self.T)
+        self.loss.zero_()
+        with self._timed("dg_loss_seed"):
+            B.dg_loss_seed(self.C, self.T, Cgt, self.R, self.lambda1, self.gC, self.gT, self.loss)
+
+    def render(self, o, d, jitter=None):
+        """Evaluation rendering (Sec. 4.4.2): forward only, every sub-model renders its segments and the partial
+        results are merged into the final colour, depth and transmittance.  Returns (C [R,3], D [R], T [R])."""
+        if self.occ is None and self.t_fixed is None:
+            self.t_fixed = torch.zeros_like(self.delta)          # sample distances, only evaluation needs them
+        self._partials(o, d, jitter, want_t=True)
+        B.dg_merge_segments(self.Ck, self.Tk, self.seg_count, self.R, self.k_max, self.C, self.T)
+        if self.occ is not None:
+            return self.C, self.depth(), self.T
+        Dk = torch.zeros(self.R, self.k_max, device=self.dev)
+        D = torch.zeros(self.R, device=self.dev)
+        for p in self.resident:
+            b, e, sl = self._slices(p)
+            if e > b:
+                B.dg_composite_segment_depth(self.sigma[sl], self.delta[sl], self.t_fixed[sl], e - b, self.S, self.seg_ray[b:e],
+                                             self.seg_slot[b:e], self.k_max, Dk)
+        B.dg_merge_depth(Dk, self.Tk, self.seg_count, self.R, self.k_max, D)
+        return self.C, D, self.T
+
+    def _partials(self, o, d, jitter=None, want_t=False):
+        """Segments, and per resident sub-model: samples, encode, MLPs, local compositing into the partial slots."""
         S = self.S
         self.segments(o, d)
         if self.occ is not None:
@@ -152,7 +183,8 @@ class TrainStep:
             jit = None if jitter is None else jitter[sl]
             with self._timed("dg_sample_segments"):
                 B.dg_sample_segments(o, d, self.seg_t, self.seg_ray[b:e], self.seg_slot[b:e], n_seg, self.k_max,
-                                     self.parts_host[p], S, self.seed, jit, self.u[sl], self.delta[sl])
+                                     self.parts_host[p], S, self.seed, jit, self.u[sl], self.delta[sl],
+                                     self.t_fixed[sl] if want_t else None)
             with self._timed("dg_dir_encode"):
                 B.dg_dir_encode(d, self.seg_ray[b:e], n_seg, self.deg, self.dir_enc[b:e])
             with self._timed("dg_hashgrid_encode_fwd"):
@@ -163,13 +195,6 @@ class TrainStep:
             with self._timed("dg_composite_segment_fwd"):
                 B.dg_composite_segment_fwd(self.sigma[sl], self.rgb[sl], self.delta[sl], n_seg, S, self.seg_ray[b:e],
                                            self.seg_slot[b:e], self.k_max, self.Ck, self.Tk)
-        if foreign is not None:
-            foreign(self)
-        with self._timed("dg_merge_segments"):
-            B.dg_merge_segments(self.Ck, self.Tk, self.seg_count, self.R, self.k_max, self.C, self.T)
-        self.loss.zero_()
-        with self._timed("dg_loss_seed"):
-            B.dg_loss_seed(self.C, self.T, Cgt, self.R, self.lambda1, self.gC, self.gT, self.loss)
 
     def _appearance_rows(self, index, n, rows):
         """Gathers the appearance vector of each row's ray (rows as for the direction encoding); None without them."""

@@ -124,6 +124,35 @@ def test_step_c8_appearance_features():
     assert float(step.models[0].dW[n_w - 64 * 48:].abs().max()) > 0
 
 
+def test_evaluation_rendering_colour_depth_transmittance():
+    say("evaluation rendering (forward only) of c3_2x2, 800 rays: colour, depth and transmittance against the oracle")
+    cfg = di.config("c3_2x2")
+    cfg["grid"] = dict(cfg["grid"], log2_T=16)
+    cfg["table_range"] = cfg["table_range"] * 3000.0
+    R, S, seed = 800, cfg["S"], 5
+    o, d = di.make_rays(cfg, seed=seed, R=R)
+    hm = ostep.make_models(cfg, seed=seed)
+    step = make_step(cfg, gpu_models(cfg, hm), R, seed=seed)
+    C, D, T = step.render(dev(o), dev(d))
+    torch.cuda.synchronize()
+    ref = ostep.run_step(cfg, hm, o, d, di.make_targets(R, seed=seed), seed=seed, want_bwd=False)
+    assert rel_err(host(C), ref["C"]) <= TOL_F16 and rel_err(host(T), ref["T"]) <= TOL_F16
+    Dk = np.zeros((R, cfg["k_max"]))
+    for p, q in ref["per"].items():
+        b, e = q["b"], q["e"]
+        _, _, t = oracle.sample_segments(o, d, ref["seg_t"], ref["seg_ray"], ref["seg_slot"], b, e, cfg["parts"][p], S, seed=seed, want_t=True)
+        Dk[ref["seg_ray"][b:e], ref["seg_slot"][b:e]] = oracle.composite_depth(q["sigma"], q["delta"], t, S)
+    refD = oracle.merge_depth(Dk, ref["Tk"], ref["seg_count"])
+    assert rel_err(host(D), refD) <= TOL_F16
+    hit = ref["seg_count"] > 0
+    assert np.all(host(D)[~hit] == 0) and np.all(host(T)[~hit] == 1)
+    # the depth of a ray lies between its first entry and its last exit, scaled by what it absorbed
+    first_in = ref["seg_t"][hit, 0, 0]
+    last_out = ref["seg_t"][np.nonzero(hit)[0], ref["seg_count"][hit] - 1, 1]
+    opacity = 1.0 - ref["T"][hit]
+    assert np.all(host(D)[hit] >= first_in * opacity * (1 - 1e-3)) and np.all(host(D)[hit] <= last_out * opacity * (1 + 1e-3))
+
+
 def test_step_c6_two_level_cascade():
     say("step c6_cascade, 1000 rays, four fine (T = 2^16) and four coarse (T = 2^14) sub-models, coarse regions with holes")
     cfg = di.config("c6_cascade")
