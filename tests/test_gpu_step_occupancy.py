@@ -158,3 +158,78 @@ def test_occupancy_refresh(iteration):
     np.testing.assert_array_equal(gb, got > np.float32(thr))        # the bits belong to the library's own densities
     assert int(host(step.occ[0].n_set)[0]) == int(gb.sum())
     assert 0 < q["last_sigma"].min() and np.unique(q["last_cell"]).size > 0.3 * q["last_cell"].size
+
+
+def test_step_occupancy_full_size_bench_configuration():
+    """c7_occ at the size and launch configuration bench.py times (2^18 rays, occupancy grid 512 x 512 x 64): rays
+    sampled from the batch through the oracle one by one, and properties that hold at any size."""
+    say("step c7_occ full size (2^18 rays, occupancy resolution 512)")
+    from paper_2405_04416_amd import binding as B
+    cfg = di.config("c7_occ")
+    R = cfg["R"]
+    o, d = di.make_rays(cfg, seed=0)
+    Cgt = di.make_targets(R, seed=0)
+    hm = ostep.make_models(cfg, seed=0)
+    hm[0]["table"] *= np.float32(3000.0)
+    ho = ostep.make_occupancy(cfg, seed=0)
+    gm = gpu_models(cfg, hm)
+    step = make_step(cfg, gm, R, loss_scale=2.0 ** 16, lambda1=1e-3, seed=0, occupancy=gpu_occupancy(cfg, ho), max_samples=R * 32)
+    step.step(dev(o), dev(d), dev(Cgt))
+    torch.cuda.synchronize()
+    assert int(host(step.status)[0]) == 0
+    n_seg = step.offsets[-1]
+    s0, N = step.samples[0]
+    first = host(step.first[:n_seg + 1]).astype(np.int64)
+    counts = np.diff(first)
+    say("segments %d, samples %d (%.2f per segment)" % (n_seg, N, N / n_seg))
+    assert s0 == 0 and first[0] == 0 and first[-1] == N and counts.min() >= 0 and 2.0 < N / n_seg < 40.0
+
+    # (a) 64 sampled rays through the oracle, each marched on its own
+    cnt = host(step.seg_count)
+    pos_of_ray = np.cumsum(cnt) - cnt                       # k_max = 1: bucket order is ray order among hits
+    seg_t = host(step.seg_t)
+    q, box = ho[0], cfg["parts"][0]
+    pick = np.random.default_rng(0).choice(np.nonzero(cnt)[0], 64, replace=False)
+    checked = 0
+    for r in pick:
+        f1, u, delta, t, ray = oracle.march_segments(o, d, seg_t, np.array([r], np.uint32), np.array([0], np.uint32), 0, 1, box,
+                                                     q["grid"], q["bits"], q["dt"], q["max_steps"], seed=0)
+        j = int(pos_of_ray[r])
+        assert counts[j] == f1[1]
+        sl = slice(int(first[j]), int(first[j + 1]))
+        np.testing.assert_array_equal(host(step.u[sl]).view(np.uint32), u.view(np.uint32))
+        np.testing.assert_array_equal(host(step.delta[sl]).view(np.uint32), delta.view(np.uint32))
+        if f1[1] == 0:
+            assert float(step.T[r]) == 1.0 and np.all(host(step.C[r]) == 0)
+            continue
+        feat = oracle.encode_fwd(hm[0]["grid"], hm[0]["table"], u)
+        sig, rgb = oracle.mlp_fwd(hm[0]["mlp"], hm[0]["weights"].astype(np.float64), feat, oracle.sh(d[ray], 4), 1)
+        Cs, Ts = oracle.composite_fwd_ragged(sig, rgb, delta.astype(np.float64), f1)
+        assert rel_err(host(step.sigma[sl]), sig) <= TOL_F16
+        assert rel_err(host(step.C[r]), Cs[0], floor=1e-3) <= TOL_F16
+        assert abs(float(step.T[r]) - Ts[0]) <= TOL_F16
+        checked += 1
+    assert checked > 30
+
+    # (b) properties that hold at any size
+    seg_ray = host(step.seg_ray[:n_seg])
+    np.testing.assert_array_equal(host(step.sample_ray[:N]), np.repeat(seg_ray, counts))       # samples are segment-major
+    some = np.random.default_rng(1).choice(N, 20000, replace=False)
+    cells = oracle.occ_cell(q["grid"], host(step.u[:N])[some])
+    assert np.all((q["bits"][cells >> 5] >> (cells & 31)) & 1)                                 # every kept sample is in an occupied cell
+    lens = seg_t[seg_ray, 0, 1] - seg_t[seg_ray, 0, 0]
+    width = host(step.delta[:N])
+    assert np.all(width <= np.float32(q["dt"]) * (1 + 1e-6))                                   # strata no wider than the marching step
+    np.testing.assert_allclose(width[first[:-1][counts > 0]], (lens / np.ceil(lens / q["dt"]))[counts > 0], rtol=1e-4)
+    m = gm[0]
+    L = m.grid.n_levels
+    dfeat = step.dfeat[:N].reshape(L, N, 2).double()
+    dtab = m.dtable.double()
+    probe = torch.rand_like(m.table) - 0.5
+    f2 = torch.zeros(L, N, 2, device=DEV)
+    B.dg_hashgrid_encode_fwd(m.grid, probe, step.u[:N], N, f2)
+    lhs = float((dfeat * f2.double()).sum()); rhs = float((dtab * probe.double()).sum())
+    mag = float((dfeat.abs() * f2.double().abs()).sum())
+    assert abs(lhs - rhs) <= TOL_F16 * mag                                                     # transpose identity of the encode
+    miss = torch.nonzero(step.seg_count == 0).flatten()
+    assert bool((step.T[miss] == 1).all()) and bool((step.C[miss] == 0).all())
