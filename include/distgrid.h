@@ -151,7 +151,7 @@ int dg_hashgrid_corner_indices(const dg_grid_desc *desc, const float *u, uint64_
                                uint32_t *idx, void *stream);
 
 /* ------------------------------------------------------------------------------------
- * Field MLPs (Sec. 3.2 "shallow MLP"; Sec. 5.1: sigmoid hidden activation in the colour
+ * Field MLPs (Sec. 3.2: a small MLP fuses the level features; Sec. 5.1: sigmoid hidden activation in the colour
  * net, outputs of both nets clipped to [-15,15] before the output activations).
  *   density: feat[n_feat] -> n_hidden_d (ReLU) -> geo[n_geo];  sigma = exp(clip(geo[0]))
  *   colour : [geo | dir_enc] -> n_hidden_c (act_c) [-> n_hidden_c (act_c)] -> 3;
@@ -198,8 +198,8 @@ int dg_composite_segment_fwd(const float *sigma, const float *rgb, const float *
                              uint32_t n_seg, uint32_t S, const uint32_t *seg_ray,
                              const uint32_t *seg_slot, uint32_t k_max, float *Ck, float *Tk,
                              void *stream);
-/* Depth for evaluation rendering (Sec. 4.4.2: the partial results are merged into "the final color, depth, and
- * transmittance"): D_k = sum_i T_i alpha_i t_i with the weights above, t [n_seg*S] the sample distances from
+/* Depth for evaluation rendering (Sec. 4.4.2: the sub-models' partial results are merged into colour, depth and
+ * transmittance of the ray): D_k = sum_i T_i alpha_i t_i with the weights above, t [n_seg*S] the sample distances from
  * dg_sample_segments; written to Dk [R,k_max] at the segment's (ray, slot). */
 int dg_composite_segment_depth(const float *sigma, const float *delta, const float *t, uint32_t n_seg, uint32_t S,
                                const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t k_max, float *Dk,

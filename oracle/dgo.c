@@ -318,7 +318,7 @@ void dgo_sh(const float *d, uint64_t n, uint32_t degree, double *out)
 }
 
 /* ------------------------------------------------------------------ */
-/* Field MLPs (Sec. 3.2 "shallow MLP"; Sec. 5.1 activations and clip)  */
+/* Field MLPs (Sec. 3.2: a small fusing MLP; Sec. 5.1 activations, clip) */
 /* ------------------------------------------------------------------ */
 
 double dgo_round_f16(double x)

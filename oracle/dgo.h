@@ -119,7 +119,7 @@ void dgo_merge_bwd(const double *Ck, const double *Tk, const uint32_t *seg_count
 double dgo_loss(const double *C, const double *T, const double *Cgt, uint32_t R, double lambda1,
                 double *gC, double *gT);
 
-/* Depth for evaluation rendering (Sec. 4.4.2: "final color, depth, and transmittance"): per segment
+/* Depth for evaluation rendering (Sec. 4.4.2: colour, depth and transmittance are merged from the partial results): per segment
  * D_k = sum_i T_i alpha_i t_i, merged as D = sum_k (prod_{j<k} T_j) D_k, i.e. like colour under Eq. 5. */
 void dgo_composite_depth(const double *sigma, const double *delta, const double *t, uint32_t n_seg, uint32_t S,
                          double *D);
