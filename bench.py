@@ -189,6 +189,19 @@ def main():
                      "touched_fraction": round(touched / n_param, 4), "algorithmic_bytes": moved,
                      "GB/s": round(moved / (ms * 1e-3) / 1e9, 1), "frac_hbm": round(moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
+    # evaluation rendering (forward only: colour, depth, transmittance; Sec. 4.4.2), apart from the metric
+    evaluation = None
+    if foreign is None:
+        step.timings = None
+        step.render(od, dd)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(3):
+            step.render(od, dd)
+        torch.cuda.synchronize()
+        ev_ms = 1e3 * (time.perf_counter() - t1) / 3
+        evaluation = {"ms_per_batch": round(ev_ms, 4), "rays_per_s": round(R / (ev_ms * 1e-3), 1), "outputs": "colour, depth, transmittance"}
+
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -252,7 +265,7 @@ def main():
                    "samples": n_samples, "levels": g["L"], "features": g["F"], "log2_T": g["log2_T"],
                    "partitions_resident": len(resident), "mlp_operands": "f16, f32 accumulate"},
         "samples_per_s": round(n_samples / (ms_per_step * 1e-3), 1),
-        "roofline": roofline, "kernels": others, "ms_per_call": breakdown, "optimiser": optimiser, "occupancy_refresh": refresh,
+        "roofline": roofline, "kernels": others, "ms_per_call": breakdown, "optimiser": optimiser, "occupancy_refresh": refresh, "evaluation": evaluation,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -276,7 +276,8 @@ class TrainStep:
     # -- occupancy refresh (Sec. 5.1; Instant-NGP App. E.2) -------------------------------------
     def refresh_occupancy(self, iteration, tries=32):
         """Decay, candidate cells, the field's density at a random point of each, maximum, new bits -- when the
-        schedule asks for it at this iteration.  Candidates are produced in pieces that fit the sample buffers."""
+        schedule asks for it at this iteration.  Candidates are produced in pieces that fit the sample buffers, which
+        serve as scratch: call it between training steps, not between a forward and its backward pass."""
         update_now, warmup, decay, threshold = B.dg_occ_schedule(iteration)
         if not update_now:
             return False
