@@ -128,6 +128,16 @@ __device__ __forceinline__ float fast_sigmoid(float x)
 }
 __device__ __forceinline__ float clip15(float x) { return fminf(fmaxf(x, -15.0f), 15.0f); }
 
+// max(x, 0) on four pairs of halves, one instruction per pair
+__device__ __forceinline__ h8 relu_pairs(h8 x)
+{
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    u4 w = __builtin_bit_cast(u4, x);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) asm("v_pk_max_f16 %0, %1, 0" : "=v"(w[i]) : "v"(w[i]));
+    return __builtin_bit_cast(h8, w);
+}
+
 // registers 8p .. 8p+7 of a result tile, activated, rounded to fp16 and packed: k-step (m, p) of the next operand
 template <int ACT>   // 0 identity, 1 ReLU, 2 sigmoid
 __device__ __forceinline__ h8 pack_half(const f16v &c, int p)
@@ -136,10 +146,11 @@ __device__ __forceinline__ h8 pack_half(const f16v &c, int p)
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         float v = c[8 * p + j];
-        if (ACT == 1) v = fmaxf(v, 0.0f);
         if (ACT == 2) v = fast_sigmoid(v);
         out[j] = (_Float16)v;
     }
+    // ReLU after the rounding gives the same values as before it (rounding is monotone and keeps 0) and works on pairs
+    if (ACT == 1) out = relu_pairs(out);
     return out;
 }
 
