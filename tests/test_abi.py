@@ -115,3 +115,10 @@ def test_optimiser_host_side():
     assert L.dg_adam_step(*args(0, 1)) == 0                 # nothing to do
     assert L.dg_adam_step(*args(8, 1)) == -1                # null pointers
     assert b"null" in L.dg_last_error()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0 and "ONE GPU" in res.stderr
