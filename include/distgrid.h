@@ -139,10 +139,11 @@ int dg_hashgrid_encode_fwd(const dg_grid_desc *desc, const float *table, const f
  * fixed.  dfeat [L, N, F] fp32 device (level-major planes); dtable "+=".
  * With ws == NULL every contribution is a global fp32 atomic (after merging lanes that share a cell).
  * With a workspace of dg_hashgrid_encode_bwd_workspace_bytes(desc, N) bytes the contributions are
- * binned by table region and summed in on-chip memory first (much faster for large N); ws must be
- * 256-byte aligned; a smaller workspace is accepted and makes the call run in batches,
- * DG_ERR_WORKSPACE if it cannot hold one tile of 512 samples (20 bytes per sample, level and pair of
- * corners, plus bookkeeping). */
+ * binned by table region and summed in on-chip memory first (much faster for large N); on that path a
+ * contribution is rounded to 18 mantissa bits (relative error at most 2^-20, unbiased) before it is
+ * summed exactly.  ws must be 256-byte aligned; a smaller workspace is accepted and makes the call run
+ * in batches, DG_ERR_WORKSPACE if it cannot hold one tile of 512 samples (16 bytes per sample, level
+ * and pair of corners, plus bookkeeping). */
 size_t dg_hashgrid_encode_bwd_workspace_bytes(const dg_grid_desc *desc, uint64_t N);
 int dg_hashgrid_encode_bwd(const dg_grid_desc *desc, const float *u, const float *dfeat,
                            uint64_t N, float *dtable, void *ws, size_t ws_bytes, void *stream);

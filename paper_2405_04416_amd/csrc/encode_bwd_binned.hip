@@ -25,7 +25,7 @@ constexpr int kChunkLog2 = 13;
 constexpr uint32_t kChunk = 1u << kChunkLog2;      // entries per bin
 constexpr int kMaxBins = 2048;                     // per level: 2^24 entries / 8192
 constexpr int kTile = 512;                         // samples per tile == threads per binning workgroup
-constexpr int kWriters = 128;                      // narrow fill sweep: threads that only copy staged records to the queues
+constexpr int kKeeper = 64;                        // narrow fill sweep: one more wavefront, which keeps the books of the 64 bins
 constexpr int kPairs = kTile * 4;                  // records staged per (tile, level): one per pair of corners along x
 constexpr uint32_t kLdsKeys = 4096;                // count sweep: (level, bin) counters kept in LDS when there are at most this many
 constexpr int kBinGrid = 768;                      // persistent binning workgroups (three per compute unit)
@@ -112,12 +112,50 @@ coarse_kernel(dg_grid_desc g, uint32_t first_level, const float *__restrict__ u,
 // added to the table directly with global atomics; both sweeps see exactly four records per emitting
 // sample and level.
 
-// A queue record: 5 words, (entry of corner 0 | entry of corner 1 << 16, both within the bin), then the 4 values.
-// One array of 20-byte records: a record is one 16-byte and one 4-byte access to the same cache line, and a run
-// of records is one contiguous piece of memory.
-constexpr int kRecordWords = 5;
+// A queue record is 16 bytes: the entry of corner 0 within the bin (13 bits), how corner 1's entry differs from it (4
+// bits: the two differ in their k low bits, all of them -- x and x + 1 do, and both index forms keep that: a sum of
+// x with multiples of the resolution, or an exclusive-or of x with hashes of y and z) and the pair's four values as
+// 27-bit floats (sign, 8 exponent bits, 18 mantissa bits: fp32 rounded to nearest even at bit 5, relative error at
+// most 2^-20 per value, unbiased).  Sixteen bytes because eight of them make one 128-byte cache line: the narrow fill
+// sweep appends in multiples of 8 records, so every append starts on a line boundary and covers whole lines; what
+// does not fill a granule yet waits in LDS.  (With 20-byte records of fp32 values, probes of the store side alone
+// measured 3.0 ms for 9.1 GB appended as it comes and 1.8 ms in whole lines; the fifth word, kept in a stream of its
+// own, cost 2.5 times its share because its appends were fractions of a line.)
+constexpr uint32_t kGran = 8;                         // append granule of the narrow fill sweep, in records
+constexpr uint32_t kSliceRound = kGran;               // a workgroup's slice of a bin is padded to this many records (zero records)
+
+// fp32 -> nearest value with 18 mantissa bits (ties to even), still as fp32
+__device__ __forceinline__ float round_record_value(float v)
+{
+    const uint32_t b = __float_as_uint(v);
+    return __uint_as_float((b + 0xfu + (b >> 5 & 1u)) & 0xffffffe0u);
+}
+
+// k such that eb == ea ^ (2^k - 1), or 15 when the two do not differ that way (ea, eb < 2^13)
+__device__ __forceinline__ uint32_t pair_code(uint32_t ea, uint32_t eb)
+{
+    const uint32_t x = ea ^ eb, k = 32u - (uint32_t)__clz((int)x);       // __clz(0) == 32
+    return x == (1u << k) - 1u ? k : 15u;
+}
+
+// (entry of corner 0 < 2^13, pair_code < 15, four values already rounded by round_record_value) <-> record.
+// x: entry, code and the low 15 bits of value 3; y, z, w: values 0..2 in the low 27 bits, more bits of value 3 above.
+__device__ __forceinline__ uint4 pack_record(uint32_t ea, uint32_t code, float v0, float v1, float v2, float v3)
+{
+    const uint32_t q0 = __float_as_uint(v0) >> 5, q1 = __float_as_uint(v1) >> 5, q2 = __float_as_uint(v2) >> 5, q3 = __float_as_uint(v3) >> 5;
+    return make_uint4(ea | code << 13 | q3 << 17, q0 | (q3 >> 15) << 27, q1 | (q3 >> 20) << 27, q2 | (q3 >> 25) << 27);
+}
+template <typename R>
+__device__ __forceinline__ void unpack_record(const R &r, uint32_t &ea, uint32_t &eb, float &v0, float &v1, float &v2, float &v3)
+{
+    ea = r.x & (kChunk - 1u);
+    eb = ea ^ ((1u << (r.x >> 13 & 15u)) - 1u);
+    v0 = __uint_as_float(r.y << 5);
+    v1 = __uint_as_float(r.z << 5);
+    v2 = __uint_as_float(r.w << 5);
+    v3 = __uint_as_float((r.x >> 17 | (r.y >> 27) << 15 | (r.z >> 27) << 20 | (r.w >> 27) << 25) << 5);
+}
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef u32x4 __attribute__((aligned(4))) u32x4_unaligned;
 
 // Which records a sample emits at a level (both sweeps take the same decision from the same data).  A
 // wavefront holds 64 consecutive samples of a ray; lanes that share a cell form a run whose 16 values are
@@ -253,6 +291,16 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v)
     return v;
 }
 
+// inclusive running maximum over the wavefront, same moves (a lane that receives nothing takes 0)
+__device__ __forceinline__ uint32_t wave_inclusive_max(uint32_t v)
+{
+#define DG_MAX_STEP(CTRL, ROW_MASK) v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, true))
+    DG_MAX_STEP(0x111, 0xF); DG_MAX_STEP(0x112, 0xF); DG_MAX_STEP(0x114, 0xF); DG_MAX_STEP(0x118, 0xF);
+    DG_MAX_STEP(0x142, 0xA); DG_MAX_STEP(0x143, 0xC);
+#undef DG_MAX_STEP
+    return v;
+}
+
 // Fill sweep.  Per step (one tile at one level): every emitting lane takes a rank in its records' bins (LDS
 // counters), the counters are scanned into staging offsets, the records are staged in LDS sorted by bin and then
 // copied to the queues, so that every bin receives contiguous runs.  A workgroup goes level after level, and
@@ -274,7 +322,8 @@ __device__ __forceinline__ void load_ahead(StepAhead &a, const float *__restrict
     a.g = dfeat[(size_t)l * N + n];
 }
 
-// values of the 8 corners of one sample at one level, runs merged where the emission says so; `largest` follows the
+// values of the 8 corners of one sample at one level, runs merged where the emission says so, rounded to what a record
+// carries; `largest` follows the
 // largest magnitude (as the bit pattern of |v|, which orders like the value) of anything a lane emits
 __device__ __forceinline__ void corner_values(const Emission &em, float2 gfe, float (&vx)[8], float (&vy)[8], uint32_t &largest)
 {
@@ -286,6 +335,8 @@ __device__ __forceinline__ void corner_values(const Emission &em, float2 gfe, fl
     if (em.emit) {
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
+            vx[c] = round_record_value(vx[c]);      // what a record can carry; the few values that go to the table directly take the same form
+            vy[c] = round_record_value(vy[c]);
             largest = max(largest, __float_as_uint(vx[c]) & 0x7fffffffu);
             largest = max(largest, __float_as_uint(vy[c]) & 0x7fffffffu);
         }
@@ -305,127 +356,245 @@ __device__ __forceinline__ void publish_largest(uint32_t largest, uint32_t *word
     if (threadIdx.x == 0 && *word) atomicMax(dst, *word);
 }
 
-// stage the record of pair p in slot s; it will go to queue position qpos
-__device__ __forceinline__ void stage_pair(uint4 *stage0, uint2 *stage1, uint32_t s, uint32_t qpos, const Emission &em, int p,
-                                           const float (&vx)[8], const float (&vy)[8], uint32_t level_offset, float *__restrict__ dtable)
+// the record of pair p; a pair that straddles a bin boundary (or, against every expectation, differs in some other way
+// than a record can say) keeps corner 0 only and its corner 1 goes to the table directly
+__device__ __forceinline__ uint4 make_record(const Emission &em, int p, const float (&vx)[8], const float (&vy)[8], uint32_t level_offset,
+                                             float *__restrict__ dtable)
 {
     const uint32_t ea = em.e[2 * p], eb = em.e[2 * p + 1];
-    const bool together = (ea >> kChunkLog2) == (eb >> kChunkLog2);
-    const uint32_t pair = (ea & (kChunk - 1u)) | (((together ? eb : ea) & (kChunk - 1u)) << 16);
-    stage0[s] = make_uint4(qpos, pair, __float_as_uint(vx[2 * p]), __float_as_uint(vy[2 * p]));
-    stage1[s] = together ? make_uint2(__float_as_uint(vx[2 * p + 1]), __float_as_uint(vy[2 * p + 1])) : make_uint2(0u, 0u);
-    if (!together) {           // the pair straddles a bin boundary: corner 1 goes to the table directly
+    uint32_t code = pair_code(ea & (kChunk - 1u), eb & (kChunk - 1u));
+    const bool together = (ea >> kChunkLog2) == (eb >> kChunkLog2) && code != 15u;
+    if (!together) {
+        code = 0u;
         float *dst = dtable + 2 * ((size_t)level_offset + eb);
         if (vx[2 * p + 1] != 0.0f) unsafeAtomicAdd(dst, vx[2 * p + 1]);
         if (vy[2 * p + 1] != 0.0f) unsafeAtomicAdd(dst + 1, vy[2 * p + 1]);
     }
+    return pack_record(ea & (kChunk - 1u), code, vx[2 * p], vy[2 * p], together ? vx[2 * p + 1] : 0.0f, together ? vy[2 * p + 1] : 0.0f);
 }
 
-// copy staged records [0, total) to their queue positions; `n_threads` threads (this one is `t`) share the work,
-// four records per thread in flight, reads clamped so they batch
-__device__ __forceinline__ void copy_out(const uint4 *stage0, const uint2 *stage1, uint32_t total, uint32_t t, uint32_t n_threads,
-                                         uint32_t *__restrict__ queue)
+// wide sweep: copy staged records [0, total) to their queue positions; `n_threads` threads (this one is `t`) share the
+// work, four records per thread in flight, reads clamped so they batch
+__device__ __forceinline__ void copy_out(const uint4 *stage, const uint32_t *stage_pos, uint32_t total, uint32_t t, uint32_t n_threads,
+                                         uint4 *__restrict__ queue)
 {
     for (uint32_t sb = 0; sb < total; sb += 4 * n_threads) {
-        uint4 r0[4];
-        uint2 r1[4];
+        uint4 rec[4];
+        uint32_t at[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const uint32_t s = min(sb + t + k * n_threads, total - 1u);
-            r0[k] = stage0[s];
-            r1[k] = stage1[s];
+            rec[k] = stage[s];
+            at[k] = stage_pos[s];
         }
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if (sb + t + k * n_threads < total) {
-                uint32_t *rec = queue + (size_t)r0[k].x * kRecordWords;
-                *reinterpret_cast<u32x4_unaligned *>(rec) = u32x4{r0[k].y, r0[k].z, r0[k].w, r1[k].x};
-                rec[4] = r1[k].y;
-            }
-        }
+        for (int k = 0; k < 4; ++k)
+            if (sb + t + k * n_threads < total) queue[at[k]] = rec[k];
     }
 }
 
 // Fill sweep for grids with at most 64 bins in every level.  kTile threads bin the samples; every one of their
-// wavefronts reads the 64 step counters and scans them itself, so staging offsets and queue cursors sit in one
-// register per lane (lane == bin) and are fetched with wavefront shuffles: two barriers per step.  The counters are
-// double-buffered so that the buffer of the next step is cleared while this step is staged; the queue cursors live
-// in LDS.  kWriters more threads do nothing but copy each staged step to the queues while the others already bin
-// the next step: they never wait for a load, so their stores drain in the background instead of stalling the
-// wavefronts that compute (a wavefront that mixes both waits for its stores whenever it waits for a load).
-__global__ void __launch_bounds__(kTile + kWriters)
+// wavefronts reads the 64 step counters and scans them itself, so the staging offsets sit in one register per lane
+// (lane == bin) and are fetched with wavefront shuffles.  The counters are double-buffered so that the buffer of the
+// next step is cleared while this step is staged.  One more wavefront keeps the books (lane == bin): the queue
+// position of every bin and the records that do not fill an append granule yet (up to 7 per bin, kept in LDS behind
+// the staged ones).  While the others stage a step, it works
+// out from the step's counters what every bin appends (whole granules) and publishes that; after the second barrier
+// all wavefronts copy the appends out, consecutive threads writing consecutive records of a bin, so that a store
+// instruction covers whole cache lines; after a third barrier the book-keeping wavefront moves what is left of the
+// step into the waiting slots while the others already rank the next step.  At the end of a level it writes the
+// waiting records out and pads this workgroup's slice of each bin to kSliceRound records with zero records, which add
+// nothing.
+__device__ __forceinline__ uint32_t lane_value(uint32_t v, uint32_t lane) { return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)lane); }
+
+constexpr uint32_t kCarry = kGran - 1;
+// append granules a step can hold: its records plus what waits in the 64 bins
+constexpr uint32_t kOwner = ((kPairs + 64 * kCarry) / kGran + 1 + 3) / 4 * 4;
+constexpr int kNarrowThreads = kTile + kKeeper;
+constexpr int kNarrowLds = 128 * 4 + (kPairs + 64 * (int)kCarry) * 16 + 64 * 8 + 16 + (int)kOwner;
+
+// K outputs per thread, all reads of a stage issued before the first is used.  Output f of the step belongs to the bin
+// owner[f / kGran]; it is record j = f - before of the bin's append: one that waited while j < waiting, else a staged
+// one (the waiting records lie behind the staged ones).  bin_info[bin] = (before | waiting << 12 | first
+// staging slot of the bin's fresh records << 16, queue position of the append).  Threads past the end repeat the last
+// output (same value to the same place): no branch.  `total` must be positive.
+template <int K>
+__device__ __forceinline__ void copy_outputs(uint32_t base, uint32_t total, uint32_t tid, const uint8_t *owner, const uint2 *bin_info,
+                                             const uint4 *stage, uint4 *__restrict__ queue)
+{
+    uint32_t f[K], o[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        f[k] = min(base + k * kNarrowThreads + tid, total - 1u);
+        o[k] = owner[f[k] / kGran];
+    }
+    uint2 info[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) info[k] = bin_info[o[k]];
+    uint32_t src[K], dst[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t j = f[k] - (info[k].x & 4095u), waiting = info[k].x >> 12 & 15u, slot0 = info[k].x >> 16;
+        const uint32_t staged = slot0 + j - waiting, waited = kPairs + o[k] * kCarry + j;
+        const uint32_t pick = 0u - (uint32_t)(j < waiting);           // all ones: take the waiting record
+        src[k] = staged ^ ((staged ^ waited) & pick);
+        dst[k] = info[k].y + j;
+    }
+    uint4 rec[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) rec[k] = stage[src[k]];
+#pragma unroll
+    for (int k = 0; k < K; ++k) queue[dst[k]] = rec[k];
+}
+
+// the step's appends -> queues, by all threads of the workgroup (the trip counts are the same for all)
+__device__ __forceinline__ void copy_step(uint32_t total, uint32_t tid, const uint8_t *owner, const uint2 *bin_info, const uint4 *stage,
+                                          uint4 *__restrict__ queue)
+{
+    for (uint32_t base = 0; base < total;) {
+        const uint32_t rounds = (total - base + kNarrowThreads - 1) / kNarrowThreads;
+#define DG_COPY(K) copy_outputs<K>(base, total, tid, owner, bin_info, stage, queue)
+        if (rounds >= 4) { DG_COPY(4); base += 4 * kNarrowThreads; }
+        else if (rounds == 3) { DG_COPY(3); break; }
+        else if (rounds == 2) { DG_COPY(2); break; }
+        else { DG_COPY(1); break; }
+#undef DG_COPY
+    }
+}
+
+__global__ void __launch_bounds__(kNarrowThreads, 7)     // three workgroups of nine wavefronts per compute unit: seven wavefronts per SIMD
 fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
                    uint64_t n0, uint64_t nb, const uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
-                   uint32_t *__restrict__ queue, float *__restrict__ dtable, uint32_t *__restrict__ largest_out)
+                   uint4 *__restrict__ queue, float *__restrict__ dtable, uint32_t *__restrict__ largest_out)
 {
     extern __shared__ uint32_t smem[];
     uint32_t *cnt = smem;                                             // [2][64] records per bin of the step
-    uint32_t *staged = cnt + 128;                                     // [2] records of the step (+ 2 words of padding)
-    uint32_t *row = staged + 4;                                       // [n_keys] this workgroup's queue cursors
-    uint4 *stage0 = reinterpret_cast<uint4 *>(row + (plan.n_keys + 3u) / 4u * 4u);      // [kPairs] queue position, entry pair, 2 values
-    uint2 *stage1 = reinterpret_cast<uint2 *>(stage0 + kPairs);                         // [kPairs] 2 values
+    uint4 *stage = reinterpret_cast<uint4 *>(cnt + 128);              // [kPairs] records of the step, sorted by bin
+    uint4 *carry = stage + kPairs;                                    // [64][kCarry] what waits, per bin
+    uint2 *bin_info = reinterpret_cast<uint2 *>(carry + 64 * kCarry);              // [64] see copy_outputs
+    uint32_t *total_out = reinterpret_cast<uint32_t *>(bin_info + 64);             // [1] outputs of the step (+ 3 unused)
+    uint8_t *owner = reinterpret_cast<uint8_t *>(total_out + 4);      // [kOwner] bin of each granule of the step
     const uint32_t tid = threadIdx.x;
-    const bool writer = tid >= (uint32_t)kTile;                       // whole wavefronts: kTile is a multiple of 64
-    const int lane = tid % dg::kWave;
+    const bool keeper = tid >= (uint32_t)kTile;                       // the last wavefront: kTile is a multiple of 64
+    const uint32_t lane = tid % dg::kWave;
     const uint32_t mask = (1u << g.log2_T) - 1u;
     const uint32_t *row_global = rows + (size_t)blockIdx.x * plan.n_keys;
-    for (uint32_t i = tid; i < plan.n_keys; i += kTile + kWriters) row[i] = binbase[i] + row_global[i];
     if (tid < 128) cnt[tid] = 0u;
     __syncthreads();
     uint32_t parity = 0, largest = 0;
     const uint64_t n_tiles = (nb + kTile - 1) / kTile;
+    const bool has_work = blockIdx.x < n_tiles;
+
+    if (keeper) {
+        // lane b keeps the books of bin b: where its next append goes and how many records wait
+        uint32_t pos = 0, waiting = 0;
+        const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
+        for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
+            const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
+            const bool mine = lane < n_bins;
+            if (mine) pos = binbase[key0 + lane] + row_global[key0 + lane];
+            for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x, parity ^= 1u) {
+                __syncthreads();                                     // ranks taken
+                // from what waits and what is fresh: how much goes out (whole granules) and how much is left; the
+                // granules of all bins laid end to end, with a table of which bin owns each
+                const uint32_t fresh = cnt[64u * parity + lane];
+                const uint32_t slot0 = wave_inclusive_scan(fresh) - fresh;
+                const uint32_t have = waiting + fresh, out = have & ~(kGran - 1u), left = have - out;
+                const uint32_t incl = wave_inclusive_scan(out), before = incl - out;
+                const uint32_t total = lane_value(incl, dg::kWave - 1);
+                if (n_bins > 16) {
+                    for (uint32_t q = 0; q < out / kGran; ++q) owner[before / kGran + q] = (uint8_t)lane;
+                } else {
+                    // few bins, long appends: every bin marks its first granule, a running maximum spreads the marks
+                    // (bins come in rising order; bin 0 is what an unmarked granule reads)
+                    const uint32_t n_gran = total / kGran;
+                    for (uint32_t g0 = 0; g0 < n_gran; g0 += dg::kWave)
+                        if (g0 + lane < n_gran) owner[g0 + lane] = 0;
+                    if (out) owner[before / kGran] = (uint8_t)lane;
+                    uint32_t run = 0;
+                    for (uint32_t g0 = 0; g0 < n_gran; g0 += dg::kWave) {
+                        const uint32_t v = max(run, wave_inclusive_max(g0 + lane < n_gran ? owner[g0 + lane] : 0u));
+                        if (g0 + lane < n_gran) owner[g0 + lane] = (uint8_t)v;
+                        run = lane_value(v, dg::kWave - 1);
+                    }
+                }
+                bin_info[lane] = make_uint2(before | waiting << 12 | slot0 << 16, pos);
+                if (lane == 0) *total_out = total;
+                __syncthreads();                                     // step staged, plan published
+                copy_step(total, tid, owner, bin_info, stage, queue);
+                __syncthreads();                                     // everything that waited has been read
+                // What is left of the step's records waits from here on.  Nothing went out (out == 0): the fresh ones
+                // queue up behind the waiting ones; else all that waited has left and the tail of the fresh ones waits.
+                // A value that does not move is written back to where it was read: straight-line code, no branch per
+                // record; all reads first, then all writes (named values for the 16-byte ones: an array of them ends
+                // up in scratch memory here).
+                {
+                    const uint32_t from = out == 0u ? slot0 : slot0 + (out - waiting), to = kPairs + lane * kCarry + (out == 0u ? waiting : 0u);
+                    const uint32_t n_move = out == 0u ? fresh : left;
+                    static_assert(kCarry == 7, "the moves below are written out for seven waiting records");
+#define DG_FROM(j) min(from + j##u, (uint32_t)kPairs - 1u)
+                    const uint4 r0 = stage[DG_FROM(0)], r1 = stage[DG_FROM(1)], r2 = stage[DG_FROM(2)], r3 = stage[DG_FROM(3)];
+                    const uint4 r4 = stage[DG_FROM(4)], r5 = stage[DG_FROM(5)], r6 = stage[DG_FROM(6)];
+#define DG_MOVE(j) stage[j##u < n_move ? to + j##u : DG_FROM(j)] = r##j
+                    DG_MOVE(0); DG_MOVE(1); DG_MOVE(2); DG_MOVE(3); DG_MOVE(4); DG_MOVE(5); DG_MOVE(6);
+#undef DG_MOVE
+#undef DG_FROM
+                    pos += out;
+                    waiting = left;
+                }
+            }
+            // end of the level: what still waits goes out, followed by zero records up to the padded end of the slice
+            if (mine) {
+                const uint32_t end = (pos + waiting + kSliceRound - 1u) / kSliceRound * kSliceRound;
+                for (uint32_t j = 0; pos + j < end; ++j) queue[pos + j] = j < waiting ? carry[lane * kCarry + j] : zero4;
+            }
+            waiting = 0u;
+        }
+        publish_largest(0u, cnt, largest_out);
+        return;
+    }
+
     StepAhead ahead = {{0.0f, 0.0f, 0.0f}, make_float2(0.0f, 0.0f)};
-    if (!writer && blockIdx.x < n_tiles) load_ahead(ahead, u, dfeat, N, n0, nb, blockIdx.x, plan.first_level, tid);
+    if (has_work) load_ahead(ahead, u, dfeat, N, n0, nb, blockIdx.x, plan.first_level, tid);
     for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
-        const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
         const LevelGeom lv = level_of(g, l);
         for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x, parity ^= 1u) {
             uint32_t *c_cur = cnt + 64u * parity;
-            if (writer) {
-                __syncthreads();                                     // ranks taken
-                __syncthreads();                                     // step staged
-                copy_out(stage0, stage1, staged[parity], tid - kTile, kWriters, queue);
-                continue;                                            // the LDS reads are complete before the next barrier
-            }
             const bool live = tile * kTile + tid < nb;
             const float uu[3] = {ahead.u[0], ahead.u[1], ahead.u[2]};
             const float2 gfe = live ? ahead.g : make_float2(0.0f, 0.0f);
-            const Emission em = classify(lv, mask, uu, live, lane);
+            const Emission em = classify(lv, mask, uu, live, (int)lane);
             uint32_t rank[4];
             if (em.emit) {
 #pragma unroll
                 for (int p = 0; p < 4; ++p) rank[p] = atomicAdd(&c_cur[em.e[2 * p] >> kChunkLog2], 1u);
             }
-            __syncthreads();
-            // lane b: records of bin b in this step, their first staging slot, and the queue position of the first
-            const uint32_t in_bin = c_cur[lane];
-            const uint32_t incl = wave_inclusive_scan(in_bin);
-            const uint32_t first_slot = incl - in_bin;
-            const uint32_t cursor = (uint32_t)lane < n_bins ? row[key0 + lane] : 0u;
-            if (tid < dg::kWave) {
-                cnt[64u * (parity ^ 1u) + tid] = 0u;                 // the other buffer: last read two barriers ago
-                if (tid == dg::kWave - 1) staged[parity] = incl;     // read by the writers after the next barrier
-            }
             float vx[8], vy[8];
-            corner_values(em, gfe, vx, vy, largest);
-            uint32_t slot[4], qpos[4];        // staging slot and queue position of each record: (first of the bin) + rank
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const int bin = (int)(em.e[2 * p] >> kChunkLog2);
-                slot[p] = __shfl(first_slot, bin, dg::kWave);
-                qpos[p] = __shfl(cursor, bin, dg::kWave);
-            }
-            if (em.emit) {
-#pragma unroll
-                for (int p = 0; p < 4; ++p) stage_pair(stage0, stage1, slot[p] + rank[p], qpos[p] + rank[p], em, p, vx, vy, lv.offset, dtable);
-            }
+            corner_values(em, gfe, vx, vy, largest);                     // needs no rank: done while the books of the last step are closed
             __syncthreads();
+            // lane b: records of bin b in this step and their first staging slot
+            const uint32_t in_bin = c_cur[lane];
+            const uint32_t first_slot = wave_inclusive_scan(in_bin) - in_bin;
+            if (tid < dg::kWave) cnt[64u * (parity ^ 1u) + tid] = 0u;    // the other buffer: last read three barriers ago
+            // The next step's inputs are asked for here, not after the copy: the wait for them also waits for every
+            // store this wavefront has issued, and at this point the stores of the last copy have had time to land.
             {
                 const bool same_level = tile + gridDim.x < n_tiles;
                 const uint32_t l_next = same_level ? l : l + 1;
                 if (l_next < g.n_levels) load_ahead(ahead, u, dfeat, N, n0, nb, same_level ? tile + gridDim.x : blockIdx.x, l_next, tid);
             }
-            if (tid < n_bins) row[key0 + tid] = cursor + in_bin;    // every wavefront read its copy before the barrier
+            uint32_t slot[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) slot[p] = __shfl(first_slot, (int)(em.e[2 * p] >> kChunkLog2), dg::kWave);
+            if (em.emit) {
+#pragma unroll
+                for (int p = 0; p < 4; ++p) stage[slot[p] + rank[p]] = make_record(em, p, vx, vy, lv.offset, dtable);
+            }
+            // the inputs are taken in here, before this wavefront issues stores again (an empty statement that uses them)
+            asm volatile("" : "+v"(ahead.u[0]), "+v"(ahead.u[1]), "+v"(ahead.u[2]), "+v"(ahead.g.x), "+v"(ahead.g.y));
+            __syncthreads();
+            copy_step(*total_out, tid, owner, bin_info, stage, queue);
+            __syncthreads();
         }
     }
     publish_largest(largest, cnt, largest_out);
@@ -436,7 +605,7 @@ fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const
 __global__ void __launch_bounds__(kTile)
 fill_wide_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
                  uint64_t n0, uint64_t nb, uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
-                 uint32_t *__restrict__ queue, float *__restrict__ dtable, uint32_t *__restrict__ largest_out)
+                 uint4 *__restrict__ queue, float *__restrict__ dtable, uint32_t *__restrict__ largest_out)
 {
     extern __shared__ uint32_t smem[];
     const uint32_t cap = plan.max_bins;
@@ -444,8 +613,8 @@ fill_wide_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const f
     uint32_t *start = cnt + cap;                                      // [cap] first staging slot of each bin
     uint32_t *cursor = start + cap;                                   // [cap] queue position of each bin's first record
     uint32_t *wave_tot = cursor + cap;                                // [16]
-    uint4 *stage0 = reinterpret_cast<uint4 *>(wave_tot + 16);         // [kPairs] queue position, entry pair, 2 values
-    uint2 *stage1 = reinterpret_cast<uint2 *>(stage0 + kPairs);       // [kPairs] 2 values
+    uint4 *stage = reinterpret_cast<uint4 *>(wave_tot + 16);          // [kPairs] records of the step, sorted by bin
+    uint32_t *stage_pos = reinterpret_cast<uint32_t *>(stage + kPairs);            // [kPairs] their queue positions
     const uint32_t tid = threadIdx.x;
     const int lane = tid % dg::kWave;
     const uint32_t mask = (1u << g.log2_T) - 1u;
@@ -483,7 +652,8 @@ fill_wide_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const f
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
                     const uint32_t bin = em.e[2 * p] >> kChunkLog2;
-                    stage_pair(stage0, stage1, start[bin] + rank[p], cursor[bin] + rank[p], em, p, vx, vy, lv.offset, dtable);
+                    stage[start[bin] + rank[p]] = make_record(em, p, vx, vy, lv.offset, dtable);
+                    stage_pos[start[bin] + rank[p]] = cursor[bin] + rank[p];
                 }
             }
             __syncthreads();
@@ -492,18 +662,18 @@ fill_wide_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const f
                 const uint32_t l_next = same_level ? l : l + 1;
                 if (l_next < g.n_levels) load_ahead(ahead, u, dfeat, N, n0, nb, same_level ? tile + gridDim.x : blockIdx.x, l_next, tid);
             }
-            copy_out(stage0, stage1, total, tid, kTile, queue);
+            copy_out(stage, stage_pos, total, tid, kTile, queue);
             __syncthreads();
         }
     }
     publish_largest(largest, cnt, largest_out);
 }
 
-// rows[b][k] (per-workgroup counts) -> exclusive prefix over workgroups; totals[k].  A workgroup serves 32
-// keys; 32 groups of threads each take a contiguous stretch of the rows.
+// rows[b][k] (per-workgroup counts, each rounded up to a multiple of `round`) -> exclusive prefix over workgroups;
+// totals[k].  A workgroup serves 32 keys; 32 groups of threads each take a contiguous stretch of the rows.
 constexpr int kScanKeys = 32, kScanGroups = 32;
 __global__ void __launch_bounds__(kScanKeys * kScanGroups)
-scan_rows_kernel(uint32_t *__restrict__ rows, uint32_t n_rows, uint32_t n_keys, uint32_t *__restrict__ totals)
+scan_rows_kernel(uint32_t *__restrict__ rows, uint32_t n_rows, uint32_t n_keys, uint32_t round, uint32_t *__restrict__ totals)
 {
     __shared__ uint32_t part[kScanGroups][kScanKeys];
     const uint32_t col = threadIdx.x % kScanKeys, group = threadIdx.x / kScanKeys;
@@ -512,14 +682,14 @@ scan_rows_kernel(uint32_t *__restrict__ rows, uint32_t n_rows, uint32_t n_keys, 
     const uint32_t lo = min(group * per, n_rows), hi = min(lo + per, n_rows);
     uint32_t sum = 0;
     if (k < n_keys)
-        for (uint32_t b = lo; b < hi; ++b) sum += rows[(size_t)b * n_keys + k];
+        for (uint32_t b = lo; b < hi; ++b) sum += (rows[(size_t)b * n_keys + k] + round - 1u) / round * round;
     part[group][col] = sum;
     __syncthreads();
     if (k >= n_keys) return;
     uint32_t run = 0;
     for (uint32_t g = 0; g < group; ++g) run += part[g][col];
     for (uint32_t b = lo; b < hi; ++b) {
-        const uint32_t t = rows[(size_t)b * n_keys + k];
+        const uint32_t t = (rows[(size_t)b * n_keys + k] + round - 1u) / round * round;     // a slice is padded to whole granules
         rows[(size_t)b * n_keys + k] = run;
         run += t;
     }
@@ -577,7 +747,7 @@ __device__ __forceinline__ void add_fixed(unsigned long long *slot, float v, dou
 
 __global__ void __launch_bounds__(kAccBlock)
 accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbase, const uint32_t *__restrict__ blkbase,
-                  const uint32_t *__restrict__ queue, float *__restrict__ dtable)
+                  const u32x4 *__restrict__ queue, float *__restrict__ dtable)
 {
     // [2][kChunk] sums, one plane per feature: an add instruction then spreads over all LDS banks instead of every other pair
     extern __shared__ unsigned long long acc_tab[];
@@ -604,21 +774,18 @@ accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbas
     if (begin < end) {
         const size_t last = end - 1;
         for (size_t i0 = begin + threadIdx.x; i0 < end; i0 += kAccDepth * kAccBlock) {
-            u32x4 head[kAccDepth];       // entry pair, 3 values
-            uint32_t tail[kAccDepth];    // 4th value
+            u32x4 rec[kAccDepth];
 #pragma unroll
             for (int k2 = 0; k2 < kAccDepth; ++k2) {
                 const size_t want = i0 + (size_t)k2 * kAccBlock, i = want < last ? want : last;
-                const uint32_t *rec = queue + i * kRecordWords;
-                head[k2] = *reinterpret_cast<const u32x4_unaligned *>(rec);
-                tail[k2] = rec[4];
+                rec[k2] = queue[i];
             }
 #pragma unroll
             for (int k2 = 0; k2 < kAccDepth; ++k2) {
-                const bool ok = i0 + (size_t)k2 * kAccBlock < end;
-                const uint32_t ea = head[k2].x & 0xffffu, eb = head[k2].x >> 16;
-                const float v0 = __uint_as_float(ok ? head[k2].y : 0u), v1 = __uint_as_float(ok ? head[k2].z : 0u),
-                            v2 = __uint_as_float(ok ? head[k2].w : 0u), v3 = __uint_as_float(ok ? tail[k2] : 0u);
+                if (!(i0 + (size_t)k2 * kAccBlock < end)) rec[k2] = u32x4{0u, 0u, 0u, 0u};      // a clamped duplicate: the zero record
+                uint32_t ea, eb;
+                float v0, v1, v2, v3;
+                unpack_record(rec[k2], ea, eb, v0, v1, v2, v3);
                 add_fixed(&tab[ea], v0, scale);
                 add_fixed(&tab[kChunk + ea], v1, scale);
                 add_fixed(&tab[eb], v2, scale);
@@ -667,21 +834,26 @@ inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 struct Layout {
     size_t rows, totals, binbase, blkbase, queue, total;
     uint64_t batch;      // samples per batch
+    uint64_t records;    // queue capacity: the records of a batch plus the padding of the slices
 };
+
+// the narrow sweep pads every workgroup's slice of every bin to whole granules
+uint64_t slice_padding(const Plan &p) { return p.max_bins <= 64 ? (uint64_t)kBinGrid * p.n_keys * (kSliceRound - 1u) : 0ull; }
 
 // workspace layout for a batch of `batch` samples
 Layout make_layout(const dg_grid_desc *d, const Plan &p, uint64_t batch)
 {
     Layout L{};
-    const uint64_t records = batch * 4ull * (d->n_levels - p.first_level);
+    const uint64_t records = (batch * 4ull * (d->n_levels - p.first_level) + slice_padding(p) + 15ull) / 16ull * 16ull;
     size_t off = 0;
     L.rows = off; off = align256(off + (size_t)kBinGrid * p.n_keys * 4);
     L.totals = off; off = align256(off + (size_t)p.n_keys * 4);
     L.binbase = off; off = align256(off + (size_t)(p.n_keys + 2) * 4);      // + the largest record magnitude
     L.blkbase = off; off = align256(off + (size_t)(p.n_keys + 1) * 4);
-    L.queue = off; off = align256(off + records * kRecordWords * 4);
+    L.queue = off; off = align256(off + records * 16);
     L.total = off;
     L.batch = batch;
+    L.records = records;
     return L;
 }
 
@@ -689,7 +861,7 @@ uint64_t max_batch(const dg_grid_desc *d, const Plan &p)
 {
     const uint64_t per_sample = 4ull * (d->n_levels - p.first_level);
     if (per_sample == 0) return ~0ull;
-    return (0xffffffffull / per_sample) / kTile * kTile;           // record offsets stay below 2^32
+    return ((0xffffffffull - slice_padding(p) - 16ull) / per_sample) / kTile * kTile;           // record offsets stay below 2^32
 }
 
 }  // namespace dg_encode_binned
@@ -715,7 +887,7 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     const Plan p = make_plan(d);
     static bool lds_opt_in = false;
     if (!lds_opt_in) {
-        const int fill_lds = (3 * kMaxBins + 16) * 4 + kPairs * 24;      // the most a launch may ask for
+        const int fill_lds = (3 * kMaxBins + 16) * 4 + kPairs * 20;      // the most a launch may ask for (the wide sweep)
         const int acc_lds = 2 * kChunk * (int)sizeof(double);
         const hipError_t e[4] = {
             hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_wide_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds),
@@ -747,11 +919,11 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     uint32_t *totals = reinterpret_cast<uint32_t *>(base + L.totals);
     uint32_t *binbase = reinterpret_cast<uint32_t *>(base + L.binbase);
     uint32_t *blkbase = reinterpret_cast<uint32_t *>(base + L.blkbase);
-    uint32_t *queue = reinterpret_cast<uint32_t *>(base + L.queue);
+    uint4 *queue = reinterpret_cast<uint4 *>(base + L.queue);
     const size_t n_rows_words = (size_t)kBinGrid * p.n_keys;
     const bool narrow = p.max_bins <= 64;                 // then n_keys <= 64 * DG_MAX_LEVELS
     const bool count_in_lds = p.n_keys <= kLdsKeys;
-    const int fill_lds = (narrow ? 132 + ((int)p.n_keys + 3) / 4 * 4 : 3 * (int)p.max_bins + 16) * 4 + kPairs * 24;
+    const int fill_lds = narrow ? kNarrowLds : (3 * (int)p.max_bins + 16) * 4 + kPairs * 20;
 
     for (uint64_t n0 = 0; n0 < N; n0 += batch) {
         const uint64_t nb = N - n0 < batch ? N - n0 : batch;
@@ -761,17 +933,18 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
             zero_u32_kernel<<<(uint32_t)((n_rows_words + 255) / 256), 256, 0, st>>>(rows, n_rows_words);
             count_global_kernel<<<kBinGrid, kTile, p.max_bins * 4, st>>>(*d, p, u, n0, nb, rows);
         }
-        scan_rows_kernel<<<(p.n_keys + kScanKeys - 1) / kScanKeys, kScanKeys * kScanGroups, 0, st>>>(rows, kBinGrid, p.n_keys, totals);
+        scan_rows_kernel<<<(p.n_keys + kScanKeys - 1) / kScanKeys, kScanKeys * kScanGroups, 0, st>>>(rows, kBinGrid, p.n_keys,
+                                                                                                narrow ? kSliceRound : 1u, totals);
         scan_totals_kernel<<<1, 1024, 0, st>>>(totals, p.n_keys, binbase, blkbase);
         if (narrow)
-            fill_narrow_kernel<<<kBinGrid, kTile + kWriters, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, queue, dtable,
-                                                                             binbase + p.n_keys + 1);
+            fill_narrow_kernel<<<kBinGrid, kNarrowThreads, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, queue,
+                                                                             dtable, binbase + p.n_keys + 1);
         else
             fill_wide_kernel<<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, queue, dtable,
                                                                 binbase + p.n_keys + 1);
-        const uint64_t records = nb * 4ull * (d->n_levels - p.first_level);
+        const uint64_t records = nb * 4ull * (d->n_levels - p.first_level) + slice_padding(p);
         const uint32_t acc_grid = (uint32_t)(records / kAccRecords) + p.n_keys;       // upper bound of the workgroups needed
-        accumulate_kernel<<<acc_grid, kAccBlock, 2 * kChunk * sizeof(double), st>>>(*d, p, binbase, blkbase, queue, dtable);
+        accumulate_kernel<<<acc_grid, kAccBlock, 2 * kChunk * sizeof(double), st>>>(*d, p, binbase, blkbase, (const u32x4 *)queue, dtable);
     }
     return launch_status("dg_hashgrid_encode_bwd");
 }
