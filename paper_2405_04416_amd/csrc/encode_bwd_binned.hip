@@ -115,21 +115,14 @@ coarse_kernel(dg_grid_desc g, uint32_t first_level, const float *__restrict__ u,
 // A queue record is 16 bytes: the entry of corner 0 within the bin (13 bits), how corner 1's entry differs from it (4
 // bits: the two differ in their k low bits, all of them -- x and x + 1 do, and both index forms keep that: a sum of
 // x with multiples of the resolution, or an exclusive-or of x with hashes of y and z) and the pair's four values as
-// 27-bit floats (sign, 8 exponent bits, 18 mantissa bits: fp32 rounded to nearest even at bit 5, relative error at
-// most 2^-20 per value, unbiased).  Sixteen bytes because eight of them make one 128-byte cache line: the narrow fill
+// 27-bit floats (sign, 8 exponent bits, 18 mantissa bits: fp32 rounded to nearest at bit 5, relative error at most
+// 2^-20 per value, the same for both signs).  Sixteen bytes because eight of them make one 128-byte cache line: the narrow fill
 // sweep appends in multiples of 8 records, so every append starts on a line boundary and covers whole lines; what
 // does not fill a granule yet waits in LDS.  (With 20-byte records of fp32 values, probes of the store side alone
 // measured 3.0 ms for 9.1 GB appended as it comes and 1.8 ms in whole lines; the fifth word, kept in a stream of its
 // own, cost 2.5 times its share because its appends were fractions of a line.)
 constexpr uint32_t kGran = 8;                         // append granule of the narrow fill sweep, in records
 constexpr uint32_t kSliceRound = kGran;               // a workgroup's slice of a bin is padded to this many records (zero records)
-
-// fp32 -> nearest value with 18 mantissa bits (ties to even), still as fp32
-__device__ __forceinline__ float round_record_value(float v)
-{
-    const uint32_t b = __float_as_uint(v);
-    return __uint_as_float((b + 0xfu + (b >> 5 & 1u)) & 0xffffffe0u);
-}
 
 // k such that eb == ea ^ (2^k - 1), or 15 when the two do not differ that way (ea, eb < 2^13)
 __device__ __forceinline__ uint32_t pair_code(uint32_t ea, uint32_t eb)
@@ -138,11 +131,13 @@ __device__ __forceinline__ uint32_t pair_code(uint32_t ea, uint32_t eb)
     return x == (1u << k) - 1u ? k : 15u;
 }
 
-// (entry of corner 0 < 2^13, pair_code < 15, four values already rounded by round_record_value) <-> record.
+// (entry of corner 0 < 2^13, pair_code < 15, four values) <-> record.  A value keeps its top 27 bits, rounded to nearest
+// (half a unit is added to the magnitude before the cut: ties go away from zero, the same way for both signs).
 // x: entry, code and the low 15 bits of value 3; y, z, w: values 0..2 in the low 27 bits, more bits of value 3 above.
 __device__ __forceinline__ uint4 pack_record(uint32_t ea, uint32_t code, float v0, float v1, float v2, float v3)
 {
-    const uint32_t q0 = __float_as_uint(v0) >> 5, q1 = __float_as_uint(v1) >> 5, q2 = __float_as_uint(v2) >> 5, q3 = __float_as_uint(v3) >> 5;
+    const uint32_t q0 = (__float_as_uint(v0) + 16u) >> 5, q1 = (__float_as_uint(v1) + 16u) >> 5, q2 = (__float_as_uint(v2) + 16u) >> 5,
+                   q3 = (__float_as_uint(v3) + 16u) >> 5;
     return make_uint4(ea | code << 13 | q3 << 17, q0 | (q3 >> 15) << 27, q1 | (q3 >> 20) << 27, q2 | (q3 >> 25) << 27);
 }
 template <typename R>
@@ -322,8 +317,7 @@ __device__ __forceinline__ void load_ahead(StepAhead &a, const float *__restrict
     a.g = dfeat[(size_t)l * N + n];
 }
 
-// values of the 8 corners of one sample at one level, runs merged where the emission says so, rounded to what a record
-// carries; `largest` follows the
+// values of the 8 corners of one sample at one level, runs merged where the emission says so; `largest` follows the
 // largest magnitude (as the bit pattern of |v|, which orders like the value) of anything a lane emits
 __device__ __forceinline__ void corner_values(const Emission &em, float2 gfe, float (&vx)[8], float (&vy)[8], uint32_t &largest)
 {
@@ -333,13 +327,10 @@ __device__ __forceinline__ void corner_values(const Emission &em, float2 gfe, fl
     for (int c = 0; c < 8; ++c) { vx[c] = w[c] * gfe.x; vy[c] = w[c] * gfe.y; }
     if (em.merge) segmented_sum(vx, vy, em.head, em.heads);
     if (em.emit) {
+        float m = 0.0f;
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            vx[c] = round_record_value(vx[c]);      // what a record can carry; the few values that go to the table directly take the same form
-            vy[c] = round_record_value(vy[c]);
-            largest = max(largest, __float_as_uint(vx[c]) & 0x7fffffffu);
-            largest = max(largest, __float_as_uint(vy[c]) & 0x7fffffffu);
-        }
+        for (int c = 0; c < 8; ++c) m = fmaxf(m, fmaxf(fabsf(vx[c]), fabsf(vy[c])));
+        largest = max(largest, __float_as_uint(m));
     }
 }
 
@@ -411,21 +402,21 @@ constexpr uint32_t kCarry = kGran - 1;
 // append granules a step can hold: its records plus what waits in the 64 bins
 constexpr uint32_t kOwner = ((kPairs + 64 * kCarry) / kGran + 1 + 3) / 4 * 4;
 constexpr int kNarrowThreads = kTile + kKeeper;
-constexpr int kNarrowLds = 128 * 4 + (kPairs + 64 * (int)kCarry) * 16 + 64 * 8 + 16 + (int)kOwner;
+constexpr int kNarrowLds = 128 * 4 + (kPairs + 2 * 64 * (int)kCarry) * 16 + 64 * 8 + 16 + (int)kOwner;
 
 // K outputs per thread, all reads of a stage issued before the first is used.  Output f of the step belongs to the bin
 // owner[f / kGran]; it is record j = f - before of the bin's append: one that waited while j < waiting, else a staged
-// one (the waiting records lie behind the staged ones).  bin_info[bin] = (before | waiting << 12 | first
+// one (the waiting records lie behind the staged ones, from index `waited0` on).  bin_info[bin] = (before | waiting << 12 | first
 // staging slot of the bin's fresh records << 16, queue position of the append).  Threads past the end repeat the last
 // output (same value to the same place): no branch.  `total` must be positive.
 template <int K>
 __device__ __forceinline__ void copy_outputs(uint32_t base, uint32_t total, uint32_t tid, const uint8_t *owner, const uint2 *bin_info,
-                                             const uint4 *stage, uint4 *__restrict__ queue)
+                                             const uint4 *stage, uint32_t waited0, uint4 *__restrict__ queue)
 {
     uint32_t f[K], o[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-        f[k] = min(base + k * kNarrowThreads + tid, total - 1u);
+        f[k] = min(base + k * kTile + tid, total - 1u);
         o[k] = owner[f[k] / kGran];
     }
     uint2 info[K];
@@ -435,7 +426,7 @@ __device__ __forceinline__ void copy_outputs(uint32_t base, uint32_t total, uint
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const uint32_t j = f[k] - (info[k].x & 4095u), waiting = info[k].x >> 12 & 15u, slot0 = info[k].x >> 16;
-        const uint32_t staged = slot0 + j - waiting, waited = kPairs + o[k] * kCarry + j;
+        const uint32_t staged = slot0 + j - waiting, waited = waited0 + o[k] * kCarry + j;
         const uint32_t pick = 0u - (uint32_t)(j < waiting);           // all ones: take the waiting record
         src[k] = staged ^ ((staged ^ waited) & pick);
         dst[k] = info[k].y + j;
@@ -447,14 +438,14 @@ __device__ __forceinline__ void copy_outputs(uint32_t base, uint32_t total, uint
     for (int k = 0; k < K; ++k) queue[dst[k]] = rec[k];
 }
 
-// the step's appends -> queues, by all threads of the workgroup (the trip counts are the same for all)
+// the step's appends -> queue, by the kTile binning threads (the trip counts are the same for all)
 __device__ __forceinline__ void copy_step(uint32_t total, uint32_t tid, const uint8_t *owner, const uint2 *bin_info, const uint4 *stage,
-                                          uint4 *__restrict__ queue)
+                                          uint32_t waited0, uint4 *__restrict__ queue)
 {
     for (uint32_t base = 0; base < total;) {
-        const uint32_t rounds = (total - base + kNarrowThreads - 1) / kNarrowThreads;
-#define DG_COPY(K) copy_outputs<K>(base, total, tid, owner, bin_info, stage, queue)
-        if (rounds >= 4) { DG_COPY(4); base += 4 * kNarrowThreads; }
+        const uint32_t rounds = (total - base + kTile - 1) / kTile;
+#define DG_COPY(K) copy_outputs<K>(base, total, tid, owner, bin_info, stage, waited0, queue)
+        if (rounds >= 4) { DG_COPY(4); base += 4 * kTile; }
         else if (rounds == 3) { DG_COPY(3); break; }
         else if (rounds == 2) { DG_COPY(2); break; }
         else { DG_COPY(1); break; }
@@ -470,8 +461,8 @@ fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const
     extern __shared__ uint32_t smem[];
     uint32_t *cnt = smem;                                             // [2][64] records per bin of the step
     uint4 *stage = reinterpret_cast<uint4 *>(cnt + 128);              // [kPairs] records of the step, sorted by bin
-    uint4 *carry = stage + kPairs;                                    // [64][kCarry] what waits, per bin
-    uint2 *bin_info = reinterpret_cast<uint2 *>(carry + 64 * kCarry);              // [64] see copy_outputs
+    uint4 *carry = stage + kPairs;                                    // [2][64][kCarry] what waits, per bin: read in one half, rebuilt in the other
+    uint2 *bin_info = reinterpret_cast<uint2 *>(carry + 2 * 64 * kCarry);          // [64] see copy_outputs
     uint32_t *total_out = reinterpret_cast<uint32_t *>(bin_info + 64);             // [1] outputs of the step (+ 3 unused)
     uint8_t *owner = reinterpret_cast<uint8_t *>(total_out + 4);      // [kOwner] bin of each granule of the step
     const uint32_t tid = threadIdx.x;
@@ -521,21 +512,20 @@ fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const
                 bin_info[lane] = make_uint2(before | waiting << 12 | slot0 << 16, pos);
                 if (lane == 0) *total_out = total;
                 __syncthreads();                                     // step staged, plan published
-                copy_step(total, tid, owner, bin_info, stage, queue);
-                __syncthreads();                                     // everything that waited has been read
-                // What is left of the step's records waits from here on.  Nothing went out (out == 0): the fresh ones
-                // queue up behind the waiting ones; else all that waited has left and the tail of the fresh ones waits.
-                // A value that does not move is written back to where it was read: straight-line code, no branch per
-                // record; all reads first, then all writes (named values for the 16-byte ones: an array of them ends
-                // up in scratch memory here).
+                // While the others copy the appends out, the records that wait from here on are put together in the
+                // other half of the waiting slots.  Nothing went out (out == 0): those that waited stay, the fresh ones
+                // queue up behind them; else all that waited leaves and the tail of the fresh ones waits.  A value
+                // beyond what waits is written back to where it was read: straight-line code, no branch per record;
+                // all reads first, then all writes (named values: an array of 16-byte values ends up in scratch
+                // memory here).
                 {
-                    const uint32_t from = out == 0u ? slot0 : slot0 + (out - waiting), to = kPairs + lane * kCarry + (out == 0u ? waiting : 0u);
-                    const uint32_t n_move = out == 0u ? fresh : left;
+                    const uint32_t keep = out == 0u ? waiting : 0u, fresh_from = out == 0u ? slot0 : slot0 + (out - waiting);
+                    const uint32_t old_at = kPairs + parity * 64u * kCarry + lane * kCarry, new_at = kPairs + (parity ^ 1u) * 64u * kCarry + lane * kCarry;
                     static_assert(kCarry == 7, "the moves below are written out for seven waiting records");
-#define DG_FROM(j) min(from + j##u, (uint32_t)kPairs - 1u)
+#define DG_FROM(j) (j##u < keep ? old_at + j##u : min(fresh_from + (j##u - keep), (uint32_t)kPairs - 1u))
                     const uint4 r0 = stage[DG_FROM(0)], r1 = stage[DG_FROM(1)], r2 = stage[DG_FROM(2)], r3 = stage[DG_FROM(3)];
                     const uint4 r4 = stage[DG_FROM(4)], r5 = stage[DG_FROM(5)], r6 = stage[DG_FROM(6)];
-#define DG_MOVE(j) stage[j##u < n_move ? to + j##u : DG_FROM(j)] = r##j
+#define DG_MOVE(j) stage[j##u < left ? new_at + j##u : DG_FROM(j)] = r##j
                     DG_MOVE(0); DG_MOVE(1); DG_MOVE(2); DG_MOVE(3); DG_MOVE(4); DG_MOVE(5); DG_MOVE(6);
 #undef DG_MOVE
 #undef DG_FROM
@@ -546,7 +536,7 @@ fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const
             // end of the level: what still waits goes out, followed by zero records up to the padded end of the slice
             if (mine) {
                 const uint32_t end = (pos + waiting + kSliceRound - 1u) / kSliceRound * kSliceRound;
-                for (uint32_t j = 0; pos + j < end; ++j) queue[pos + j] = j < waiting ? carry[lane * kCarry + j] : zero4;
+                for (uint32_t j = 0; pos + j < end; ++j) queue[pos + j] = j < waiting ? carry[(parity * 64u + lane) * kCarry + j] : zero4;
             }
             waiting = 0u;
         }
@@ -593,8 +583,7 @@ fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const
             // the inputs are taken in here, before this wavefront issues stores again (an empty statement that uses them)
             asm volatile("" : "+v"(ahead.u[0]), "+v"(ahead.u[1]), "+v"(ahead.u[2]), "+v"(ahead.g.x), "+v"(ahead.g.y));
             __syncthreads();
-            copy_step(*total_out, tid, owner, bin_info, stage, queue);
-            __syncthreads();
+            copy_step(*total_out, tid, owner, bin_info, stage, kPairs + parity * 64u * kCarry, queue);
         }
     }
     publish_largest(largest, cnt, largest_out);
