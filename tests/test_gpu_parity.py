@@ -216,6 +216,32 @@ def test_encode_bwd(key, N, flavour, mode):
     assert np.all(got[ref == 0] == 0)                                 # untouched entries stay untouched
 
 
+@pytest.mark.parametrize("key,N,flavour", [("c2", 30011, "rays"), ("wide", 20011, "points")])
+def test_encode_bwd_binned_value_range(key, N, flavour):
+    """The binned pass rounds a contribution to 18 mantissa bits and sums in fixed point scaled to the batch's largest
+    magnitude: per entry the error stays within 2^-19 of the sum of |contributions| plus 2^-20 of that largest
+    magnitude, for gradients that span 18 decades and sit right below powers of two (where rounding carries into the
+    exponent)."""
+    say("encode bwd value range %s N=%d %s" % (key, N, flavour))
+    g, r, _ = _both_grids(key)
+    L = g.n_levels
+    u = _coords(N, flavour, seed=15)
+    rng = np.random.default_rng(16)
+    dfeat = (10.0 ** rng.uniform(-12, 6, (N, 2 * L)) * rng.choice([-1.0, 1.0], (N, 2 * L))).astype(np.float32)
+    edge = np.nextafter(np.float32(2.0) ** rng.integers(-8, 8, (N // 5, 2 * L)).astype(np.float32), np.float32(0))
+    dfeat[::5][:edge.shape[0]] = edge
+    dtable = torch.zeros(r.n_entries, 2, device=DEV)
+    ws = torch.zeros(B.dg_hashgrid_encode_bwd_workspace_bytes(g, N) // 4 + 64, device=DEV)
+    B.dg_hashgrid_encode_bwd(g, dev(u), dev(to_planes(dfeat)), N, dtable, ws)
+    ref = oracle.encode_bwd(r, u, dfeat.astype(np.float64))
+    mass = oracle.encode_bwd(r, u, np.abs(dfeat).astype(np.float64))      # sum of |contributions| per entry
+    got = host(dtable).astype(np.float64)
+    largest = float(np.abs(dfeat).max())
+    err = np.abs(got - ref)
+    assert np.all(err <= 2.0 ** -19 * mass + 2.0 ** -20 * largest), float(np.max(err / (2.0 ** -19 * mass + 2.0 ** -20 * largest)))
+    assert np.all(got[mass == 0] == 0)
+
+
 @pytest.mark.parametrize("S,n_seg,k_max", [(64, 501, 4), (32, 77, 1), (100, 33, 3), (7, 1000, 12)])
 def test_depth_channel(S, n_seg, k_max):
     """Evaluation depth (Sec. 4.4.2): per-segment expected distance and its merge, against the oracle."""
