@@ -191,7 +191,8 @@ def test_encode_fwd_and_indices(key, N):
 @pytest.mark.parametrize("key,N,flavour", [("c1", 32768, "points"), ("c2", 10007, "points"), ("mixed_small", 3333, "points"),
                                            ("one_level_dense", 700, "points"), ("c2", 20011, "rays"),
                                            ("dense_odd", 150001, "points"), ("dense_odd", 30000, "rays"),
-                                           ("wide", 20011, "points"), ("wide", 9000, "rays"), ("huge", 20011, "points")])
+                                           ("wide", 20011, "points"), ("wide", 9000, "rays"), ("huge", 20011, "points"),
+                                           ("c2", 1, "points"), ("c2", 7, "rays"), ("c2", 513, "rays"), ("c2", 2048 * 3 + 5, "rays")])
 def test_encode_bwd(key, N, flavour, mode):
     say("encode bwd %s N=%d %s %s" % (key, N, flavour, mode))
     g, r, _ = _both_grids(key)
@@ -214,6 +215,19 @@ def test_encode_bwd(key, N, flavour, mode):
         sl = slice(r.first[l], r.first[l + 1])
         assert rel_err(got[sl], ref[sl]) <= TOL_F16, l
     assert np.all(got[ref == 0] == 0)                                 # untouched entries stay untouched
+
+
+@pytest.mark.parametrize("with_ws", [False, True])
+def test_encode_bwd_empty_batch(with_ws):
+    """N = 0 adds nothing, with and without a workspace."""
+    say("encode bwd empty batch ws=%s" % with_ws)
+    g, r, _ = _both_grids("c2")
+    dtable = torch.full((r.n_entries, 2), 3.0, device=DEV)
+    ws = torch.zeros(B.dg_hashgrid_encode_bwd_workspace_bytes(g, 0) // 4 + 64, device=DEV) if with_ws else None
+    empty = torch.zeros(1, 3, device=DEV)[:0]
+    B.dg_hashgrid_encode_bwd(g, empty, torch.zeros(g.n_levels, 0, 2, device=DEV), 0, dtable, ws)
+    torch.cuda.synchronize()
+    assert bool((dtable == 3.0).all())
 
 
 @pytest.mark.parametrize("key,N,flavour", [("c2", 30011, "rays"), ("wide", 20011, "points")])
