@@ -10,9 +10,9 @@
 //     those tables and flush it once;
 //   * every other level is cut into bins of 8192 entries (128 KB of 64-bit sums in LDS).  A counting sweep
 //     and a filling sweep over the samples (same persistent tiling, so each workgroup owns a private,
-//     pre-computed slice of every bin's queue: no global atomics, no overflow) write one 20-byte record
+//     pre-computed slice of every bin's queue: no global atomics, no overflow) write one 16-byte record
 //     (two entries within the bin, 4 values) per pair of corners along x, staged through LDS so that each
-//     bin receives contiguous runs.  Then workgroups balanced by record count stream the queues,
+//     bin receives contiguous runs.  Then workgroups balanced by record count stream the queue,
 //     accumulate in LDS (as scaled 64-bit integers: integer adds are the fastest LDS atomics) and add the
 //     finished bin into dtable with coalesced atomics.
 #include "encode_common.h"
@@ -389,13 +389,12 @@ __device__ __forceinline__ void copy_out(const uint4 *stage, const uint32_t *sta
 // (lane == bin) and are fetched with wavefront shuffles.  The counters are double-buffered so that the buffer of the
 // next step is cleared while this step is staged.  One more wavefront keeps the books (lane == bin): the queue
 // position of every bin and the records that do not fill an append granule yet (up to 7 per bin, kept in LDS behind
-// the staged ones).  While the others stage a step, it works
+// the staged ones, in two halves: one is read while the other is rebuilt).  While the others stage a step, it works
 // out from the step's counters what every bin appends (whole granules) and publishes that; after the second barrier
-// all wavefronts copy the appends out, consecutive threads writing consecutive records of a bin, so that a store
-// instruction covers whole cache lines; after a third barrier the book-keeping wavefront moves what is left of the
-// step into the waiting slots while the others already rank the next step.  At the end of a level it writes the
-// waiting records out and pads this workgroup's slice of each bin to kSliceRound records with zero records, which add
-// nothing.
+// the binning threads copy the appends out, consecutive threads writing consecutive records of a bin, so that a store
+// instruction covers whole cache lines, while the book-keeping wavefront puts together what waits from here on.  Two
+// barriers per step.  At the end of a level the book-keeper writes the waiting records out and pads this workgroup's
+// slice of each bin to kSliceRound records with zero records, which add nothing.
 __device__ __forceinline__ uint32_t lane_value(uint32_t v, uint32_t lane) { return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)lane); }
 
 constexpr uint32_t kCarry = kGran - 1;
@@ -565,7 +564,7 @@ fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const
             // lane b: records of bin b in this step and their first staging slot
             const uint32_t in_bin = c_cur[lane];
             const uint32_t first_slot = wave_inclusive_scan(in_bin) - in_bin;
-            if (tid < dg::kWave) cnt[64u * (parity ^ 1u) + tid] = 0u;    // the other buffer: last read three barriers ago
+            if (tid < dg::kWave) cnt[64u * (parity ^ 1u) + tid] = 0u;    // the other buffer: last read two barriers ago
             // The next step's inputs are asked for here, not after the copy: the wait for them also waits for every
             // store this wavefront has issued, and at this point the stores of the last copy have had time to land.
             {
