@@ -545,6 +545,8 @@ fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const
 
     StepAhead ahead = {{0.0f, 0.0f, 0.0f}, make_float2(0.0f, 0.0f)};
     if (has_work) load_ahead(ahead, u, dfeat, N, n0, nb, blockIdx.x, plan.first_level, tid);
+    // taken in before the loop, as every later load is before its step ends: the top of a step then waits for nothing
+    asm volatile("" : "+v"(ahead.u[0]), "+v"(ahead.u[1]), "+v"(ahead.u[2]), "+v"(ahead.g.x), "+v"(ahead.g.y));
     for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
         const LevelGeom lv = level_of(g, l);
         for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x, parity ^= 1u) {
@@ -552,6 +554,14 @@ fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const
             const bool live = tile * kTile + tid < nb;
             const float uu[3] = {ahead.u[0], ahead.u[1], ahead.u[2]};
             const float2 gfe = live ? ahead.g : make_float2(0.0f, 0.0f);
+            // The next step's inputs are asked for right away and taken in at the end of the staging: the whole step
+            // hides their latency.  (Asked for after the copy, the wait for them would also wait for the copy's
+            // stores, which have only just been issued.)
+            {
+                const bool same_level = tile + gridDim.x < n_tiles;
+                const uint32_t l_next = same_level ? l : l + 1;
+                if (l_next < g.n_levels) load_ahead(ahead, u, dfeat, N, n0, nb, same_level ? tile + gridDim.x : blockIdx.x, l_next, tid);
+            }
             const Emission em = classify(lv, mask, uu, live, (int)lane);
             uint32_t rank[4];
             if (em.emit) {
@@ -565,13 +575,6 @@ fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const
             const uint32_t in_bin = c_cur[lane];
             const uint32_t first_slot = wave_inclusive_scan(in_bin) - in_bin;
             if (tid < dg::kWave) cnt[64u * (parity ^ 1u) + tid] = 0u;    // the other buffer: last read two barriers ago
-            // The next step's inputs are asked for here, not after the copy: the wait for them also waits for every
-            // store this wavefront has issued, and at this point the stores of the last copy have had time to land.
-            {
-                const bool same_level = tile + gridDim.x < n_tiles;
-                const uint32_t l_next = same_level ? l : l + 1;
-                if (l_next < g.n_levels) load_ahead(ahead, u, dfeat, N, n0, nb, same_level ? tile + gridDim.x : blockIdx.x, l_next, tid);
-            }
             uint32_t slot[4];
 #pragma unroll
             for (int p = 0; p < 4; ++p) slot[p] = __shfl(first_slot, (int)(em.e[2 * p] >> kChunkLog2), dg::kWave);
