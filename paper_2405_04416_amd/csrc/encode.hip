@@ -42,6 +42,59 @@ encode_fwd_kernel(dg_grid_desc g, const float2 *__restrict__ table, const float 
     }
 }
 
+// The same with two lanes per sample: lane 2i takes the four corners with cx = 0, lane 2i + 1 those with cx = 1, and a
+// DPP move adds the two halves.  The two entries of an x-pair almost always share a cache line, and neighbouring lanes
+// that ask for the same line cost the vector cache one look-up instead of two.
+template <bool kHalf>
+__global__ void __launch_bounds__(kBlock)
+encode_fwd_pair_kernel(dg_grid_desc g, const float2 *__restrict__ table, const float *__restrict__ u, uint64_t N,
+                       void *__restrict__ feat, uint32_t n_tiles)
+{
+    const uint32_t l = blockIdx.x / n_tiles;
+    const uint64_t s = (uint64_t)(blockIdx.x % n_tiles) * (kBlock / 2) + threadIdx.x / 2;
+    const uint32_t cx = threadIdx.x & 1u;
+    const bool live = s < N;
+    const uint64_t n = live ? s : N - 1;                 // every lane stays in for the exchange
+    const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
+    const uint32_t mask = (1u << g.log2_T) - 1u;
+    const LevelGeom lv = level_of(g, l);
+    uint32_t cell[3], e[4];
+    float frac[3];
+    locate(lv, uu, cell, frac);
+    if (lv.dense) {
+        const uint32_t nx = lv.res[0] + 1u, nxy = nx * (lv.res[1] + 1u);
+        const uint32_t base = cell[0] + cx + nx * cell[1] + nxy * cell[2];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) e[k] = base + (k & 1) * nx + (k >> 1) * nxy;
+    } else {
+        const uint32_t hy0 = cell[1] * kPrimeY, hy1 = hy0 + kPrimeY;
+        const uint32_t hz0 = cell[2] * kPrimeZ, hz1 = hz0 + kPrimeZ;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) e[k] = ((cell[0] + cx) ^ ((k & 1) ? hy1 : hy0) ^ ((k & 2) ? hz1 : hz0)) & mask;
+    }
+    const float wx = cx ? frac[0] : 1.0f - frac[0];
+    const float wy[2] = {1.0f - frac[1], frac[1]}, wz[2] = {1.0f - frac[2], frac[2]};
+    float2 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = table[(size_t)lv.offset + e[k]];
+    float f0 = 0.0f, f1 = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float w = wx * wy[k & 1] * wz[k >> 1];
+        f0 = fmaf(w, v[k].x, f0);
+        f1 = fmaf(w, v[k].y, f1);
+    }
+    // the partner's half: lanes swapped within pairs (quad_perm 1, 0, 3, 2)
+    f0 += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(f0), 0xB1, 0xF, 0xF, true));
+    f1 += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(f1), 0xB1, 0xF, 0xF, true));
+    if (!live || cx) return;
+    if (kHalf) {
+        reinterpret_cast<__half2 *>(feat)[(size_t)l * N + n] = __floats2half2_rn(f0, f1);
+    } else {
+        reinterpret_cast<float2 *>(feat)[(size_t)l * N + n] = make_float2(f0, f1);
+    }
+}
+
 // Backward scatter.  A wavefront holds 64 consecutive samples, i.e. a stretch of one ray, so at the
 // coarser levels neighbouring lanes sit in the same cell and add into the same 8 entries.  Global
 // fp32 atomics retire at a fixed rate per distinct cache line touched by an instruction, whatever the
@@ -166,9 +219,20 @@ extern "C" int dg_hashgrid_encode_fwd(const dg_grid_desc *desc, const float *tab
     DG_REQUIRE(dg::aligned(table, 8) && dg::aligned(feat, feat_dtype == DG_F16 ? 4 : 8), DG_ERR_ARG,
                "dg_hashgrid_encode_fwd: table/feat misaligned");
     uint32_t n_blocks;
+    hipStream_t st = (hipStream_t)stream;
+    // Two lanes per sample while the tables are small enough to be served from cache (c2, T = 2^19: 3.09 -> 2.33 ms;
+    // T = 2^22: 9 % faster); with T = 2^24 the gather waits for HBM and the spare lanes only cost (3 % slower).
+    if (desc->log2_T <= 22) {
+        if (int rc = grid_for(2 * N, desc->n_levels, &n_blocks, "dg_hashgrid_encode_fwd")) return rc;
+        const uint32_t n_tiles = n_blocks / desc->n_levels;
+        if (feat_dtype == DG_F16)
+            encode_fwd_pair_kernel<true><<<n_blocks, kBlock, 0, st>>>(*desc, (const float2 *)table, u, N, feat, n_tiles);
+        else
+            encode_fwd_pair_kernel<false><<<n_blocks, kBlock, 0, st>>>(*desc, (const float2 *)table, u, N, feat, n_tiles);
+        return dg::launch_status("dg_hashgrid_encode_fwd");
+    }
     if (int rc = grid_for(N, desc->n_levels, &n_blocks, "dg_hashgrid_encode_fwd")) return rc;
     const uint32_t n_tiles = n_blocks / desc->n_levels;
-    hipStream_t st = (hipStream_t)stream;
     if (feat_dtype == DG_F16)
         encode_fwd_kernel<true><<<n_blocks, kBlock, 0, st>>>(*desc, (const float2 *)table, u, N, feat, n_tiles);
     else

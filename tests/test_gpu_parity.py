@@ -158,7 +158,7 @@ def _both_grids(key):
 
 
 @pytest.mark.parametrize("key,N", [("c1", 32768), ("c2", 10007), ("mixed_small", 3333), ("one_level_dense", 257),
-                                   ("c2", 1), ("c2", 0)])
+                                   ("c2", 1), ("c2", 0), ("dense_odd", 4099), ("wide", 5003), ("huge", 5003)])
 def test_encode_fwd_and_indices(key, N):
     say("encode fwd %s N=%d" % (key, N))
     g, r, rng_range = _both_grids(key)
