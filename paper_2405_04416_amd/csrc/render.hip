@@ -1,71 +1,80 @@
 // Local volume rendering of segments, segmented merge and loss seeds (Eq. 3, Eq. 5-10).
 //
-// Compositing: one 64-lane wavefront per segment, one sample per lane (S = 64 fills a wavefront
-// exactly; other S run in chunks of 64 with a carried transmittance), so sigma / rgb / delta are
-// read coalesced and the front-to-back product becomes a wavefront prefix scan.
+// Compositing: a group of G lanes per segment, one sample per lane (G = 64, a whole wavefront, for the fixed sample
+// counts: S = 64 fills it exactly; other S run in chunks of G with a carried transmittance), so sigma / rgb / delta
+// are read coalesced and the front-to-back product becomes a prefix scan over the group.  Segments of different
+// lengths (occupancy-guided sampling keeps 7 samples per segment on average) take G = 16: four segments per wavefront.
 #include "dg_internal.h"
 
 namespace {
 
 constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / dg::kWave;
+constexpr int kRaggedGroup = 16;                   // lanes per segment where segments differ in length
+constexpr int kRaggedPerBlock = kBlock / kRaggedGroup;
 
-__device__ __forceinline__ float wave_inclusive_product(float v, int lane)
+template <int G>
+__device__ __forceinline__ float group_inclusive_product(float v, int lane)
 {
 #pragma unroll
-    for (int off = 1; off < dg::kWave; off <<= 1) {
-        const float up = __shfl_up(v, off, dg::kWave);
+    for (int off = 1; off < G; off <<= 1) {
+        const float up = __shfl_up(v, off, G);
         if (lane >= off) v *= up;
     }
     return v;
 }
 
-__device__ __forceinline__ float wave_inclusive_sum(float v, int lane)
+template <int G>
+__device__ __forceinline__ float group_inclusive_sum(float v, int lane)
 {
 #pragma unroll
-    for (int off = 1; off < dg::kWave; off <<= 1) {
-        const float up = __shfl_up(v, off, dg::kWave);
+    for (int off = 1; off < G; off <<= 1) {
+        const float up = __shfl_up(v, off, G);
         if (lane >= off) v += up;
     }
     return v;
 }
 
-__device__ __forceinline__ float wave_sum(float v)
+template <int G>
+__device__ __forceinline__ float group_sum(float v)
 {
 #pragma unroll
-    for (int off = dg::kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, dg::kWave);
+    for (int off = G / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, G);
     return v;
 }
 
+// Every exchange below stays inside a group, and the lanes of a group run the same loops and branches (they depend on
+// the segment alone), so a lane never reads from one that is switched off.
+template <int G>
 __global__ void __launch_bounds__(kBlock)
 composite_fwd_kernel(const float *__restrict__ sigma, const float *__restrict__ rgb, const float *__restrict__ delta,
                      uint32_t n_seg, uint32_t S_fixed, const uint32_t *__restrict__ first, const uint32_t *__restrict__ seg_ray,
                      const uint32_t *__restrict__ seg_slot, uint32_t k_max, float *__restrict__ Ck,
                      float *__restrict__ Tk)
 {
-    const uint32_t j = blockIdx.x * kWavesPerBlock + threadIdx.x / dg::kWave;
-    const int lane = threadIdx.x % dg::kWave;
+    const uint32_t j = blockIdx.x * (kBlock / G) + threadIdx.x / G;
+    const int lane = threadIdx.x % G;
     if (j >= n_seg) return;
     const size_t begin = first ? (size_t)first[j] : (size_t)j * S_fixed;      // segments of different lengths bring their offsets
     const uint32_t S = first ? first[j + 1] - first[j] : S_fixed;
     float trans = 1.0f, c0 = 0.0f, c1 = 0.0f, c2 = 0.0f;
-    for (uint32_t base = 0; base < S; base += dg::kWave) {
+    for (uint32_t base = 0; base < S; base += G) {
         const uint32_t s = base + lane;
         const bool live = s < S;
         const size_t n = begin + (live ? s : 0);
         const float x = live ? sigma[n] * delta[n] : 0.0f;
         const float keep = expf(-x);                        // 1 - alpha
         const float alpha = -expm1f(-x);
-        const float incl = wave_inclusive_product(keep, lane);
-        float before = __shfl_up(incl, 1, dg::kWave);
+        const float incl = group_inclusive_product<G>(keep, lane);
+        float before = __shfl_up(incl, 1, G);
         if (lane == 0) before = 1.0f;
         const float wgt = live ? trans * before * alpha : 0.0f;
         c0 += wgt * (live ? rgb[3 * n] : 0.0f);
         c1 += wgt * (live ? rgb[3 * n + 1] : 0.0f);
         c2 += wgt * (live ? rgb[3 * n + 2] : 0.0f);
-        trans *= __shfl(incl, dg::kWave - 1, dg::kWave);
+        trans *= __shfl(incl, G - 1, G);
     }
-    c0 = wave_sum(c0); c1 = wave_sum(c1); c2 = wave_sum(c2);
+    c0 = group_sum<G>(c0); c1 = group_sum<G>(c1); c2 = group_sum<G>(c2);
     if (lane == 0) {
         const size_t dst = (size_t)seg_ray[j] * k_max + seg_slot[j];
         Ck[3 * dst] = c0; Ck[3 * dst + 1] = c1; Ck[3 * dst + 2] = c2;
@@ -74,41 +83,43 @@ composite_fwd_kernel(const float *__restrict__ sigma, const float *__restrict__ 
 }
 
 // Depth of evaluation rendering (Sec. 4.4.2): D_k = sum_i T_i alpha_i t_i, the colour rule applied to the sample distances
+template <int G>
 __global__ void __launch_bounds__(kBlock)
 composite_depth_kernel(const float *__restrict__ sigma, const float *__restrict__ delta, const float *__restrict__ t,
                        uint32_t n_seg, uint32_t S_fixed, const uint32_t *__restrict__ first, const uint32_t *__restrict__ seg_ray,
                        const uint32_t *__restrict__ seg_slot, uint32_t k_max, float *__restrict__ Dk)
 {
-    const uint32_t j = blockIdx.x * kWavesPerBlock + threadIdx.x / dg::kWave;
-    const int lane = threadIdx.x % dg::kWave;
+    const uint32_t j = blockIdx.x * (kBlock / G) + threadIdx.x / G;
+    const int lane = threadIdx.x % G;
     if (j >= n_seg) return;
     const size_t begin = first ? (size_t)first[j] : (size_t)j * S_fixed;      // segments of different lengths bring their offsets
     const uint32_t S = first ? first[j + 1] - first[j] : S_fixed;
     float trans = 1.0f, depth = 0.0f;
-    for (uint32_t base = 0; base < S; base += dg::kWave) {
+    for (uint32_t base = 0; base < S; base += G) {
         const uint32_t s = base + lane;
         const bool live = s < S;
         const size_t n = begin + (live ? s : 0);
         const float x = live ? sigma[n] * delta[n] : 0.0f;
-        const float incl = wave_inclusive_product(expf(-x), lane);
-        float before = __shfl_up(incl, 1, dg::kWave);
+        const float incl = group_inclusive_product<G>(expf(-x), lane);
+        float before = __shfl_up(incl, 1, G);
         if (lane == 0) before = 1.0f;
         depth += live ? trans * before * -expm1f(-x) * t[n] : 0.0f;
-        trans *= __shfl(incl, dg::kWave - 1, dg::kWave);
+        trans *= __shfl(incl, G - 1, G);
     }
-    depth = wave_sum(depth);
+    depth = group_sum<G>(depth);
     if (lane == 0) Dk[(size_t)seg_ray[j] * k_max + seg_slot[j]] = depth;
 }
 
 // d sigma_i = delta_i [ gC.(T_{i+1} c_i) - sum_{j>i} w_j gC.c_j - gT T_k ],  d c_i = w_i gC
+template <int G>
 __global__ void __launch_bounds__(kBlock)
 composite_bwd_kernel(const float *__restrict__ sigma, const float *__restrict__ rgb, const float *__restrict__ delta,
                      uint32_t n_seg, uint32_t S_fixed, const uint32_t *__restrict__ first, const uint32_t *__restrict__ seg_ray,
                      const uint32_t *__restrict__ seg_slot, uint32_t k_max, const float *__restrict__ gCk,
                      const float *__restrict__ gTk, float *__restrict__ dsigma, float *__restrict__ drgb)
 {
-    const uint32_t j = blockIdx.x * kWavesPerBlock + threadIdx.x / dg::kWave;
-    const int lane = threadIdx.x % dg::kWave;
+    const uint32_t j = blockIdx.x * (kBlock / G) + threadIdx.x / G;
+    const int lane = threadIdx.x % G;
     if (j >= n_seg) return;
     const size_t begin = first ? (size_t)first[j] : (size_t)j * S_fixed;      // segments of different lengths bring their offsets
     const uint32_t S = first ? first[j + 1] - first[j] : S_fixed;
@@ -117,44 +128,44 @@ composite_bwd_kernel(const float *__restrict__ sigma, const float *__restrict__ 
 
     // pass 1 (only needed when the segment spans several chunks): total of q_j = w_j gC.c_j and T_k
     float total_q = 0.0f, trans_all = 1.0f;
-    if (S > (uint32_t)dg::kWave) {
+    if (S > (uint32_t)G) {
         float trans = 1.0f, q = 0.0f;
-        for (uint32_t base = 0; base < S; base += dg::kWave) {
+        for (uint32_t base = 0; base < S; base += G) {
             const uint32_t s = base + lane;
             const bool live = s < S;
             const size_t n = begin + (live ? s : 0);
             const float x = live ? sigma[n] * delta[n] : 0.0f;
-            const float incl = wave_inclusive_product(expf(-x), lane);
-            float before = __shfl_up(incl, 1, dg::kWave);
+            const float incl = group_inclusive_product<G>(expf(-x), lane);
+            float before = __shfl_up(incl, 1, G);
             if (lane == 0) before = 1.0f;
             const float wgt = live ? trans * before * -expm1f(-x) : 0.0f;
             if (live) q += wgt * (g0 * rgb[3 * n] + g1 * rgb[3 * n + 1] + g2 * rgb[3 * n + 2]);
-            trans *= __shfl(incl, dg::kWave - 1, dg::kWave);
+            trans *= __shfl(incl, G - 1, G);
         }
-        total_q = wave_sum(q);
+        total_q = group_sum<G>(q);
         trans_all = trans;
     }
 
     float trans = 1.0f, q_before = 0.0f;      // running transmittance and running sum of q over earlier chunks
-    for (uint32_t base = 0; base < S; base += dg::kWave) {
+    for (uint32_t base = 0; base < S; base += G) {
         const uint32_t s = base + lane;
         const bool live = s < S;
         const size_t n = begin + (live ? s : 0);
         const float dl = live ? delta[n] : 0.0f;
         const float x = live ? sigma[n] * dl : 0.0f;
         const float keep = expf(-x);
-        const float incl = wave_inclusive_product(keep, lane);
-        float before = __shfl_up(incl, 1, dg::kWave);
+        const float incl = group_inclusive_product<G>(keep, lane);
+        float before = __shfl_up(incl, 1, G);
         if (lane == 0) before = 1.0f;
         const float t_before = trans * before;
         const float wgt = live ? t_before * -expm1f(-x) : 0.0f;
         const float r0 = live ? rgb[3 * n] : 0.0f, r1 = live ? rgb[3 * n + 1] : 0.0f, r2 = live ? rgb[3 * n + 2] : 0.0f;
         const float gc = g0 * r0 + g1 * r1 + g2 * r2;
         const float q = wgt * gc;
-        const float q_incl = wave_inclusive_sum(q, lane);
-        const float chunk_q = __shfl(q_incl, dg::kWave - 1, dg::kWave);
-        const float chunk_keep = __shfl(incl, dg::kWave - 1, dg::kWave);
-        if (S <= (uint32_t)dg::kWave) { total_q = chunk_q; trans_all = chunk_keep; }
+        const float q_incl = group_inclusive_sum<G>(q, lane);
+        const float chunk_q = __shfl(q_incl, G - 1, G);
+        const float chunk_keep = __shfl(incl, G - 1, G);
+        if (S <= (uint32_t)G) { total_q = chunk_q; trans_all = chunk_keep; }
         const float behind = total_q - (q_before + q_incl);
         if (live) {
             dsigma[n] = dl * (t_before * keep * gc - behind - gt * trans_all);
@@ -254,7 +265,7 @@ loss_seed_kernel(const float *__restrict__ C, const float *__restrict__ T, const
         if (lambda1 != 0.0f) mine -= lambda1 * inv_r * logf(clamped ? 1e-6f : opaque);
     }
     if (loss) {
-        mine = wave_sum(mine);
+        mine = group_sum<dg::kWave>(mine);
         if (threadIdx.x % dg::kWave == 0) partial[threadIdx.x / dg::kWave] = mine;
         __syncthreads();
         if (threadIdx.x == 0) {
@@ -282,7 +293,7 @@ extern "C" int dg_composite_segment_fwd(const float *sigma, const float *rgb, co
     if (n_seg == 0) return DG_OK;
     DG_REQUIRE(sigma && rgb && delta && seg_ray && seg_slot && Ck && Tk, DG_ERR_ARG, "dg_composite_segment_fwd: null pointer");
     const uint32_t n_blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
-    composite_fwd_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, S, nullptr, seg_ray,
+    composite_fwd_kernel<dg::kWave><<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, S, nullptr, seg_ray,
                                                                        seg_slot, k_max, Ck, Tk);
     return dg::launch_status("dg_composite_segment_fwd");
 }
@@ -295,7 +306,7 @@ extern "C" int dg_composite_segment_depth(const float *sigma, const float *delta
     if (n_seg == 0) return DG_OK;
     DG_REQUIRE(sigma && delta && t && seg_ray && seg_slot && Dk, DG_ERR_ARG, "dg_composite_segment_depth: null pointer");
     const uint32_t n_blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
-    composite_depth_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, delta, t, n_seg, S, nullptr, seg_ray, seg_slot,
+    composite_depth_kernel<dg::kWave><<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, delta, t, n_seg, S, nullptr, seg_ray, seg_slot,
                                                                          k_max, Dk);
     return dg::launch_status("dg_composite_segment_depth");
 }
@@ -309,7 +320,7 @@ extern "C" int dg_composite_segment_bwd(const float *sigma, const float *rgb, co
     DG_REQUIRE(sigma && rgb && delta && seg_ray && seg_slot && gCk && gTk && dsigma && drgb, DG_ERR_ARG,
                "dg_composite_segment_bwd: null pointer");
     const uint32_t n_blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
-    composite_bwd_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, S, nullptr, seg_ray,
+    composite_bwd_kernel<dg::kWave><<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, S, nullptr, seg_ray,
                                                                        seg_slot, k_max, gCk, gTk, dsigma, drgb);
     return dg::launch_status("dg_composite_segment_bwd");
 }
@@ -322,8 +333,8 @@ extern "C" int dg_composite_ragged_fwd(const float *sigma, const float *rgb, con
     if (int rc = seg_args_ok(n_seg, 1, k_max, "dg_composite_ragged_fwd")) return rc;
     if (n_seg == 0) return DG_OK;
     DG_REQUIRE(sigma && rgb && delta && first && seg_ray && seg_slot && Ck && Tk, DG_ERR_ARG, "dg_composite_ragged_fwd: null pointer");
-    const uint32_t n_blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
-    composite_fwd_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, 0, first, seg_ray, seg_slot,
+    const uint32_t n_blocks = (n_seg + kRaggedPerBlock - 1) / kRaggedPerBlock;
+    composite_fwd_kernel<kRaggedGroup><<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, 0, first, seg_ray, seg_slot,
                                                                        k_max, Ck, Tk);
     return dg::launch_status("dg_composite_ragged_fwd");
 }
@@ -335,8 +346,8 @@ extern "C" int dg_composite_ragged_depth(const float *sigma, const float *delta,
     if (int rc = seg_args_ok(n_seg, 1, k_max, "dg_composite_ragged_depth")) return rc;
     if (n_seg == 0) return DG_OK;
     DG_REQUIRE(sigma && delta && t && first && seg_ray && seg_slot && Dk, DG_ERR_ARG, "dg_composite_ragged_depth: null pointer");
-    const uint32_t n_blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
-    composite_depth_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, delta, t, n_seg, 0, first, seg_ray, seg_slot,
+    const uint32_t n_blocks = (n_seg + kRaggedPerBlock - 1) / kRaggedPerBlock;
+    composite_depth_kernel<kRaggedGroup><<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, delta, t, n_seg, 0, first, seg_ray, seg_slot,
                                                                          k_max, Dk);
     return dg::launch_status("dg_composite_ragged_depth");
 }
@@ -349,8 +360,8 @@ extern "C" int dg_composite_ragged_bwd(const float *sigma, const float *rgb, con
     if (n_seg == 0) return DG_OK;
     DG_REQUIRE(sigma && rgb && delta && first && seg_ray && seg_slot && gCk && gTk && dsigma && drgb, DG_ERR_ARG,
                "dg_composite_ragged_bwd: null pointer");
-    const uint32_t n_blocks = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
-    composite_bwd_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, 0, first, seg_ray, seg_slot,
+    const uint32_t n_blocks = (n_seg + kRaggedPerBlock - 1) / kRaggedPerBlock;
+    composite_bwd_kernel<kRaggedGroup><<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(sigma, rgb, delta, n_seg, 0, first, seg_ray, seg_slot,
                                                                        k_max, gCk, gTk, dsigma, drgb);
     return dg::launch_status("dg_composite_ragged_bwd");
 }
