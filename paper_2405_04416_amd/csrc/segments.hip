@@ -242,7 +242,19 @@ dir_encode_kernel(const float *__restrict__ d, const uint32_t *__restrict__ inde
     v[14] = 1.445305721320277f * z * (xx - yy);
     v[15] = -0.5900435899266435f * x * (xx - 3.0f * yy);
     const uint32_t nd = degree * degree;
-    for (uint32_t k = 0; k < nd; ++k) out[i * nd + k] = __float2half_rn(v[k]);
+    if (degree == 4 && (reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
+        // the full row as two 16-byte stores (a loop over a run-time count would index v[] through memory)
+        __half2 h[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) h[k] = __floats2half2_rn(v[2 * k], v[2 * k + 1]);
+        uint4 *dst = reinterpret_cast<uint4 *>(out + i * 16);
+        dst[0] = *reinterpret_cast<const uint4 *>(&h[0]);
+        dst[1] = *reinterpret_cast<const uint4 *>(&h[4]);
+        return;
+    }
+#pragma unroll
+    for (uint32_t k = 0; k < 16; ++k)
+        if (k < nd) out[i * nd + k] = __float2half_rn(v[k]);
 }
 
 // appearance rows (Sec. 4.4.3): one 16-byte piece of a row per thread
