@@ -154,7 +154,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Which records a sample emits at a level (both sweeps take the same decision from the same data).  A
 // wavefront holds 64 consecutive samples of a ray; lanes that share a cell form a run whose 16 values are
-// summed into the run's last lane, which alone emits records.  Skipped where runs are short.
+// summed into the run's last lane, which alone emits records.  Skipped where no two lanes share a cell.
 struct Emission {
     uint32_t e[8];
     float frac[3];
@@ -172,7 +172,7 @@ __device__ __forceinline__ Emission classify(const LevelGeom &lv, uint32_t mask,
 #pragma unroll
     for (int a = 0; a < 3; ++a) o.head |= from_lane_below(cell[a]) != cell[a];
     o.heads = __ballot(o.head);
-    o.merge = __popcll(o.heads) <= 44;
+    o.merge = __popcll(o.heads) < dg::kWave;      // any run at all: the merge steps cost less than the records they save
     const bool tail = lane == dg::kWave - 1 || ((o.heads >> ((lane + 1) & 63)) & 1ull);
     o.emit = live && (!o.merge || tail);
     return o;
