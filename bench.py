@@ -27,7 +27,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA, published
 # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (scaled by a known elementwise kernel), summed over the
 # kernels an entry point launches; measured once per workload and recorded in profiles/<workload>_hbm_traffic.md
 MEASURED_TRAFFIC_BYTES = {
-    "c2_ngp": {"dg_hashgrid_encode_bwd": 18.3e9, "dg_hashgrid_encode_fwd": 7.33e9, "dg_mlp_fwd": 1.08e9, "dg_mlp_bwd": 4.6e9},
+    "c2_ngp": {"dg_hashgrid_encode_bwd": 17.5e9, "dg_hashgrid_encode_fwd": 7.33e9, "dg_mlp_fwd": 1.08e9, "dg_mlp_bwd": 4.6e9},
 }
 
 
