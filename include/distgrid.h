@@ -143,9 +143,7 @@ int dg_hashgrid_encode_fwd(const dg_grid_desc *desc, const float *table, const f
  * contribution is rounded to 18 mantissa bits (relative error at most 2^-20, unbiased) before it is
  * summed exactly.  ws must be 256-byte aligned; a smaller workspace is accepted and makes the call run
  * in batches, DG_ERR_WORKSPACE if it cannot hold one tile of 512 samples (16 bytes per sample, level
- * and pair of corners, plus bookkeeping).  On the workspace path one kernel may run on a stream of the
- * library's own, ordered after everything enqueued on `stream` before the call; `stream` waits for it
- * before the call's work counts as done, so callers see ordinary stream order. */
+ * and pair of corners, plus bookkeeping). */
 size_t dg_hashgrid_encode_bwd_workspace_bytes(const dg_grid_desc *desc, uint64_t N);
 int dg_hashgrid_encode_bwd(const dg_grid_desc *desc, const float *u, const float *dfeat,
                            uint64_t N, float *dtable, void *ws, size_t ws_bytes, void *stream);
