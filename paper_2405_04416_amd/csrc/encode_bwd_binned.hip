@@ -871,30 +871,6 @@ size_t encode_bwd_binned_workspace_bytes(const dg_grid_desc *d, uint64_t N)
     return make_layout(d, p, batch).total;
 }
 
-// one more stream per device (default priority) with the two events that order it against the caller's stream;
-// created on first use and kept until the process ends
-struct SideStream {
-    hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
-    int state = 0;      // 0 not tried yet, 1 ready, -1 not available (then everything stays on the caller's stream)
-};
-
-SideStream *side_stream()
-{
-    static SideStream per_device[16];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
-    SideStream &s = per_device[dev];
-    if (s.state == 0) {
-        const bool ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
-                        hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) == hipSuccess &&
-                        hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess;
-        if (!ok) (void)hipGetLastError();
-        s.state = ok ? 1 : -1;
-    }
-    return s.state == 1 ? &s : nullptr;
-}
-
 int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat, uint64_t N, float *dtable, void *ws,
                       size_t ws_bytes, hipStream_t st)
 {
@@ -913,39 +889,22 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
             if (x != hipSuccess) return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot reserve LDS: %s", hipGetErrorString(x));
         lds_opt_in = true;
     }
-    uint64_t batch = 0;
-    Layout L{};
-    if (p.n_keys > 0) {
-        // largest batch the workspace holds
-        batch = (N + kTile - 1) / kTile * kTile;
-        const uint64_t cap = max_batch(d, p);
-        if (batch > cap) batch = cap;
-        while (batch > kTile && make_layout(d, p, batch).total > ws_bytes) batch = (batch / 2 + kTile - 1) / kTile * kTile;
-        L = make_layout(d, p, batch);
-        if (L.total > ws_bytes)
-            return fail(DG_ERR_WORKSPACE, "dg_hashgrid_encode_bwd: workspace %zu bytes cannot hold one tile (%zu needed)", ws_bytes, L.total);
-    }
-    // The coarse prefix shares nothing with the binned levels but dtable, which both only add to: it runs beside
-    // the count sweep on a stream of its own (it keeps few wavefronts per compute unit busy, the count sweep needs
-    // next to no LDS) and the caller's stream waits for it at the end.
-    SideStream *side = nullptr;
     if (p.first_level > 0) {
-        hipStream_t cs = st;
-        if (p.n_keys > 0 && (side = side_stream()) != nullptr) {
-            if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
-                return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot order the side stream: %s", hipGetErrorString(hipGetLastError()));
-            cs = side->stream;
-        }
         const uint64_t tiles = (N + kCoarseBlock - 1) / kCoarseBlock;
         const uint32_t grid = (uint32_t)(tiles < kCoarseGrid ? tiles : kCoarseGrid);
-        coarse_kernel<<<grid, kCoarseBlock, 2 * d->offset[p.first_level] * sizeof(double), cs>>>(
+        coarse_kernel<<<grid, kCoarseBlock, 2 * d->offset[p.first_level] * sizeof(double), st>>>(
             *d, p.first_level, u, (const float2 *)dfeat, N, dtable);
-        // joined right away in stream order of the side stream; the caller's stream picks the event up below
-        if (side && hipEventRecord(side->join, side->stream) != hipSuccess)
-            return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot mark the side stream: %s", hipGetErrorString(hipGetLastError()));
     }
     if (p.n_keys == 0) return launch_status("dg_hashgrid_encode_bwd");
 
+    // largest batch the workspace holds
+    uint64_t batch = (N + kTile - 1) / kTile * kTile;
+    const uint64_t cap = max_batch(d, p);
+    if (batch > cap) batch = cap;
+    while (batch > kTile && make_layout(d, p, batch).total > ws_bytes) batch = (batch / 2 + kTile - 1) / kTile * kTile;
+    const Layout L = make_layout(d, p, batch);
+    if (L.total > ws_bytes)
+        return fail(DG_ERR_WORKSPACE, "dg_hashgrid_encode_bwd: workspace %zu bytes cannot hold one tile (%zu needed)", ws_bytes, L.total);
     char *base = static_cast<char *>(ws);
     uint32_t *rows = reinterpret_cast<uint32_t *>(base + L.rows);
     uint32_t *totals = reinterpret_cast<uint32_t *>(base + L.totals);
@@ -978,8 +937,6 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
         const uint32_t acc_grid = (uint32_t)(records / kAccRecords) + p.n_keys;       // upper bound of the workgroups needed
         accumulate_kernel<<<acc_grid, kAccBlock, 2 * kChunk * sizeof(double), st>>>(*d, p, binbase, blkbase, (const u32x4 *)queue, dtable);
     }
-    if (side && hipStreamWaitEvent(st, side->join, 0) != hipSuccess)
-        return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot wait for the side stream: %s", hipGetErrorString(hipGetLastError()));
     return launch_status("dg_hashgrid_encode_bwd");
 }
 
