@@ -129,6 +129,8 @@ GRIDS = {
     "one_level_dense": lambda: (None, dict(L=1, F=2, log2_T=12, n_min=15, growth=1.0, extent=[1.0, 1.0, 1.0])),
     # 37^3 vertices in one dense level: 7 bins of 8192 entries, odd row length, so x-pairs straddle bin boundaries
     "dense_odd": lambda: (None, dict(L=1, F=2, log2_T=16, n_min=36, growth=1.0, extent=[1.0, 1.0, 1.0])),
+    # two dense levels of 18^3 = 5832 entries: the first fits the LDS prefix, the second is binned and is a single bin
+    "one_bin": lambda: (None, dict(L=2, F=2, log2_T=16, n_min=17, growth=1.0, extent=[1.0, 1.0, 1.0])),
     # T = 2^21: a dense level of 34 bins and hashed levels of 256 bins (more than one wavefront's worth)
     "wide": lambda: (None, dict(L=4, F=2, log2_T=21, n_min=64, growth=2.0, extent=[1.0, 1.0, 1.0])),
     # T = 2^24, three hashed levels: 6144 (level, bin) pairs, too many for the counters to sit in LDS
@@ -192,7 +194,8 @@ def test_encode_fwd_and_indices(key, N):
                                            ("one_level_dense", 700, "points"), ("c2", 20011, "rays"),
                                            ("dense_odd", 150001, "points"), ("dense_odd", 30000, "rays"),
                                            ("wide", 20011, "points"), ("wide", 9000, "rays"), ("huge", 20011, "points"),
-                                           ("c2", 1, "points"), ("c2", 7, "rays"), ("c2", 513, "rays"), ("c2", 2048 * 3 + 5, "rays")])
+                                           ("c2", 1, "points"), ("c2", 7, "rays"), ("c2", 513, "rays"), ("c2", 2048 * 3 + 5, "rays"),
+                                           ("one_bin", 60011, "rays"), ("one_bin", 3001, "points")])
 def test_encode_bwd(key, N, flavour, mode):
     say("encode bwd %s N=%d %s %s" % (key, N, flavour, mode))
     g, r, _ = _both_grids(key)
