@@ -595,7 +595,7 @@ fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const
 // workgroup-wide scan, this workgroup's cursors of all (level, bin) pairs in global memory.
 __global__ void __launch_bounds__(kTile)
 fill_wide_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
-                 uint64_t n0, uint64_t nb, uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
+                 uint64_t n0, uint64_t nb, const uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
                  uint4 *__restrict__ queue, float *__restrict__ dtable, uint32_t *__restrict__ largest_out)
 {
     extern __shared__ uint32_t smem[];
@@ -609,18 +609,28 @@ fill_wide_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const f
     const uint32_t tid = threadIdx.x;
     const int lane = tid % dg::kWave;
     const uint32_t mask = (1u << g.log2_T) - 1u;
-    uint32_t *row = rows + (size_t)blockIdx.x * plan.n_keys;
+    const uint32_t *row = rows + (size_t)blockIdx.x * plan.n_keys;
     uint32_t largest = 0;
     const uint64_t n_tiles = (nb + kTile - 1) / kTile;
     StepAhead ahead = {{0.0f, 0.0f, 0.0f}, make_float2(0.0f, 0.0f)};
     if (blockIdx.x < n_tiles) load_ahead(ahead, u, dfeat, N, n0, nb, blockIdx.x, plan.first_level, tid);
+    // taken in before the loop, as every later load is before its step's copy: no step then waits for its own stores
+    asm volatile("" : "+v"(ahead.u[0]), "+v"(ahead.u[1]), "+v"(ahead.u[2]), "+v"(ahead.g.x), "+v"(ahead.g.y));
     for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
         const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
         const LevelGeom lv = level_of(g, l);
+        // this workgroup's queue positions of the level: read once, then kept in LDS and advanced step by step (a read
+        // of global memory in every step would wait for the stores of the step before)
+        for (uint32_t i = tid; i < n_bins; i += kTile) cursor[i] = row[key0 + i] + binbase[key0 + i];
         for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
             const bool live = tile * kTile + tid < nb;
             const float uu[3] = {ahead.u[0], ahead.u[1], ahead.u[2]};
             const float2 gfe = live ? ahead.g : make_float2(0.0f, 0.0f);
+            {
+                const bool same_level = tile + gridDim.x < n_tiles;
+                const uint32_t l_next = same_level ? l : l + 1;
+                if (l_next < g.n_levels) load_ahead(ahead, u, dfeat, N, n0, nb, same_level ? tile + gridDim.x : blockIdx.x, l_next, tid);
+            }
             for (uint32_t i = tid; i < n_bins; i += kTile) cnt[i] = 0u;
             __syncthreads();
             const Emission em = classify(lv, mask, uu, live, lane);
@@ -629,16 +639,12 @@ fill_wide_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const f
 #pragma unroll
                 for (int p = 0; p < 4; ++p) rank[p] = atomicAdd(&cnt[em.e[2 * p] >> kChunkLog2], 1u);
             }
-            __syncthreads();
-            block_exclusive_scan(cnt, start, n_bins, wave_tot);
-            for (uint32_t i = tid; i < n_bins; i += kTile) {
-                cursor[i] = row[key0 + i] + binbase[key0 + i];
-                row[key0 + i] += cnt[i];
-            }
-            const uint32_t total = start[n_bins - 1] + cnt[n_bins - 1];
-            __syncthreads();
             float vx[8], vy[8];
             corner_values(em, gfe, vx, vy, largest);
+            __syncthreads();
+            block_exclusive_scan(cnt, start, n_bins, wave_tot);
+            const uint32_t total = start[n_bins - 1] + cnt[n_bins - 1];
+            __syncthreads();
             if (em.emit) {
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
@@ -647,12 +653,10 @@ fill_wide_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const f
                     stage_pos[start[bin] + rank[p]] = cursor[bin] + rank[p];
                 }
             }
+            // the inputs of the next step are taken in here, before this wavefront issues stores again
+            asm volatile("" : "+v"(ahead.u[0]), "+v"(ahead.u[1]), "+v"(ahead.u[2]), "+v"(ahead.g.x), "+v"(ahead.g.y));
             __syncthreads();
-            {
-                const bool same_level = tile + gridDim.x < n_tiles;
-                const uint32_t l_next = same_level ? l : l + 1;
-                if (l_next < g.n_levels) load_ahead(ahead, u, dfeat, N, n0, nb, same_level ? tile + gridDim.x : blockIdx.x, l_next, tid);
-            }
+            for (uint32_t i = tid; i < n_bins; i += kTile) cursor[i] += cnt[i];
             copy_out(stage, stage_pos, total, tid, kTile, queue);
             __syncthreads();
         }
