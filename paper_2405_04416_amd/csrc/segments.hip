@@ -278,27 +278,19 @@ extern "C" size_t dg_segments_workspace_bytes(uint32_t R, uint32_t P)
     return (n_blocks ? n_blocks : 1) * (size_t)P * sizeof(uint32_t);
 }
 
-extern "C" int dg_ray_aabb_segments(const float *o, const float *d, uint32_t R, const float *parts, const float *holes,
-                                    uint32_t P, float t_min, uint32_t k_max, uint32_t *seg_count, float *seg_t,
-                                    int32_t *seg_part, uint32_t *part_offset, uint32_t *seg_ray,
-                                    uint32_t *seg_slot, uint32_t *status, void *ws, size_t ws_bytes, void *stream)
+namespace {
+
+// shared by the two entry points below: argument checks and the four launches; hist is the [P, n_blocks] counter table
+int ray_aabb_segments(const char *who, const float *o, const float *d, uint32_t R, const float *parts, const float *holes,
+                      uint32_t P, float t_min, uint32_t k_max, uint32_t *seg_count, float *seg_t, int32_t *seg_part,
+                      uint32_t *part_offset, uint32_t *seg_ray, uint32_t *seg_slot, uint32_t *status, uint32_t *hist,
+                      hipStream_t st)
 {
-    DG_REQUIRE(P >= 1 && P <= DG_MAX_PARTITIONS, DG_ERR_UNSUPPORTED, "dg_ray_aabb_segments: P=%u outside 1..%d", P, DG_MAX_PARTITIONS);
-    DG_REQUIRE(k_max >= 1 && k_max <= kMaxK, DG_ERR_UNSUPPORTED, "dg_ray_aabb_segments: k_max=%u outside 1..%u", k_max, kMaxK);
-    DG_REQUIRE(parts && status, DG_ERR_ARG, "dg_ray_aabb_segments: null parts/status");
-    DG_REQUIRE(R == 0 || (o && d && seg_count && seg_t && seg_part), DG_ERR_ARG, "dg_ray_aabb_segments: null ray or output pointer");
-    hipStream_t st = (hipStream_t)stream;
     const uint32_t n_blocks = (R + kBlock - 1) / kBlock;
-    if (part_offset) {
-        DG_REQUIRE(R == 0 || (seg_ray && seg_slot), DG_ERR_ARG, "dg_ray_aabb_segments: part_offset given without seg_ray/seg_slot");
-        DG_REQUIRE(ws && ws_bytes >= dg_segments_workspace_bytes(R, P), DG_ERR_WORKSPACE,
-                   "dg_ray_aabb_segments: workspace %zu < %zu bytes", ws_bytes, dg_segments_workspace_bytes(R, P));
-    }
     if (R > 0) {
         ray_aabb_kernel<<<n_blocks, kBlock, 0, st>>>(o, d, R, parts, holes, P, t_min, k_max, seg_count, seg_t, seg_part, status);
     }
     if (part_offset) {
-        uint32_t *hist = (uint32_t *)ws;
         if (R > 0)
             bucket_count_kernel<<<n_blocks, kBlock, 0, st>>>(seg_count, seg_part, R, k_max, P, n_blocks, hist);
         bucket_scan_kernel<<<1, kScanThreads, 0, st>>>(P, n_blocks, hist, part_offset);
@@ -306,7 +298,35 @@ extern "C" int dg_ray_aabb_segments(const float *o, const float *d, uint32_t R, 
             bucket_scatter_kernel<<<n_blocks, kBlock, 0, st>>>(seg_count, seg_part, R, k_max, P, n_blocks, hist,
                                                                part_offset, seg_ray, seg_slot);
     }
-    return dg::launch_status("dg_ray_aabb_segments");
+    return dg::launch_status(who);
+}
+
+int check_segment_args(const char *who, const float *o, const float *d, uint32_t R, const float *parts, uint32_t P, uint32_t k_max,
+                       const uint32_t *seg_count, const float *seg_t, const int32_t *seg_part, const uint32_t *part_offset,
+                       const uint32_t *seg_ray, const uint32_t *seg_slot, const uint32_t *status)
+{
+    DG_REQUIRE(P >= 1 && P <= DG_MAX_PARTITIONS, DG_ERR_UNSUPPORTED, "%s: P=%u outside 1..%d", who, P, DG_MAX_PARTITIONS);
+    DG_REQUIRE(k_max >= 1 && k_max <= kMaxK, DG_ERR_UNSUPPORTED, "%s: k_max=%u outside 1..%u", who, k_max, kMaxK);
+    DG_REQUIRE(parts && status, DG_ERR_ARG, "%s: null parts/status", who);
+    DG_REQUIRE(R == 0 || (o && d && seg_count && seg_t && seg_part), DG_ERR_ARG, "%s: null ray or output pointer", who);
+    DG_REQUIRE(!part_offset || R == 0 || (seg_ray && seg_slot), DG_ERR_ARG, "%s: part_offset given without seg_ray/seg_slot", who);
+    return DG_OK;
+}
+
+}  // namespace
+
+extern "C" int dg_ray_aabb_segments(const float *o, const float *d, uint32_t R, const float *parts, const float *holes,
+                                    uint32_t P, float t_min, uint32_t k_max, uint32_t *seg_count, float *seg_t,
+                                    int32_t *seg_part, uint32_t *part_offset, uint32_t *seg_ray,
+                                    uint32_t *seg_slot, uint32_t *status, void *ws, size_t ws_bytes, void *stream)
+{
+    const char *who = "dg_ray_aabb_segments";
+    if (int rc = check_segment_args(who, o, d, R, parts, P, k_max, seg_count, seg_t, seg_part, part_offset, seg_ray, seg_slot, status)) return rc;
+    if (part_offset)
+        DG_REQUIRE(ws && ws_bytes >= dg_segments_workspace_bytes(R, P), DG_ERR_WORKSPACE,
+                   "dg_ray_aabb_segments: workspace %zu < %zu bytes", ws_bytes, dg_segments_workspace_bytes(R, P));
+    return ray_aabb_segments(who, o, d, R, parts, holes, P, t_min, k_max, seg_count, seg_t, seg_part, part_offset, seg_ray, seg_slot,
+                             status, (uint32_t *)ws, (hipStream_t)stream);
 }
 
 extern "C" int dg_sample_segments(const float *o, const float *d, const float *seg_t, const uint32_t *seg_ray,
