@@ -103,6 +103,21 @@ int dg_ray_aabb_segments(const float *o, const float *d, uint32_t R,
                          uint32_t *part_offset, uint32_t *seg_ray, uint32_t *seg_slot,
                          uint32_t *status, void *ws, size_t ws_bytes, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid it): dg_ray_aabb_segments with the counter table of the distribution step in a fixed device array of the
+ * library (1 MiB per GPU the library runs on, held until the process ends) instead of a workspace.  Same arguments
+ * without ws / ws_bytes, same results.  Limit: ceil(R/256) * P <= DG_SEGMENTS_STATIC_COUNTERS = 2^18 counters (2^20
+ * rays with 64 boxes, 2^24 rays with 4); beyond that DG_ERR_WORKSPACE and nothing is enqueued.  The call allocates and
+ * frees nothing; the first call on a device looks the array's address up (hipGetSymbolAddress) with that device
+ * current.  Every call on a GPU uses that GPU's one array (each call rewrites all counters it reads, so nothing is
+ * cleared in between): calls that overlap on one GPU -- two streams, two threads -- race; serialise them. */
+#define DG_SEGMENTS_STATIC_COUNTERS (1u << 18)
+int dg_ray_aabb_segments_static(const float *o, const float *d, uint32_t R,
+                                const float *parts, const float *holes, uint32_t P, float t_min, uint32_t k_max,
+                                uint32_t *seg_count, float *seg_t, int32_t *seg_part,
+                                uint32_t *part_offset, uint32_t *seg_ray, uint32_t *seg_slot,
+                                uint32_t *status, void *stream);
+
 /* Stratified jittered samples of the n_seg segments listed in seg_ray/seg_slot (device,
  * already offset to one box's list), all inside box `box` (host, 6 floats).
  * Sample s of a segment: dt = (t_out-t_in)/S, t = t_in + (s+xi)*dt, x = fma(t,d,o),

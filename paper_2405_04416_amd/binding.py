@@ -52,6 +52,9 @@ _SIGNATURES = {
     "dg_ray_aabb_segments": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32, C.c_float, C.c_uint32,
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_size_t, C.c_void_p]),
+    "dg_ray_aabb_segments_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32, C.c_float, C.c_uint32,
+                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_void_p]),
     "dg_sample_segments": (C.c_int, [C.c_void_p] * 5 + [C.c_uint32, C.c_uint32, C.POINTER(C.c_float), C.c_uint32,
                                                         C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "dg_dir_encode": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p]),
@@ -184,6 +187,20 @@ def dg_ray_aabb_segments(o, d, parts, t_min, k_max, seg_count, seg_t, seg_part, 
         _ptr(seg_count, torch.int32), _ptr(seg_t, torch.float32), _ptr(seg_part, torch.int32),
         _ptr(part_offset, torch.int32, True), _ptr(seg_ray, torch.int32, True), _ptr(seg_slot, torch.int32, True),
         _ptr(status, torch.int32), _ptr(ws, None, True), 0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+SEGMENTS_STATIC_COUNTERS = 1 << 18
+
+
+def dg_ray_aabb_segments_static(o, d, parts, t_min, k_max, seg_count, seg_t, seg_part, status, part_offset=None, seg_ray=None,
+                                seg_slot=None, holes=None):
+    R, P = o.shape[0], parts.shape[0]
+    assert holes is None or tuple(holes.shape) == tuple(parts.shape)
+    _check(lib().dg_ray_aabb_segments_static(
+        _ptr(o, torch.float32), _ptr(d, torch.float32), R, _ptr(parts, torch.float32), _ptr(holes, torch.float32, True), P, t_min, k_max,
+        _ptr(seg_count, torch.int32), _ptr(seg_t, torch.float32), _ptr(seg_part, torch.int32),
+        _ptr(part_offset, torch.int32, True), _ptr(seg_ray, torch.int32, True), _ptr(seg_slot, torch.int32, True),
+        _ptr(status, torch.int32), _stream()))
 
 
 def dg_sample_segments(o, d, seg_t, seg_ray, seg_slot, n_seg, k_max, box, S, seed, jitter, u, delta, t=None):

@@ -6,6 +6,7 @@
 // for bit between boxes), so this file is built with -ffp-contract=off.
 #include "dg_internal.h"
 #include "sample_common.h"
+#include <mutex>
 
 #pragma clang fp contract(off)
 
@@ -327,6 +328,54 @@ extern "C" int dg_ray_aabb_segments(const float *o, const float *d, uint32_t R, 
                    "dg_ray_aabb_segments: workspace %zu < %zu bytes", ws_bytes, dg_segments_workspace_bytes(R, P));
     return ray_aabb_segments(who, o, d, R, parts, holes, P, t_min, k_max, seg_count, seg_t, seg_part, part_offset, seg_ray, seg_slot,
                              status, (uint32_t *)ws, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------- the same call for callers that cannot allocate
+// The counter table of the distribution step lives in a fixed device array instead of a caller's workspace.
+constexpr size_t kStaticCounters = DG_SEGMENTS_STATIC_COUNTERS;        // 1 MiB: R/256 blocks x P boxes, e.g. 2^20 rays x 64 boxes
+static __device__ __align__(256) uint32_t scratch[kStaticCounters];   // one copy per GPU, held until the process ends
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+uint32_t *g_scratch_ptr[kMaxDevices] = {};     // device address of `scratch` on each GPU, looked up once per device
+
+// `scratch` as host code sees it is only a handle: the address kernels can use comes from the runtime, per device
+int static_counters(uint32_t **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return dg::fail(DG_ERR_HIP, "dg_ray_aabb_segments_static: hipGetDevice: %s", hipGetErrorString(e));
+    DG_REQUIRE(dev >= 0 && dev < kMaxDevices, DG_ERR_UNSUPPORTED, "dg_ray_aabb_segments_static: device %d outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return dg::fail(DG_ERR_HIP, "dg_ray_aabb_segments_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = (uint32_t *)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DG_OK;
+}
+}  // namespace
+
+extern "C" int dg_ray_aabb_segments_static(const float *o, const float *d, uint32_t R, const float *parts, const float *holes,
+                                           uint32_t P, float t_min, uint32_t k_max, uint32_t *seg_count, float *seg_t,
+                                           int32_t *seg_part, uint32_t *part_offset, uint32_t *seg_ray, uint32_t *seg_slot,
+                                           uint32_t *status, void *stream)
+{
+    const char *who = "dg_ray_aabb_segments_static";
+    if (int rc = check_segment_args(who, o, d, R, parts, P, k_max, seg_count, seg_t, seg_part, part_offset, seg_ray, seg_slot, status)) return rc;
+    const size_t counters = dg_segments_workspace_bytes(R, P) / sizeof(uint32_t);
+    DG_REQUIRE(counters <= kStaticCounters, DG_ERR_WORKSPACE,
+               "dg_ray_aabb_segments_static: ceil(R/256) * P = %zu counters exceed the fixed table of %zu (R=%u, P=%u); use "
+               "dg_ray_aabb_segments with a workspace", counters, kStaticCounters, R, P);
+    uint32_t *hist = nullptr;
+    if (int rc = static_counters(&hist)) return rc;
+    // nothing to clear: the counting kernel writes every counter [p < P, block < ceil(R/256)] the later kernels read
+    return ray_aabb_segments(who, o, d, R, parts, holes, P, t_min, k_max, seg_count, seg_t, seg_part, part_offset, seg_ray, seg_slot,
+                             status, hist, (hipStream_t)stream);
 }
 
 extern "C" int dg_sample_segments(const float *o, const float *d, const float *seg_t, const uint32_t *seg_ray,
