@@ -16,6 +16,7 @@
 //     accumulate in LDS (as scaled 64-bit integers: integer adds are the fastest LDS atomics) and add the
 //     finished bin into dtable with coalesced atomics.
 #include "encode_common.h"
+#include <mutex>
 
 namespace dg_encode_binned {
 
@@ -27,7 +28,7 @@ constexpr int kMaxBins = 2048;                     // per level: 2^24 entries / 
 constexpr int kTile = 512;                         // samples per tile == threads per binning workgroup
 constexpr int kKeeper = 64;                        // narrow fill sweep: one more wavefront, which keeps the books of the 64 bins
 constexpr int kPairs = kTile * 4;                  // records staged per (tile, level): one per pair of corners along x
-constexpr uint32_t kLdsKeys = 4096;                // count sweep: (level, bin) counters kept in LDS when there are at most this many
+constexpr uint32_t kMaxKeys = DG_MAX_LEVELS * kMaxBins;   // (level, bin) pairs at most: the count sweep keeps one counter each in LDS (128 KB)
 constexpr int kBinGrid = 768;                      // persistent binning workgroups (three per compute unit)
 constexpr int kAccBlock = 1024;                    // threads of an accumulate workgroup (one per compute unit: its table fills LDS)
 constexpr int kAccDepth = 4;                       // records in flight per accumulate thread
@@ -43,12 +44,6 @@ struct Plan {
     uint32_t n_bins[DG_MAX_LEVELS];
     uint32_t max_bins;
 };
-
-__global__ void __launch_bounds__(256) zero_u32_kernel(uint32_t *p, size_t n)
-{
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = 0u;
-}
 
 // ------------------------------------------------------------------ coarse prefix: accumulate in LDS
 __global__ void __launch_bounds__(kCoarseBlock)
@@ -209,65 +204,6 @@ count_lds_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, uint64_
     for (uint32_t i = tid; i < plan.n_keys; i += kTile) row_global[i] = row[i];
 }
 
-// count sweep with the counters of one level in LDS and this workgroup's row of all (level, bin) counters in
-// global memory (grids with too many bins for LDS)
-__global__ void __launch_bounds__(kTile)
-count_global_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, uint64_t n0, uint64_t nb, uint32_t *__restrict__ rows)
-{
-    extern __shared__ uint32_t smem[];
-    uint32_t *cnt = smem;                                // [max_bins]
-    const uint32_t tid = threadIdx.x;
-    const int lane = tid % dg::kWave;
-    const uint32_t mask = (1u << g.log2_T) - 1u;
-    uint32_t *row = rows + (size_t)blockIdx.x * plan.n_keys;
-    const uint64_t n_tiles = (nb + kTile - 1) / kTile;
-    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const uint64_t rel = tile * kTile + tid;
-        const bool live = rel < nb;
-        const uint64_t n = n0 + (live ? rel : nb - 1);
-        const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
-        for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
-            const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
-            for (uint32_t i = tid; i < n_bins; i += kTile) cnt[i] = 0u;
-            __syncthreads();
-            const Emission em = classify(level_of(g, l), mask, uu, live, lane);
-            if (em.emit) {
-#pragma unroll
-                for (int p = 0; p < 4; ++p) atomicAdd(&cnt[em.e[2 * p] >> kChunkLog2], 1u);
-            }
-            __syncthreads();
-            for (uint32_t i = tid; i < n_bins; i += kTile) row[key0 + i] += cnt[i];
-            __syncthreads();
-        }
-    }
-}
-
-// exclusive scan of cnt[0, n) into start[0, n) by the whole workgroup, 2 * kTile counters per round
-__device__ __forceinline__ void block_exclusive_scan(const uint32_t *cnt, uint32_t *start, uint32_t n, uint32_t *wave_tot)
-{
-    const uint32_t t = threadIdx.x, lane = t % dg::kWave, wave = t / dg::kWave;
-    uint32_t carry = 0;
-    for (uint32_t lo = 0; lo < n; lo += 2 * kTile) {
-        const uint32_t i0 = lo + 2 * t, i1 = i0 + 1;
-        const uint32_t a = i0 < n ? cnt[i0] : 0u, b = i1 < n ? cnt[i1] : 0u;
-        uint32_t incl = a + b;
-#pragma unroll
-        for (int off = 1; off < dg::kWave; off <<= 1) {
-            const uint32_t up = __shfl_up(incl, off, dg::kWave);
-            if ((int)lane >= off) incl += up;
-        }
-        if (lane == dg::kWave - 1) wave_tot[wave] = incl;
-        __syncthreads();
-        uint32_t base = carry, all = 0;
-        for (uint32_t w = 0; w < kTile / dg::kWave; ++w) { if (w < wave) base += wave_tot[w]; all += wave_tot[w]; }
-        const uint32_t excl = base + incl - (a + b);
-        if (i0 < n) start[i0] = excl;
-        if (i1 < n) start[i1] = excl + a;
-        carry += all;
-        __syncthreads();
-    }
-}
-
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ void scan_step(uint32_t &v)
 {
@@ -362,26 +298,6 @@ __device__ __forceinline__ uint4 make_record(const Emission &em, int p, const fl
         if (vy[2 * p + 1] != 0.0f) unsafeAtomicAdd(dst + 1, vy[2 * p + 1]);
     }
     return pack_record(ea & (kChunk - 1u), code, vx[2 * p], vy[2 * p], together ? vx[2 * p + 1] : 0.0f, together ? vy[2 * p + 1] : 0.0f);
-}
-
-// wide sweep: copy staged records [0, total) to their queue positions; `n_threads` threads (this one is `t`) share the
-// work, four records per thread in flight, reads clamped so they batch
-__device__ __forceinline__ void copy_out(const uint4 *stage, const uint32_t *stage_pos, uint32_t total, uint32_t t, uint32_t n_threads,
-                                         uint4 *__restrict__ queue)
-{
-    for (uint32_t sb = 0; sb < total; sb += 4 * n_threads) {
-        uint4 rec[4];
-        uint32_t at[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint32_t s = min(sb + t + k * n_threads, total - 1u);
-            rec[k] = stage[s];
-            at[k] = stage_pos[s];
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if (sb + t + k * n_threads < total) queue[at[k]] = rec[k];
-    }
 }
 
 // Fill sweep for grids with at most 64 bins in every level.  kTile threads bin the samples; every one of their
@@ -591,21 +507,22 @@ fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const
     publish_largest(largest, cnt, largest_out);
 }
 
-// Fill sweep for any number of bins: counters, staging offsets and queue cursors of the step in LDS arrays,
-// workgroup-wide scan, this workgroup's cursors of all (level, bin) pairs in global memory.
+// Fill sweep for any number of bins.  With hundreds or thousands of bins per level a tile of 512 samples brings a bin
+// one record or none, so sorting a step's records by bin in LDS first (as the narrow sweep does) orders nothing: here
+// a record goes straight to its place.  The workgroup's queue cursors of the level's bins sit in LDS; a lane takes
+// the position of each of its four records with one LDS add that returns the old value and stores the record there.
+// The count sweep has sized this workgroup's slice of every bin for exactly these records, so no cursor can run into
+// a neighbour's slice, and because the sums are integers the order in which lanes take positions does not matter.
+// No barrier inside a level: the wavefronts of a workgroup drift apart freely; two barriers where the level changes
+// and the cursors are reloaded.  Consecutive steps of a workgroup extend the same slices, so the cache lines at
+// their ends are completed while they still sit in L2.
 __global__ void __launch_bounds__(kTile)
-fill_wide_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
-                 uint64_t n0, uint64_t nb, const uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
-                 uint4 *__restrict__ queue, float *__restrict__ dtable, uint32_t *__restrict__ largest_out)
+fill_direct_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
+                   uint64_t n0, uint64_t nb, const uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
+                   uint4 *__restrict__ queue, float *__restrict__ dtable, uint32_t *__restrict__ largest_out)
 {
     extern __shared__ uint32_t smem[];
-    const uint32_t cap = plan.max_bins;
-    uint32_t *cnt = smem;                                             // [cap]
-    uint32_t *start = cnt + cap;                                      // [cap] first staging slot of each bin
-    uint32_t *cursor = start + cap;                                   // [cap] queue position of each bin's first record
-    uint32_t *wave_tot = cursor + cap;                                // [16]
-    uint4 *stage = reinterpret_cast<uint4 *>(wave_tot + 16);          // [kPairs] records of the step, sorted by bin
-    uint32_t *stage_pos = reinterpret_cast<uint32_t *>(stage + kPairs);            // [kPairs] their queue positions
+    uint32_t *cursor = smem;                                          // [max_bins] queue position of each bin's next record
     const uint32_t tid = threadIdx.x;
     const int lane = tid % dg::kWave;
     const uint32_t mask = (1u << g.log2_T) - 1u;
@@ -614,54 +531,36 @@ fill_wide_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const f
     const uint64_t n_tiles = (nb + kTile - 1) / kTile;
     StepAhead ahead = {{0.0f, 0.0f, 0.0f}, make_float2(0.0f, 0.0f)};
     if (blockIdx.x < n_tiles) load_ahead(ahead, u, dfeat, N, n0, nb, blockIdx.x, plan.first_level, tid);
-    // taken in before the loop, as every later load is before its step's copy: no step then waits for its own stores
-    asm volatile("" : "+v"(ahead.u[0]), "+v"(ahead.u[1]), "+v"(ahead.u[2]), "+v"(ahead.g.x), "+v"(ahead.g.y));
     for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
         const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
         const LevelGeom lv = level_of(g, l);
-        // this workgroup's queue positions of the level: read once, then kept in LDS and advanced step by step (a read
-        // of global memory in every step would wait for the stores of the step before)
+        __syncthreads();                                              // nobody is still on the last level's cursors
         for (uint32_t i = tid; i < n_bins; i += kTile) cursor[i] = row[key0 + i] + binbase[key0 + i];
+        __syncthreads();
         for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
             const bool live = tile * kTile + tid < nb;
             const float uu[3] = {ahead.u[0], ahead.u[1], ahead.u[2]};
             const float2 gfe = live ? ahead.g : make_float2(0.0f, 0.0f);
+            // the next step's inputs are asked for before this step's stores: loads and stores of a wavefront retire
+            // in order, so a load issued behind the stores could only be awaited together with them
             {
                 const bool same_level = tile + gridDim.x < n_tiles;
                 const uint32_t l_next = same_level ? l : l + 1;
                 if (l_next < g.n_levels) load_ahead(ahead, u, dfeat, N, n0, nb, same_level ? tile + gridDim.x : blockIdx.x, l_next, tid);
             }
-            for (uint32_t i = tid; i < n_bins; i += kTile) cnt[i] = 0u;
-            __syncthreads();
             const Emission em = classify(lv, mask, uu, live, lane);
-            uint32_t rank[4];
-            if (em.emit) {
-#pragma unroll
-                for (int p = 0; p < 4; ++p) rank[p] = atomicAdd(&cnt[em.e[2 * p] >> kChunkLog2], 1u);
-            }
             float vx[8], vy[8];
             corner_values(em, gfe, vx, vy, largest);
-            __syncthreads();
-            block_exclusive_scan(cnt, start, n_bins, wave_tot);
-            const uint32_t total = start[n_bins - 1] + cnt[n_bins - 1];
-            __syncthreads();
             if (em.emit) {
+                uint32_t at[4];
 #pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    const uint32_t bin = em.e[2 * p] >> kChunkLog2;
-                    stage[start[bin] + rank[p]] = make_record(em, p, vx, vy, lv.offset, dtable);
-                    stage_pos[start[bin] + rank[p]] = cursor[bin] + rank[p];
-                }
+                for (int p = 0; p < 4; ++p) at[p] = atomicAdd(&cursor[em.e[2 * p] >> kChunkLog2], 1u);
+#pragma unroll
+                for (int p = 0; p < 4; ++p) queue[at[p]] = make_record(em, p, vx, vy, lv.offset, dtable);
             }
-            // the inputs of the next step are taken in here, before this wavefront issues stores again
-            asm volatile("" : "+v"(ahead.u[0]), "+v"(ahead.u[1]), "+v"(ahead.u[2]), "+v"(ahead.g.x), "+v"(ahead.g.y));
-            __syncthreads();
-            for (uint32_t i = tid; i < n_bins; i += kTile) cursor[i] += cnt[i];
-            copy_out(stage, stage_pos, total, tid, kTile, queue);
-            __syncthreads();
         }
     }
-    publish_largest(largest, cnt, largest_out);
+    publish_largest(largest, cursor, largest_out);
 }
 
 // rows[b][k] (per-workgroup counts, each rounded up to a multiple of `round`) -> exclusive prefix over workgroups;
@@ -880,19 +779,20 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
 {
     using namespace dg_encode_binned;
     const Plan p = make_plan(d);
-    static bool lds_opt_in = false;
-    if (!lds_opt_in) {
-        const int fill_lds = (3 * kMaxBins + 16) * 4 + kPairs * 20;      // the most a launch may ask for (the wide sweep)
-        const int acc_lds = 2 * kChunk * (int)sizeof(double);
+    // kernels that use more LDS than a launch gets by default: asked for once per process, whichever thread comes first
+    static std::once_flag lds_once;
+    static hipError_t lds_status = hipSuccess;
+    std::call_once(lds_once, [] {
+        const int acc_lds = 2 * kChunk * (int)sizeof(double), count_lds = (int)kMaxKeys * 4;
         const hipError_t e[4] = {
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_wide_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds),
-            hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_narrow_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, fill_lds),
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&count_lds_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, count_lds),
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_narrow_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kNarrowLds),
             hipFuncSetAttribute(reinterpret_cast<const void *>(&accumulate_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, acc_lds),
             hipFuncSetAttribute(reinterpret_cast<const void *>(&coarse_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, acc_lds)};
         for (const hipError_t x : e)
-            if (x != hipSuccess) return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot reserve LDS: %s", hipGetErrorString(x));
-        lds_opt_in = true;
-    }
+            if (x != hipSuccess) lds_status = x;
+    });
+    if (lds_status != hipSuccess) return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot reserve LDS: %s", hipGetErrorString(lds_status));
     if (p.first_level > 0) {
         const uint64_t tiles = (N + kCoarseBlock - 1) / kCoarseBlock;
         const uint32_t grid = (uint32_t)(tiles < kCoarseGrid ? tiles : kCoarseGrid);
@@ -915,28 +815,21 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     uint32_t *binbase = reinterpret_cast<uint32_t *>(base + L.binbase);
     uint32_t *blkbase = reinterpret_cast<uint32_t *>(base + L.blkbase);
     uint4 *queue = reinterpret_cast<uint4 *>(base + L.queue);
-    const size_t n_rows_words = (size_t)kBinGrid * p.n_keys;
     const bool narrow = p.max_bins <= 64;                 // then n_keys <= 64 * DG_MAX_LEVELS
-    const bool count_in_lds = p.n_keys <= kLdsKeys;
-    const int fill_lds = narrow ? kNarrowLds : (3 * (int)p.max_bins + 16) * 4 + kPairs * 20;
+    if (p.n_keys > kMaxKeys) return fail(DG_ERR_UNSUPPORTED, "dg_hashgrid_encode_bwd: %u table regions exceed %u", p.n_keys, kMaxKeys);
 
     for (uint64_t n0 = 0; n0 < N; n0 += batch) {
         const uint64_t nb = N - n0 < batch ? N - n0 : batch;
-        if (count_in_lds) {
-            count_lds_kernel<<<kBinGrid, kTile, p.n_keys * 4, st>>>(*d, p, u, n0, nb, rows);
-        } else {
-            zero_u32_kernel<<<(uint32_t)((n_rows_words + 255) / 256), 256, 0, st>>>(rows, n_rows_words);
-            count_global_kernel<<<kBinGrid, kTile, p.max_bins * 4, st>>>(*d, p, u, n0, nb, rows);
-        }
+        count_lds_kernel<<<kBinGrid, kTile, p.n_keys * 4, st>>>(*d, p, u, n0, nb, rows);
         scan_rows_kernel<<<(p.n_keys + kScanKeys - 1) / kScanKeys, kScanKeys * kScanGroups, 0, st>>>(rows, kBinGrid, p.n_keys,
                                                                                                 narrow ? kSliceRound : 1u, totals);
         scan_totals_kernel<<<1, 1024, 0, st>>>(totals, p.n_keys, binbase, blkbase);
         if (narrow)
-            fill_narrow_kernel<<<kBinGrid, kNarrowThreads, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, queue,
+            fill_narrow_kernel<<<kBinGrid, kNarrowThreads, kNarrowLds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, queue,
                                                                              dtable, binbase + p.n_keys + 1);
         else
-            fill_wide_kernel<<<kBinGrid, kTile, fill_lds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, queue, dtable,
-                                                                binbase + p.n_keys + 1);
+            fill_direct_kernel<<<kBinGrid, kTile, p.max_bins * 4, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, queue, dtable,
+                                                                        binbase + p.n_keys + 1);
         const uint64_t records = nb * 4ull * (d->n_levels - p.first_level) + slice_padding(p);
         const uint32_t acc_grid = (uint32_t)(records / kAccRecords) + p.n_keys;       // upper bound of the workgroups needed
         accumulate_kernel<<<acc_grid, kAccBlock, 2 * kChunk * sizeof(double), st>>>(*d, p, binbase, blkbase, (const u32x4 *)queue, dtable);

@@ -29,6 +29,13 @@ def test_library_exports_every_declared_symbol():
     assert set(B.EXPORTS) == set(names)
 
 
+def test_peaks_library_exports_its_symbols():
+    from paper_2405_04416_amd import peaks
+    handle = C.CDLL(peaks.LIB_PATH)
+    for n in peaks.EXPORTS:
+        assert hasattr(handle, n), n
+
+
 def test_no_oracle_in_product_path():
     pkg = os.path.join(ROOT, "paper_2405_04416_amd")
     for dirpath, _, files in os.walk(pkg):
