@@ -3,12 +3,16 @@
 One "step" is one forward + backward pass of every hot-path stage (ray/box segments, distribution,
 sampling, direction encoding, hash-grid encode, MLPs, segment compositing, merge, loss seeds and
 all their backward passes, including zeroing the gradient buffers) over one batch of synthetic
-rays that is already resident in HBM.  The workload is the Instant-NGP-scale single-partition
-configuration (2^18 rays x 64 samples, L=16, F=2, T=2^19).  Prints ONE JSON line.
+rays that is already resident in HBM.  The headline workload is the largest single-GPU
+configuration: one GPU's share of a 2 x 4 tiling (c5_share: 2^20 rays x 64 samples, L=16, F=2,
+T=2^24, all eight boxes traced, one sub-model resident, the other boxes' partials synthetic).
+The other paper-scale configurations are timed after it and reported as blocks of the same
+line (`also`).  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_ngp] [--no-cpu-baseline] [--no-optimizer]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5_share] [--also c4_big,c2_ngp]
+                    [--no-cpu-baseline] [--no-optimizer] [--no-peaks]
 
---workload c7_occ runs the same scene with occupancy-guided sampling (Sec. 3.2, Sec. 5.1) instead of 64 stratified
+--workload c7_occ runs c2's scene with occupancy-guided sampling (Sec. 3.2, Sec. 5.1) instead of 64 stratified
 samples per segment, and also times the occupancy refresh.
 """
 import argparse
@@ -23,11 +27,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA, published
+LINE_BYTES = 128               # what one L2 miss fetches
 
-# HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (scaled by a known elementwise kernel), summed over the
-# kernels an entry point launches; measured once per workload and recorded in profiles/<workload>_hbm_traffic.md
+# HBM-side bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (scaled by a plain copy kernel of known size), summed
+# over the kernels an entry point launches: (fetched, written).  Measured once per workload with the kernels as they
+# stand; the runs, their commands and the calibration are in profiles/<workload>_hbm_traffic.md.
 MEASURED_TRAFFIC_BYTES = {
-    "c2_ngp": {"dg_hashgrid_encode_bwd": 17.5e9, "dg_hashgrid_encode_fwd": 7.33e9, "dg_mlp_fwd": 1.08e9, "dg_mlp_bwd": 4.6e9},
+    "c2_ngp": {"dg_hashgrid_encode_bwd": (10.7e9, 6.8e9), "dg_hashgrid_encode_fwd": (6.48e9, 0.85e9), "dg_mlp_fwd": (0.87e9, 0.21e9),
+               "dg_mlp_bwd": (2.36e9, 2.2e9)},
 }
 
 
@@ -51,57 +58,83 @@ def algorithmic_work(entry, L, F, n_samples, mlp_flops_fwd):
     return "hbm", None
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2_ngp")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rays", type=int, default=16384)
-    ap.add_argument("--no-optimizer", action="store_true", help="skip the separate timing of the Adam sweep")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="after the timed region, stream 1 GiB through one elementwise kernel (known traffic, for scaling "
-                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not available. "
-                 "value is the one GPU's throughput." % args.gpus)
+def workload_config(name):
+    """The configuration with the partition set the benchmark traces and the partitions whose sub-models are resident."""
+    import dg_inputs as di
+    cfg = di.config(name)
+    P = cfg["parts"].shape[0]
+    resident = [cfg["resident"]] if "resident" in cfg else list(range(P))
+    return cfg, resident
 
+
+# ------------------------------------------------------------------------------------------------ CPU baseline
+def _oracle_pass(job):
+    """One forward + backward pass of the oracle over rays [lo, hi) of the batch (runs in a forked worker or in place)."""
+    import oracle.step as ostep
+    lo, hi = job
+    cfg, hm, ho, app, resident, o, d, Cgt = _ORACLE_STATE
+    t = time.perf_counter()
+    ostep.run_step(cfg, hm, o[lo:hi], d[lo:hi], Cgt[lo:hi], seed=0, lambda1=1e-3, loss_scale=65536.0, resident=resident, occ=ho,
+                   appearance=None if app is None else (app[0], app[1][lo:hi]))
+    return time.perf_counter() - t
+
+
+_ORACLE_STATE = None
+
+
+def cpu_baseline(name, rays_per_core):
+    """The oracle as it stands on this machine's host cores: first on one core, then one process per core, each over
+    its own `rays_per_core` rays of the same batch with the full-size tables (forked after the tables are built, so the
+    workers share them).  Must run before anything initialises the GPU: the workers are forks of this process."""
+    global _ORACLE_STATE
+    import multiprocessing as mp
+    import dg_inputs as di
+    import oracle.step as ostep
+    cfg, resident = workload_config(name)
+    R = cfg["R"]
+    o, d = di.make_rays(cfg, seed=0)
+    Cgt = di.make_targets(R, seed=0)
+    hm = ostep.make_models(dict(cfg, resident_list=resident), seed=0)
+    ho = ostep.make_occupancy(cfg, seed=0) if "occ" in cfg else None
+    app = di.make_appearance(cfg["n_images"], cfg["mlp"]["n_app"], R, seed=0) if cfg["mlp"].get("n_app") else None
+    _ORACLE_STATE = (cfg, hm, ho, app, resident, o, d, Cgt)
+    Rc = min(rays_per_core, R)
+    single_s = _oracle_pass((0, Rc))
+    # the box gives this job 16 cores whatever the machine reports
+    cores = max(1, min(16, os.cpu_count() or 1, R // Rc))
+    jobs = [(k * Rc, (k + 1) * Rc) for k in range(cores)]
+    t = time.perf_counter()
+    with mp.get_context("fork").Pool(cores) as pool:
+        pool.map(_oracle_pass, jobs)
+    all_s = time.perf_counter() - t
+    _ORACLE_STATE = None
+    model = ""
+    try:
+        model = next(l.split(":", 1)[1].strip() for l in open("/proc/cpuinfo") if l.startswith("model name"))
+    except (OSError, StopIteration):
+        pass
+    return {"value": round(cores * Rc / all_s, 2), "unit": "rays/s", "cores": cores, "kind": "oracle",
+            "sample": "%d rays per core of the same batch (%s), full-size tables, one fwd+bwd pass, one process per core, %.1f s"
+                      % (Rc, name, all_s),
+            "single_core": {"value": round(Rc / single_s, 2), "unit": "rays/s", "cores": 1,
+                            "sample": "first %d rays, %.1f s" % (Rc, single_s)},
+            "nproc": os.cpu_count(), "cpu_model": model}
+
+
+# ------------------------------------------------------------------------------------------------ one workload on the GPU
+def run_workload(name, steps, warmup, peaks, with_optimiser=True, with_evaluation=True):
     import numpy as np
     import torch
     import dg_inputs as di
     from paper_2405_04416_amd import binding as B
     from paper_2405_04416_amd.step import Occupancy, SubModel, TrainStep, split_appearance_columns
 
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
-    B.lib()                                    # fail loudly if the HIP library is not built
     dev = torch.device("cuda:0")
-    cfg = di.config(args.workload)
+    cfg, resident = workload_config(name)
     g, m = cfg["grid"], cfg["mlp"]
     R, S, k_max = cfg["R"], cfg["S"], cfg["k_max"]
-    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-    foreign = None
-    if "resident" in cfg:
-        # one GPU's share of a larger tiling: only the resident box is traced; for a seeded fraction of the rays
-        # 1..k_max-1 partials of other partitions are synthetic (colour, transmittance) pairs placed around the local one
-        cfg["parts"] = cfg["parts"][cfg["resident"]:cfg["resident"] + 1]
-        cfg["rays"] = "oblique"
-        before, after, fC, fT = di.make_extra_partials(R, k_max, cfg["extra_fraction"], seed=0)
-        before_d, total_d = to_dev(before.astype(np.int64)), to_dev((before + after + 1).astype(np.int32))
-        fC_d, fT_d = to_dev(fC), to_dev(fT)
-
-        def foreign(st):
-            n = st.offsets[1]
-            ray = st.seg_ray[:n].long()
-            loc_c, loc_t = st.Ck[ray, 0].clone(), st.Tk[ray, 0].clone()
-            st.Ck.copy_(fC_d); st.Tk.copy_(fT_d)
-            st.Ck[ray, before_d[ray]] = loc_c; st.Tk[ray, before_d[ray]] = loc_t
-            st.seg_slot[:n] = before_d[ray].int()
-            st.seg_count.mul_(total_d)
     P = cfg["parts"].shape[0]
-    resident = list(range(P))
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
 
     # seeded synthetic inputs, moved to HBM before anything is timed
     o, d = di.make_rays(cfg, seed=0)
@@ -130,57 +163,65 @@ def main():
             occupancy[p] = Occupancy(desc, density, bits, np.float32(float(ext.max()) * np.sqrt(3.0) / 1024), cfg["occ"]["max_steps"])
             B.dg_occ_bits(density, 0.6, bits, occupancy[p].n_set)
         extra = dict(occupancy=occupancy, max_samples=R * 32)
-    app_host = None
     if m.get("n_app"):
         # appearance vectors per image as further colour-net inputs (Sec. 4.4.3): seeded stand-ins, every ray in a random image
         app_host = di.make_appearance(cfg["n_images"], m["n_app"], R, seed=0)
         extra["appearance"] = (to_dev(app_host[0]), to_dev(app_host[1].view(np.int32)))
+    # room for the resident sub-models' segments: a ray crosses a box once (twice where the box has a hole)
+    max_segments = R * min(k_max, 4) if len(resident) == P else R * len(resident)
     step = TrainStep(to_dev(cfg["parts"]), models, resident, R, S, k_max, m["sh_degree"], loss_scale=65536.0,
                      lambda1=1e-3, seed=0, holes=to_dev(cfg["holes"]) if "holes" in cfg else None,
-                     max_segments=R * min(k_max, 4), **extra)  # rays of these recipes average well under four segments
+                     max_segments=max_segments, foreign_prefilled=len(resident) < P, encode_ws_cap=72 << 30, **extra)
+    if len(resident) < P:
+        # partial results of the boxes whose sub-models live on other GPUs: synthetic (colour, transmittance) in every
+        # slot, written once -- the local rendering overwrites the slots of the resident box's segments every step, the
+        # merge reads the first seg_count[r] slots of a ray
+        fC, fT = di.make_foreign_partials(R, k_max, seed=0)
+        step.Ck.copy_(to_dev(fC)); step.Tk.copy_(to_dev(fT))
 
-    for w in range(args.warmup):
+    for w in range(warmup):
         step.seed = w
-        step.step(od, dd, Cd, None, foreign)
+        step.step(od, dd, Cd)
     torch.cuda.synchronize()
     step.timings = {}
     t0 = time.perf_counter()
-    for k in range(args.steps):
-        step.seed = args.warmup + k            # fresh jitter every step, drawn inside the sampling kernel
-        step.step(od, dd, Cd, None, foreign)
+    for k in range(steps):
+        step.seed = warmup + k                 # fresh jitter every step, drawn inside the sampling kernel
+        step.step(od, dd, Cd)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = 1e3 * wall / args.steps
+    ms_per_step = 1e3 * wall / steps
     n_seg = sum(step.offsets[p + 1] - step.offsets[p] for p in resident)
     n_samples = n_seg * S if occupancy is None else sum(n for _, n in step.samples.values())
     per_call = step.timing_summary()           # HIP events on the launch stream, inside the timed region
+    seg_hist = torch.bincount(step.seg_count, minlength=k_max + 1).cpu().tolist()
 
     # the occupancy refresh (every 16th iteration, Sec. 5.1), measured apart from the metric, in both of its forms
     refresh = None
     if occupancy is not None:
         cells = sum(q.desc.n_cells for q in occupancy.values())
         refresh = {"cells": cells, "occupied_fraction": round(sum(int(q.n_set.item()) for q in occupancy.values()) / cells, 4)}
-        for name, it in (("warmup_all_cells", 16), ("half_uniform_half_occupied", 4112)):
+        for label, it in (("warmup_all_cells", 16), ("half_uniform_half_occupied", 4112)):
             saved = {p: (q.density.clone(), q.bits.clone()) for p, q in occupancy.items()}
             torch.cuda.synchronize()
             t1 = time.perf_counter()
             step.timings = None
             step.refresh_occupancy(it)
             torch.cuda.synchronize()
-            refresh[name] = {"ms": round(1e3 * (time.perf_counter() - t1), 3),
-                             "candidates": sum(q.desc.n_cells // (1 if it < 4096 else 2) for q in occupancy.values())}
+            refresh[label] = {"ms": round(1e3 * (time.perf_counter() - t1), 3),
+                              "candidates": sum(q.desc.n_cells // (1 if it < 4096 else 2) for q in occupancy.values())}
             for p, q in occupancy.items():         # the random-weight field is no scene: put the stand-in grid back
                 q.density.copy_(saved[p][0]); q.bits.copy_(saved[p][1])
 
     # the optimiser sweep (Sec. 5.1: Adam), measured apart from the metric: `value` stays the forward+backward rate
     optimiser = None
-    if not args.no_optimizer:
+    if with_optimiser:
         n_param = sum(models[p].table.numel() for p in resident)
         touched = sum(int(torch.count_nonzero(models[p].dtable)) for p in resident)
         step.timings = {}
         for k in range(3):
             if k:
-                step.step(od, dd, Cd, None, foreign)       # fresh gradients for every sweep
+                step.step(od, dd, Cd)                      # fresh gradients for every sweep
             step.optimiser_step(k)
         calls, total_ms = step.timing_summary()["dg_adam_step"]
         ms = total_ms / 3
@@ -191,7 +232,7 @@ def main():
 
     # evaluation rendering (forward only: colour, depth, transmittance; Sec. 4.4.2), apart from the metric
     evaluation = None
-    if foreign is None:
+    if with_evaluation:
         step.timings = None
         step.render(od, dd)
         torch.cuda.synchronize()
@@ -202,71 +243,145 @@ def main():
         ev_ms = 1e3 * (time.perf_counter() - t1) / 3
         evaluation = {"ms_per_batch": round(ev_ms, 4), "rays_per_s": round(R / (ev_ms * 1e-3), 1), "outputs": "colour, depth, transmittance"}
 
-    if args.copy_calibration:
-        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        torch.add(src, 1.0, out=dst)           # 1 GiB read + 1 GiB written by one plain elementwise kernel
-        torch.cuda.synchronize()
-
     shapes = di.mlp_layer_shapes(n_feat, m)
     mlp_flops_fwd = 2 * sum(no * ni for no, ni in shapes)
-    breakdown = {k: round(ms / args.steps, 4) for k, (n, ms) in sorted(per_call.items(), key=lambda kv: -kv[1][1])}
+    breakdown = {k: round(ms / steps, 4) for k, (n, ms) in sorted(per_call.items(), key=lambda kv: -kv[1][1])}
+    per_launch_samples = n_samples / max(len(resident), 1)
+    traffic = MEASURED_TRAFFIC_BYTES.get(name, {})
+    copy_peak = (peaks or {}).get("stream_copy_GBps")
+    gather_peak = (peaks or {}).get("random_gather_16B_1024MiB_Gps")
+    atomic_peak = (peaks or {}).get("random_atomic_add_f32_1024MiB_Gps")
+    mfma_peak = (peaks or {}).get("mfma_f16_32x32x16_TFLOPs")
+
+    # every headline entry point: time per launch, algorithmic rate against the datasheet peak, the rate by measured HBM
+    # traffic where a profile of this workload exists, and the rate against the yardstick measured in this run
+    kernels = {}
+    for entry in ("dg_hashgrid_encode_fwd", "dg_hashgrid_encode_bwd", "dg_mlp_fwd", "dg_mlp_bwd"):
+        if entry not in per_call:
+            continue
+        c, t = per_call[entry]
+        sec = t / c * 1e-3
+        bound, work = algorithmic_work(entry, g["L"], g["F"], per_launch_samples, mlp_flops_fwd)
+        k = {"avg_launch_ms": round(t / c, 4)}
+        if bound == "hbm":
+            k["algorithmic_GBps"] = round(work / sec / 1e9, 1)
+            k["algorithmic_frac_of_hbm_peak"] = round(work / sec / 1e9 / HBM_PEAK_GBS, 4)
+            if entry in traffic:
+                fetched, written = traffic[entry]
+                k["hbm_traffic_bytes"] = fetched + written
+                k["hbm_GBps_by_counters"] = round((fetched + written) / sec / 1e9, 1)
+                k["counters_frac_of_hbm_peak"] = round((fetched + written) / sec / 1e9 / HBM_PEAK_GBS, 4)
+                k["traffic_over_algorithmic"] = round((fetched + written) / work, 2)
+                if copy_peak:
+                    k["counters_frac_of_measured_copy"] = round((fetched + written) / sec / 1e9 / copy_peak, 3)
+                if entry == "dg_hashgrid_encode_fwd" and gather_peak:
+                    lines = fetched / LINE_BYTES / sec / 1e9
+                    k["lines_fetched_Gps"] = round(lines, 2)
+                    k["frac_of_measured_random_gather"] = round(lines / gather_peak, 3)
+            if entry == "dg_hashgrid_encode_bwd":
+                adds = per_launch_samples * g["L"] * 8 * g["F"] / sec / 1e9
+                k["scatter_adds_Gps"] = round(adds, 1)
+                if atomic_peak:
+                    k["vs_measured_atomic_add"] = round(adds / atomic_peak, 2)
+        else:
+            k["TFLOPs"] = round(work / sec / 1e12, 2)
+            k["frac_of_mfma_peak"] = round(work / sec / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)
+            if mfma_peak:
+                k["frac_of_measured_mfma_loop"] = round(work / sec / 1e12 / mfma_peak, 4)
+        kernels[entry] = k
+
     dominant = next(iter(breakdown))
     calls, total_ms = per_call[dominant]
     avg_ms = total_ms / calls
-    per_launch_samples = n_samples / max(len(resident), 1)
     bound, work = algorithmic_work(dominant, g["L"], g["F"], per_launch_samples, mlp_flops_fwd)
-    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dominant)
+    moved = sum(traffic[dominant]) if dominant in traffic else None
     if work is None:
         roofline = {"kernel": dominant, "bound": bound, "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": None, "traffic": None, "avg_launch_ms": round(avg_ms, 4)}
     elif bound == "hbm":
         ach = work / (avg_ms * 1e-3) / 1e9
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic, "algorithmic_bytes": work,
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": moved, "algorithmic_bytes": work,
                     "avg_launch_ms": round(avg_ms, 4)}
     else:
         ach = work / (avg_ms * 1e-3) / 1e12
         roofline = {"kernel": dominant, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_F16_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(ach / MFMA_F16_PEAK_TFLOPS, 4), "traffic": traffic,
+                    "unit": "TFLOP/s", "frac": round(ach / MFMA_F16_PEAK_TFLOPS, 4), "traffic": moved,
                     "avg_launch_ms": round(avg_ms, 4)}
-    # the other headline kernels, same accounting
-    others = {}
-    for entry in ("dg_hashgrid_encode_fwd", "dg_hashgrid_encode_bwd", "dg_mlp_fwd", "dg_mlp_bwd"):
-        if entry in per_call:
-            c, t = per_call[entry]
-            b, wk = algorithmic_work(entry, g["L"], g["F"], per_launch_samples, mlp_flops_fwd)
-            rate = wk / (t / c * 1e-3)
-            others[entry] = ({"GB/s": round(rate / 1e9, 1), "frac_hbm": round(rate / 1e9 / HBM_PEAK_GBS, 4)} if b == "hbm"
-                             else {"TFLOP/s": round(rate / 1e12, 2), "frac_mfma": round(rate / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)})
-
-    cpu = None
-    if not args.no_cpu_baseline:
-        import oracle.step as ostep            # the oracle, as it stands, on the host cores of this machine
-        Rc = min(args.cpu_rays, R)
-        hm = ostep.make_models(dict(cfg, resident_list=resident), seed=0)
-        ho = ostep.make_occupancy(cfg, seed=0) if occupancy is not None else None     # built outside the timed call, like the tables
-        t1 = time.perf_counter()
-        ostep.run_step(cfg, hm, o[:Rc], d[:Rc], Cgt[:Rc], seed=0, lambda1=1e-3, loss_scale=65536.0, resident=resident, occ=ho,
-                       appearance=None if app_host is None else (app_host[0], app_host[1][:Rc]))   # (without the synthetic foreign partials)
-        cpu_s = time.perf_counter() - t1
-        cpu = {"value": round(Rc / cpu_s, 2), "unit": "rays/s", "cores": 1, "kind": "oracle",
-               "sample": "first %d rays of the same batch, full-size tables, one fwd+bwd pass, %.1f s" % (Rc, cpu_s)}
 
     out = {
-        "metric": "training rays/s (fwd+bwd)", "value": round(R / (ms_per_step * 1e-3), 1), "unit": "rays/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
-        "data": "synthetic",
-        "config": {"workload": args.workload, "rays": R,
+        "value": round(R / (ms_per_step * 1e-3), 1), "ms_per_step": round(ms_per_step, 4), "steps": steps, "warmup": warmup,
+        "config": {"workload": name, "rays": R,
                    "samples_per_segment": S if occupancy is None else round(n_samples / max(n_seg, 1), 2), "segments": n_seg,
+                   "segments_per_ray_histogram": seg_hist,
                    "sampling": "stratified" if occupancy is None else "occupancy-guided, resolution %d" % cfg["occ"]["res"],
                    "samples": n_samples, "levels": g["L"], "features": g["F"], "log2_T": g["log2_T"],
-                   "partitions_resident": len(resident), "mlp_operands": "f16, f32 accumulate"},
+                   "partitions_traced": P, "partitions_resident": len(resident), "mlp_operands": "f16, f32 accumulate"},
         "samples_per_s": round(n_samples / (ms_per_step * 1e-3), 1),
-        "roofline": roofline, "kernels": others, "ms_per_call": breakdown, "optimiser": optimiser, "occupancy_refresh": refresh, "evaluation": evaluation,
-        "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": kernels, "ms_per_call": breakdown, "optimiser": optimiser, "occupancy_refresh": refresh,
+        "evaluation": evaluation,
+    }
+    del step, models
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c5_share")
+    ap.add_argument("--also", default=None, help="comma-separated workloads timed after the headline one and reported as blocks of the "
+                                                 "same line (default: c4_big,c2_ngp when the headline is c5_share, else none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rays", type=int, default=1024, help="rays per host core of the oracle's pass")
+    ap.add_argument("--no-optimizer", action="store_true", help="skip the separate timing of the Adam sweep")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the yardstick kernels (stream copy, random gather, atomics, MFMA loop)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="after the timed region, stream 1 GiB through one elementwise kernel (known traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not available. "
+                 "value is the one GPU's throughput." % args.gpus)
+    also = args.also if args.also is not None else ("c4_big,c2_ngp" if args.workload == "c5_share" else "")
+    also = [w for w in also.split(",") if w and w != args.workload]
+
+    # the oracle on the host cores first: its workers are forks, which must exist before this process touches the GPU
+    cpu = None if args.no_cpu_baseline else cpu_baseline(args.workload, args.cpu_rays)
+
+    import torch
+    from paper_2405_04416_amd import binding as B
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    B.lib()                                    # fail loudly if the HIP library is not built
+    peaks = None
+    if not args.no_peaks:
+        from paper_2405_04416_amd import peaks as P
+        peaks = P.measure("cuda:0")
+        torch.cuda.empty_cache()
+
+    head = run_workload(args.workload, args.steps, args.warmup, peaks, with_optimiser=not args.no_optimizer)
+    others = {w: run_workload(w, max(1, min(args.steps, 10)), min(args.warmup, 3), peaks, with_optimiser=False, with_evaluation=False)
+              for w in also}
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1.0, out=dst)           # 1 GiB read + 1 GiB written by one plain elementwise kernel
+        torch.cuda.synchronize()
+
+    out = {
+        "metric": "training rays/s (fwd+bwd)", "value": head["value"], "unit": "rays/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": head["config"], "samples_per_s": head["samples_per_s"], "roofline": head["roofline"],
+        "kernels": head["kernels"], "ms_per_call": head["ms_per_call"], "optimiser": head["optimiser"],
+        "occupancy_refresh": head["occupancy_refresh"], "evaluation": head["evaluation"],
+        "peaks_measured": peaks, "peaks_datasheet": {"hbm_GBps": HBM_PEAK_GBS, "mfma_f16_TFLOPs": MFMA_F16_PEAK_TFLOPS},
+        "also": others, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 

@@ -42,9 +42,11 @@ CONFIGS = {
         parts=_tile([-1, 1], [-1, 1], 0, 0.2), rays="aerial", cam_height=1.5, tilt_deg=30.0, R=1 << 19, S=48,
         k_max=1, grid=dict(L=16, F=2, log2_T=24, n_min=16, n_max=8192), table_range=1e-4,
         mlp=dict(n_hidden_d=64, n_geo=16, sh_degree=4, n_hidden_c=64, n_layers_c=2)),
+    # One GPU's share of a 2 x 4 tiling: all eight boxes are traced, only box `resident` has its sub-model here; the
+    # partials of the other boxes' segments are synthetic.  r_max is set so that 60 % of the rays also cross 1..3 other boxes.
     "c5_share": dict(
-        parts=_tile([-4, -2, 0, 2, 4], [-2, 0, 2], 0, 0.25), resident=1, rays="through_resident", r_max=3.0,
-        cam_height=1.5, R=1 << 20, S=64, k_max=4, extra_fraction=0.6,
+        parts=_tile([-4, -2, 0, 2, 4], [-2, 0, 2], 0, 0.25), resident=1, rays="through_resident", r_max=3.35,
+        cam_height=1.5, R=1 << 20, S=64, k_max=4,
         grid=dict(L=16, F=2, log2_T=24, n_min=16, n_max=8192), table_range=1e-4,
         mlp=dict(n_hidden_d=64, n_geo=16, sh_degree=4, n_hidden_c=64, n_layers_c=2)),
     # Two-level cascade of Sec. 4.2.2: fine sub-models tile the inner box, coarse sub-models (T = 2^19) tile the outer
@@ -223,18 +225,11 @@ def make_unit_coords(n, seed=0):
     return np.random.default_rng([seed, 67]).random((n, 3), dtype=np.float32)
 
 
-def make_extra_partials(R, k_max, fraction, seed=0):
-    """For a seeded fraction of rays: 1..k_max-1 foreign partials (colour, transmittance ~ U[0,1]).
-
-    Returns (n_before [R], n_after [R], Ck [R,k_max,3], Tk [R,k_max]); slots not used stay 0 / 1.
-    """
+def make_foreign_partials(R, k_max, seed=0):
+    """Stand-ins for the partial results other GPUs would send: (colour, transmittance) ~ U[0,1] for every slot of
+    every ray, Ck [R,k_max,3], Tk [R,k_max]; the slots of resident segments are overwritten by the local rendering."""
     rng = np.random.default_rng([seed, 71])
-    extra = np.where(rng.random(R) < fraction, rng.integers(1, k_max, size=R), 0)
-    before = (rng.random(R) * (extra + 1)).astype(np.int64)
-    before = np.minimum(before, extra)
-    Ck = rng.random((R, k_max, 3), dtype=np.float32)
-    Tk = rng.random((R, k_max), dtype=np.float32)
-    return before.astype(np.uint32), (extra - before).astype(np.uint32), Ck, Tk
+    return rng.random((R, k_max, 3), dtype=np.float32), rng.random((R, k_max), dtype=np.float32)
 
 
 # ---------------------------------------------------------------------------

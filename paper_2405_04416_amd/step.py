@@ -56,8 +56,12 @@ class Occupancy:
 class TrainStep:
     def __init__(self, parts, models, resident, R, S, k_max, sh_degree, loss_scale=65536.0, lambda1=0.0, seed=0,
                  device="cuda:0", max_segments=None, binned_backward=True, encode_ws_cap=48 << 30, holes=None,
-                 occupancy=None, max_samples=None, appearance=None):
+                 occupancy=None, max_samples=None, appearance=None, foreign_prefilled=False):
         """parts: [P,6] float tensor (device); models: {partition index: SubModel}; resident: partition indices served;
+        max_segments: room for the segments of the RESIDENT partitions (default R * k_max);
+        foreign_prefilled: the caller keeps the partial slots Ck / Tk of segments in non-resident partitions filled (in a
+        deployment the exchange of Fig. 2 step 5 writes them); otherwise a step with non-resident partitions needs a
+        `foreign` callable or it raises -- such slots are never silently read as whatever the buffers hold;
         holes: None or [P,6] (device): the box subtracted from each partition (coarse level of the cascade, Sec. 4.2.2);
         occupancy: None (S stratified samples per segment) or {partition index: Occupancy}: occupancy-guided sampling
         (Sec. 3.2, Sec. 5.1), at most max_samples samples per step over all resident partitions (S is then unused);
@@ -84,7 +88,7 @@ class TrainStep:
         self.u, self.delta = z(n, 3), z(n)
         self.dir_enc = z(cap if occupancy is None else n, sh_degree * sh_degree, dt=f16)
         if occupancy is not None:
-            self.first = z(cap + self.P + 1, dt=i32)       # per partition: n_seg + 1 sample offsets, at [b + p, e + p]
+            self.first = z(R * k_max + self.P + 1, dt=i32)   # per partition: n_seg + 1 sample offsets, at [b + p, e + p]
             self.t, self.sample_ray = z(n), z(n, dt=i32)
             self.ws_march = z(B.dg_march_workspace_bytes(cap) // 4, dt=i32)
             self.samples = {}                               # partition -> (first sample, number of samples) of this step
@@ -102,7 +106,9 @@ class TrainStep:
         # workspace of the binned table-gradient pass, capped (the call batches itself when it is smaller than ideal)
         want = max(B.dg_hashgrid_encode_bwd_workspace_bytes(mm.grid, n) for mm in models.values())
         self.ws_enc = torch.zeros(min(want, encode_ws_cap) // 4 + 64, dtype=f32, device=self.dev) if binned_backward else None
+        self.foreign_prefilled = bool(foreign_prefilled)
         self.offsets = None
+        self.local = {}         # resident partition -> index of its first segment among the resident segments (sample buffers)
         self.t_fixed = None
         self.timings = None     # set to {} to collect (start, end) event pairs per entry point
 
@@ -130,15 +136,30 @@ class TrainStep:
             B.dg_ray_aabb_segments(o, d, self.parts, t_min, self.k_max, self.seg_count, self.seg_t, self.seg_part,
                                    self.status, self.part_offset, self.seg_ray, self.seg_slot, self.ws_seg, holes=self.holes)
         self.offsets = self.part_offset.cpu().tolist()      # P+1 integers: how many segments each sub-model got
-        if self.offsets[-1] > self.cap:
-            raise B.DistGridError("segment capacity %d exceeded (%d)" % (self.cap, self.offsets[-1]))
+        # the sample buffers hold the segments of the resident partitions only, back to back in the order of `resident`
+        run = 0
+        for p in self.resident:
+            self.local[p] = run
+            run += self.offsets[p + 1] - self.offsets[p]
+        if run > self.cap:
+            raise B.DistGridError("segment capacity %d exceeded (%d)" % (self.cap, run))
 
     def _slices(self, p):
+        """Segment range [b, e) of partition p in seg_ray / seg_slot, and the range of its samples in the sample buffers."""
         b, e = self.offsets[p], self.offsets[p + 1]
-        return b, e, slice(b * self.S, e * self.S)
+        first = self.local[p]
+        return b, e, slice(first * self.S, (first + e - b) * self.S)
+
+    def _rows(self, p):
+        """Rows of partition p in the per-segment tables (direction encoding, appearance rows)."""
+        first = self.local[p]
+        return slice(first, first + self.offsets[p + 1] - self.offsets[p])
 
     def forward(self, o, d, Cgt, jitter=None, foreign=None):
         """foreign: optional callable(self) that fills partials of non-resident partitions into Ck/Tk."""
+        if foreign is None and not self.foreign_prefilled and len(self.resident) < self.P:
+            raise B.DistGridError("partitions %s are not resident: pass `foreign` to fill their partials, or construct with "
+                                  "foreign_prefilled=True" % sorted(set(range(self.P)) - set(self.resident)))
         self._partials(o, d, jitter)
         if foreign is not None:
             foreign(self)
@@ -185,13 +206,14 @@ class TrainStep:
                 B.dg_sample_segments(o, d, self.seg_t, self.seg_ray[b:e], self.seg_slot[b:e], n_seg, self.k_max,
                                      self.parts_host[p], S, self.seed, jit, self.u[sl], self.delta[sl],
                                      self.t_fixed[sl] if want_t else None)
+            rows = self._rows(p)
             with self._timed("dg_dir_encode"):
-                B.dg_dir_encode(d, self.seg_ray[b:e], n_seg, self.deg, self.dir_enc[b:e])
+                B.dg_dir_encode(d, self.seg_ray[b:e], n_seg, self.deg, self.dir_enc[rows])
             with self._timed("dg_hashgrid_encode_fwd"):
                 B.dg_hashgrid_encode_fwd(m.grid, m.table, self.u[sl], N, self.feat[sl])
-            app = self._appearance_rows(self.seg_ray[b:e], n_seg, slice(b, e))
+            app = self._appearance_rows(self.seg_ray[b:e], n_seg, rows)
             with self._timed("dg_mlp_fwd"):
-                B.dg_mlp_fwd_app(m.mlp, m.weights, self.feat[sl], self.dir_enc[b:e], app, S, N, self.sigma[sl], self.rgb[sl])
+                B.dg_mlp_fwd_app(m.mlp, m.weights, self.feat[sl], self.dir_enc[rows], app, S, N, self.sigma[sl], self.rgb[sl])
             with self._timed("dg_composite_segment_fwd"):
                 B.dg_composite_segment_fwd(self.sigma[sl], self.rgb[sl], self.delta[sl], n_seg, S, self.seg_ray[b:e],
                                            self.seg_slot[b:e], self.k_max, self.Ck, self.Tk)
@@ -330,8 +352,9 @@ class TrainStep:
             with self._timed("dg_composite_segment_bwd"):
                 B.dg_composite_segment_bwd(self.sigma[sl], self.rgb[sl], self.delta[sl], n_seg, S, self.seg_ray[b:e],
                                            self.seg_slot[b:e], self.k_max, self.gCk, self.gTk, self.dsigma[sl], self.drgb[sl])
+            rows = self._rows(p)
             with self._timed("dg_mlp_bwd"):
-                B.dg_mlp_bwd_app(m.mlp, m.weights, self.feat[sl], self.dir_enc[b:e], None if self.app_rows is None else self.app_rows[b:e],
+                B.dg_mlp_bwd_app(m.mlp, m.weights, self.feat[sl], self.dir_enc[rows], None if self.app_rows is None else self.app_rows[rows],
                                  S, N, self.dsigma[sl], self.drgb[sl], self.loss_scale, self.dfeat[sl], m.dW, self.ws_mlp)
             with self._timed("dg_hashgrid_encode_bwd"):
                 B.dg_hashgrid_encode_bwd(m.grid, self.u[sl], self.dfeat[sl], N, m.dtable, self.ws_enc)
