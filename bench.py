@@ -335,7 +335,7 @@ def main():
     ap.add_argument("--also", default=None, help="comma-separated workloads timed after the headline one and reported as blocks of the "
                                                  "same line (default: c4_big,c2_ngp when the headline is c5_share, else none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rays", type=int, default=1024, help="rays per host core of the oracle's pass")
+    ap.add_argument("--cpu-rays", type=int, default=8192, help="rays per host core of the oracle's pass")
     ap.add_argument("--no-optimizer", action="store_true", help="skip the separate timing of the Adam sweep")
     ap.add_argument("--no-peaks", action="store_true", help="skip the yardstick kernels (stream copy, random gather, atomics, MFMA loop)")
     ap.add_argument("--copy-calibration", action="store_true",

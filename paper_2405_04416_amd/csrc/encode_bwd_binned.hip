@@ -173,20 +173,22 @@ __device__ __forceinline__ Emission classify(const LevelGeom &lv, uint32_t mask,
     return o;
 }
 
-// count sweep with this workgroup's counters in LDS: one LDS add per record, no barriers inside the sweep
-__global__ void __launch_bounds__(kTile)
+// count sweep with this workgroup's counters in LDS: one LDS add per record, no barriers inside the sweep.  Launched
+// with the fill sweep's grid and tiling: kTile threads that take one tile per step, or 2 * kTile that take two.
+__global__ void __launch_bounds__(2 * kTile)
 count_lds_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, uint64_t n0, uint64_t nb, uint32_t *__restrict__ rows)
 {
     extern __shared__ uint32_t smem[];
     uint32_t *row = smem;                                // [n_keys]
-    const uint32_t tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x, in_tile = tid % kTile;
     const int lane = tid % dg::kWave;
     const uint32_t mask = (1u << g.log2_T) - 1u;
-    for (uint32_t i = tid; i < plan.n_keys; i += kTile) row[i] = 0u;
+    for (uint32_t i = tid; i < plan.n_keys; i += blockDim.x) row[i] = 0u;
     __syncthreads();
     const uint64_t n_tiles = (nb + kTile - 1) / kTile;
-    for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const uint64_t rel = tile * kTile + tid;
+    const uint64_t stride = (uint64_t)(blockDim.x / kTile) * gridDim.x;
+    for (uint64_t tile = blockIdx.x + (uint64_t)(tid / kTile) * gridDim.x; tile < n_tiles; tile += stride) {
+        const uint64_t rel = tile * kTile + in_tile;
         const bool live = rel < nb;
         const uint64_t n = n0 + (live ? rel : nb - 1);
         const float uu[3] = {u[3 * n], u[3 * n + 1], u[3 * n + 2]};
@@ -201,7 +203,7 @@ count_lds_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, uint64_
     }
     __syncthreads();
     uint32_t *row_global = rows + (size_t)blockIdx.x * plan.n_keys;
-    for (uint32_t i = tid; i < plan.n_keys; i += kTile) row_global[i] = row[i];
+    for (uint32_t i = tid; i < plan.n_keys; i += blockDim.x) row_global[i] = row[i];
 }
 
 template <int CTRL, int ROW_MASK>
@@ -507,60 +509,141 @@ fill_narrow_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const
     publish_largest(largest, cnt, largest_out);
 }
 
-// Fill sweep for any number of bins.  With hundreds or thousands of bins per level a tile of 512 samples brings a bin
-// one record or none, so sorting a step's records by bin in LDS first (as the narrow sweep does) orders nothing: here
-// a record goes straight to its place.  The workgroup's queue cursors of the level's bins sit in LDS; a lane takes
-// the position of each of its four records with one LDS add that returns the old value and stores the record there.
-// The count sweep has sized this workgroup's slice of every bin for exactly these records, so no cursor can run into
-// a neighbour's slice, and because the sums are integers the order in which lanes take positions does not matter.
-// No barrier inside a level: the wavefronts of a workgroup drift apart freely; two barriers where the level changes
-// and the cursors are reloaded.  Consecutive steps of a workgroup extend the same slices, so the cache lines at
-// their ends are completed while they still sit in L2.
-__global__ void __launch_bounds__(kTile)
-fill_direct_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
-                   uint64_t n0, uint64_t nb, const uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
-                   uint4 *__restrict__ queue, float *__restrict__ dtable, uint32_t *__restrict__ largest_out)
+// Fill sweep for many bins, appends in 64-byte granules.  Memory takes a lone 16-byte record badly (measured on this
+// chip with 2048 open queue slices per workgroup: 72 G records/s as single records, 208 G/s as aligned groups of four
+// written by four neighbouring lanes, 295 G/s as whole lines), and with thousands of bins a step brings a bin one
+// record or none, so the groups have to be collected over several steps.  One workgroup of 1024 threads per compute
+// unit keeps, for every bin of the level, the granule its queue slice is being filled at: four record slots in LDS
+// (128 KB for 2048 bins), the position of the bin's next record, and the position `from` which the granule is kept
+// in LDS (records of the granule below that were written to memory directly).
+// A step bins two tiles of 512 samples, in rounds of one pair of corners each.  Phase 1 of a round: every record takes
+// its queue position with an LDS add on the bin's counter (the count sweep has sized this workgroup's slice of every
+// bin for exactly its records, and integer sums do not care in which order lanes take positions); a position inside
+// the bin's granule puts the record into its LDS slot, and the record that takes the granule's last position enters
+// the bin into the round's list; a position beyond the granule (the bin got more in this round than its granule had
+// room for) is written to the queue directly.  Phase 2, after a barrier: groups of four lanes write the listed
+// granules out, one 64-byte store per group, and move the bin on to the granule of its counter -- what lies between
+// was written directly.  A second barrier keeps the next round's records off the slots until they have been read.
+// At the end of a level the granules that are still open go out, filled up with zero records, which add nothing; the
+// count sweep has sized every slice in whole granules for that.  Levels with few bins see many records per bin and
+// round, most of which go to the queue directly -- into few open cache lines, which L2 completes (226 G records/s
+// measured for lone records into 64 slices per workgroup).
+// Measured at T = 2^24 (19.8 M samples, 14 binned levels, 2048 bins in seven of them): records sorted per step in LDS
+// and copied out 10.7 ms, every record stored directly 10.2 ms, granules with all four pairs in one round 8.0 ms, two
+// rounds 7.4 ms, four rounds 7.1 ms.
+constexpr int kRingThreads = 1024, kRingGrid = 256, kRingSlots = 4, kRingRounds = 4;
+constexpr int kRingLds = kMaxBins * (kRingSlots * 16 + 4 + 4 + 2 * 2) + 16;
+
+__global__ void __launch_bounds__(kRingThreads)
+fill_ring_kernel(dg_grid_desc g, Plan plan, const float *__restrict__ u, const float2 *__restrict__ dfeat, uint64_t N,
+                 uint64_t n0, uint64_t nb, const uint32_t *__restrict__ rows, const uint32_t *__restrict__ binbase,
+                 uint4 *__restrict__ queue, float *__restrict__ dtable, uint32_t *__restrict__ largest_out)
 {
     extern __shared__ uint32_t smem[];
-    uint32_t *cursor = smem;                                          // [max_bins] queue position of each bin's next record
+    const uint32_t cap = plan.max_bins;
+    uint4 *ring = reinterpret_cast<uint4 *>(smem);                    // [cap][4] the granule each bin is being filled at
+    uint32_t *pos = smem + (size_t)cap * kRingSlots * 4;              // [cap] queue position of the bin's next record
+    uint32_t *from = pos + cap;                                       // [cap] the granule is in LDS from this position on
+    uint32_t *n_list = from + cap;                                    // [2] entries of the two lists (+ 2 unused words)
+    uint16_t *list = reinterpret_cast<uint16_t *>(n_list + 4);        // [2][cap] bins whose granule filled up in a step
     const uint32_t tid = threadIdx.x;
     const int lane = tid % dg::kWave;
+    const uint32_t half = tid / kTile, in_tile = tid % kTile;         // the workgroup takes two tiles per step
     const uint32_t mask = (1u << g.log2_T) - 1u;
     const uint32_t *row = rows + (size_t)blockIdx.x * plan.n_keys;
-    uint32_t largest = 0;
+    const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
+    uint32_t largest = 0, parity = 0;
     const uint64_t n_tiles = (nb + kTile - 1) / kTile;
+    const uint64_t stride = 2ull * gridDim.x;                         // tiles between two steps of one half
+    const uint64_t first_tile = blockIdx.x + (uint64_t)half * gridDim.x;
+    // steps of the workgroup: until its first half runs out of tiles (the second half's tiles come later in the order)
+    const uint64_t n_steps = blockIdx.x < n_tiles ? (n_tiles - blockIdx.x + stride - 1) / stride : 0;
     StepAhead ahead = {{0.0f, 0.0f, 0.0f}, make_float2(0.0f, 0.0f)};
-    if (blockIdx.x < n_tiles) load_ahead(ahead, u, dfeat, N, n0, nb, blockIdx.x, plan.first_level, tid);
+    if (first_tile < n_tiles) load_ahead(ahead, u, dfeat, N, n0, nb, first_tile, plan.first_level, in_tile);
+    if (tid < 2) n_list[tid] = 0u;
     for (uint32_t l = plan.first_level; l < g.n_levels; ++l) {
         const uint32_t n_bins = plan.n_bins[l], key0 = plan.key_base[l];
         const LevelGeom lv = level_of(g, l);
-        __syncthreads();                                              // nobody is still on the last level's cursors
-        for (uint32_t i = tid; i < n_bins; i += kTile) cursor[i] = row[key0 + i] + binbase[key0 + i];
+        __syncthreads();                                              // the last level's books are closed
+        for (uint32_t i = tid; i < n_bins; i += kRingThreads) { const uint32_t p0 = row[key0 + i] + binbase[key0 + i]; pos[i] = p0; from[i] = p0; }
         __syncthreads();
-        for (uint64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-            const bool live = tile * kTile + tid < nb;
+        for (uint64_t step = 0; step < n_steps; ++step) {
+            const uint64_t tile = first_tile + step * stride;
+            const bool in_range = tile < n_tiles;
+            const bool live = in_range && tile * kTile + in_tile < nb;
             const float uu[3] = {ahead.u[0], ahead.u[1], ahead.u[2]};
             const float2 gfe = live ? ahead.g : make_float2(0.0f, 0.0f);
-            // the next step's inputs are asked for before this step's stores: loads and stores of a wavefront retire
-            // in order, so a load issued behind the stores could only be awaited together with them
+            // the next step's inputs are asked for before this step's stores (loads and stores of a wavefront retire in order)
             {
-                const bool same_level = tile + gridDim.x < n_tiles;
+                const bool same_level = step + 1 < n_steps;
                 const uint32_t l_next = same_level ? l : l + 1;
-                if (l_next < g.n_levels) load_ahead(ahead, u, dfeat, N, n0, nb, same_level ? tile + gridDim.x : blockIdx.x, l_next, tid);
+                const uint64_t t_next = same_level ? tile + stride : first_tile;
+                if (l_next < g.n_levels && t_next < n_tiles) load_ahead(ahead, u, dfeat, N, n0, nb, t_next, l_next, in_tile);
             }
             const Emission em = classify(lv, mask, uu, live, lane);
             float vx[8], vy[8];
             corner_values(em, gfe, vx, vy, largest);
-            if (em.emit) {
-                uint32_t at[4];
+            // The step's records go in kRingRounds rounds, each followed by its own write-out: the fewer records a bin
+            // gets per round, the less often its granule overflows and records go to the queue one by one.
 #pragma unroll
-                for (int p = 0; p < 4; ++p) at[p] = atomicAdd(&cursor[em.e[2 * p] >> kChunkLog2], 1u);
+            for (int round = 0; round < kRingRounds; ++round, parity ^= 1u) {
+                constexpr int kPer = 4 / kRingRounds;                 // pairs of corners per round
+                uint16_t *mine = list + parity * cap;
+                uint32_t at[kPer], end[kPer];                         // position of each record, end of its bin's granule
+                if (em.emit) {
 #pragma unroll
-                for (int p = 0; p < 4; ++p) queue[at[p]] = make_record(em, p, vx, vy, lv.offset, dtable);
+                    for (int k = 0; k < kPer; ++k) {
+                        const uint32_t bin = em.e[2 * (kPer * round + k)] >> kChunkLog2;
+                        at[k] = atomicAdd(&pos[bin], 1u);
+                        end[k] = (from[bin] & ~(kRingSlots - 1u)) + kRingSlots;
+                    }
+#pragma unroll
+                    for (int k = 0; k < kPer; ++k) {
+                        const uint32_t bin = em.e[2 * (kPer * round + k)] >> kChunkLog2;
+                        const uint4 rec = make_record(em, kPer * round + k, vx, vy, lv.offset, dtable);
+                        if (at[k] < end[k]) ring[bin * kRingSlots + (at[k] & (kRingSlots - 1u))] = rec;
+                        else queue[at[k]] = rec;
+                    }
+                }
+                // bins whose granule this round completes go into the list: one LDS add per wavefront and pair of corners,
+                // not one per bin (hundreds of adds on one word would take turns)
+#pragma unroll
+                for (int k = 0; k < kPer; ++k) {
+                    const bool full = em.emit && at[k] == end[k] - 1u;
+                    const unsigned long long votes = __ballot(full);
+                    if (votes) {                                      // wavefront-uniform
+                        const int leader = __ffsll((long long)votes) - 1;
+                        uint32_t first = 0;
+                        if (lane == leader) first = atomicAdd(&n_list[parity], (uint32_t)__popcll(votes));
+                        first = lane_value(first, (uint32_t)leader);
+                        if (full) mine[first + __popcll(votes & ((1ull << lane) - 1ull))] = (uint16_t)(em.e[2 * (kPer * round + k)] >> kChunkLog2);
+                    }
+                }
+                __syncthreads();                                      // slots written, list complete
+                {
+                    const uint32_t n = n_list[parity], slot = tid % kRingSlots;
+                    for (uint32_t i = tid / kRingSlots; i < n; i += kRingThreads / kRingSlots) {
+                        const uint32_t bin = mine[i];
+                        const uint32_t kept = from[bin], first = kept & ~(kRingSlots - 1u);
+                        const uint4 rec = ring[bin * kRingSlots + slot];
+                        if (first + slot >= kept) queue[first + slot] = rec;
+                        if (slot == 0) from[bin] = pos[bin];          // what lies between went to the queue directly
+                    }
+                    if (tid == 0) n_list[parity ^ 1u] = 0u;           // the other list: last read before the barrier above
+                }
+                __syncthreads();                                      // slots read, bins moved on
+            }
+        }
+        // end of the level: open granules go out, filled up with zero records
+        {
+            const uint32_t slot = tid % kRingSlots;
+            for (uint32_t bin = tid / kRingSlots; bin < n_bins; bin += kRingThreads / kRingSlots) {
+                const uint32_t kept = from[bin], first = kept & ~(kRingSlots - 1u), next = pos[bin], at = first + slot;
+                if (next > first && at >= kept) queue[at] = at < next ? ring[bin * kRingSlots + slot] : zero4;
             }
         }
     }
-    publish_largest(largest, cursor, largest_out);
+    publish_largest(largest, n_list, largest_out);
 }
 
 // rows[b][k] (per-workgroup counts, each rounded up to a multiple of `round`) -> exclusive prefix over workgroups;
@@ -731,8 +814,10 @@ struct Layout {
     uint64_t records;    // queue capacity: the records of a batch plus the padding of the slices
 };
 
-// the narrow sweep pads every workgroup's slice of every bin to whole granules
-uint64_t slice_padding(const Plan &p) { return p.max_bins <= 64 ? (uint64_t)kBinGrid * p.n_keys * (kSliceRound - 1u) : 0ull; }
+// both sweeps pad every workgroup's slice of every bin to whole granules: 8 records with few bins, 4 with many
+uint32_t sweep_grid(const Plan &p) { return p.max_bins <= 64 ? (uint32_t)kBinGrid : (uint32_t)kRingGrid; }
+uint32_t slice_round(const Plan &p) { return p.max_bins <= 64 ? kSliceRound : (uint32_t)kRingSlots; }
+uint64_t slice_padding(const Plan &p) { return (uint64_t)sweep_grid(p) * p.n_keys * (slice_round(p) - 1u); }
 
 // workspace layout for a batch of `batch` samples
 Layout make_layout(const dg_grid_desc *d, const Plan &p, uint64_t batch)
@@ -740,7 +825,7 @@ Layout make_layout(const dg_grid_desc *d, const Plan &p, uint64_t batch)
     Layout L{};
     const uint64_t records = (batch * 4ull * (d->n_levels - p.first_level) + slice_padding(p) + 15ull) / 16ull * 16ull;
     size_t off = 0;
-    L.rows = off; off = align256(off + (size_t)kBinGrid * p.n_keys * 4);
+    L.rows = off; off = align256(off + (size_t)sweep_grid(p) * p.n_keys * 4);
     L.totals = off; off = align256(off + (size_t)p.n_keys * 4);
     L.binbase = off; off = align256(off + (size_t)(p.n_keys + 2) * 4);      // + the largest record magnitude
     L.blkbase = off; off = align256(off + (size_t)(p.n_keys + 1) * 4);
@@ -784,7 +869,8 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     static hipError_t lds_status = hipSuccess;
     std::call_once(lds_once, [] {
         const int acc_lds = 2 * kChunk * (int)sizeof(double), count_lds = (int)kMaxKeys * 4;
-        const hipError_t e[4] = {
+        const hipError_t e[5] = {
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_ring_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kRingLds),
             hipFuncSetAttribute(reinterpret_cast<const void *>(&count_lds_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, count_lds),
             hipFuncSetAttribute(reinterpret_cast<const void *>(&fill_narrow_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kNarrowLds),
             hipFuncSetAttribute(reinterpret_cast<const void *>(&accumulate_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, acc_lds),
@@ -816,20 +902,20 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
     uint32_t *blkbase = reinterpret_cast<uint32_t *>(base + L.blkbase);
     uint4 *queue = reinterpret_cast<uint4 *>(base + L.queue);
     const bool narrow = p.max_bins <= 64;                 // then n_keys <= 64 * DG_MAX_LEVELS
+    const uint32_t grid = sweep_grid(p);                  // persistent workgroups of the count and fill sweeps (same tiling)
     if (p.n_keys > kMaxKeys) return fail(DG_ERR_UNSUPPORTED, "dg_hashgrid_encode_bwd: %u table regions exceed %u", p.n_keys, kMaxKeys);
 
     for (uint64_t n0 = 0; n0 < N; n0 += batch) {
         const uint64_t nb = N - n0 < batch ? N - n0 : batch;
-        count_lds_kernel<<<kBinGrid, kTile, p.n_keys * 4, st>>>(*d, p, u, n0, nb, rows);
-        scan_rows_kernel<<<(p.n_keys + kScanKeys - 1) / kScanKeys, kScanKeys * kScanGroups, 0, st>>>(rows, kBinGrid, p.n_keys,
-                                                                                                narrow ? kSliceRound : 1u, totals);
+        count_lds_kernel<<<grid, narrow ? kTile : kRingThreads, p.n_keys * 4, st>>>(*d, p, u, n0, nb, rows);
+        scan_rows_kernel<<<(p.n_keys + kScanKeys - 1) / kScanKeys, kScanKeys * kScanGroups, 0, st>>>(rows, grid, p.n_keys, slice_round(p), totals);
         scan_totals_kernel<<<1, 1024, 0, st>>>(totals, p.n_keys, binbase, blkbase);
         if (narrow)
             fill_narrow_kernel<<<kBinGrid, kNarrowThreads, kNarrowLds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, queue,
                                                                              dtable, binbase + p.n_keys + 1);
         else
-            fill_direct_kernel<<<kBinGrid, kTile, p.max_bins * 4, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, queue, dtable,
-                                                                        binbase + p.n_keys + 1);
+            fill_ring_kernel<<<grid, kRingThreads, p.max_bins * (kRingSlots * 16 + 12) + 16, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows,
+                                                                                                  binbase, queue, dtable, binbase + p.n_keys + 1);
         const uint64_t records = nb * 4ull * (d->n_levels - p.first_level) + slice_padding(p);
         const uint32_t acc_grid = (uint32_t)(records / kAccRecords) + p.n_keys;       // upper bound of the workgroups needed
         accumulate_kernel<<<acc_grid, kAccBlock, 2 * kChunk * sizeof(double), st>>>(*d, p, binbase, blkbase, (const u32x4 *)queue, dtable);
