@@ -90,8 +90,9 @@ int dg_grid_desc_init(dg_grid_desc *desc, uint32_t L, uint32_t F, uint32_t log2_
  * holes: NULL, or [P,6] fp32 device boxes: partition p then covers parts[p] minus holes[p]
  * (Sec. 4.2.2: the coarse sub-models of the two-level cascade cover the outer box around the
  * inner one, split by the same planes).  The hole's interval on the ray comes from the same
- * slab expressions; the region is met in up to two pieces, [t_in, hole entry] and [hole exit,
- * t_out], each kept if it has positive length and listed under box index p.  A hole with no
+ * slab expressions; the region is met in up to two pieces, [t_in, min(hole entry, t_out)] and
+ * [max(hole exit, t_in), t_out] (a hole may overhang its box, e.g. the whole inner box given as
+ * the hole of every outer partition), each kept if it has positive length and listed under box index p.  A hole with no
  * volume (hi <= lo on some axis) is no hole.  Faces that a hole shares with another box give
  * bit-identical times, so fine and coarse pieces pave the ray as plain boxes do.
  * P <= DG_MAX_PARTITIONS, 1 <= k_max <= 12.

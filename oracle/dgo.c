@@ -203,8 +203,10 @@ void dgo_ray_aabb_segments(const float *o, const float *d, uint32_t R, const flo
             float h_in, h_out;
             if (hlo && hhi[0] > hlo[0] && hhi[1] > hlo[1] && hhi[2] > hlo[2] &&
                 slab_interval(o + 3 * r, d + 3 * r, hlo, hhi, t_min, &h_in, &h_out)) {
-                if (h_in > t_in) insert_segment(st, sp, &cnt, k_max, status, t_in, h_in, (int32_t)p);
-                if (t_out > h_out) insert_segment(st, sp, &cnt, k_max, status, h_out, t_out, (int32_t)p);
+                /* the hole may reach beyond the box: both pieces stay inside the box's own interval */
+                float first_end = fminf(h_in, t_out), second_begin = fmaxf(h_out, t_in);
+                if (first_end > t_in) insert_segment(st, sp, &cnt, k_max, status, t_in, first_end, (int32_t)p);
+                if (t_out > second_begin) insert_segment(st, sp, &cnt, k_max, status, second_begin, t_out, (int32_t)p);
             } else {
                 insert_segment(st, sp, &cnt, k_max, status, t_in, t_out, (int32_t)p);
             }

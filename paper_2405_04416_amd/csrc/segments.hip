@@ -83,8 +83,10 @@ ray_aabb_kernel(const float *__restrict__ o, const float *__restrict__ d, uint32
         if (!slab_interval(oo, dd, inv, lo, hi, t_min, t_in, t_out)) continue;
         const bool has_hole = hhi[0] > hlo[0] && hhi[1] > hlo[1] && hhi[2] > hlo[2];      // a hole with no volume is no hole
         if (has_hole && slab_interval(oo, dd, inv, hlo, hhi, t_min, h_in, h_out)) {
-            if (h_in > t_in) insert_segment(L, k_max, t_in, h_in, (int32_t)p);
-            if (t_out > h_out) insert_segment(L, k_max, h_out, t_out, (int32_t)p);
+            // a hole may overhang its box: the pieces are cut to the box's own interval
+            const float first_end = fminf(h_in, t_out), second_begin = fmaxf(h_out, t_in);
+            if (first_end > t_in) insert_segment(L, k_max, t_in, first_end, (int32_t)p);
+            if (t_out > second_begin) insert_segment(L, k_max, second_begin, t_out, (int32_t)p);
         } else {
             insert_segment(L, k_max, t_in, t_out, (int32_t)p);
         }

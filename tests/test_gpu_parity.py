@@ -75,6 +75,22 @@ def test_segments_bit_exact(name, R, k_max):
     np.testing.assert_array_equal(slot[:n], rslot)
 
 
+def test_segments_hole_that_overhangs_its_box():
+    """The whole inner box given as the hole of every outer partition (Sec. 4.2.2 read as outer box minus inner box):
+    the pieces are cut to each partition's own interval; bit for bit against the oracle."""
+    say("segments with overhanging holes")
+    cfg = di.config("c6_cascade")
+    parts = cfg["parts"][4:]
+    holes = np.tile(np.array([-1, -1, 0, 1, 1, 0.25], np.float32), (4, 1))
+    o, d = di.make_rays(cfg, seed=12, R=4001)
+    cnt, seg_t, part, status, off, ray, slot = _run_segments(o, d, parts, 8, holes=holes)
+    rc, rt, rp, rs = oracle.ray_aabb_segments(o, d, parts, 0.0, 8, holes=holes)
+    np.testing.assert_array_equal(cnt, rc)
+    np.testing.assert_array_equal(seg_t.view(np.uint32), rt.view(np.uint32))
+    np.testing.assert_array_equal(part, rp)
+    assert status == rs and rc.max() >= 3
+
+
 def test_segments_empty_batch():
     cfg = di.config("c3_2x2")
     cnt, seg_t, part, status, off, ray, slot = _run_segments(np.zeros((0, 3), np.float32), np.zeros((0, 3), np.float32),

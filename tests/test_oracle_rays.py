@@ -286,3 +286,39 @@ def test_single_box_with_a_centred_hole():
     np.testing.assert_array_equal(t[0, :2], [[1, 2], [4, 5]])
     np.testing.assert_array_equal(t[1, 0], [1, 5])                        # passes beside the hole
     np.testing.assert_array_equal(t[2, 0], [1, 2])                        # starts inside the hole (t_min = 0): only the far piece
+
+
+def test_hole_that_overhangs_its_box_is_cut_to_the_box():
+    """Sec. 4.2.2 reading: a coarse partition covers its outer box minus the inner box.  Given the WHOLE inner box as the
+    hole of every outer partition, the hole reaches beyond each partition: the pieces must stay inside the partition's own
+    interval on the ray.  Checked by brute force: points along the ray, labelled by box membership minus hole membership."""
+    outer = np.array([[-3, -3, 0, 0, 0, 0.5], [0, -3, 0, 3, 0, 0.5], [-3, 0, 0, 0, 3, 0.5], [0, 0, 0, 3, 3, 0.5]], np.float32)
+    inner = np.tile(np.array([-1, -1, 0, 1, 1, 0.25], np.float32), (4, 1))           # overhangs every outer box
+    rng = np.random.default_rng(5)
+    R = 400
+    o = np.stack([rng.uniform(-3, 3, R), rng.uniform(-3, 3, R), np.full(R, 1.5)], 1).astype(np.float32)
+    tgt = np.stack([rng.uniform(-3, 3, R), rng.uniform(-3, 3, R), np.zeros(R)], 1)
+    d = (tgt - o); d = (d / np.linalg.norm(d, axis=1, keepdims=True)).astype(np.float32)
+    cnt, seg_t, part, status = oracle.ray_aabb_segments(o, d, outer, 0.0, 8, holes=inner)
+    assert status == 0
+    seen_cut = 0
+    for r in range(R):
+        K = cnt[r]
+        t = seg_t[r, :K].astype(np.float64)
+        assert np.all(t[:, 1] > t[:, 0]) and np.all(t[1:, 0] >= t[:-1, 1])          # ordered, never overlapping
+        # brute force: total length per partition of {points in box p and outside the hole}
+        ts = np.linspace(0.0, 10.0, 100001)
+        x = o[r].astype(np.float64)[None] + ts[:, None] * d[r].astype(np.float64)[None]
+        in_hole = np.all((x >= inner[0, :3]) & (x < inner[0, 3:]), axis=1)
+        for p in range(4):
+            inside = np.all((x >= outer[p, :3]) & (x < outer[p, 3:]), axis=1) & ~in_hole
+            want = inside.sum() * (ts[1] - ts[0])
+            got = sum(t[k, 1] - t[k, 0] for k in range(K) if part[r, k] == p)
+            assert abs(got - want) <= 5e-4, (r, p, got, want)
+        # every piece lies inside its own box (this is what fails without the cut)
+        for k in range(K):
+            mid = o[r].astype(np.float64) + 0.5 * (t[k, 0] + t[k, 1]) * d[r].astype(np.float64)
+            p = part[r, k]
+            assert np.all(mid >= outer[p, :3] - 1e-6) and np.all(mid <= outer[p, 3:] + 1e-6)
+        seen_cut += int(in_hole.any() and K >= 2)
+    assert seen_cut > 20
