@@ -157,7 +157,10 @@ int dg_hashgrid_encode_fwd(const dg_grid_desc *desc, const float *table, const f
  * With a workspace of dg_hashgrid_encode_bwd_workspace_bytes(desc, N) bytes the contributions are
  * binned by table region and summed in on-chip memory first (much faster for large N); on that path a
  * contribution is rounded to 18 mantissa bits (relative error at most 2^-20, unbiased) before it is
- * summed exactly.  ws must be 256-byte aligned; a smaller workspace is accepted and makes the call run
+ * summed exactly (in fixed point scaled to the batch's largest magnitude: a contribution below 2^-33 of that magnitude
+ * adds nothing).  If any contribution of the batch is infinite or NaN the sums cannot be formed: every table region
+ * that received contributions then gets NaN in its first entry, so the gradient is visibly non-finite as it would be
+ * with fp32 atomics.  ws must be 256-byte aligned; a smaller workspace is accepted and makes the call run
  * in batches, DG_ERR_WORKSPACE if it cannot hold one tile of 512 samples (16 bytes per sample, level
  * and pair of corners, plus bookkeeping). */
 size_t dg_hashgrid_encode_bwd_workspace_bytes(const dg_grid_desc *desc, uint64_t N);
@@ -264,6 +267,19 @@ int dg_mlp_bwd_app(const dg_mlp_desc *desc, const void *weights, const void *fea
  * table [n_images, n_app] fp16, image_of_ray [R] uint32, out [n, n_app] fp16; n_app a multiple of 8. */
 int dg_appearance_rows(const void *table, const uint32_t *image_of_ray, const uint32_t *index, uint64_t n,
                        uint32_t n_app, void *out, void *stream);
+
+/* Evaluation rendering (Sec. 4.4.2: every sub-model renders its segments, the partial colour, depth and transmittance are
+ * merged into the final result), forward only and fused: dg_mlp_fwd_app, dg_composite_segment_fwd and
+ * dg_composite_segment_depth on the n_seg segments of S samples each in one kernel, so that the densities and colours of
+ * the samples are never written to memory.  Inputs as for dg_mlp_fwd_app with N = n_seg * S (feat [n_feat/2, N, 2] fp16,
+ * dir_enc / app one row per segment), delta and t [N] from dg_sample_segments; outputs Ck [R,k_max,3], Tk [R,k_max] and
+ * Dk [R,k_max] at each segment's (ray, slot).  t == NULL and Dk == NULL together: no depth.  Same arithmetic as the three
+ * separate calls.  DG_ERR_UNSUPPORTED unless the network is the 32-64-16 / (32 + n_app)-64-64-3 one and S <= 64 (one
+ * wavefront renders a segment); callers then use the separate entry points. */
+int dg_mlp_composite_fwd(const dg_mlp_desc *desc, const void *weights, const void *feat, const void *dir_enc,
+                         const void *app, uint32_t S, uint32_t n_seg, const float *delta, const float *t,
+                         const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t k_max, float *Ck, float *Tk,
+                         float *Dk, void *stream);
 
 /* One Adam step (Sec. 5.1 names the optimiser; the update is Algorithm 1 of Kingma & Ba) on n fp32 values, in place:
  *   g' = g + l2 * p;  m = beta1 m + (1 - beta1) g';  v = beta2 v + (1 - beta2) g'^2;

@@ -75,6 +75,8 @@ _SIGNATURES = {
     "dg_mlp_bwd_app_workspace_bytes": (C.c_size_t, [C.POINTER(MlpDesc), C.c_uint64, C.c_uint32]),
     "dg_mlp_bwd_app": (C.c_int, [C.POINTER(MlpDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64,
                                  C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "dg_mlp_composite_fwd": (C.c_int, [C.POINTER(MlpDesc)] + [C.c_void_p] * 4 + [C.c_uint32, C.c_uint32] + [C.c_void_p] * 4 + [C.c_uint32]
+                             + [C.c_void_p] * 4),
     "dg_appearance_rows": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_void_p]),
     "dg_composite_segment_fwd": (C.c_int, [C.c_void_p] * 3 + [C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32,
                                                               C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -393,6 +395,17 @@ def dg_mlp_fwd_app(desc, weights, feat, dir_enc, app, S, N, sigma, rgb):
     assert dir_enc.numel() >= rows * desc.n_dir and (app is None or app.numel() >= rows * desc.n_app)
     _check(lib().dg_mlp_fwd_app(C.byref(desc), _ptr(weights, torch.float16), _ptr(feat, torch.float16), _ptr(dir_enc, torch.float16),
                                 _ptr(app, torch.float16, True), S, N, _ptr(sigma, torch.float32), _ptr(rgb, torch.float32), _stream()))
+
+
+def dg_mlp_composite_fwd(desc, weights, feat, dir_enc, app, S, n_seg, delta, t, seg_ray, seg_slot, k_max, Ck, Tk, Dk):
+    N = n_seg * S
+    assert dir_enc.numel() >= n_seg * desc.n_dir and (app is None or app.numel() >= n_seg * desc.n_app)
+    assert feat.numel() >= N * desc.n_feat and delta.numel() >= N and (t is None or t.numel() >= N)
+    assert min(seg_ray.numel(), seg_slot.numel()) >= n_seg
+    _check(lib().dg_mlp_composite_fwd(C.byref(desc), _ptr(weights, torch.float16), _ptr(feat, torch.float16), _ptr(dir_enc, torch.float16),
+                                      _ptr(app, torch.float16, True), S, n_seg, _ptr(delta, torch.float32), _ptr(t, torch.float32, True),
+                                      _ptr(seg_ray, torch.int32), _ptr(seg_slot, torch.int32), k_max, _ptr(Ck, torch.float32),
+                                      _ptr(Tk, torch.float32), _ptr(Dk, torch.float32, True), _stream()))
 
 
 def dg_mlp_bwd_app(desc, weights, feat, dir_enc, app, S, N, dsigma, drgb, loss_scale, dfeat, dW, ws):

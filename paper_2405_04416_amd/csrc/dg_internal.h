@@ -43,6 +43,9 @@ size_t mlp_mfma_workspace_bytes(uint64_t N, uint32_t n_app, uint32_t S);
 size_t mlp_mfma_weight_count(uint32_t n_app);
 void mlp_mfma_fwd(const void *weights, const void *feat, const void *dir_enc, const void *app, uint32_t n_app, uint32_t S,
                   uint64_t N, uint32_t act_c, float *sigma, float *rgb, hipStream_t st);
+void mlp_mfma_render(const void *weights, const void *feat, const void *dir_enc, const void *app, uint32_t n_app, uint32_t S,
+                     uint32_t n_seg, uint32_t act_c, const float *delta, const float *t, const uint32_t *seg_ray,
+                     const uint32_t *seg_slot, uint32_t k_max, float *Ck, float *Tk, float *Dk, hipStream_t st);
 void mlp_mfma_bwd(const void *weights, const void *feat, const void *dir_enc, const void *app, uint32_t n_app, uint32_t S,
                   uint64_t N, uint32_t act_c, const float *dsigma, const float *drgb, float loss_scale, float *dfeat, float *dW,
                   void *ws, hipStream_t st);

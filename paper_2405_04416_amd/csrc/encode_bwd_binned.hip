@@ -270,6 +270,9 @@ __device__ __forceinline__ void corner_values(const Emission &em, float2 gfe, fl
         for (int c = 0; c < 8; ++c) m = fmaxf(m, fmaxf(fabsf(vx[c]), fabsf(vy[c])));
         largest = max(largest, __float_as_uint(m));
     }
+    // fmaxf passes over NaN: a NaN gradient is reported as such (its bit pattern orders above infinity's), by whichever
+    // lane holds it, whether or not that lane emits
+    if (gfe.x != gfe.x || gfe.y != gfe.y) largest = max(largest, 0x7fc00000u);
 }
 
 // largest over the workgroup -> *dst (one atomic per workgroup); `word` is an LDS word nobody else uses any more
@@ -744,6 +747,17 @@ accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbas
     const int k = 50 - kAccRecordsLog2 - 1 - ((int)(top ? top : 1u) - 127);
     const double scale = __longlong_as_double((long long)(1023 + k) << 52);
     const double inv_scale = __longlong_as_double((long long)(1023 - k) << 52);
+    if (top == 255u) {
+        // an infinite or NaN contribution somewhere in the batch: the scale above means nothing and integer sums cannot
+        // carry it.  The gradient is marked instead: every bin that has records gets NaN in its first entry, as sums
+        // with fp32 atomics would end up non-finite too.
+        if (threadIdx.x == 0 && begin < end) {
+            uint32_t lv = plan.first_level;
+            while (lv + 1 < g.n_levels && key >= plan.key_base[lv + 1]) ++lv;
+            dtable[2 * ((size_t)g.offset[lv] + (size_t)(key - plan.key_base[lv]) * kChunk)] = __uint_as_float(0x7fc00000u);
+        }
+        return;
+    }
     for (uint32_t i = threadIdx.x; i < 2 * kChunk; i += kAccBlock) tab[i] = 0ull;
     __syncthreads();
     // several records in flight per thread so that the queue streams at memory speed: the loads are unconditional

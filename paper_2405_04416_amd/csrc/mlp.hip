@@ -267,6 +267,26 @@ extern "C" int dg_mlp_fwd_app(const dg_mlp_desc *desc, const void *weights, cons
     return dg::launch_status("dg_mlp_fwd");
 }
 
+extern "C" int dg_mlp_composite_fwd(const dg_mlp_desc *desc, const void *weights, const void *feat, const void *dir_enc,
+                                    const void *app, uint32_t S, uint32_t n_seg, const float *delta, const float *t,
+                                    const uint32_t *seg_ray, const uint32_t *seg_slot, uint32_t k_max, float *Ck, float *Tk,
+                                    float *Dk, void *stream)
+{
+    const int net = which_net(desc, "dg_mlp_composite_fwd");
+    if (net < 0) return net;
+    DG_REQUIRE(net == 1, DG_ERR_UNSUPPORTED, "dg_mlp_composite_fwd: only the 32-64-16 / 64-64-3 networks have a fused kernel");
+    DG_REQUIRE(S >= 1 && S <= 64, DG_ERR_UNSUPPORTED, "dg_mlp_composite_fwd: S=%u outside 1..64 (one wavefront renders a segment)", S);
+    DG_REQUIRE(k_max >= 1, DG_ERR_ARG, "dg_mlp_composite_fwd: k_max must be >= 1");
+    if (n_seg == 0) return DG_OK;
+    DG_REQUIRE(weights && feat && dir_enc && delta && seg_ray && seg_slot && Ck && Tk, DG_ERR_ARG, "dg_mlp_composite_fwd: null pointer");
+    DG_REQUIRE((t == nullptr) == (Dk == nullptr), DG_ERR_ARG, "dg_mlp_composite_fwd: t and Dk go together");
+    DG_REQUIRE(desc->n_app == 0 || (app && dg::aligned(app, 16)), DG_ERR_ARG, "dg_mlp_composite_fwd: appearance rows missing or not 16-byte aligned");
+    DG_REQUIRE(dg::aligned(feat, 4) && dg::aligned(dir_enc, 16), DG_ERR_ARG, "dg_mlp_composite_fwd: feat must be 4-byte, dir_enc 16-byte aligned");
+    dg::mlp_mfma_render(weights, feat, dir_enc, app, desc->n_app, S, n_seg, desc->act_c, delta, t, seg_ray, seg_slot, k_max, Ck, Tk, Dk,
+                        (hipStream_t)stream);
+    return dg::launch_status("dg_mlp_composite_fwd");
+}
+
 extern "C" size_t dg_mlp_bwd_workspace_bytes(const dg_mlp_desc *desc, uint64_t N)
 {
     return dg_mlp_bwd_app_workspace_bytes(desc, N, 1);

@@ -262,6 +262,82 @@ fwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, 
     }
 }
 
+// ---------------------------------------------------------------------------------------- evaluation rendering, fused
+// Forward-only rendering (Sec. 4.4.2: every sub-model renders its segments, the partial colour, depth and transmittance
+// are merged afterwards): the field networks and the local volume rendering (Eq. 3) of one segment in one wavefront.
+// A segment of S <= 64 samples is two tiles of the forward above (samples 0..31 and 32..S-1); their densities and
+// colours end up on lanes 0..31, the second tile's are moved to lanes 32..63, and the front-to-back product over the
+// 64 lanes is a prefix scan -- sigma and rgb never leave the registers.  The arithmetic of the scan is that of the
+// separate compositing kernels (alpha from expm1, transmittance as a running product of exp(-sigma delta)).
+__device__ __forceinline__ float wave_inclusive_product(float v, int lane)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const float up = __shfl_up(v, off, 64);
+        if (lane >= off) v *= up;
+    }
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+template <int NA>
+__global__ void __launch_bounds__(kBlock, 4)
+render_fwd_kernel(const __half *__restrict__ weights, const __half *__restrict__ feat, const __half *__restrict__ dir_enc,
+                  const __half *__restrict__ app, uint32_t S, uint32_t n_seg, uint32_t act_c, const float *__restrict__ delta,
+                  const float *__restrict__ t_samples, const uint32_t *__restrict__ seg_ray, const uint32_t *__restrict__ seg_slot,
+                  uint32_t k_max, float *__restrict__ Ck, float *__restrict__ Tk, float *__restrict__ Dk)
+{
+    __shared__ __attribute__((aligned(16))) __half lds[(kFwdChunks + 2 * (NA / 16)) * 512];
+    build_forward_images(lds, weights);
+    if (NA > 0) build_image(lds + kFwdChunks * 512, weights + kTotal, HC, NA, HC, NA, 2, NA / 16, 1, false);
+    __syncthreads();
+    const int lane = threadIdx.x & 63, h = lane >> 5;
+    const uint64_t n_samples = (uint64_t)n_seg * S;
+    const uint32_t wave = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6), n_waves = gridDim.x * kWavesPerBlock;
+    for (uint32_t seg = wave; seg < n_seg; seg += n_waves) {
+        const uint64_t first = (uint64_t)seg * S;
+        float sig[2], col[2][3];
+#pragma unroll
+        for (int part = 0; part < 2; ++part) {
+            const uint32_t s = 32u * part + (lane & 31);
+            const bool valid = s < S;
+            Tile t;
+            load_inputs<NA>(feat, dir_enc, app, S, n_samples, first + (valid ? s : 0), valid, h, t);
+            forward_tile<NA>(lds, opaque(lane), act_c, t, kFwdChunks);
+            sig[part] = t.sigma;
+            col[part][0] = t.rgb[0]; col[part][1] = t.rgb[1]; col[part][2] = t.rgb[2];
+        }
+        // sample `lane` of the segment: first tile on lanes 0..31 as it stands, second tile fetched from lanes 0..31
+        // (every lane takes part in the exchange; the choice comes afterwards: a lane must not read from lanes that a
+        // branch has switched off)
+        const float s_up = __shfl(sig[1], lane & 31, 64), a_up = __shfl(col[1][0], lane & 31, 64);
+        const float b_up = __shfl(col[1][1], lane & 31, 64), c_up = __shfl(col[1][2], lane & 31, 64);
+        const float sigma_s = h ? s_up : sig[0], r0 = h ? a_up : col[0][0], r1 = h ? b_up : col[0][1], r2 = h ? c_up : col[0][2];
+        const bool live = (uint32_t)lane < S;
+        const uint64_t n = first + (live ? lane : 0);
+        const float x = live ? sigma_s * delta[n] : 0.0f;
+        const float incl = wave_inclusive_product(expf(-x), lane);
+        float before = __shfl_up(incl, 1, 64);
+        if (lane == 0) before = 1.0f;
+        const float wgt = live ? before * -expm1f(-x) : 0.0f;
+        const float c0 = wave_sum(wgt * r0), c1 = wave_sum(wgt * r1), c2 = wave_sum(wgt * r2);
+        const float depth = t_samples ? wave_sum(live ? wgt * t_samples[n] : 0.0f) : 0.0f;
+        const float trans = __shfl(incl, 63, 64);
+        if (lane == 0) {
+            const size_t dst = (size_t)seg_ray[seg] * k_max + seg_slot[seg];
+            Ck[3 * dst] = c0; Ck[3 * dst + 1] = c1; Ck[3 * dst + 2] = c2;
+            Tk[dst] = trans;
+            if (Dk) Dk[dst] = depth;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------- backward
 
 // transpose of one 32-feature tile of a packed tensor: x0 / x1 are the two k-steps that hold the tile,
@@ -700,6 +776,19 @@ void mlp_mfma_fwd(const void *weights, const void *feat, const void *dir_enc, co
     if (n_app == 0) fwd_kernel<0><<<grid, kBlock, 0, st>>>(w, f, dr, ap, S, N, act_c, sigma, rgb);
     else if (n_app == 16) fwd_kernel<16><<<grid, kBlock, 0, st>>>(w, f, dr, ap, S, N, act_c, sigma, rgb);
     else fwd_kernel<48><<<grid, kBlock, 0, st>>>(w, f, dr, ap, S, N, act_c, sigma, rgb);
+}
+
+void mlp_mfma_render(const void *weights, const void *feat, const void *dir_enc, const void *app, uint32_t n_app, uint32_t S,
+                     uint32_t n_seg, uint32_t act_c, const float *delta, const float *t, const uint32_t *seg_ray,
+                     const uint32_t *seg_slot, uint32_t k_max, float *Ck, float *Tk, float *Dk, hipStream_t st)
+{
+    using namespace dg_mlp_mfma;
+    const uint32_t blocks_needed = (n_seg + kWavesPerBlock - 1) / kWavesPerBlock;
+    const uint32_t grid = blocks_needed < 2048 ? blocks_needed : 2048;
+    const __half *w = (const __half *)weights, *f = (const __half *)feat, *dr = (const __half *)dir_enc, *ap = (const __half *)app;
+    if (n_app == 0) render_fwd_kernel<0><<<grid, kBlock, 0, st>>>(w, f, dr, ap, S, n_seg, act_c, delta, t, seg_ray, seg_slot, k_max, Ck, Tk, Dk);
+    else if (n_app == 16) render_fwd_kernel<16><<<grid, kBlock, 0, st>>>(w, f, dr, ap, S, n_seg, act_c, delta, t, seg_ray, seg_slot, k_max, Ck, Tk, Dk);
+    else render_fwd_kernel<48><<<grid, kBlock, 0, st>>>(w, f, dr, ap, S, n_seg, act_c, delta, t, seg_ray, seg_slot, k_max, Ck, Tk, Dk);
 }
 
 void mlp_mfma_bwd(const void *weights, const void *feat, const void *dir_enc, const void *app, uint32_t n_app, uint32_t S,

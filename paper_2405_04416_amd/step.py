@@ -169,18 +169,22 @@ class TrainStep:
         with self._timed("dg_loss_seed"):
             B.dg_loss_seed(self.C, self.T, Cgt, self.R, self.lambda1, self.gC, self.gT, self.loss)
 
-    def render(self, o, d, jitter=None):
+    def render(self, o, d, jitter=None, fused=None):
         """Evaluation rendering (Sec. 4.4.2): forward only, every sub-model renders its segments and the partial
-        results are merged into the final colour, depth and transmittance.  Returns (C [R,3], D [R], T [R])."""
+        results are merged into the final colour, depth and transmittance.  Returns (C [R,3], D [R], T [R]).
+        fused: None = use the fused networks + rendering kernel where it applies; False = the separate entry points."""
         if self.occ is None and self.t_fixed is None:
             self.t_fixed = torch.zeros_like(self.delta)          # sample distances, only evaluation needs them
-        self._partials(o, d, jitter, want_t=True)
+        Dk = torch.zeros(self.R, self.k_max, device=self.dev)
+        D = torch.zeros(self.R, device=self.dev)
+        # networks and local rendering in one kernel where the library has one (fixed S <= 64, the 32-64-16 / 64-64-3 nets)
+        mlp = next(iter(self.models.values())).mlp
+        fused = fused if fused is not None else (self.occ is None and self.S <= 64 and (mlp.n_feat, mlp.n_hidden_d, mlp.n_layers_c) == (32, 64, 2))
+        self._partials(o, d, jitter, want_t=True, fused_depth=Dk if fused else None)
         B.dg_merge_segments(self.Ck, self.Tk, self.seg_count, self.R, self.k_max, self.C, self.T)
         if self.occ is not None:
             return self.C, self.depth(), self.T
-        Dk = torch.zeros(self.R, self.k_max, device=self.dev)
-        D = torch.zeros(self.R, device=self.dev)
-        for p in self.resident:
+        for p in () if fused else self.resident:
             b, e, sl = self._slices(p)
             if e > b:
                 B.dg_composite_segment_depth(self.sigma[sl], self.delta[sl], self.t_fixed[sl], e - b, self.S, self.seg_ray[b:e],
@@ -188,8 +192,9 @@ class TrainStep:
         B.dg_merge_depth(Dk, self.Tk, self.seg_count, self.R, self.k_max, D)
         return self.C, D, self.T
 
-    def _partials(self, o, d, jitter=None, want_t=False):
-        """Segments, and per resident sub-model: samples, encode, MLPs, local compositing into the partial slots."""
+    def _partials(self, o, d, jitter=None, want_t=False, fused_depth=None):
+        """Segments, and per resident sub-model: samples, encode, MLPs, local compositing into the partial slots.
+        fused_depth: None, or Dk [R,k_max]: networks, compositing and depth in one call (evaluation rendering)."""
         S = self.S
         self.segments(o, d)
         if self.occ is not None:
@@ -212,6 +217,12 @@ class TrainStep:
             with self._timed("dg_hashgrid_encode_fwd"):
                 B.dg_hashgrid_encode_fwd(m.grid, m.table, self.u[sl], N, self.feat[sl])
             app = self._appearance_rows(self.seg_ray[b:e], n_seg, rows)
+            if fused_depth is not None:
+                with self._timed("dg_mlp_composite_fwd"):
+                    B.dg_mlp_composite_fwd(m.mlp, m.weights, self.feat[sl], self.dir_enc[rows], app, S, n_seg, self.delta[sl],
+                                           self.t_fixed[sl], self.seg_ray[b:e], self.seg_slot[b:e], self.k_max, self.Ck, self.Tk,
+                                           fused_depth)
+                continue
             with self._timed("dg_mlp_fwd"):
                 B.dg_mlp_fwd_app(m.mlp, m.weights, self.feat[sl], self.dir_enc[rows], app, S, N, self.sigma[sl], self.rgb[sl])
             with self._timed("dg_composite_segment_fwd"):
@@ -364,9 +375,19 @@ class TrainStep:
         self.backward()
 
     # -- optimiser (Sec. 5.1) -----------------------------------------------------------------
-    def optimiser_step(self, iteration, total_iterations=300000, lr0=0.05, lr1=0.005, l2_weights=1e-6):
+    def optimiser_step(self, iteration, total_iterations=300000, lr0=0.05, lr1=0.005, l2_weights=1e-6, check_overflow=False):
         """Adam on every resident sub-model, learning rate from the cosine schedule; consumes (clears) the gradients.
-        iteration counts from 0."""
+        iteration counts from 0.
+        check_overflow: the back-propagated deltas are fp16 values times loss_scale; where one overflows, the weight
+        gradient (and the table gradient) of that step is not finite.  With this flag the weight gradients are looked
+        at first (one small device-to-host read); if any is not finite the step is dropped -- gradients cleared, no
+        update, loss_scale halved -- and None is returned."""
+        if check_overflow and not all(bool(torch.isfinite(self.models[p].dW).all()) for p in self.resident):
+            for p in self.resident:
+                self.models[p].dW.zero_()
+                self.models[p].dtable.zero_()
+            self.loss_scale *= 0.5
+            return None
         lr = B.dg_cosine_lr(lr0, lr1, iteration, total_iterations)
         for p in self.resident:
             m = self.models[p]

@@ -267,6 +267,23 @@ def test_encode_bwd_several_tiles_per_workgroup(key, N, capped):
     assert np.all(got[ref == 0] == 0)
 
 
+@pytest.mark.parametrize("bad", [np.inf, np.nan])
+def test_encode_bwd_binned_marks_non_finite_gradients(bad):
+    """A feature gradient that is infinite or NaN (an fp16 delta that overflowed under the loss scale) must not turn into
+    finite numbers: the binned pass marks the table gradient with NaN."""
+    say("encode bwd non-finite input %s" % bad)
+    g, r, _ = _both_grids("c2")
+    N = 5003
+    u = _coords(N, "rays", seed=35)
+    dfeat = (np.random.default_rng(36).standard_normal((N, 2 * g.n_levels)) * 1e-3).astype(np.float32)
+    dfeat[1234, 20] = bad
+    dtable = torch.zeros(r.n_entries, 2, device=DEV)
+    ws = torch.zeros(B.dg_hashgrid_encode_bwd_workspace_bytes(g, N) // 4 + 64, device=DEV)
+    B.dg_hashgrid_encode_bwd(g, dev(u), dev(to_planes(dfeat)), N, dtable, ws)
+    torch.cuda.synchronize()
+    assert not bool(torch.isfinite(dtable).all())
+
+
 @pytest.mark.parametrize("with_ws", [False, True])
 def test_encode_bwd_empty_batch(with_ws):
     """N = 0 adds nothing, with and without a workspace."""
@@ -416,6 +433,52 @@ def test_mlp_bwd_several_tiles_per_wavefront():
     for (no, ni) in di.mlp_layer_shapes(feat.shape[1], cfg["mlp"]):
         assert rel_err(host(dW)[pos:pos + no * ni], rdw[pos:pos + no * ni]) <= TOL_F16
         pos += no * ni
+
+
+@pytest.mark.parametrize("S,n_seg,n_app", [(64, 1201, 0), (48, 700, 0), (20, 333, 0), (1, 50, 0), (33, 257, 48)])
+def test_mlp_composite_fused_forward(S, n_seg, n_app):
+    """Evaluation rendering (Sec. 4.4.2) with networks and local rendering in one kernel: partial colour, transmittance
+    and depth of every segment against the oracle's networks + quadrature, and against the separate entry points."""
+    say("fused networks + rendering S=%d n_seg=%d n_app=%d" % (S, n_seg, n_app))
+    cfg = di.config("c8_app" if n_app else "c2_ngp")
+    n = n_seg * S
+    w, feat, dir_enc, odesc = _mlp_inputs(cfg, n, S, seed=31, scale=0.5)
+    rng = np.random.default_rng(32)
+    n_feat = feat.shape[1]
+    if n_app:
+        app = rng.standard_normal((n_seg, n_app)).astype(np.float16)
+        odesc = oracle.mlp_desc(n_feat, 64, 16, 16 + n_app, 64, 2, 1, 1)
+        rows = np.concatenate([dir_enc, app], axis=1)
+        from gpu_util import split_appearance_weights
+        w_gpu = split_appearance_weights(w, n_feat, cfg["mlp"])
+    else:
+        app, rows, w_gpu = None, dir_enc, w
+    delta = (rng.random(n) * 0.02 + 1e-3).astype(np.float32)
+    t = np.sort(rng.random((n_seg, S)) * 4.0, axis=1).reshape(-1).astype(np.float32)
+    R, k_max = n_seg + 3, 3
+    seg_ray = rng.permutation(R)[:n_seg].astype(np.int32)
+    seg_slot = rng.integers(0, k_max, n_seg).astype(np.int32)
+    mdesc = gpu_mlp(cfg)
+    fd, dd, ad = dev(to_planes(feat)), dev(dir_enc), None if app is None else dev(app)
+    Ck = torch.zeros(R, k_max, 3, device=DEV); Tk = torch.ones(R, k_max, device=DEV); Dk = torch.zeros(R, k_max, device=DEV)
+    B.dg_mlp_composite_fwd(mdesc, dev(w_gpu), fd, dd, ad, S, n_seg, dev(delta), dev(t), dev(seg_ray), dev(seg_slot), k_max, Ck, Tk, Dk)
+    # the separate entry points on the same inputs
+    sigma = torch.zeros(n, device=DEV); rgb = torch.zeros(n, 3, device=DEV)
+    Ck2 = torch.zeros_like(Ck); Tk2 = torch.ones_like(Tk); Dk2 = torch.zeros_like(Dk)
+    B.dg_mlp_fwd_app(mdesc, dev(w_gpu), fd, dd, ad, S, n, sigma, rgb)
+    B.dg_composite_segment_fwd(sigma, rgb, dev(delta), n_seg, S, dev(seg_ray), dev(seg_slot), k_max, Ck2, Tk2)
+    B.dg_composite_segment_depth(sigma, dev(delta), dev(t), n_seg, S, dev(seg_ray), dev(seg_slot), k_max, Dk2)
+    torch.cuda.synchronize()
+    for a, b in ((Ck, Ck2), (Tk, Tk2), (Dk, Dk2)):
+        assert rel_err(host(a)[seg_ray, seg_slot], host(b)[seg_ray, seg_slot]) <= 1e-5
+    rs, rr = oracle.mlp_fwd(odesc, w.astype(np.float64), feat.astype(np.float64), rows.astype(np.float64), S)
+    rC, rT = oracle.composite_fwd(rs, rr, delta.astype(np.float64), S)
+    rD = oracle.composite_depth(rs, delta.astype(np.float64), t.astype(np.float64), S)
+    assert rel_err(host(Ck)[seg_ray, seg_slot], rC) <= TOL_F16
+    assert rel_err(host(Tk)[seg_ray, seg_slot], rT) <= TOL_F16
+    assert rel_err(host(Dk)[seg_ray, seg_slot], rD) <= TOL_F16
+    untouched = np.ones((R, k_max), bool); untouched[seg_ray, seg_slot] = False
+    assert np.all(host(Tk)[untouched] == 1) and np.all(host(Dk)[untouched] == 0)
 
 
 # ---------------------------------------------------------------------------- rendering

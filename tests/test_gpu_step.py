@@ -133,8 +133,11 @@ def test_evaluation_rendering_colour_depth_transmittance():
     o, d = di.make_rays(cfg, seed=seed, R=R)
     hm = ostep.make_models(cfg, seed=seed)
     step = make_step(cfg, gpu_models(cfg, hm), R, seed=seed)
-    C, D, T = step.render(dev(o), dev(d))
+    C, D, T = (x.clone() for x in step.render(dev(o), dev(d), fused=False))          # the separate entry points
+    C2, D2, T2 = step.render(dev(o), dev(d))                                          # networks + rendering in one kernel
     torch.cuda.synchronize()
+    for a, b in ((C, C2), (D, D2), (T, T2)):
+        assert rel_err(host(b), host(a)) <= 1e-5
     ref = ostep.run_step(cfg, hm, o, d, di.make_targets(R, seed=seed), seed=seed, want_bwd=False)
     assert rel_err(host(C), ref["C"]) <= TOL_F16 and rel_err(host(T), ref["T"]) <= TOL_F16
     Dk = np.zeros((R, cfg["k_max"]))
