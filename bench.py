@@ -307,6 +307,11 @@ def run_workload(name, steps, warmup, peaks, with_optimiser=True, with_evaluatio
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": moved, "algorithmic_bytes": work,
                     "avg_launch_ms": round(avg_ms, 4)}
+        if moved:
+            # what the memory system actually moved for this launch, as a rate: a random 8-byte gather out of tables that no
+            # cache holds fetches a whole 128-byte line per miss, so this rate, not the algorithmic one, is what HBM sees
+            roofline["achieved_by_traffic"] = round(moved / (avg_ms * 1e-3) / 1e9, 1)
+            roofline["frac_by_traffic"] = round(moved / (avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
     else:
         ach = work / (avg_ms * 1e-3) / 1e12
         roofline = {"kernel": dominant, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_F16_PEAK_TFLOPS,

@@ -9,7 +9,7 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdgpeaks.so")
-EXPORTS = ("pk_stream_copy", "pk_random_gather", "pk_random_atomic_add", "pk_mfma_loop")
+EXPORTS = ("pk_stream_copy", "pk_stream_read", "pk_random_gather", "pk_random_atomic_add", "pk_mfma_loop")
 _lib = None
 
 
@@ -20,6 +20,7 @@ def lib():
             raise RuntimeError("libdgpeaks.so is not built: run `python -m paper_2405_04416_amd.build`")
         h = C.CDLL(LIB_PATH)
         h.pk_stream_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        h.pk_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         h.pk_random_gather.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p]
         h.pk_random_atomic_add.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p]
         h.pk_mfma_loop.argtypes = [C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p]
@@ -53,6 +54,12 @@ def stream_copy(src, dst):
     assert rc == 0, rc
 
 
+def stream_read(src, sink):
+    assert sink.numel() >= 256 * 4096
+    rc = lib().pk_stream_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _stream())
+    assert rc == 0, rc
+
+
 def random_gather(table, log2_entries, entry_bytes, n_lanes, per_lane, seed, sink):
     assert table.numel() * table.element_size() >= (entry_bytes << log2_entries) and sink.numel() >= n_lanes
     rc = lib().pk_random_gather(table.data_ptr(), log2_entries, entry_bytes, n_lanes, per_lane, seed, sink.data_ptr(), _stream())
@@ -81,7 +88,9 @@ def measure(device="cuda:0"):
     ms = _time_ms(lambda: stream_copy(src, dst))
     out["stream_copy_GBps"] = round(2 * gib / ms / 1e6, 1)                       # read + written
     n_lanes, per_lane = 256 * 2048, 64
-    sink = torch.empty(n_lanes, dtype=torch.int32, device=device)
+    sink = torch.empty(256 * 4096, dtype=torch.int32, device=device)
+    ms = _time_ms(lambda: stream_read(buf, sink))
+    out["stream_read_GBps"] = round(2 * gib / ms / 1e6, 1)
     gathers = n_lanes * per_lane
     for entry_bytes in (16, 8):
         for mib in (128, 1024):

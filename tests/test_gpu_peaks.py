@@ -27,6 +27,15 @@ def test_stream_copy_copies():
     assert torch.equal(src, dst)
 
 
+def test_stream_read_reads_everything():
+    src = torch.randint(0, 2 ** 31 - 1, (1 << 20,), dtype=torch.int32, device=DEV)
+    sink = torch.zeros(256 * 4096, dtype=torch.int32, device=DEV)
+    P.stream_read(src, sink)
+    torch.cuda.synchronize()
+    want = np.bitwise_xor.reduce(src.cpu().numpy().view(np.uint32))
+    assert np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32)) == want
+
+
 @pytest.mark.parametrize("entry_bytes", [8, 16])
 def test_random_gather_reads_the_entries_of_its_counter_sequence(entry_bytes):
     log2_entries, n_lanes, per_lane, seed = 12, 512, 16, 5
