@@ -9,7 +9,7 @@ T=2^24, all eight boxes traced, one sub-model resident, the other boxes' partial
 The other paper-scale configurations are timed after it and reported as blocks of the same
 line (`also`).  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5_share] [--also c4_big,c2_ngp]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5_share] [--also c4_big,c3_2x2,c2_ngp,c1_tiny]
                     [--no-cpu-baseline] [--no-optimizer] [--no-peaks]
 
 --workload c7_occ runs c2's scene with occupancy-guided sampling (Sec. 3.2, Sec. 5.1) instead of 64 stratified
@@ -342,7 +342,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c5_share")
     ap.add_argument("--also", default=None, help="comma-separated workloads timed after the headline one and reported as blocks of the "
-                                                 "same line (default: c4_big,c2_ngp when the headline is c5_share, else none)")
+                                                 "same line (default: the other four configurations when the headline is c5_share, else none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rays", type=int, default=8192, help="rays per host core of the oracle's pass")
     ap.add_argument("--no-optimizer", action="store_true", help="skip the separate timing of the Adam sweep")
@@ -354,7 +354,7 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not available. "
                  "value is the one GPU's throughput." % args.gpus)
-    also = args.also if args.also is not None else ("c4_big,c2_ngp" if args.workload == "c5_share" else "")
+    also = args.also if args.also is not None else ("c4_big,c3_2x2,c2_ngp,c1_tiny" if args.workload == "c5_share" else "")
     also = [w for w in also.split(",") if w and w != args.workload]
 
     # the oracle on the host cores first: its workers are forks, which must exist before this process touches the GPU
