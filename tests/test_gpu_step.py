@@ -332,3 +332,41 @@ def test_optimiser_step_after_a_training_step():
         np.testing.assert_allclose(host(st["w_master"]), w, rtol=0, atol=2e-6 * (it + 1) * 0.05 + 2e-7)
         np.testing.assert_array_equal(host(m.weights).reshape(-1), host(st["w_master"]).astype(np.float16))
         assert torch.count_nonzero(m.dtable).item() == 0 and torch.count_nonzero(m.dW).item() == 0
+
+
+def test_step_refuses_to_merge_slots_nobody_fills():
+    """A step that serves only some of the partitions needs to be told who fills the other partitions' partial slots."""
+    say("step with non-resident partitions and no source for their partials")
+    cfg = di.config("c3_2x2")
+    cfg["grid"] = dict(cfg["grid"], log2_T=14)
+    R = 300
+    o, d = di.make_rays(cfg, seed=1, R=R)
+    hm = ostep.make_models(dict(cfg, resident_list=[2]), seed=1)
+    step = make_step(cfg, gpu_models(cfg, hm), R, resident=[2])
+    with pytest.raises(B.DistGridError):
+        step.step(dev(o), dev(d), dev(di.make_targets(R, seed=1)))
+    # with neutral partials (C = 0, T = 1) in every slot the same step runs: the other boxes then count as empty space
+    step = make_step(cfg, gpu_models(cfg, hm), R, resident=[2], foreign_prefilled=True)
+    step.Ck.zero_(); step.Tk.fill_(1.0)
+    step.step(dev(o), dev(d), dev(di.make_targets(R, seed=1)))
+    ref = ostep.run_step(cfg, hm, o, d, di.make_targets(R, seed=1), resident=[2])
+    assert rel_err(host(step.C), ref["C"]) <= TOL_F16 and rel_err(host(step.T), ref["T"]) <= TOL_F16
+
+
+def test_optimiser_step_drops_a_step_whose_gradients_overflowed():
+    say("optimiser step with a non-finite weight gradient")
+    cfg = di.config("c1_tiny")
+    R = 256
+    o, d = di.make_rays(cfg, seed=3, R=R)
+    gm = gpu_models(cfg, ostep.make_models(cfg, seed=3))
+    step = make_step(cfg, gm, R, loss_scale=1024.0, seed=3)
+    step.step(dev(o), dev(d), dev(di.make_targets(R, seed=3)))
+    m = gm[0]
+    before_table, before_w = m.table.clone(), m.weights.clone()
+    m.dW[5] = float("inf")
+    assert step.optimiser_step(0, check_overflow=True) is None
+    assert step.loss_scale == 512.0
+    assert torch.equal(m.table, before_table) and torch.equal(m.weights, before_w)
+    assert torch.count_nonzero(m.dW).item() == 0 and torch.count_nonzero(m.dtable).item() == 0
+    step.step(dev(o), dev(d), dev(di.make_targets(R, seed=3)))
+    assert step.optimiser_step(0, check_overflow=True) is not None and not torch.equal(m.table, before_table)
