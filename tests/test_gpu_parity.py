@@ -211,7 +211,9 @@ def test_encode_fwd_and_indices(key, N):
                                            ("dense_odd", 150001, "points"), ("dense_odd", 30000, "rays"),
                                            ("wide", 20011, "points"), ("wide", 9000, "rays"), ("huge", 20011, "points"),
                                            ("c2", 1, "points"), ("c2", 7, "rays"), ("c2", 513, "rays"), ("c2", 2048 * 3 + 5, "rays"),
-                                           ("one_bin", 60011, "rays"), ("one_bin", 3001, "points")])
+                                           ("one_bin", 60011, "rays"), ("one_bin", 3001, "points"),
+                                           # the sweep for many bins with one tile, one and a bit, two and a bit (a workgroup takes two per step)
+                                           ("huge", 1, "points"), ("wide", 513, "rays"), ("huge", 1025, "rays"), ("wide", 512 * 257 + 3, "rays")])
 def test_encode_bwd(key, N, flavour, mode):
     say("encode bwd %s N=%d %s %s" % (key, N, flavour, mode))
     g, r, _ = _both_grids(key)
