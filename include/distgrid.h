@@ -166,6 +166,19 @@ int dg_hashgrid_encode_fwd(const dg_grid_desc *desc, const float *table, const f
 size_t dg_hashgrid_encode_bwd_workspace_bytes(const dg_grid_desc *desc, uint64_t N);
 int dg_hashgrid_encode_bwd(const dg_grid_desc *desc, const float *u, const float *dfeat,
                            uint64_t N, float *dtable, void *ws, size_t ws_bytes, void *stream);
+/* The binned pass in two parts, for callers that want the first part out of the way early: the sizes of the bin queues
+ * depend on the coordinates alone, so they can be counted as soon as u exists -- on another stream, beside the forward
+ * pass -- and the backward pass then starts with the queues laid out.
+ * dg_hashgrid_encode_bwd_count: the count sweep and its scans for all N samples; ws must hold them in one batch
+ * (dg_hashgrid_encode_bwd_workspace_bytes(desc, N) bytes), else DG_ERR_WORKSPACE.
+ * dg_hashgrid_encode_bwd_counted: dg_hashgrid_encode_bwd without that part.  The counts must come from a
+ * dg_hashgrid_encode_bwd_count call with the same desc, u, N, ws and ws_bytes that has completed before this call's work
+ * starts (same stream, or an event between the streams), and nothing else may have used ws in between; the results are
+ * those of dg_hashgrid_encode_bwd. */
+int dg_hashgrid_encode_bwd_count(const dg_grid_desc *desc, const float *u, uint64_t N, void *ws, size_t ws_bytes,
+                                 void *stream);
+int dg_hashgrid_encode_bwd_counted(const dg_grid_desc *desc, const float *u, const float *dfeat,
+                                   uint64_t N, float *dtable, void *ws, size_t ws_bytes, void *stream);
 /* Absolute table entry of every corner: idx [N, L, 8] uint32, corner c = cx + 2cy + 4cz. */
 int dg_hashgrid_corner_indices(const dg_grid_desc *desc, const float *u, uint64_t N,
                                uint32_t *idx, void *stream);

@@ -63,6 +63,9 @@ _SIGNATURES = {
     "dg_hashgrid_encode_bwd_workspace_bytes": (C.c_size_t, [C.POINTER(GridDesc), C.c_uint64]),
     "dg_hashgrid_encode_bwd": (C.c_int, [C.POINTER(GridDesc), C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p,
                                          C.c_size_t, C.c_void_p]),
+    "dg_hashgrid_encode_bwd_count": (C.c_int, [C.POINTER(GridDesc), C.c_void_p, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "dg_hashgrid_encode_bwd_counted": (C.c_int, [C.POINTER(GridDesc), C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p,
+                                                 C.c_size_t, C.c_void_p]),
     "dg_hashgrid_corner_indices": (C.c_int, [C.POINTER(GridDesc), C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
     "dg_mlp_weight_count": (C.c_size_t, [C.POINTER(MlpDesc)]),
     "dg_mlp_fwd": (C.c_int, [C.POINTER(MlpDesc), C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p,
@@ -232,6 +235,15 @@ def dg_hashgrid_encode_bwd(desc, u, dfeat, N, dtable, ws=None):
     _check(lib().dg_hashgrid_encode_bwd(C.byref(desc), _ptr(u, torch.float32), _ptr(dfeat, torch.float32), N,
                                         _ptr(dtable, torch.float32), _ptr(ws, None, True),
                                         0 if ws is None else ws.numel() * ws.element_size(), _stream()))
+
+
+def dg_hashgrid_encode_bwd_count(desc, u, N, ws):
+    _check(lib().dg_hashgrid_encode_bwd_count(C.byref(desc), _ptr(u, torch.float32), N, _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+def dg_hashgrid_encode_bwd_counted(desc, u, dfeat, N, dtable, ws):
+    _check(lib().dg_hashgrid_encode_bwd_counted(C.byref(desc), _ptr(u, torch.float32), _ptr(dfeat, torch.float32), N,
+                                                _ptr(dtable, torch.float32), _ptr(ws), ws.numel() * ws.element_size(), _stream()))
 
 
 def dg_hashgrid_corner_indices(desc, u, N, idx):

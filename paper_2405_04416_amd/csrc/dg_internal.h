@@ -36,7 +36,8 @@ constexpr int kWave = 64;
 // binned backward of the hash-grid encode (encode_bwd_binned.hip)
 size_t encode_bwd_binned_workspace_bytes(const dg_grid_desc *d, uint64_t N);
 int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat, uint64_t N, float *dtable, void *ws,
-                      size_t ws_bytes, hipStream_t st);
+                      size_t ws_bytes, bool counted, hipStream_t st);
+int encode_bwd_binned_count(const dg_grid_desc *d, const float *u, uint64_t N, void *ws, size_t ws_bytes, hipStream_t st);
 
 // matrix-core path of the 32-64-16 / (32 + n_app)-64-64-3 field MLPs (mlp_mfma.hip); n_app = 0, 16 or 48
 size_t mlp_mfma_workspace_bytes(uint64_t N, uint32_t n_app, uint32_t S);

@@ -246,22 +246,47 @@ extern "C" size_t dg_hashgrid_encode_bwd_workspace_bytes(const dg_grid_desc *des
     return dg::encode_bwd_binned_workspace_bytes(desc, N);
 }
 
-extern "C" int dg_hashgrid_encode_bwd(const dg_grid_desc *desc, const float *u, const float *dfeat, uint64_t N,
-                                      float *dtable, void *ws, size_t ws_bytes, void *stream)
+extern "C" int dg_hashgrid_encode_bwd_count(const dg_grid_desc *desc, const float *u, uint64_t N, void *ws, size_t ws_bytes,
+                                            void *stream)
+{
+    if (int rc = check_desc(desc, "dg_hashgrid_encode_bwd_count")) return rc;
+    if (N == 0) return DG_OK;
+    DG_REQUIRE(u && ws, DG_ERR_ARG, "dg_hashgrid_encode_bwd_count: null pointer");
+    DG_REQUIRE(dg::aligned(ws, 256), DG_ERR_ARG, "dg_hashgrid_encode_bwd_count: workspace must be 256-byte aligned");
+    return dg::encode_bwd_binned_count(desc, u, N, ws, ws_bytes, (hipStream_t)stream);
+}
+
+namespace {
+int encode_bwd(const dg_grid_desc *desc, const float *u, const float *dfeat, uint64_t N, float *dtable, void *ws, size_t ws_bytes,
+               bool counted, void *stream)
 {
     if (int rc = check_desc(desc, "dg_hashgrid_encode_bwd")) return rc;
     if (N == 0) return DG_OK;
     DG_REQUIRE(u && dfeat && dtable, DG_ERR_ARG, "dg_hashgrid_encode_bwd: null pointer");
     DG_REQUIRE(dg::aligned(dfeat, 8) && dg::aligned(dtable, 8), DG_ERR_ARG, "dg_hashgrid_encode_bwd: misaligned pointer");
+    DG_REQUIRE(ws || !counted, DG_ERR_ARG, "dg_hashgrid_encode_bwd_counted: the workspace that holds the counts is missing");
     if (ws) {
         DG_REQUIRE(dg::aligned(ws, 256), DG_ERR_ARG, "dg_hashgrid_encode_bwd: workspace must be 256-byte aligned");
-        return dg::encode_bwd_binned(desc, u, dfeat, N, dtable, ws, ws_bytes, (hipStream_t)stream);
+        return dg::encode_bwd_binned(desc, u, dfeat, N, dtable, ws, ws_bytes, counted, (hipStream_t)stream);
     }
     const uint32_t n_groups = desc->n_levels < 8 ? desc->n_levels : 8;
     uint32_t n_blocks;
     if (int rc = grid_for(N, n_groups, &n_blocks, "dg_hashgrid_encode_bwd")) return rc;
     encode_bwd_kernel<<<n_blocks, kBlock, 0, (hipStream_t)stream>>>(*desc, u, (const float2 *)dfeat, N, dtable, n_groups);
     return dg::launch_status("dg_hashgrid_encode_bwd");
+}
+}  // namespace
+
+extern "C" int dg_hashgrid_encode_bwd(const dg_grid_desc *desc, const float *u, const float *dfeat, uint64_t N,
+                                      float *dtable, void *ws, size_t ws_bytes, void *stream)
+{
+    return encode_bwd(desc, u, dfeat, N, dtable, ws, ws_bytes, false, stream);
+}
+
+extern "C" int dg_hashgrid_encode_bwd_counted(const dg_grid_desc *desc, const float *u, const float *dfeat, uint64_t N,
+                                              float *dtable, void *ws, size_t ws_bytes, void *stream)
+{
+    return encode_bwd(desc, u, dfeat, N, dtable, ws, ws_bytes, true, stream);
 }
 
 extern "C" int dg_hashgrid_corner_indices(const dg_grid_desc *desc, const float *u, uint64_t N, uint32_t *idx,

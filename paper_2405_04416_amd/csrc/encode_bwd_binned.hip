@@ -873,11 +873,23 @@ size_t encode_bwd_binned_workspace_bytes(const dg_grid_desc *d, uint64_t N)
     return make_layout(d, p, batch).total;
 }
 
-int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat, uint64_t N, float *dtable, void *ws,
-                      size_t ws_bytes, hipStream_t st)
+namespace {
+
+using namespace dg_encode_binned;
+
+// what a call works with: the plan of the grid, the batch the workspace holds and the workspace's parts
+struct Prepared {
+    Plan p;
+    Layout L;
+    uint32_t *rows, *totals, *binbase, *blkbase;
+    uint4 *queue;
+    uint32_t grid;
+    bool narrow;
+};
+
+int prepare(const char *who, const dg_grid_desc *d, uint64_t N, void *ws, size_t ws_bytes, Prepared &q)
 {
-    using namespace dg_encode_binned;
-    const Plan p = make_plan(d);
+    q.p = make_plan(d);
     // kernels that use more LDS than a launch gets by default: asked for once per process, whichever thread comes first
     static std::once_flag lds_once;
     static hipError_t lds_status = hipSuccess;
@@ -892,49 +904,85 @@ int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat,
         for (const hipError_t x : e)
             if (x != hipSuccess) lds_status = x;
     });
-    if (lds_status != hipSuccess) return fail(DG_ERR_HIP, "dg_hashgrid_encode_bwd: cannot reserve LDS: %s", hipGetErrorString(lds_status));
+    if (lds_status != hipSuccess) return dg::fail(DG_ERR_HIP, "%s: cannot reserve LDS: %s", who, hipGetErrorString(lds_status));
+    if (q.p.n_keys == 0) return DG_OK;
+    if (q.p.n_keys > kMaxKeys) return dg::fail(DG_ERR_UNSUPPORTED, "%s: %u table regions exceed %u", who, q.p.n_keys, kMaxKeys);
+    // largest batch the workspace holds
+    uint64_t batch = (N + kTile - 1) / kTile * kTile;
+    const uint64_t cap = max_batch(d, q.p);
+    if (batch > cap) batch = cap;
+    while (batch > kTile && make_layout(d, q.p, batch).total > ws_bytes) batch = (batch / 2 + kTile - 1) / kTile * kTile;
+    q.L = make_layout(d, q.p, batch);
+    if (q.L.total > ws_bytes)
+        return dg::fail(DG_ERR_WORKSPACE, "%s: workspace %zu bytes cannot hold one tile (%zu needed)", who, ws_bytes, q.L.total);
+    char *base = static_cast<char *>(ws);
+    q.rows = reinterpret_cast<uint32_t *>(base + q.L.rows);
+    q.totals = reinterpret_cast<uint32_t *>(base + q.L.totals);
+    q.binbase = reinterpret_cast<uint32_t *>(base + q.L.binbase);
+    q.blkbase = reinterpret_cast<uint32_t *>(base + q.L.blkbase);
+    q.queue = reinterpret_cast<uint4 *>(base + q.L.queue);
+    q.narrow = q.p.max_bins <= 64;                 // then n_keys <= 64 * DG_MAX_LEVELS
+    q.grid = sweep_grid(q.p);                      // persistent workgroups of the count and fill sweeps (same tiling)
+    return DG_OK;
+}
+
+// count sweep and scans of samples [n0, n0 + nb): every workgroup's slice of every bin's queue, the bins' queue ranges,
+// the accumulate workgroups per bin; also clears the slot of the batch's largest magnitude
+void launch_count(const Prepared &q, const dg_grid_desc *d, const float *u, uint64_t n0, uint64_t nb, hipStream_t st)
+{
+    const Plan &p = q.p;
+    count_lds_kernel<<<q.grid, q.narrow ? kTile : kRingThreads, p.n_keys * 4, st>>>(*d, p, u, n0, nb, q.rows);
+    scan_rows_kernel<<<(p.n_keys + kScanKeys - 1) / kScanKeys, kScanKeys * kScanGroups, 0, st>>>(q.rows, q.grid, p.n_keys, slice_round(p), q.totals);
+    scan_totals_kernel<<<1, 1024, 0, st>>>(q.totals, p.n_keys, q.binbase, q.blkbase);
+}
+
+}  // namespace
+
+int encode_bwd_binned_count(const dg_grid_desc *d, const float *u, uint64_t N, void *ws, size_t ws_bytes, hipStream_t st)
+{
+    const char *who = "dg_hashgrid_encode_bwd_count";
+    Prepared q;
+    if (int rc = prepare(who, d, N, ws, ws_bytes, q)) return rc;
+    if (q.p.n_keys == 0) return DG_OK;
+    if (q.L.batch < N)
+        return fail(DG_ERR_WORKSPACE, "%s: counting ahead needs a workspace that holds all %llu samples in one batch (it holds %llu)", who,
+                    (unsigned long long)N, (unsigned long long)q.L.batch);
+    launch_count(q, d, u, 0, N, st);
+    return launch_status(who);
+}
+
+int encode_bwd_binned(const dg_grid_desc *d, const float *u, const float *dfeat, uint64_t N, float *dtable, void *ws,
+                      size_t ws_bytes, bool counted, hipStream_t st)
+{
+    const char *who = "dg_hashgrid_encode_bwd";
+    Prepared q;
+    if (int rc = prepare(who, d, N, ws, ws_bytes, q)) return rc;
+    const Plan &p = q.p;
+    if (counted && p.n_keys && q.L.batch < N)
+        return fail(DG_ERR_WORKSPACE, "%s: the workspace holds %llu of %llu samples: no counts from dg_hashgrid_encode_bwd_count can be in it",
+                    who, (unsigned long long)q.L.batch, (unsigned long long)N);
     if (p.first_level > 0) {
         const uint64_t tiles = (N + kCoarseBlock - 1) / kCoarseBlock;
         const uint32_t grid = (uint32_t)(tiles < kCoarseGrid ? tiles : kCoarseGrid);
         coarse_kernel<<<grid, kCoarseBlock, 2 * d->offset[p.first_level] * sizeof(double), st>>>(
             *d, p.first_level, u, (const float2 *)dfeat, N, dtable);
     }
-    if (p.n_keys == 0) return launch_status("dg_hashgrid_encode_bwd");
-
-    // largest batch the workspace holds
-    uint64_t batch = (N + kTile - 1) / kTile * kTile;
-    const uint64_t cap = max_batch(d, p);
-    if (batch > cap) batch = cap;
-    while (batch > kTile && make_layout(d, p, batch).total > ws_bytes) batch = (batch / 2 + kTile - 1) / kTile * kTile;
-    const Layout L = make_layout(d, p, batch);
-    if (L.total > ws_bytes)
-        return fail(DG_ERR_WORKSPACE, "dg_hashgrid_encode_bwd: workspace %zu bytes cannot hold one tile (%zu needed)", ws_bytes, L.total);
-    char *base = static_cast<char *>(ws);
-    uint32_t *rows = reinterpret_cast<uint32_t *>(base + L.rows);
-    uint32_t *totals = reinterpret_cast<uint32_t *>(base + L.totals);
-    uint32_t *binbase = reinterpret_cast<uint32_t *>(base + L.binbase);
-    uint32_t *blkbase = reinterpret_cast<uint32_t *>(base + L.blkbase);
-    uint4 *queue = reinterpret_cast<uint4 *>(base + L.queue);
-    const bool narrow = p.max_bins <= 64;                 // then n_keys <= 64 * DG_MAX_LEVELS
-    const uint32_t grid = sweep_grid(p);                  // persistent workgroups of the count and fill sweeps (same tiling)
-    if (p.n_keys > kMaxKeys) return fail(DG_ERR_UNSUPPORTED, "dg_hashgrid_encode_bwd: %u table regions exceed %u", p.n_keys, kMaxKeys);
-
+    if (p.n_keys == 0) return launch_status(who);
+    const uint64_t batch = q.L.batch;
     for (uint64_t n0 = 0; n0 < N; n0 += batch) {
         const uint64_t nb = N - n0 < batch ? N - n0 : batch;
-        count_lds_kernel<<<grid, narrow ? kTile : kRingThreads, p.n_keys * 4, st>>>(*d, p, u, n0, nb, rows);
-        scan_rows_kernel<<<(p.n_keys + kScanKeys - 1) / kScanKeys, kScanKeys * kScanGroups, 0, st>>>(rows, grid, p.n_keys, slice_round(p), totals);
-        scan_totals_kernel<<<1, 1024, 0, st>>>(totals, p.n_keys, binbase, blkbase);
-        if (narrow)
-            fill_narrow_kernel<<<kBinGrid, kNarrowThreads, kNarrowLds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows, binbase, queue,
-                                                                             dtable, binbase + p.n_keys + 1);
+        if (!counted) launch_count(q, d, u, n0, nb, st);
+        if (q.narrow)
+            fill_narrow_kernel<<<kBinGrid, kNarrowThreads, kNarrowLds, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, q.rows, q.binbase, q.queue,
+                                                                             dtable, q.binbase + p.n_keys + 1);
         else
-            fill_ring_kernel<<<grid, kRingThreads, p.max_bins * (kRingSlots * 16 + 12) + 16, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, rows,
-                                                                                                  binbase, queue, dtable, binbase + p.n_keys + 1);
+            fill_ring_kernel<<<q.grid, kRingThreads, p.max_bins * (kRingSlots * 16 + 12) + 16, st>>>(*d, p, u, (const float2 *)dfeat, N, n0, nb, q.rows,
+                                                                                                    q.binbase, q.queue, dtable, q.binbase + p.n_keys + 1);
         const uint64_t records = nb * 4ull * (d->n_levels - p.first_level) + slice_padding(p);
         const uint32_t acc_grid = (uint32_t)(records / kAccRecords) + p.n_keys;       // upper bound of the workgroups needed
-        accumulate_kernel<<<acc_grid, kAccBlock, 2 * kChunk * sizeof(double), st>>>(*d, p, binbase, blkbase, (const u32x4 *)queue, dtable);
+        accumulate_kernel<<<acc_grid, kAccBlock, 2 * kChunk * sizeof(double), st>>>(*d, p, q.binbase, q.blkbase, (const u32x4 *)q.queue, dtable);
     }
-    return launch_status("dg_hashgrid_encode_bwd");
+    return launch_status(who);
 }
 
 }  // namespace dg

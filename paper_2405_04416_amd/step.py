@@ -107,6 +107,12 @@ class TrainStep:
         want = max(B.dg_hashgrid_encode_bwd_workspace_bytes(mm.grid, n) for mm in models.values())
         self.ws_enc = torch.zeros(min(want, encode_ws_cap) // 4 + 64, dtype=f32, device=self.dev) if binned_backward else None
         self.foreign_prefilled = bool(foreign_prefilled)
+        # The queue sizes of the binned table-gradient pass depend on the sample coordinates alone: for the sub-model whose
+        # backward pass comes first they are counted on a second stream as soon as its samples exist, beside the forward
+        # pass (which waits for memory and leaves the arithmetic units idle), together with the clearing of its gradient
+        # buffers.  One workspace serves all sub-models, so only one count can be ahead.
+        self.side = torch.cuda.Stream(device=self.dev) if binned_backward and occupancy is None else None
+        self.counted = None     # (partition, samples, event) of a count that is ahead
         self.offsets = None
         self.local = {}         # resident partition -> index of its first segment among the resident segments (sample buffers)
         self.t_fixed = None
@@ -160,7 +166,7 @@ class TrainStep:
         if foreign is None and not self.foreign_prefilled and len(self.resident) < self.P:
             raise B.DistGridError("partitions %s are not resident: pass `foreign` to fill their partials, or construct with "
                                   "foreign_prefilled=True" % sorted(set(range(self.P)) - set(self.resident)))
-        self._partials(o, d, jitter)
+        self._partials(o, d, jitter, training=True)
         if foreign is not None:
             foreign(self)
         with self._timed("dg_merge_segments"):
@@ -192,9 +198,32 @@ class TrainStep:
         B.dg_merge_depth(Dk, self.Tk, self.seg_count, self.R, self.k_max, D)
         return self.C, D, self.T
 
-    def _partials(self, o, d, jitter=None, want_t=False, fused_depth=None):
+    def _count_ahead(self, p, sl, N):
+        """Starts the count sweep of sub-model p's table-gradient pass (and clears its gradient buffers) on the second
+        stream, behind the work already queued on this one; the backward pass picks it up."""
+        m = self.models[p]
+        if B.dg_hashgrid_encode_bwd_workspace_bytes(m.grid, N) > self.ws_enc.numel() * self.ws_enc.element_size():
+            return                                  # the workspace would batch: counted with each batch, as usual
+        here = torch.cuda.Event()
+        here.record()
+        go = torch.cuda.Event()
+        with torch.cuda.stream(self.side):
+            self.side.wait_event(here)
+            go.record()
+            B.dg_hashgrid_encode_bwd_count(m.grid, self.u[sl], N, self.ws_enc)
+            m.dtable.zero_()
+            m.dW.zero_()
+            done = torch.cuda.Event()
+            done.record()
+        # this stream goes on once the second one has got that far: the count sweep's few workgroups are then handed out
+        # before the forward gather's millions arrive and fill every wavefront slot of the chip
+        torch.cuda.current_stream().wait_event(go)
+        self.counted = (p, N, done)
+
+    def _partials(self, o, d, jitter=None, want_t=False, fused_depth=None, training=False):
         """Segments, and per resident sub-model: samples, encode, MLPs, local compositing into the partial slots.
         fused_depth: None, or Dk [R,k_max]: networks, compositing and depth in one call (evaluation rendering)."""
+        self.counted = None
         S = self.S
         self.segments(o, d)
         if self.occ is not None:
@@ -212,6 +241,8 @@ class TrainStep:
                                      self.parts_host[p], S, self.seed, jit, self.u[sl], self.delta[sl],
                                      self.t_fixed[sl] if want_t else None)
             rows = self._rows(p)
+            if training and self.side is not None and self.counted is None:
+                self._count_ahead(p, sl, N)
             with self._timed("dg_dir_encode"):
                 B.dg_dir_encode(d, self.seg_ray[b:e], n_seg, self.deg, self.dir_enc[rows])
             with self._timed("dg_hashgrid_encode_fwd"):
@@ -354,9 +385,14 @@ class TrainStep:
             b, e, sl = self._slices(p)
             n_seg = e - b
             m = self.models[p]
-            with self._timed("zero_gradients"):
-                m.dtable.zero_()
-                m.dW.zero_()
+            ahead = self.counted is not None and self.counted[0] == p
+            if ahead:
+                torch.cuda.current_stream().wait_event(self.counted[2])     # queues counted, gradient buffers cleared
+                self.counted = None
+            else:
+                with self._timed("zero_gradients"):
+                    m.dtable.zero_()
+                    m.dW.zero_()
             if n_seg == 0:
                 continue
             N = n_seg * S
@@ -368,7 +404,10 @@ class TrainStep:
                 B.dg_mlp_bwd_app(m.mlp, m.weights, self.feat[sl], self.dir_enc[rows], None if self.app_rows is None else self.app_rows[rows],
                                  S, N, self.dsigma[sl], self.drgb[sl], self.loss_scale, self.dfeat[sl], m.dW, self.ws_mlp)
             with self._timed("dg_hashgrid_encode_bwd"):
-                B.dg_hashgrid_encode_bwd(m.grid, self.u[sl], self.dfeat[sl], N, m.dtable, self.ws_enc)
+                if ahead:
+                    B.dg_hashgrid_encode_bwd_counted(m.grid, self.u[sl], self.dfeat[sl], N, m.dtable, self.ws_enc)
+                else:
+                    B.dg_hashgrid_encode_bwd(m.grid, self.u[sl], self.dfeat[sl], N, m.dtable, self.ws_enc)
 
     def step(self, o, d, Cgt, jitter=None, foreign=None):
         self.forward(o, d, Cgt, jitter, foreign)

@@ -269,6 +269,45 @@ def test_encode_bwd_several_tiles_per_workgroup(key, N, capped):
     assert np.all(got[ref == 0] == 0)
 
 
+@pytest.mark.parametrize("key,N", [("c2", 40011), ("huge", 30011), ("c1", 5000)])
+def test_encode_bwd_counted_ahead(key, N):
+    """The binned pass in two parts (queue sizes counted early, on another stream; the rest later) gives what the one call gives,
+    and the oracle's result."""
+    say("encode bwd counted ahead %s N=%d" % (key, N))
+    g, r, _ = _both_grids(key)
+    L = g.n_levels
+    u = _coords(N, "rays", seed=45)
+    dfeat = (np.random.default_rng(46).standard_normal((N, 2 * L)) * 1e-3).astype(np.float32)
+    ud, dd = dev(u), dev(to_planes(dfeat))
+    ws = torch.zeros(B.dg_hashgrid_encode_bwd_workspace_bytes(g, N) // 4 + 64, device=DEV)
+    whole = torch.zeros(r.n_entries, 2, device=DEV)
+    B.dg_hashgrid_encode_bwd(g, ud, dd, N, whole, ws)
+    torch.cuda.synchronize()
+    ws.fill_(float("nan"))                                   # nothing of the first call may be left to lean on
+    parts = torch.zeros(r.n_entries, 2, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.dg_hashgrid_encode_bwd_count(g, ud, N, ws)
+        done = torch.cuda.Event()
+        done.record()
+    torch.cuda.current_stream().wait_event(done)
+    B.dg_hashgrid_encode_bwd_counted(g, ud, dd, N, parts, ws)
+    torch.cuda.synchronize()
+    ref = oracle.encode_bwd(r, u, dfeat.astype(np.float64))
+    a, b = host(whole).astype(np.float64), host(parts).astype(np.float64)
+    for l in range(L):
+        sl = slice(r.first[l], r.first[l + 1])
+        assert rel_err(b[sl], a[sl]) <= 1e-6 and rel_err(b[sl], ref[sl]) <= TOL_F16, l
+    # a workspace that cannot hold all samples in one batch is refused by both parts
+    small = torch.zeros(B.dg_hashgrid_encode_bwd_workspace_bytes(g, max(N // 4, 512)) // 4, device=DEV)
+    if small.numel() * 4 < B.dg_hashgrid_encode_bwd_workspace_bytes(g, N) and key != "c1":
+        with pytest.raises(B.DistGridError):
+            B.dg_hashgrid_encode_bwd_count(g, ud, N, small)
+        with pytest.raises(B.DistGridError):
+            B.dg_hashgrid_encode_bwd_counted(g, ud, dd, N, parts, small)
+
+
 @pytest.mark.parametrize("bad", [np.inf, np.nan])
 def test_encode_bwd_binned_marks_non_finite_gradients(bad):
     """A feature gradient that is infinite or NaN (an fp16 delta that overflowed under the loss scale) must not turn into
