@@ -32,22 +32,27 @@ adam_kernel(float *__restrict__ param, float *__restrict__ grad, float *__restri
 {
     const uint64_t n4 = n / 4, i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i < n4) {
-        const float4 g = reinterpret_cast<const float4 *>(grad)[i];
+        // every array is touched once per sweep and is far larger than the caches: non-temporal loads and stores
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const f4 g = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(grad) + i);
         const bool touched = g.x != 0.0f || g.y != 0.0f || g.z != 0.0f || g.w != 0.0f;
         if (touched || !c.skip_zero) {
-            float4 p = reinterpret_cast<float4 *>(param)[i], mm = reinterpret_cast<float4 *>(m)[i], vv = reinterpret_cast<float4 *>(v)[i];
-            if (g.x != 0.0f || !c.skip_zero) adam_one(p.x, g.x, mm.x, vv.x, c);
-            if (g.y != 0.0f || !c.skip_zero) adam_one(p.y, g.y, mm.y, vv.y, c);
-            if (g.z != 0.0f || !c.skip_zero) adam_one(p.z, g.z, mm.z, vv.z, c);
-            if (g.w != 0.0f || !c.skip_zero) adam_one(p.w, g.w, mm.w, vv.w, c);
-            reinterpret_cast<float4 *>(param)[i] = p;
-            reinterpret_cast<float4 *>(m)[i] = mm;
-            reinterpret_cast<float4 *>(v)[i] = vv;
-            if (touched) reinterpret_cast<float4 *>(grad)[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            const f4 p0 = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(param) + i);
+            const f4 m0 = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(m) + i);
+            const f4 v0 = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(v) + i);
+            float p[4] = {p0.x, p0.y, p0.z, p0.w}, mm[4] = {m0.x, m0.y, m0.z, m0.w}, vv[4] = {v0.x, v0.y, v0.z, v0.w};
+            const float gg[4] = {g.x, g.y, g.z, g.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (gg[k] != 0.0f || !c.skip_zero) adam_one(p[k], gg[k], mm[k], vv[k], c);
+            __builtin_nontemporal_store(f4{p[0], p[1], p[2], p[3]}, reinterpret_cast<f4 *>(param) + i);
+            __builtin_nontemporal_store(f4{mm[0], mm[1], mm[2], mm[3]}, reinterpret_cast<f4 *>(m) + i);
+            __builtin_nontemporal_store(f4{vv[0], vv[1], vv[2], vv[3]}, reinterpret_cast<f4 *>(v) + i);
+            if (touched) __builtin_nontemporal_store(f4{0.0f, 0.0f, 0.0f, 0.0f}, reinterpret_cast<f4 *>(grad) + i);
             if (param_half) {
                 __half2 *h = reinterpret_cast<__half2 *>(param_half) + 2 * i;
-                h[0] = __floats2half2_rn(p.x, p.y);
-                h[1] = __floats2half2_rn(p.z, p.w);
+                h[0] = __floats2half2_rn(p[0], p[1]);
+                h[1] = __floats2half2_rn(p[2], p[3]);
             }
         }
     }
