@@ -17,8 +17,10 @@
  *
  * Parity pins (tests/test_oracle_*.py): every function below is pinned to a
  * closed form, an invariant, a library routine or brute force; none is
- * "parity unpinned" except dgo_grid_param_count against the two parameter
- * totals the paper prints (Sec. 5.3), whose scene extents are not given.
+ * "parity unpinned".  dgo_grid_param_count is pinned by brute force (every
+ * vertex of every level of small grids visited, the reached entries counted)
+ * and to the bound of Sec. 3.2; the two totals the paper prints (Sec. 5.3)
+ * cannot be reproduced, the scenes' extents and base resolution are not given.
  */
 #ifndef DGO_H
 #define DGO_H
