@@ -353,6 +353,45 @@ def test_step_refuses_to_merge_slots_nobody_fills():
     assert rel_err(host(step.C), ref["C"]) <= TOL_F16 and rel_err(host(step.T), ref["T"]) <= TOL_F16
 
 
+def test_step_with_a_workspace_that_only_the_smaller_sub_model_fits():
+    """Two resident sub-models, the first with more samples than the table-gradient workspace holds at once (its pass
+    runs in batches), the second with fewer: the second one's queue sizes must not be counted ahead into the workspace
+    the first one's pass is about to use.  Gradients against a step with room for everything."""
+    say("step on two sub-models with a workspace between their needs")
+    cfg = dict(di.config("c3_2x2"))
+    cfg["grid"] = dict(cfg["grid"], log2_T=16)
+    R, S = 3000, cfg["S"]
+    o, d = di.make_rays(cfg, seed=21, R=R)
+    Cgt = di.make_targets(R, seed=21)
+    hm = ostep.make_models(cfg, seed=21)
+    for m in hm.values():
+        m["table"] *= np.float32(3000.0)
+    # segments per partition, to pick a large and a small sub-model
+    probe = make_step(cfg, gpu_models(cfg, hm), R, loss_scale=2.0 ** 14, lambda1=1e-3, seed=21)
+    probe.segments(dev(o), dev(d))
+    n = [probe.offsets[p + 1] - probe.offsets[p] for p in range(4)]
+    big, small = int(np.argmax(n)), int(np.argmin(n))
+    assert n[small] > 0 and n[big] > n[small]
+    grads = []
+    for cap in (None, "between"):
+        gm = gpu_models(cfg, hm)
+        kw = {}
+        if cap:
+            need_small = B.dg_hashgrid_encode_bwd_workspace_bytes(gm[small].grid, n[small] * S)
+            need_big = B.dg_hashgrid_encode_bwd_workspace_bytes(gm[big].grid, n[big] * S)
+            assert need_small < need_big
+            kw["encode_ws_cap"] = (need_small + need_big) // 2 // 256 * 256
+        step = make_step(cfg, gm, R, resident=[big, small], loss_scale=2.0 ** 14, lambda1=1e-3, seed=21, foreign_prefilled=True, **kw)
+        step.step(dev(o), dev(d), dev(Cgt), None)
+        torch.cuda.synchronize()
+        grads.append({p: (host(gm[p].dtable).astype(np.float64), host(gm[p].dW).astype(np.float64)) for p in (big, small)})
+    for p in (big, small):
+        for got, want, what in zip(grads[1][p], grads[0][p], ("dtable", "dW")):
+            scale = np.abs(want).max()
+            assert scale > 0
+            assert np.abs(got - want).max() <= 1e-5 * scale, "%s of sub-model %d" % (what, p)
+
+
 def test_optimiser_step_drops_a_step_whose_gradients_overflowed():
     say("optimiser step with a non-finite weight gradient")
     cfg = di.config("c1_tiny")
