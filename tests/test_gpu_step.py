@@ -301,26 +301,34 @@ def test_step_full_size_bench_configuration():
     assert bool((step.T[miss] == 1).all()) and bool((step.C[miss] == 0).all())
 
 
-def test_step_full_size_headline_configuration():
-    """c5 (one GPU's share of the 2 x 4 tiling, 2^20 rays, T = 2^24) at the size and launch configuration bench.py
-    times: the ray bookkeeping of the whole batch against the oracle, sampled rays through every stage of the oracle,
-    and properties of the gradients that hold at any size."""
-    say("step c5_share full size (2^20 rays x 64 samples, T = 2^24)")
-    cfg = di.config("c5_share")
+@pytest.mark.parametrize("name", ["c5_share", "c4_big", "c3_2x2"])
+def test_step_full_size_headline_configuration(name):
+    """The workloads bench.py times at T >= 2^22 -- c5 (the headline: one GPU's share of the 2 x 4 tiling, 2^20 rays,
+    T = 2^24), c4 (2^19 rays, T = 2^24, 48 samples per segment) and c3 (four resident sub-models, T = 2^22) -- at their
+    full size and in bench.py's launch configuration: the ray bookkeeping of the whole batch against the oracle,
+    sampled rays through every stage of the oracle, and properties of the gradients that hold at any size."""
+    say("step %s full size" % name)
+    cfg = di.config(name)
     cfg["table_range"] = cfg["table_range"] * 3000.0          # lift sigma off ~1 so compositing is exercised
-    R, S, k_max, res = cfg["R"], cfg["S"], cfg["k_max"], cfg["resident"]
+    R, S, k_max = cfg["R"], cfg["S"], cfg["k_max"]
     P = cfg["parts"].shape[0]
+    resident = [cfg["resident"]] if "resident" in cfg else list(range(P))
+    share = len(resident) < P
     o, d = di.make_rays(cfg, seed=0)
     Cgt = di.make_targets(R, seed=0)
-    fC, fT = di.make_foreign_partials(R, k_max, seed=0)
-    hm = ostep.make_models(dict(cfg, resident_list=[res]), seed=0)
+    hm = ostep.make_models(dict(cfg, resident_list=resident), seed=0)
     gm = gpu_models(cfg, hm)
-    step = make_step(cfg, gm, R, resident=[res], loss_scale=2.0 ** 16, lambda1=1e-3, seed=0, max_segments=R, foreign_prefilled=True)
-    step.Ck.copy_(dev(fC)); step.Tk.copy_(dev(fT))
+    step = make_step(cfg, gm, R, resident=resident, loss_scale=2.0 ** 16, lambda1=1e-3, seed=0,
+                     max_segments=R * len(resident) if share else R * min(k_max, 4), foreign_prefilled=share)
+    if share:                                                   # partial results of the boxes that live on other GPUs
+        fC, fT = di.make_foreign_partials(R, k_max, seed=0)
+        step.Ck.copy_(dev(fC)); step.Tk.copy_(dev(fT))
+    else:
+        fC, fT = np.zeros((R, k_max, 3), np.float32), np.zeros((R, k_max), np.float32)
     step.step(dev(o), dev(d), dev(Cgt))
     torch.cuda.synchronize()
 
-    # (a) segments of every ray through all eight boxes and their distribution: bit for bit
+    # (a) segments of every ray through every box and their distribution: bit for bit
     cnt, seg_t, seg_part, status = oracle.ray_aabb_segments(o, d, cfg["parts"], 0.0, k_max)
     assert status == 0
     np.testing.assert_array_equal(host(step.seg_count), cnt)
@@ -330,54 +338,59 @@ def test_step_full_size_headline_configuration():
     off, seg_ray, seg_slot = oracle.bucket_segments(cnt, seg_part, P)
     np.testing.assert_array_equal(host(step.part_offset), off)
     n_all = int(off[-1])
-    np.testing.assert_array_equal(host(step.seg_ray)[:n_all], seg_ray[:n_all])
-    np.testing.assert_array_equal(host(step.seg_slot)[:n_all], seg_slot[:n_all])
-    b, e = int(off[res]), int(off[res + 1])
-    assert e - b == R                                           # every ray crosses the resident box once
-    N = (e - b) * S
+    np.testing.assert_array_equal(host(step.seg_ray)[:n_all], seg_ray)
+    np.testing.assert_array_equal(host(step.seg_slot)[:n_all], seg_slot)
+    if share:
+        assert int(off[resident[0] + 1]) - int(off[resident[0]]) == R    # every ray crosses the resident box once
+    where = np.full(R * k_max, -1, np.int64)                    # (ray, slot) -> place in the distributed list
+    where[seg_ray.astype(np.int64) * k_max + seg_slot] = np.arange(n_all)
 
-    # (b) 64 sampled rays through the oracle: samples, encode, networks, local rendering, merge with the foreign partials
-    m = hm[res]
-    w64 = m["weights"].astype(np.float64)
-    slot_of_ray = np.argmax((seg_part == res) & used, axis=1)
-    pos_in_bucket = np.empty(R, np.int64)
-    pos_in_bucket[seg_ray[b:e]] = np.arange(e - b)
-    sigma_d, u_d = step.sigma, step.u
-    for r in np.random.default_rng(0).choice(R, 64, replace=False):
-        j, k = int(pos_in_bucket[r]), int(slot_of_ray[r])
-        u, delta = oracle.sample_segments(o, d, seg_t, np.array([r], np.uint32), np.array([k], np.uint32), 0, 1,
-                                          cfg["parts"][res], S, seed=0)
-        np.testing.assert_array_equal(host(u_d[j * S:(j + 1) * S]).view(np.uint32), u.view(np.uint32))
-        feat = oracle.encode_fwd(m["grid"], m["table"], u)
-        sig, rgb = oracle.mlp_fwd(m["mlp"], w64, feat, oracle.sh(d[r:r + 1], cfg["mlp"]["sh_degree"]), S)
-        Cs, Ts = oracle.composite_fwd(sig, rgb, delta.astype(np.float64), S)
-        assert rel_err(host(sigma_d[j * S:(j + 1) * S]), sig) <= TOL_F16
+    # (b) sampled rays through the oracle: samples, encode, networks, local rendering, merge
+    w64 = {p: hm[p]["weights"].astype(np.float64) for p in resident}
+    hits = np.flatnonzero(cnt > 0)
+    for r in np.random.default_rng(0).choice(hits, 48, replace=False):
         Ck = fC[r:r + 1].astype(np.float64).copy(); Tk = fT[r:r + 1].astype(np.float64).copy()
-        Ck[0, k] = Cs[0]; Tk[0, k] = Ts[0]
+        for k in range(int(cnt[r])):
+            p = int(seg_part[r, k])
+            if p not in resident:
+                continue
+            j = step.local[p] + int(where[r * k_max + k]) - int(off[p])      # the segment's place in the sample buffers
+            u, delta = oracle.sample_segments(o, d, seg_t, np.array([r], np.uint32), np.array([k], np.uint32), 0, 1,
+                                              cfg["parts"][p], S, seed=0)
+            np.testing.assert_array_equal(host(step.u[j * S:(j + 1) * S]).view(np.uint32), u.view(np.uint32))
+            feat = oracle.encode_fwd(hm[p]["grid"], hm[p]["table"], u)
+            sig, rgb = oracle.mlp_fwd(hm[p]["mlp"], w64[p], feat, oracle.sh(d[r:r + 1], cfg["mlp"]["sh_degree"]), S)
+            Cs, Ts = oracle.composite_fwd(sig, rgb, delta.astype(np.float64), S)
+            assert rel_err(host(step.sigma[j * S:(j + 1) * S]), sig) <= TOL_F16
+            assert rel_err(host(step.Ck[r, k]), Cs[0], floor=1e-3) <= TOL_F16 and abs(float(step.Tk[r, k]) - Ts[0]) <= TOL_F16
+            Ck[0, k] = Cs[0]; Tk[0, k] = Ts[0]
         Cm, Tm = oracle.merge_fwd(Ck, Tk, cnt[r:r + 1])
-        assert rel_err(host(step.Ck[r, k]), Cs[0], floor=1e-3) <= TOL_F16 and abs(float(step.Tk[r, k]) - Ts[0]) <= TOL_F16
         assert rel_err(host(step.C[r]), Cm[0], floor=1e-3) <= TOL_F16 and abs(float(step.T[r]) - Tm[0]) <= TOL_F16
 
-    # (c) properties that hold at any size
-    g = gm[res]
-    L = g.grid.n_levels
-    dfeat = step.dfeat[:N].reshape(L, N, 2)                     # level-major planes
-    dtab = g.dtable
-    assert bool(torch.isfinite(dtab).all()) and bool(torch.isfinite(g.dW).all()) and float(g.dW.abs().max()) > 0
-    # trilinear weights sum to one: per level and feature, the table gradient sums to the feature gradient;
-    # transpose identity <dfeat, E(theta')> = <dtable, theta'> with a second random table (level by level: 17 GB otherwise)
-    probe = torch.rand_like(g.table) - 0.5
-    f2 = torch.zeros(L, N, 2, device=DEV)
-    B.dg_hashgrid_encode_fwd(g.grid, probe, step.u[:N], N, f2)
-    lhs = mag_all = 0.0
-    for l in range(L):
-        df = dfeat[l].double()
-        tot = dtab[g.grid.offset[l]:g.grid.offset[l + 1]].double().sum(0).cpu().numpy()
-        assert np.all(np.abs(tot - df.sum(0).cpu().numpy()) <= TOL_F16 * df.abs().sum(0).cpu().numpy()), l
-        prod = df * f2[l].double()
-        lhs += float(prod.sum()); mag_all += float(prod.abs().sum())
-    rhs = float((dtab.double() * probe.double()).sum())
-    assert abs(lhs - rhs) <= TOL_F16 * mag_all
+    # (c) properties that hold at any size, per resident sub-model
+    for p in resident:
+        g = gm[p]
+        b, e, sl = step._slices(p)
+        N = (e - b) * S
+        L = g.grid.n_levels
+        dfeat = step.dfeat[sl].reshape(L, N, 2)                 # level-major planes
+        dtab = g.dtable
+        assert bool(torch.isfinite(dtab).all()) and bool(torch.isfinite(g.dW).all()) and float(g.dW.abs().max()) > 0
+        # trilinear weights sum to one: per level and feature, the table gradient sums to the feature gradient;
+        # transpose identity <dfeat, E(theta')> = <dtable, theta'> with a second random table (level by level: 17 GB otherwise)
+        probe = torch.rand_like(g.table) - 0.5
+        f2 = torch.zeros(L, N, 2, device=DEV)
+        B.dg_hashgrid_encode_fwd(g.grid, probe, step.u[sl], N, f2)
+        lhs = mag_all = 0.0
+        for l in range(L):
+            df = dfeat[l].double()
+            tot = dtab[g.grid.offset[l]:g.grid.offset[l + 1]].double().sum(0).cpu().numpy()
+            assert np.all(np.abs(tot - df.sum(0).cpu().numpy()) <= TOL_F16 * df.abs().sum(0).cpu().numpy()), (p, l)
+            prod = df * f2[l].double()
+            lhs += float(prod.sum()); mag_all += float(prod.abs().sum())
+        rhs = float((dtab.double() * probe.double()).sum())
+        assert abs(lhs - rhs) <= TOL_F16 * mag_all
+        del probe, f2
 
 
 def test_optimiser_step_after_a_training_step():
