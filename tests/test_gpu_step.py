@@ -15,7 +15,6 @@ import oracle
 import oracle.step as ostep
 from paper_2405_04416_amd import binding as B
 
-import oracle
 from gpu_util import (DEV, TOL_F16, TOL_F32, assert_close_robust, dev, from_planes, gpu_models, have_gpu, host, make_step,
                       rel_err, split_appearance_weights)
 
