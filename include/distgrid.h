@@ -157,7 +157,7 @@ int dg_hashgrid_encode_fwd(const dg_grid_desc *desc, const float *table, const f
  * With a workspace of dg_hashgrid_encode_bwd_workspace_bytes(desc, N) bytes the contributions are
  * binned by table region and summed in on-chip memory first (much faster for large N); on that path a
  * contribution is rounded to 18 mantissa bits (relative error at most 2^-20, unbiased) before it is
- * summed exactly (in fixed point scaled to the batch's largest magnitude: a contribution below 2^-33 of that magnitude
+ * summed exactly (in fixed point scaled to the batch's largest magnitude: a contribution below 2^-32 of that magnitude
  * adds nothing).  If any contribution of the batch is infinite or NaN the sums cannot be formed: every table region
  * that received contributions then gets NaN in its first entry, so the gradient is visibly non-finite as it would be
  * with fp32 atomics.  ws must be 256-byte aligned; a smaller workspace is accepted and makes the call run

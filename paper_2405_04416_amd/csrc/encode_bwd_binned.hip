@@ -33,7 +33,11 @@ constexpr int kBinGrid = 768;                      // persistent binning workgro
 constexpr int kAccBlock = 1024;                    // threads of an accumulate workgroup (one per compute unit: its table fills LDS)
 constexpr int kAccDepth = 4;                       // records in flight per accumulate thread
 constexpr int kAccRecordsLog2 = 17;
-constexpr uint32_t kAccRecords = 1u << kAccRecordsLog2;   // records one accumulate workgroup sums
+constexpr uint32_t kAccRecords = 1u << kAccRecordsLog2;   // an accumulate workgroup sums at least this many records of a bin (or all it has) ...
+constexpr int kAccMaxLog2 = kAccRecordsLog2 + 1;          // ... and fewer than this many: a bin is cut into floor(records / kAccRecords) equal pieces
+// pieces a bin of `total` records is cut into: a bin with less than two pieces' worth stays whole (a second workgroup
+// would clear and write out a table of its own for little)
+__host__ __device__ __forceinline__ uint32_t acc_pieces(uint32_t total) { return total == 0u ? 0u : (total >> kAccRecordsLog2 ? total >> kAccRecordsLog2 : 1u); }
 constexpr int kCoarseBlock = 1024;                 // coarse prefix: threads per workgroup, persistent workgroups (one per compute unit)
 constexpr int kCoarseGrid = 256;
 
@@ -677,7 +681,7 @@ scan_rows_kernel(uint32_t *__restrict__ rows, uint32_t n_rows, uint32_t n_keys, 
 }
 
 // binbase = exclusive scan of totals; blkbase = exclusive scan of the number of accumulate workgroups each
-// bin gets (one per kAccRecords records), so that work is balanced whatever the bins hold
+// bin gets (acc_pieces of its record count), so that work is balanced whatever the bins hold
 // (one workgroup; n_keys is at most a few tens of thousands)
 __global__ void __launch_bounds__(1024)
 scan_totals_kernel(const uint32_t *__restrict__ totals, uint32_t n_keys, uint32_t *__restrict__ binbase,
@@ -686,7 +690,7 @@ scan_totals_kernel(const uint32_t *__restrict__ totals, uint32_t n_keys, uint32_
     __shared__ uint32_t part[1024], part_b[1024];
     const uint32_t per = (n_keys + 1023) / 1024, lo = threadIdx.x * per;
     uint32_t s = 0, sb = 0;
-    for (uint32_t i = lo; i < lo + per && i < n_keys; ++i) { s += totals[i]; sb += (totals[i] + kAccRecords - 1) / kAccRecords; }
+    for (uint32_t i = lo; i < lo + per && i < n_keys; ++i) { s += totals[i]; sb += acc_pieces(totals[i]); }
     part[threadIdx.x] = s;
     part_b[threadIdx.x] = sb;
     __syncthreads();
@@ -705,17 +709,17 @@ scan_totals_kernel(const uint32_t *__restrict__ totals, uint32_t n_keys, uint32_
     uint32_t run = part[threadIdx.x], run_b = part_b[threadIdx.x];
     for (uint32_t i = lo; i < lo + per && i < n_keys; ++i) {
         binbase[i] = run; blkbase[i] = run_b;
-        run += totals[i]; run_b += (totals[i] + kAccRecords - 1) / kAccRecords;
+        run += totals[i]; run_b += acc_pieces(totals[i]);
     }
 }
 
 // ------------------------------------------------------------------ accumulate one (bin, split)
 // The sums are kept as 64-bit integers in LDS: integer adds there run at almost twice the rate of fp64 adds
 // (2.7 against 1.5 T adds/s measured).  A value v becomes round(v * 2^k) with k chosen from the largest record
-// magnitude of the batch so that the sum of a workgroup's kAccRecords records stays below 2^50; the conversion is the
-// add of 1.5 * 2^52 in fp64, after which the low mantissa bits hold the integer in two's complement.  The quantum is
-// 2^-32 of the largest magnitude or finer, a thousand times below the fp32 rounding of the value itself, and integer
-// sums do not depend on the order of the additions.
+// magnitude of the batch so that the sum of a workgroup's records (fewer than 2^kAccMaxLog2) stays below 2^50; the
+// conversion is the add of 1.5 * 2^52 in fp64, after which the low mantissa bits hold the integer in two's complement.
+// The quantum is 2^-31 of the largest magnitude or finer, hundreds of times below the fp32 rounding of the value itself,
+// and integer sums do not depend on the order of the additions.
 constexpr double kIntegerMagic = 6755399441055744.0;     // 1.5 * 2^52
 
 __device__ __forceinline__ void add_fixed(unsigned long long *slot, float v, double scale)
@@ -740,11 +744,14 @@ accumulate_kernel(dg_grid_desc g, Plan plan, const uint32_t *__restrict__ binbas
         if (blkbase[mid] <= blockIdx.x) lo_k = mid; else hi_k = mid;
     }
     const uint32_t key = lo_k, part = blockIdx.x - blkbase[key];
-    const size_t begin = (size_t)binbase[key] + (size_t)part * kAccRecords;
-    const size_t end = min(begin + (size_t)kAccRecords, (size_t)binbase[key + 1]);
-    // 2^k with k = 50 - log2(kAccRecords) - 1 - (exponent of the largest magnitude): kAccRecords values of that size sum to < 2^50
+    // this workgroup's piece of the bin: the bin's records in equal shares (fewer than 2^kAccMaxLog2 each)
+    const uint32_t total = binbase[key + 1] - binbase[key], pieces = blkbase[key + 1] - blkbase[key];
+    const uint32_t share = (total + pieces - 1u) / pieces;
+    const size_t begin = (size_t)binbase[key] + (size_t)part * share;
+    const size_t end = min(begin + (size_t)share, (size_t)binbase[key + 1]);
+    // 2^k with k = 50 - kAccMaxLog2 - 1 - (exponent of the largest magnitude): 2^kAccMaxLog2 values of that size sum to < 2^50
     const uint32_t top = binbase[plan.n_keys + 1] >> 23;                 // biased exponent (0 for zero / denormal: no smaller k needed)
-    const int k = 50 - kAccRecordsLog2 - 1 - ((int)(top ? top : 1u) - 127);
+    const int k = 50 - kAccMaxLog2 - 1 - ((int)(top ? top : 1u) - 127);
     const double scale = __longlong_as_double((long long)(1023 + k) << 52);
     const double inv_scale = __longlong_as_double((long long)(1023 - k) << 52);
     if (top == 255u) {
