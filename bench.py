@@ -33,11 +33,11 @@ LINE_BYTES = 128               # what one L2 miss fetches
 # over the kernels an entry point launches: (fetched, written).  Measured once per workload with the kernels as they
 # stand; the runs, their commands and the calibration are in profiles/<workload>_hbm_traffic.md.
 MEASURED_TRAFFIC_BYTES = {
-    "c5_share": {"dg_hashgrid_encode_fwd": (283.1e9, 4.295e9), "dg_hashgrid_encode_bwd": (71.49e9, 56.18e9), "dg_mlp_fwd": (4.368e9, 1.074e9),
+    "c5_share": {"dg_hashgrid_encode_fwd": (283.1e9, 4.295e9), "dg_hashgrid_encode_bwd": (71.77e9, 55.86e9), "dg_mlp_fwd": (4.368e9, 1.074e9),
                  "dg_mlp_bwd": (11.96e9, 10.82e9)},
-    "c4_big": {"dg_hashgrid_encode_fwd": (82.81e9, 1.275e9), "dg_hashgrid_encode_bwd": (19.02e9, 15.01e9), "dg_mlp_fwd": (1.456e9, 0.3168e9),
-               "dg_mlp_bwd": (3.938e9, 3.247e9)},
-    "c2_ngp": {"dg_hashgrid_encode_fwd": (6.505e9, 0.854e9), "dg_hashgrid_encode_bwd": (10.69e9, 6.802e9), "dg_mlp_fwd": (0.8681e9, 0.2135e9),
+    "c4_big": {"dg_hashgrid_encode_fwd": (82.81e9, 1.275e9), "dg_hashgrid_encode_bwd": (19.05e9, 14.98e9), "dg_mlp_fwd": (1.456e9, 0.3168e9),
+               "dg_mlp_bwd": (3.939e9, 3.247e9)},
+    "c2_ngp": {"dg_hashgrid_encode_fwd": (6.503e9, 0.854e9), "dg_hashgrid_encode_bwd": (10.91e9, 6.764e9), "dg_mlp_fwd": (0.8681e9, 0.2135e9),
                "dg_mlp_bwd": (2.44e9, 2.214e9)},
 }
 
